@@ -1,0 +1,166 @@
+"""CPU oracle for Gumbel-max list sampling -- TEST INFRASTRUCTURE, not product.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg import this
+package.  It wraps oracle/libllc_ref.so (scalar fp64 C++, built by
+oracle/build.py) and holds two small pure-Python companions used to pin it:
+philox_py (big-integer Philox) and lml (the list matching lemma's bounds).
+It imports nothing from the HIP package.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+F32, BF16 = 0, 1
+LOGITS, PROBS, LOGW = 0, 1, 2
+
+_lib = None
+
+
+class _Args(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int64), ("K", ctypes.c_int64), ("V", ctypes.c_int64),
+        ("dtype", ctypes.c_int32), ("kind", ctypes.c_int32),
+        ("draft", ctypes.c_void_p),
+        ("draft_stride_b", ctypes.c_int64), ("draft_stride_k", ctypes.c_int64),
+        ("target", ctypes.c_void_p), ("target_stride_b", ctypes.c_int64),
+        ("temp_target", ctypes.c_float),
+        ("temp_draft", ctypes.c_void_p),
+        ("temp_draft_all", ctypes.c_float),
+        ("seed", ctypes.c_uint64), ("row_offset", ctypes.c_uint64),
+        ("X", ctypes.c_void_p), ("Y", ctypes.c_void_p), ("accept", ctypes.c_void_p),
+        ("match_k", ctypes.c_void_p),
+        ("keyX", ctypes.c_void_p), ("keyY", ctypes.c_void_p),
+        ("Yk", ctypes.c_void_p), ("keyYk", ctypes.c_void_p),
+        ("gapX", ctypes.c_void_p), ("gapY", ctypes.c_void_p), ("gapYk", ctypes.c_void_p),
+        ("threads", ctypes.c_int32),
+    ]
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build()
+        _lib = ctypes.CDLL(path)
+        _lib.llc_couple_ref.argtypes = [ctypes.POINTER(_Args)]
+        _lib.llc_couple_ref.restype = ctypes.c_int
+        _lib.llc_ref_philox4x32_10.argtypes = [ctypes.c_void_p] * 3
+        _lib.llc_ref_philox4x32_10.restype = None
+        _lib.llc_ref_shared_word.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint32,
+                                             ctypes.c_uint64]
+        _lib.llc_ref_shared_word.restype = ctypes.c_uint32
+        _lib.llc_ref_race_time.argtypes = [ctypes.c_uint32]
+        _lib.llc_ref_race_time.restype = ctypes.c_double
+        _lib.llc_ref_threads.restype = ctypes.c_int
+        _lib.llc_couple_is_ref.argtypes = (
+            [ctypes.c_int64] * 3 + [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                                    ctypes.c_int64, ctypes.c_int64, ctypes.c_uint64,
+                                    ctypes.c_uint64] + [ctypes.c_void_p] * 8 + [ctypes.c_int32])
+        _lib.llc_couple_is_ref.restype = ctypes.c_int
+    return _lib
+
+
+def philox4x32_10(ctr, key):
+    """The C++ oracle's Philox4x32-10 block function: 4 counter words, 2 key words -> 4 words."""
+    c = np.asarray(ctr, dtype=np.uint32).copy()
+    k = np.asarray(key, dtype=np.uint32).copy()
+    out = np.zeros(4, dtype=np.uint32)
+    lib().llc_ref_philox4x32_10(c.ctypes.data, k.ctypes.data, out.ctypes.data)
+    return out
+
+
+def shared_word(seed, row, k, i):
+    return int(lib().llc_ref_shared_word(seed, row, k, i))
+
+
+def race_time(x):
+    return float(lib().llc_ref_race_time(x))
+
+
+def threads():
+    return int(lib().llc_ref_threads())
+
+
+def _check_input(arr, dtype):
+    arr = np.asarray(arr)
+    if dtype == F32:
+        assert arr.dtype == np.float32, arr.dtype
+    else:
+        assert arr.dtype == np.uint16, "bf16 inputs are passed as their uint16 bit patterns"
+    assert arr.strides[-1] == arr.itemsize, "last dimension must be contiguous"
+    return arr
+
+
+def couple(draft, target, K, *, dtype=F32, kind=LOGITS, temp_target=1.0, temp_draft=None,
+           temp_draft_all=1.0, seed=0, row_offset=0, threads=0, partials=False):
+    """Algorithm 1 on host arrays.
+
+    draft: [B,V] (one proposal per row, shared by the K drafts) or [B,K,V];
+    target: [B,V].  Returns a dict of numpy arrays: X [B,K], Y [B], accept [B],
+    match_k [B], keyX [B,K], keyY [B], gapX [B,K], gapY [B] (relative gap to the
+    runner-up), and with partials=True also Yk, keyYk, gapYk [B,K].
+    """
+    draft = _check_input(draft, dtype)
+    target = _check_input(target, dtype)
+    B, V = target.shape
+    it = draft.itemsize
+    if draft.ndim == 2:
+        assert draft.shape == (B, V)
+        sb, sk = draft.strides[0] // it, 0
+    else:
+        assert draft.shape == (B, K, V)
+        sb, sk = draft.strides[0] // it, draft.strides[1] // it
+    out = {
+        "X": np.full((B, K), -2, np.int32), "Y": np.full(B, -2, np.int32),
+        "accept": np.zeros(B, np.uint8), "match_k": np.full(B, -2, np.int32),
+        "keyX": np.zeros((B, K)), "keyY": np.zeros(B),
+        "gapX": np.zeros((B, K)), "gapY": np.zeros(B),
+    }
+    if partials:
+        out.update(Yk=np.full((B, K), -2, np.int32), keyYk=np.zeros((B, K)),
+                   gapYk=np.zeros((B, K)))
+    a = _Args()
+    a.B, a.K, a.V = B, K, V
+    a.dtype, a.kind = dtype, kind
+    a.draft, a.draft_stride_b, a.draft_stride_k = draft.ctypes.data, sb, sk
+    a.target, a.target_stride_b = target.ctypes.data, target.strides[0] // it
+    a.temp_target = temp_target
+    td = None
+    if temp_draft is not None:
+        td = np.ascontiguousarray(temp_draft, dtype=np.float32)
+        assert td.shape == (K,)
+        a.temp_draft = td.ctypes.data
+    a.temp_draft_all = temp_draft_all
+    a.seed, a.row_offset = seed, row_offset
+    for name in out:
+        setattr(a, name, out[name].ctypes.data)
+    a.threads = threads
+    rc = lib().llc_couple_ref(ctypes.byref(a))
+    if rc != 0:
+        raise ValueError("llc_couple_ref rejected its arguments")
+    return out
+
+
+def couple_is(logw_enc, logw_dec, *, seed=0, row_offset=0, threads=0):
+    """Importance-weight form (Appendix C): logw_enc [B,N], logw_dec [B,L,N], fp32."""
+    enc = _check_input(logw_enc, F32)
+    dec = _check_input(logw_dec, F32)
+    B, N = enc.shape
+    L = dec.shape[1]
+    assert dec.shape == (B, L, N)
+    out = {
+        "X": np.full((B, L), -2, np.int32), "Y": np.full(B, -2, np.int32),
+        "accept": np.zeros(B, np.uint8), "match_k": np.full(B, -2, np.int32),
+        "keyX": np.zeros((B, L)), "keyY": np.zeros(B),
+        "gapX": np.zeros((B, L)), "gapY": np.zeros(B),
+    }
+    rc = lib().llc_couple_is_ref(
+        B, L, N, enc.ctypes.data, enc.strides[0] // 4, dec.ctypes.data, dec.strides[0] // 4,
+        dec.strides[1] // 4, seed, row_offset, out["X"].ctypes.data, out["Y"].ctypes.data,
+        out["accept"].ctypes.data, out["match_k"].ctypes.data, out["keyX"].ctypes.data,
+        out["keyY"].ctypes.data, out["gapX"].ctypes.data, out["gapY"].ctypes.data, threads)
+    if rc != 0:
+        raise ValueError("llc_couple_is_ref rejected its arguments")
+    return out

@@ -1,0 +1,297 @@
+// CPU oracle for Gumbel-max list sampling (GLS).  TEST INFRASTRUCTURE ONLY.
+//
+// This file is the slow, literal, scalar fp64 statement of what the sampler
+// computes.  Only the test-suite, the smoke check and the benchmark's
+// cpu_baseline leg may load it; the product (the HIP library) never does, and
+// shares no source, header, table or helper with it.
+//
+// What is computed, per row (paper Section 3, Algorithm 1):
+//   * shared uniforms U_i^(k), race times S_i^(k) = -ln U_i^(k)      (Alg. 1, step 2)
+//   * Y       = argmin_i min_k S_i^(k) / q_i                          (Alg. 1, step 3)
+//   * X^(k)   = argmin_i S_i^(k) / p_i^(k)                            (Alg. 1, step 4;
+//               distinct proposals p^(k): Appendix A.3)
+//   * accept  = [ Y in {X^(1..K)} ]                                   (Alg. 1, step 5)
+// The importance-weight form (Appendix C, the normalised weights lambda_q,
+// lambda_p^(k) and the selection rule below them) is the same computation with
+// p, q proportional to exp(log-weight).
+//
+// Readings the paper leaves open (each is also listed in the design notes):
+//   * generator: Philox4x32 with 10 rounds (Salmon et al., SC'11); key = the
+//     two halves of `seed`; counter = (i >> 2, k, lo32(row), hi32(row)); element
+//     i uses output word (i & 3).  row = row_offset + b.
+//   * U on the open interval: U = (x + 1/2) / 2^32 for the 32-bit word x.
+//   * argmin ties: smallest key, then smallest i, then (pool only) smallest k.
+//   * entries that are NaN or +inf (logit kinds) / NaN, +inf or negative
+//     (probability kind) carry zero probability.  A reduction with no finite
+//     key returns index -1.
+//   * temperature: p = softmax(logit / T), T the fp32 value widened to fp64.
+//
+// Build: g++ -O2 -fno-fast-math -fopenmp -shared -fPIC (see build.py).
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <limits>
+#include <vector>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+namespace {
+
+const double kInf = std::numeric_limits<double>::infinity();
+
+// ---- Philox4x32-10 ---------------------------------------------------------
+// One round: two 32x32->64 products, the high halves are mixed with the other
+// counter words and the round key, the low halves pass through.
+void philox_round(uint32_t c[4], const uint32_t k[2]) {
+  const uint64_t prod0 = (uint64_t)0xD2511F53u * (uint64_t)c[0];
+  const uint64_t prod1 = (uint64_t)0xCD9E8D57u * (uint64_t)c[2];
+  const uint32_t hi0 = (uint32_t)(prod0 >> 32), lo0 = (uint32_t)prod0;
+  const uint32_t hi1 = (uint32_t)(prod1 >> 32), lo1 = (uint32_t)prod1;
+  const uint32_t n0 = hi1 ^ c[1] ^ k[0];
+  const uint32_t n1 = lo1;
+  const uint32_t n2 = hi0 ^ c[3] ^ k[1];
+  const uint32_t n3 = lo0;
+  c[0] = n0; c[1] = n1; c[2] = n2; c[3] = n3;
+}
+
+void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  uint32_t c[4] = {ctr[0], ctr[1], ctr[2], ctr[3]};
+  uint32_t k[2] = {key[0], key[1]};
+  for (int r = 0; r < 10; ++r) {
+    if (r > 0) {  // Weyl key schedule: bump before every round but the first
+      k[0] += 0x9E3779B9u;
+      k[1] += 0xBB67AE85u;
+    }
+    philox_round(c, k);
+  }
+  for (int j = 0; j < 4; ++j) out[j] = c[j];
+}
+
+// 32-bit word for element (row, k, i).
+uint32_t shared_word(uint64_t seed, uint64_t row, uint32_t k, uint64_t i) {
+  const uint32_t ctr[4] = {(uint32_t)(i >> 2), k, (uint32_t)row, (uint32_t)(row >> 32)};
+  const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  uint32_t out[4];
+  philox4x32_10(ctr, key, out);
+  return out[i & 3];
+}
+
+// S = -ln U with U = (x + 1/2) 2^-32 (exact in fp64).  Section 3: S_i^(k) = -ln U_i^(k).
+double race_time(uint32_t x) {
+  const double U = ((double)x + 0.5) * (1.0 / 4294967296.0);
+  return -std::log(U);
+}
+
+// ---- inputs ---------------------------------------------------------------
+enum { DT_F32 = 0, DT_BF16 = 1 };
+enum { KIND_LOGITS = 0, KIND_PROBS = 1, KIND_LOGW = 2 };
+
+double load_elem(const void *base, int dtype, int64_t off) {
+  if (dtype == DT_F32) {
+    return (double)((const float *)base)[off];
+  }
+  // bfloat16 = the top 16 bits of an fp32
+  const uint16_t h = ((const uint16_t *)base)[off];
+  const uint32_t w = (uint32_t)h << 16;
+  float f;
+  std::memcpy(&f, &w, 4);
+  return (double)f;
+}
+
+// Fill prob[0..V) with the distribution one input row denotes; return the
+// normaliser's log (0 for the probability kind, which is used as given).
+// logit kinds: p = softmax(x / T).  log-weight kind: p = exp(x) / sum exp(x).
+void row_distribution(const void *base, int dtype, int64_t off, int64_t V, int kind,
+                      double T, std::vector<double> &prob) {
+  prob.resize((size_t)V);
+  if (kind == KIND_PROBS) {
+    for (int64_t i = 0; i < V; ++i) {
+      const double v = load_elem(base, dtype, off + i);
+      prob[i] = (std::isfinite(v) && v > 0.0) ? v : 0.0;
+    }
+    return;
+  }
+  const double temp = (kind == KIND_LOGITS) ? T : 1.0;
+  double zmax = -kInf;
+  for (int64_t i = 0; i < V; ++i) {
+    double z = load_elem(base, dtype, off + i) / temp;
+    if (std::isnan(z) || z == kInf) z = -kInf;
+    prob[i] = z;
+    if (z > zmax) zmax = z;
+  }
+  if (zmax == -kInf) {
+    for (int64_t i = 0; i < V; ++i) prob[i] = 0.0;
+    return;
+  }
+  double sum = 0.0;
+  for (int64_t i = 0; i < V; ++i) sum += std::exp(prob[i] - zmax);
+  const double lse = zmax + std::log(sum);
+  for (int64_t i = 0; i < V; ++i) prob[i] = std::exp(prob[i] - lse);
+}
+
+// Running (smallest, runner-up) of a race; `second` is the smallest key among
+// entries whose index differs from the leader's index.
+struct Race {
+  double best = kInf;
+  int64_t idx = -1;
+  int64_t k = -1;
+  double second = kInf;
+  void offer(double key, int64_t i, int64_t kk) {
+    if (!(key < kInf)) return;
+    bool wins = false;
+    if (idx < 0) wins = true;
+    else if (key < best) wins = true;
+    else if (key == best) {
+      if (i < idx) wins = true;
+      else if (i == idx && kk < k) wins = true;
+    }
+    if (wins) {
+      if (idx >= 0 && idx != i) {
+        if (best < second) second = best;
+      }
+      best = key; idx = i; k = kk;
+    } else if (i != idx) {
+      if (key < second) second = key;
+    }
+  }
+  double rel_gap() const {
+    if (idx < 0) return kInf;
+    if (!(second < kInf)) return kInf;
+    if (best == 0.0) return second > 0.0 ? kInf : 0.0;
+    return (second - best) / best;
+  }
+};
+
+}  // namespace
+
+extern "C" {
+
+struct llc_ref_args {
+  int64_t B, K, V;
+  int32_t dtype, kind;
+  const void *draft;   // host
+  int64_t draft_stride_b, draft_stride_k;  // elements; stride_k == 0: one p per row
+  const void *target;  // host
+  int64_t target_stride_b;
+  float temp_target;
+  const float *temp_draft;  // K entries or NULL
+  float temp_draft_all;
+  uint64_t seed, row_offset;
+  // outputs (host); any of the optional ones may be NULL
+  int32_t *X;        // [B,K]
+  int32_t *Y;        // [B]
+  uint8_t *accept;   // [B]
+  int32_t *match_k;  // [B]   optional
+  double *keyX;      // [B,K] optional: winning S/p
+  double *keyY;      // [B]   optional: winning S/q over the pool
+  int32_t *Yk;       // [B,K] optional: argmin_i S_i^(k)/q_i
+  double *keyYk;     // [B,K] optional
+  double *gapX;      // [B,K] optional: (runner-up - best)/best on the draft side
+  double *gapY;      // [B]   optional: same for the pool, runner-up with index != Y
+  double *gapYk;     // [B,K] optional
+  int32_t threads;   // <=0: all
+};
+
+void llc_ref_philox4x32_10(const uint32_t *ctr, const uint32_t *key, uint32_t *out) {
+  philox4x32_10(ctr, key, out);
+}
+
+uint32_t llc_ref_shared_word(uint64_t seed, uint64_t row, uint32_t k, uint64_t i) {
+  return shared_word(seed, row, k, i);
+}
+
+double llc_ref_race_time(uint32_t x) { return race_time(x); }
+
+int llc_ref_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+// Algorithm 1 over a batch of rows.  Returns 0, or -1 on a malformed call.
+int llc_couple_ref(const llc_ref_args *a) {
+  if (!a || !a->draft || !a->target || !a->X || !a->Y || !a->accept) return -1;
+  if (a->B < 0 || a->K < 1 || a->V < 1) return -1;
+  const int64_t B = a->B, K = a->K, V = a->V;
+  int nthreads = a->threads;
+#ifdef _OPENMP
+  if (nthreads <= 0) nthreads = omp_get_max_threads();
+#else
+  nthreads = 1;
+#endif
+
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+  for (int64_t b = 0; b < B; ++b) {
+    const uint64_t row = a->row_offset + (uint64_t)b;
+    std::vector<double> q, p;
+    row_distribution(a->target, a->dtype, b * a->target_stride_b, V, a->kind,
+                     (double)a->temp_target, q);
+    Race pool;                 // over all (k, i): the flattened K*V race of Theorem 1's proof
+    int64_t match = -1;
+    std::vector<int64_t> xs((size_t)K);
+    for (int64_t k = 0; k < K; ++k) {
+      if (k == 0 || a->draft_stride_k != 0 || a->temp_draft) {
+        const double Tk = a->temp_draft ? (double)a->temp_draft[k] : (double)a->temp_draft_all;
+        row_distribution(a->draft, a->dtype, b * a->draft_stride_b + k * a->draft_stride_k,
+                         V, a->kind, Tk, p);
+      }
+      Race draft, tk;
+      for (int64_t i = 0; i < V; ++i) {
+        const double S = race_time(shared_word(a->seed, row, (uint32_t)k, (uint64_t)i));
+        const double kx = p[i] > 0.0 ? S / p[i] : kInf;
+        const double ky = q[i] > 0.0 ? S / q[i] : kInf;
+        draft.offer(kx, i, k);
+        tk.offer(ky, i, k);
+        pool.offer(ky, i, k);
+      }
+      xs[k] = draft.idx;
+      a->X[b * K + k] = (int32_t)draft.idx;
+      if (a->keyX) a->keyX[b * K + k] = draft.best;
+      if (a->gapX) a->gapX[b * K + k] = draft.rel_gap();
+      if (a->Yk) a->Yk[b * K + k] = (int32_t)tk.idx;
+      if (a->keyYk) a->keyYk[b * K + k] = tk.best;
+      if (a->gapYk) a->gapYk[b * K + k] = tk.rel_gap();
+    }
+    a->Y[b] = (int32_t)pool.idx;
+    if (a->keyY) a->keyY[b] = pool.best;
+    if (a->gapY) a->gapY[b] = pool.rel_gap();
+    if (pool.idx >= 0) {
+      for (int64_t k = 0; k < K; ++k) {
+        if (xs[k] == pool.idx) { match = k; break; }
+      }
+    }
+    a->accept[b] = (uint8_t)(match >= 0);
+    if (a->match_k) a->match_k[b] = (int32_t)match;
+  }
+  return 0;
+}
+
+// Importance-weight form (Appendix C): the encoder's index is the pool argmin
+// under lambda_q, decoder l's index is the argmin under lambda_p^(l); weights
+// are given as logs and normalised over the N candidates.
+int llc_couple_is_ref(int64_t B, int64_t L, int64_t N,
+                      const float *logw_enc, int64_t enc_stride_b,
+                      const float *logw_dec, int64_t dec_stride_b, int64_t dec_stride_l,
+                      uint64_t seed, uint64_t row_offset,
+                      int32_t *X, int32_t *Y, uint8_t *accept, int32_t *match_l,
+                      double *keyX, double *keyY, double *gapX, double *gapY, int32_t threads) {
+  llc_ref_args a;
+  std::memset(&a, 0, sizeof(a));
+  a.B = B; a.K = L; a.V = N;
+  a.dtype = DT_F32; a.kind = KIND_LOGW;
+  a.draft = logw_dec; a.draft_stride_b = dec_stride_b; a.draft_stride_k = dec_stride_l;
+  a.target = logw_enc; a.target_stride_b = enc_stride_b;
+  a.temp_target = 1.0f; a.temp_draft = nullptr; a.temp_draft_all = 1.0f;
+  a.seed = seed; a.row_offset = row_offset;
+  a.X = X; a.Y = Y; a.accept = accept; a.match_k = match_l;
+  a.keyX = keyX; a.keyY = keyY; a.gapX = gapX; a.gapY = gapY;
+  a.threads = threads;
+  return llc_couple_ref(&a);
+}
+
+}  // extern "C"

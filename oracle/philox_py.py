@@ -1,0 +1,45 @@
+"""Philox4x32-10 in unbounded Python integers (test infrastructure).
+
+Written from the published description of the generator (Salmon, Moraes, Dror,
+Shaw, "Parallel random numbers: as easy as 1, 2, 3", SC'11): a 4-word counter, a
+2-word key, ten rounds; each round multiplies counter words 0 and 2 by fixed
+odd constants, keeps the low halves and folds the high halves into the other
+two words together with the round key; the key advances by a Weyl constant
+between rounds.  Used to cross-check the C++ oracle's generator and to
+brute-force tiny cases of Algorithm 1 without touching the C++ code.
+"""
+import math
+
+MASK = 0xFFFFFFFF
+MUL_A = 0xD2511F53
+MUL_B = 0xCD9E8D57
+WEYL_A = 0x9E3779B9
+WEYL_B = 0xBB67AE85
+
+
+def philox4x32(ctr, key, rounds=10):
+    c0, c1, c2, c3 = (int(v) & MASK for v in ctr)
+    k0, k1 = (int(v) & MASK for v in key)
+    for r in range(rounds):
+        pa = MUL_A * c0
+        pb = MUL_B * c2
+        c0, c1, c2, c3 = ((pb >> 32) ^ c1 ^ k0) & MASK, pb & MASK, ((pa >> 32) ^ c3 ^ k1) & MASK, pa & MASK
+        k0 = (k0 + WEYL_A) & MASK
+        k1 = (k1 + WEYL_B) & MASK
+    return [c0, c1, c2, c3]
+
+
+def shared_word(seed, row, k, i):
+    """The 32-bit word of element (row, draft k, index i): four consecutive i share one block."""
+    out = philox4x32([i >> 2, k, row & MASK, (row >> 32) & MASK], [seed & MASK, (seed >> 32) & MASK])
+    return out[i & 3]
+
+
+def uniform(x):
+    """Open-interval uniform from a 32-bit word: the midpoint of its 2^-32 cell."""
+    return (x + 0.5) / 4294967296.0
+
+
+def race_time(x):
+    """Exp(1) race time S = -ln U (Section 3)."""
+    return -math.log(uniform(x))
