@@ -1,0 +1,154 @@
+/* llc.h -- list-level Gumbel-max coupling (Gumbel-max list sampling, GLS) on MI355X.
+ *
+ * C ABI of libllc_hip.so.  All data pointers are DEVICE pointers owned by the
+ * caller (allocated by whatever the caller likes, e.g. torch); the library
+ * allocates nothing, keeps no state between calls, enqueues its kernels on
+ * `stream` and never synchronises.  Every entry point returns 0 (LLC_OK) or a
+ * negative LLC_E_* code and never throws or aborts; argument errors are found
+ * on the host before anything is launched.  Data-dependent conditions are not
+ * errors: a reduction in which no entry has positive probability returns index
+ * -1 (and accept = 0 for the row).
+ *
+ * Shared randomness (a reading, the paper only asks for i.i.d. uniforms):
+ * Philox4x32 with 10 rounds, key = (lo32(seed), hi32(seed)), counter =
+ * (i >> 2, k, lo32(row), hi32(row)) with row = row_offset + b; element i takes
+ * output word (i & 3); U = (word + 1/2) / 2^32 and S = -ln U.
+ * Ties in an argmin go to the smaller index, then (pool) to the smaller k.
+ */
+#ifndef LLC_H_
+#define LLC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LLC_VERSION 100
+
+enum {
+  LLC_OK = 0,
+  LLC_E_NULL = -1,      /* a required pointer is NULL                                   */
+  LLC_E_SHAPE = -2,     /* B < 0, K < 1, V < 1, V >= 2^31 - 4, K > 65535, bad strides   */
+  LLC_E_TEMP = -3,      /* a host-visible temperature is not finite and > 0             */
+  LLC_E_DTYPE = -4,     /* unknown dtype / kind, or a combination that is not built     */
+  LLC_E_ALIGN = -5,     /* an input base pointer is not aligned to its element size     */
+  LLC_E_WORKSPACE = -6, /* workspace missing, misaligned (256 B) or too small           */
+  LLC_E_LAUNCH = -7,    /* the HIP runtime refused a launch (hipGetLastError)           */
+  LLC_E_OPTION = -8     /* v_chunks / k_tile / flags out of range                       */
+};
+
+enum { LLC_F32 = 0, LLC_BF16 = 1 };
+
+/* How an input row denotes a distribution. */
+enum {
+  LLC_LOGITS = 0, /* p = softmax(x / T)                                              */
+  LLC_PROBS = 1,  /* p = x as given (>= 0; need not sum to 1); temperatures ignored   */
+  LLC_LOGW = 2    /* p = exp(x) / sum exp(x) (log-weights); temperatures ignored      */
+};
+
+enum {
+  LLC_FLAG_EXACT_SCAN = 1 /* debugging: evaluate every key in fp64, no prefilter     */
+};
+
+/* Optional device counters, accumulated with atomics (zero them yourself). */
+typedef struct llc_stats {
+  unsigned long long survivors;   /* elements that passed the integer prefilter              */
+  unsigned long long exact_evals; /* keys evaluated in fp64                                  */
+  unsigned long long slow_blocks; /* workgroups that fell back to the all-fp64 scan          */
+  unsigned long long degenerate;  /* reductions that found no entry with positive probability */
+} llc_stats;
+
+/* Arguments of llc_couple: one call runs Algorithm 1 of the paper on B rows.
+ *
+ * Inputs.  draft is [B,K,V] addressed as draft[b*draft_stride_b + k*draft_stride_k + i]
+ * (strides in elements, last dimension contiguous); draft_stride_k == 0 means the K
+ * drafts of a row are i.i.d. from one proposal p_X (Section 4.1: a single draft model),
+ * otherwise draft k has its own p^(k) (Appendix A.3).  target is [B,V].  Rows should
+ * start on 16-byte boundaries for full-width loads; other layouts are read element-wise.
+ *
+ * Outputs.  X[b,k] = argmin_i S_i^(k) / p_i^(k);  Y[b] = argmin_i min_k S_i^(k) / q_i;
+ * accept[b] = 1 iff Y[b] is one of X[b,0..K) (Section 3, Algorithm 1).
+ * match_k[b] = the first k with X[b,k] == Y[b], else -1 (Section 4.1).
+ * keyX / keyY = the winning values of S/p and S/q, with p, q normalised for the logit
+ * and log-weight kinds and as given for the probability kind (+inf where the index is -1).
+ */
+typedef struct llc_couple_args {
+  int64_t B, K, V;
+  int32_t dtype;            /* LLC_F32 | LLC_BF16 (both inputs)                          */
+  int32_t kind;             /* LLC_LOGITS | LLC_PROBS | LLC_LOGW (both inputs)           */
+  const void *draft;        /* device */
+  int64_t draft_stride_b, draft_stride_k;
+  const void *target;       /* device */
+  int64_t target_stride_b;
+  float temp_target;        /* > 0; LLC_LOGITS only                                      */
+  float temp_draft_all;     /* > 0; used when temp_draft == NULL                         */
+  const float *temp_draft;  /* device, K entries, or NULL.  Entries must be finite and
+                               > 0; they are not checked on the host, a bad entry makes
+                               that draft's X equal -1.                                  */
+  uint64_t seed;
+  uint64_t row_offset;      /* global row of b = 0 (sharding, successive steps)          */
+  int32_t *X;               /* [B,K] required                                            */
+  int32_t *Y;               /* [B]   required                                            */
+  uint8_t *accept;          /* [B]   required                                            */
+  int32_t *match_k;         /* [B]   optional                                            */
+  float *keyX;              /* [B,K] optional                                            */
+  float *keyY;              /* [B]   optional                                            */
+  llc_stats *stats;         /* optional device counters                                  */
+  void *workspace;          /* device, 256-byte aligned, >= llc_couple_workspace_size()  */
+  size_t workspace_bytes;
+  void *stream;             /* hipStream_t; NULL = the default stream                    */
+  int32_t flags;            /* LLC_FLAG_*                                                */
+  int32_t v_chunks;         /* 0 = choose; else split V over this many workgroups (1..4096).
+                               Results do not depend on it.                              */
+  int32_t k_tile;           /* 0 = choose; else drafts per workgroup pass: 1, 2, 4 or 8.
+                               Results do not depend on it.                              */
+} llc_couple_args;
+
+/* Importance-weight form (Appendix C: lossy compression with K decoders, here L).
+ * logw_enc[b,i] = ln of the encoder's unnormalised weight of candidate i (lambda~_q),
+ * logw_dec[b,l,i] = ln of decoder l's (lambda~_p^(l)); fp32; -inf marks a candidate a
+ * party has excluded.  Y[b] = the encoder's index (pool argmin under lambda_q),
+ * X[b,l] = decoder l's index, accept[b] = 1 iff some decoder recovers Y[b].
+ * Equivalent to llc_couple with kind = LLC_LOGW, draft = logw_dec, target = logw_enc.
+ */
+typedef struct llc_couple_is_args {
+  int64_t B, L, N;
+  const float *logw_enc;    /* device [B,N]   */
+  int64_t enc_stride_b;
+  const float *logw_dec;    /* device [B,L,N] */
+  int64_t dec_stride_b, dec_stride_l;
+  uint64_t seed, row_offset;
+  int32_t *X;               /* [B,L] required */
+  int32_t *Y;               /* [B]   required */
+  uint8_t *accept;          /* [B]   required */
+  int32_t *match_l;         /* [B]   optional */
+  float *keyX;              /* [B,L] optional */
+  float *keyY;              /* [B]   optional */
+  llc_stats *stats;
+  void *workspace;          /* >= llc_couple_workspace_size(B, L, N) */
+  size_t workspace_bytes;
+  void *stream;
+  int32_t flags, v_chunks, k_tile;
+} llc_couple_is_args;
+
+/* Algorithm 1 on a batch (Section 3).  Asynchronous on a->stream. */
+int llc_couple(const llc_couple_args *a);
+
+/* Appendix C's index selection at the encoder and the L decoders.  Asynchronous. */
+int llc_couple_is(const llc_couple_is_args *a);
+
+/* Bytes of device scratch either call needs for this shape (any options); 0 on bad shapes. */
+size_t llc_couple_workspace_size(int64_t B, int64_t K, int64_t V);
+
+/* Text for a return code (static storage). */
+const char *llc_status_string(int code);
+
+/* LLC_VERSION of the built library. */
+int llc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LLC_H_ */

@@ -1,0 +1,233 @@
+"""ctypes binding of libllc_hip.so: argument marshalling only.
+
+Every step of the sampler runs in the HIP kernels; torch supplies device
+memory and the current stream.  There is no CPU fallback: if the library is
+missing, `load()` raises.
+"""
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libllc_hip.so")
+
+F32, BF16 = 0, 1
+LOGITS, PROBS, LOGW = 0, 1, 2
+FLAG_EXACT_SCAN = 1
+
+_KINDS = {"logits": LOGITS, "probs": PROBS, "logw": LOGW}
+EXPORTS = ["llc_couple", "llc_couple_is", "llc_couple_workspace_size", "llc_status_string",
+           "llc_version"]
+
+
+class LlcStats(ctypes.Structure):
+    _fields_ = [("survivors", ctypes.c_ulonglong), ("exact_evals", ctypes.c_ulonglong),
+                ("slow_blocks", ctypes.c_ulonglong), ("degenerate", ctypes.c_ulonglong)]
+
+
+class CoupleArgs(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int64), ("K", ctypes.c_int64), ("V", ctypes.c_int64),
+        ("dtype", ctypes.c_int32), ("kind", ctypes.c_int32),
+        ("draft", ctypes.c_void_p),
+        ("draft_stride_b", ctypes.c_int64), ("draft_stride_k", ctypes.c_int64),
+        ("target", ctypes.c_void_p), ("target_stride_b", ctypes.c_int64),
+        ("temp_target", ctypes.c_float), ("temp_draft_all", ctypes.c_float),
+        ("temp_draft", ctypes.c_void_p),
+        ("seed", ctypes.c_uint64), ("row_offset", ctypes.c_uint64),
+        ("X", ctypes.c_void_p), ("Y", ctypes.c_void_p), ("accept", ctypes.c_void_p),
+        ("match_k", ctypes.c_void_p), ("keyX", ctypes.c_void_p), ("keyY", ctypes.c_void_p),
+        ("stats", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("stream", ctypes.c_void_p),
+        ("flags", ctypes.c_int32), ("v_chunks", ctypes.c_int32), ("k_tile", ctypes.c_int32),
+    ]
+
+
+class CoupleIsArgs(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int64), ("L", ctypes.c_int64), ("N", ctypes.c_int64),
+        ("logw_enc", ctypes.c_void_p), ("enc_stride_b", ctypes.c_int64),
+        ("logw_dec", ctypes.c_void_p),
+        ("dec_stride_b", ctypes.c_int64), ("dec_stride_l", ctypes.c_int64),
+        ("seed", ctypes.c_uint64), ("row_offset", ctypes.c_uint64),
+        ("X", ctypes.c_void_p), ("Y", ctypes.c_void_p), ("accept", ctypes.c_void_p),
+        ("match_l", ctypes.c_void_p), ("keyX", ctypes.c_void_p), ("keyY", ctypes.c_void_p),
+        ("stats", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("stream", ctypes.c_void_p),
+        ("flags", ctypes.c_int32), ("v_chunks", ctypes.c_int32), ("k_tile", ctypes.c_int32),
+    ]
+
+
+_lib = None
+
+
+def load():
+    """Load the HIP library (built by paper_2506_05632_amd/build.py); raise if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2506_05632_amd.build` "
+                               "(there is no CPU fallback)")
+        lib = ctypes.CDLL(LIB_PATH)
+        lib.llc_couple.argtypes = [ctypes.POINTER(CoupleArgs)]
+        lib.llc_couple.restype = ctypes.c_int
+        lib.llc_couple_is.argtypes = [ctypes.POINTER(CoupleIsArgs)]
+        lib.llc_couple_is.restype = ctypes.c_int
+        lib.llc_couple_workspace_size.argtypes = [ctypes.c_int64] * 3
+        lib.llc_couple_workspace_size.restype = ctypes.c_size_t
+        lib.llc_status_string.argtypes = [ctypes.c_int]
+        lib.llc_status_string.restype = ctypes.c_char_p
+        lib.llc_version.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+class LlcError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        super().__init__(f"llc error {code}: {load().llc_status_string(code).decode()}")
+
+
+def llc_version() -> int:
+    return load().llc_version()
+
+
+def llc_status_string(code: int) -> str:
+    return load().llc_status_string(code).decode()
+
+
+def llc_couple_workspace_size(B: int, K: int, V: int) -> int:
+    return load().llc_couple_workspace_size(B, K, V)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _stream_handle(device):
+    return torch.cuda.current_stream(device).cuda_stream
+
+
+def new_stats(device) -> torch.Tensor:
+    """Four zeroed 64-bit device counters laid out as llc_stats."""
+    return torch.zeros(4, dtype=torch.int64, device=device)
+
+
+def llc_couple(draft: torch.Tensor, target: torch.Tensor, K: int, *, kind="logits",
+               temp_target: float = 1.0, temp_draft: float = 1.0,
+               temp_draft_per_k: Optional[torch.Tensor] = None, seed: int = 0, row_offset: int = 0,
+               want_keys: bool = False, want_match: bool = True, stats: Optional[torch.Tensor] = None,
+               workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None,
+               flags: int = 0, v_chunks: int = 0, k_tile: int = 0) -> dict:
+    """Algorithm 1 on device tensors.
+
+    draft: [B,V] (the K drafts of a row share it) or [B,K,V]; target: [B,V]; both
+    float32 or bfloat16 with a contiguous last dimension.  Returns device tensors
+    X [B,K] int32, Y [B] int32, accept [B] uint8 and, if asked, match_k, keyX, keyY.
+    The call is asynchronous on torch's current stream.
+    """
+    lib = load()
+    if not (draft.is_cuda and target.is_cuda):
+        raise ValueError("llc_couple needs device tensors (there is no CPU path)")
+    if draft.dtype != target.dtype or draft.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("draft and target must both be float32 or both bfloat16")
+    if draft.stride(-1) != 1 or target.stride(-1) != 1 or target.dim() != 2:
+        raise ValueError("last dimension must be contiguous; target must be [B,V]")
+    B, V = target.shape
+    if draft.dim() == 2:
+        if tuple(draft.shape) != (B, V):
+            raise ValueError("draft must be [B,V] or [B,K,V]")
+        sb, sk = draft.stride(0), 0
+    else:
+        if tuple(draft.shape) != (B, K, V):
+            raise ValueError("draft must be [B,V] or [B,K,V]")
+        sb, sk = draft.stride(0), draft.stride(1)
+    dev = target.device
+    if out is None:
+        out = {"X": torch.empty(B, K, dtype=torch.int32, device=dev),
+               "Y": torch.empty(B, dtype=torch.int32, device=dev),
+               "accept": torch.empty(B, dtype=torch.uint8, device=dev)}
+        if want_match:
+            out["match_k"] = torch.empty(B, dtype=torch.int32, device=dev)
+        if want_keys:
+            out["keyX"] = torch.empty(B, K, dtype=torch.float32, device=dev)
+            out["keyY"] = torch.empty(B, dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = new_workspace(B, K, V, dev)
+    a = CoupleArgs()
+    a.B, a.K, a.V = B, K, V
+    a.dtype = F32 if draft.dtype == torch.float32 else BF16
+    a.kind = _KINDS[kind]
+    a.draft, a.draft_stride_b, a.draft_stride_k = draft.data_ptr(), sb, sk
+    a.target, a.target_stride_b = target.data_ptr(), target.stride(0)
+    a.temp_target, a.temp_draft_all = temp_target, temp_draft
+    if temp_draft_per_k is not None:
+        if temp_draft_per_k.dtype != torch.float32 or temp_draft_per_k.numel() != K or not temp_draft_per_k.is_cuda:
+            raise ValueError("temp_draft_per_k must be K float32 values on the device")
+        a.temp_draft = temp_draft_per_k.data_ptr()
+    a.seed, a.row_offset = seed, row_offset
+    a.X, a.Y, a.accept = out["X"].data_ptr(), out["Y"].data_ptr(), out["accept"].data_ptr()
+    a.match_k = _ptr(out.get("match_k"))
+    a.keyX, a.keyY = _ptr(out.get("keyX")), _ptr(out.get("keyY"))
+    a.stats = _ptr(stats)
+    a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
+    a.stream = _stream_handle(dev)
+    a.flags, a.v_chunks, a.k_tile = flags, v_chunks, k_tile
+    rc = lib.llc_couple(ctypes.byref(a))
+    if rc != 0:
+        raise LlcError(rc)
+    return out
+
+
+def llc_couple_is(logw_enc: torch.Tensor, logw_dec: torch.Tensor, *, seed: int = 0,
+                  row_offset: int = 0, want_keys: bool = False,
+                  stats: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                  flags: int = 0, v_chunks: int = 0, k_tile: int = 0) -> dict:
+    """Importance-weight form: logw_enc [B,N], logw_dec [B,L,N], float32 device tensors."""
+    lib = load()
+    if not (logw_enc.is_cuda and logw_dec.is_cuda):
+        raise ValueError("llc_couple_is needs device tensors (there is no CPU path)")
+    if logw_enc.dtype != torch.float32 or logw_dec.dtype != torch.float32:
+        raise ValueError("log-weights must be float32")
+    B, N = logw_enc.shape
+    L = logw_dec.shape[1]
+    if tuple(logw_dec.shape) != (B, L, N) or logw_enc.stride(-1) != 1 or logw_dec.stride(-1) != 1:
+        raise ValueError("logw_dec must be [B,L,N] with a contiguous last dimension")
+    dev = logw_enc.device
+    out = {"X": torch.empty(B, L, dtype=torch.int32, device=dev),
+           "Y": torch.empty(B, dtype=torch.int32, device=dev),
+           "accept": torch.empty(B, dtype=torch.uint8, device=dev),
+           "match_k": torch.empty(B, dtype=torch.int32, device=dev)}
+    if want_keys:
+        out["keyX"] = torch.empty(B, L, dtype=torch.float32, device=dev)
+        out["keyY"] = torch.empty(B, dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = new_workspace(B, L, N, dev)
+    a = CoupleIsArgs()
+    a.B, a.L, a.N = B, L, N
+    a.logw_enc, a.enc_stride_b = logw_enc.data_ptr(), logw_enc.stride(0)
+    a.logw_dec, a.dec_stride_b, a.dec_stride_l = logw_dec.data_ptr(), logw_dec.stride(0), logw_dec.stride(1)
+    a.seed, a.row_offset = seed, row_offset
+    a.X, a.Y, a.accept = out["X"].data_ptr(), out["Y"].data_ptr(), out["accept"].data_ptr()
+    a.match_l = out["match_k"].data_ptr()
+    a.keyX, a.keyY = _ptr(out.get("keyX")), _ptr(out.get("keyY"))
+    a.stats = _ptr(stats)
+    a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
+    a.stream = _stream_handle(dev)
+    a.flags, a.v_chunks, a.k_tile = flags, v_chunks, k_tile
+    rc = lib.llc_couple_is(ctypes.byref(a))
+    if rc != 0:
+        raise LlcError(rc)
+    return out
+
+
+def new_workspace(B: int, K: int, V: int, device, v_chunks: int = 0) -> torch.Tensor:
+    """Device scratch for one call; larger explicit v_chunks need proportionally more."""
+    n = llc_couple_workspace_size(B, K, V)
+    if v_chunks > 16:
+        n = n * ((v_chunks + 15) // 16)
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=device)

@@ -1,0 +1,644 @@
+// The scan kernel: one pass over a row's (draft k, index i) pairs that finds, for
+// each of the K drafts, argmin_i S_i^(k)/p_i^(k) and, for the target, the argmin
+// over the K x V pool of S_i^(k)/q_i (paper Section 3, Algorithm 1, steps 2-4).
+//
+// Work per element is dominated by the random word itself, so the kernel is
+// organised to do nothing else for almost every element:
+//
+//  level 1 (every element, integer): a race time S = -ln U can only beat the
+//    best key seen so far, 2^tau, if 1 - U <= S <= 2^tau * p.  With the 32-bit
+//    word x and xt = ~x, 1 - U = (xt + 1/2) 2^-32, so the test is xt <= t with an
+//    integer threshold t >= 2^(32 + tau) p.  t is built from the raw input by one
+//    fused multiply-add into the exponent/mantissa field of a float (a
+//    piecewise-linear 2^y that never under-estimates) and one conversion.
+//    The draft-side and target-side thresholds are merged by a median-of-three.
+//  level 2 (survivors, fp32): an approximate key a = log2 S - log2 p; survivors
+//    within a band of the running best are recorded in an LDS list and lower tau.
+//  level 3 (end of the scan, fp64): records still within the band of the final
+//    tau are evaluated exactly -- ln(-ln U) - x/T in fp64 -- and reduced with
+//    64-bit LDS atomics; ties go to the smaller index, then the smaller k.
+//
+// Because every element whose exact key could be the minimum passes levels 1
+// and 2 (the margins below bound the fp32 error of both), the result is the
+// exact fp64 argmin, independent of grid shape and of the order of arrival.
+#pragma once
+
+#include "common.hpp"
+
+namespace llc {
+
+struct F32In { using elem = float; };
+struct BF16In { using elem = uint16_t; };
+
+// ---- margins (log2 units) ---------------------------------------------------
+// |tau| <= kTauLimit is enforced (else the workgroup redoes its chunk in fp64).
+// Level-2 keys then carry an error below 3.4e-4, level-1 exponents below 1.4e-4.
+constexpr float kEps2 = 0x1p-9f;       // band around tau for "may be the minimum"
+constexpr float kEps1 = 0x1p-7f;       // slack of the integer prefilter
+constexpr float kPseudoLog = 0.0861f;  // max of log2(1+f) - f: slack when log2 p is read off the bits
+constexpr float kTauLimit = 1024.0f;
+constexpr float kTwo23 = 8388608.0f;
+constexpr float kCap = 1333788672.0f;  // 159 * 2^23: bit pattern of 2^32
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLog2Ln2 = -0.5287663729448977f;  // log2(ln 2)
+
+// ---- Philox4x32, ten rounds (Salmon et al., SC'11) ----------------------------
+__device__ __forceinline__ void philox_block(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                             uint32_t k0, uint32_t k1, uint32_t (&out)[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t pa = (uint64_t)c0 * 0xD2511F53ull;
+    const uint64_t pb = (uint64_t)c2 * 0xCD9E8D57ull;
+    const uint32_t n0 = (uint32_t)(pb >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(pa >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)pb;
+    c3 = (uint32_t)pa;
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// ---- small helpers ------------------------------------------------------------
+__device__ __forceinline__ int ord32(float f) {  // order-preserving float -> int
+  const int b = __float_as_int(f);
+  return b ^ ((b >> 31) & 0x7FFFFFFF);
+}
+__device__ __forceinline__ float unord32(int o) {
+  return __int_as_float(o ^ ((o >> 31) & 0x7FFFFFFF));
+}
+__device__ __forceinline__ unsigned long long ord64(double d) {  // order-preserving double -> u64
+  const unsigned long long b = (unsigned long long)__double_as_longlong(d);
+  return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+}
+__device__ __forceinline__ double unord64(unsigned long long o) {
+  const unsigned long long b = (o >> 63) ? (o & 0x7FFFFFFFFFFFFFFFull) : ~o;
+  return __longlong_as_double((long long)b);
+}
+constexpr unsigned long long kOrdInf64 = 0xFFF0000000000000ull;  // ord64(+inf)
+
+__device__ __forceinline__ uint32_t cvt_u32_saturating(float f) {
+  uint32_t r;  // hardware conversion: clamps to [0, 2^32 - 1], NaN -> 0
+  asm("v_cvt_u32_f32 %0, %1" : "=v"(r) : "v"(f));
+  return r;
+}
+
+// Integer threshold from a scaled exponent F in [0, kCap]: the float whose bit
+// pattern is int(F) is >= 2^(F/2^23 - 127); its integer part is t, and the test
+// xt <= t is carried out on x as x >= ~t.
+__device__ __forceinline__ uint32_t not_threshold(float F) {
+  return ~cvt_u32_saturating(__int_as_float((int)F));
+}
+
+template <typename T>
+__device__ __forceinline__ void load4(const typename T::elem *row, int i0, int V, bool vec,
+                                      float fill, float (&v)[4]);
+
+template <>
+__device__ __forceinline__ void load4<F32In>(const float *row, int i0, int V, bool vec, float fill,
+                                             float (&v)[4]) {
+  if (vec && i0 + 3 < V) {
+    const float4 t = *reinterpret_cast<const float4 *>(row + i0);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = (i0 + j < V) ? row[i0 + j] : fill;
+  }
+}
+
+template <>
+__device__ __forceinline__ void load4<BF16In>(const uint16_t *row, int i0, int V, bool vec,
+                                              float fill, float (&v)[4]) {
+  if (vec && i0 + 3 < V) {
+    const uint2 t = *reinterpret_cast<const uint2 *>(row + i0);
+    v[0] = __uint_as_float(t.x << 16);
+    v[1] = __uint_as_float(t.x & 0xFFFF0000u);
+    v[2] = __uint_as_float(t.y << 16);
+    v[3] = __uint_as_float(t.y & 0xFFFF0000u);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      v[j] = (i0 + j < V) ? __uint_as_float((uint32_t)row[i0 + j] << 16) : fill;
+  }
+}
+
+template <typename T>
+__device__ __forceinline__ float load1(const typename T::elem *row, int i);
+template <>
+__device__ __forceinline__ float load1<F32In>(const float *row, int i) { return row[i]; }
+template <>
+__device__ __forceinline__ float load1<BF16In>(const uint16_t *row, int i) {
+  return __uint_as_float((uint32_t)row[i] << 16);
+}
+
+// log2 of the race time S = -ln U, U = (x + 1/2) 2^-32, in fp32 (relative error of S
+// below 2^-16).  Near U = 1 the series of -ln(1 - W), W = 1 - U = (~x + 1/2) 2^-32.
+__device__ __forceinline__ float approx_log2_race_time(uint32_t x) {
+  const uint32_t xt = ~x;
+  if (xt < (1u << 25)) {
+    const float W = ((float)xt + 0.5f) * 0x1p-32f;
+    const float S = W * fmaf(W, fmaf(W, 0.33333334f, 0.5f), 1.0f);
+    return log2f(S);
+  }
+  const float U = ((float)x + 0.5f) * 0x1p-32f;
+  return log2f(-log2f(U)) + kLog2Ln2;
+}
+
+// The race time S = -ln U in fp64.
+__device__ __forceinline__ double exact_race_time(uint32_t x) {
+  const double U = ((double)x + 0.5) * 0x1p-32;
+  return -log(U);
+}
+
+// What an input value contributes to the level-1 exponent: the logit itself, or for
+// probabilities the float's own bits (a piecewise-linear log2 that never over-estimates).
+template <bool PROBS>
+__device__ __forceinline__ float level1_value(float v) {
+  return PROBS ? (float)__float_as_int(v) : v;
+}
+
+// log2 of the unnormalised probability an input value stands for; false if it carries no mass.
+template <bool PROBS>
+__device__ __forceinline__ bool approx_log2_mass(float v, float c, float &ell) {
+  if (PROBS) {
+    if (!(v > 0.0f && v < __builtin_huge_valf())) return false;
+    ell = log2f(v);
+    return true;
+  }
+  if (!(v < __builtin_huge_valf())) return false;  // NaN or +inf
+  ell = v * c;
+  return true;
+}
+
+// Exact key in fp64: ln S - x/T for logits and log-weights, S/p for probabilities.
+template <bool PROBS>
+__device__ __forceinline__ double exact_key(double S, float v, double T) {
+  if (PROBS) {
+    if (!(v > 0.0f && v < __builtin_huge_valf())) return __builtin_huge_val();
+    return S / (double)v;
+  }
+  if (!(v < __builtin_huge_valf())) return __builtin_huge_val();
+  return log(S) - (double)v / T;
+}
+
+struct Lds {
+  int tau[9];            // ordered-int log2 keys: drafts 0..KT-1, pool at [KT]
+  int O[9];              // bits of the level-1 offsets (tau + slack + bias) 2^23; shared layout: [0] = max over drafts
+  int count;             // records appended (may exceed kListCap)
+  int unsafe;            // chunk must be redone in fp64
+  unsigned long long best[9];
+  unsigned long long where[9];
+  unsigned long long n_survivors, n_exact;
+  float rec_a[kListCap];
+  int rec_i[kListCap];
+  int rec_tag[kListCap];
+};
+
+template <bool PROBS>
+__device__ __forceinline__ float make_offset(float tau) {
+  // logits: exponent bias 127 plus the 2^32 scale of the integer word; probabilities: the
+  // bias is already in the float's own bits
+  return (tau + ((PROBS ? 32.0f + kPseudoLog : 159.0f) + kEps1)) * kTwo23;
+}
+__device__ __forceinline__ void store_offset(int *slot, float O) {
+  __atomic_store_n(slot, __float_as_int(O), __ATOMIC_RELAXED);
+}
+__device__ __forceinline__ float load_offset(const int *slot) {
+  return __int_as_float(__atomic_load_n(slot, __ATOMIC_RELAXED));
+}
+template <bool PROBS>
+__device__ __forceinline__ uint32_t element_not_threshold(float v, float c23, float O, float FY) {
+  return not_threshold(__builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(v), c23, O), FY, kCap));
+}
+
+// Lower tau[slot] to `a` and refresh the level-1 offset that depends on it.
+template <int KT, bool SHARED, bool PROBS>
+__device__ __forceinline__ void publish(Lds &s, int slot, float a) {
+  atomicMin(&s.tau[slot], ord32(a));
+  if (!(fabsf(a) <= kTauLimit)) s.unsafe = 1;
+  if (SHARED && slot < KT) {
+    int m = s.tau[0];
+#pragma unroll
+    for (int kk = 1; kk < KT; ++kk) m = max(m, __atomic_load_n(&s.tau[kk], __ATOMIC_RELAXED));
+    store_offset(&s.O[0], make_offset<PROBS>(unord32(m)));
+  } else {
+    store_offset(&s.O[slot], make_offset<PROBS>(unord32(__atomic_load_n(&s.tau[slot], __ATOMIC_RELAXED))));
+  }
+}
+
+// Level 2 for one survivor of level 1.
+template <int KT, bool SHARED, bool PROBS>
+__device__ __forceinline__ void level2(Lds &s, uint32_t x, float vd, float vq, int i, int kk,
+                                       bool draft_ok, float cd, float cq) {
+  const float l2S = approx_log2_race_time(x);
+  float ell;
+  if (draft_ok && approx_log2_mass<PROBS>(vd, cd, ell)) {
+    const float a = l2S - ell;
+    const float tau = unord32(__atomic_load_n(&s.tau[kk], __ATOMIC_RELAXED));
+    if (a <= tau + kEps2) {
+      const int pos = atomicAdd(&s.count, 1);
+      if (pos < kListCap) { s.rec_a[pos] = a; s.rec_i[pos] = i; s.rec_tag[pos] = kk; }
+      if (a < tau) publish<KT, SHARED, PROBS>(s, kk, a);
+    }
+  }
+  if (approx_log2_mass<PROBS>(vq, cq, ell)) {
+    const float a = l2S - ell;
+    const float tau = unord32(__atomic_load_n(&s.tau[KT], __ATOMIC_RELAXED));
+    if (a <= tau + kEps2) {
+      const int pos = atomicAdd(&s.count, 1);
+      if (pos < kListCap) { s.rec_a[pos] = a; s.rec_i[pos] = i; s.rec_tag[pos] = KT + kk; }
+      if (a < tau) publish<KT, SHARED, PROBS>(s, KT, a);
+    }
+  }
+}
+
+// Offer an exact key to reduction `slot` (phase 1: smallest key).
+__device__ __forceinline__ void offer_key(Lds &s, int slot, double key) {
+  if (key < __builtin_huge_val()) atomicMin(&s.best[slot], ord64(key));
+}
+// Phase 2: among the holders of the smallest key, the smallest (index, k).
+__device__ __forceinline__ void offer_where(Lds &s, int slot, double key, int i, int k) {
+  if (key < __builtin_huge_val() && ord64(key) == s.best[slot])
+    atomicMin(&s.where[slot], ((unsigned long long)(uint32_t)i << 32) | (uint32_t)k);
+}
+
+template <typename T, int KT, bool SHARED, bool PROBS>
+__global__ void __launch_bounds__(kBlock) scan_kernel(const ScanParams p) {
+  using elem = typename T::elem;
+  __shared__ Lds s;
+
+  const int tid = threadIdx.x;
+  const unsigned bid = blockIdx.x;
+  const int chunk = (int)(bid % (unsigned)p.n_chunks);
+  const int kg = (int)((bid / (unsigned)p.n_chunks) % (unsigned)p.n_kgroups);
+  const long long b = (long long)(bid / ((unsigned)p.n_chunks * (unsigned)p.n_kgroups));
+  const int kbase = kg * KT;
+  const int V = p.V;
+  const int G = (V + 3) >> 2;
+  const int g_begin = chunk * p.groups_per_chunk;
+  const int g_end = min(g_begin + p.groups_per_chunk, G);
+  const int iters = (g_end - g_begin + kBlock - 1) / kBlock;
+  const bool vec = p.vector_loads != 0;
+  const float fill = PROBS ? 0.0f : -__builtin_huge_valf();
+
+  const unsigned long long row = p.row_offset + (unsigned long long)b;
+  const uint32_t row_lo = (uint32_t)row, row_hi = (uint32_t)(row >> 32);
+
+  const elem *trow = reinterpret_cast<const elem *>(p.target) + b * p.target_stride_b;
+  const elem *drow0 = reinterpret_cast<const elem *>(p.draft) + b * p.draft_stride_b;
+
+  // per-draft constants (wave-uniform)
+  float cd[KT], cd23[KT];
+  bool kok[KT];
+#pragma unroll
+  for (int kk = 0; kk < KT; ++kk) {
+    const int k = kbase + kk;
+    float t = p.temp_draft_all;
+    if (p.temp_draft != nullptr && k < p.K) t = p.temp_draft[k];
+    kok[kk] = (k < p.K) && (t > 0.0f) && (t < __builtin_huge_valf());
+    cd[kk] = PROBS ? 1.0f : kLog2e / t;
+    cd23[kk] = PROBS ? 1.0f : cd[kk] * kTwo23;
+  }
+  const float Tq = p.temp_target;
+  const float cq = PROBS ? 1.0f : kLog2e / Tq;
+  const float cq23 = PROBS ? 1.0f : cq * kTwo23;
+
+  if (tid < 9) {
+    // unused draft slots sit at -inf so the shared layout's max over drafts ignores them
+    const bool used = (tid == KT) || (tid < KT && kbase + tid < p.K);
+    s.tau[tid] = used ? 0x7F800000 : (int)0x80800000;  // ord32(+inf) : ord32(-inf)
+    s.O[tid] = 0x7F800000;
+    s.best[tid] = kOrdInf64;
+    s.where[tid] = ~0ull;
+  }
+  if (tid == 0) { s.count = 0; s.unsafe = p.force_exact ? 1 : 0; s.n_survivors = 0; s.n_exact = 0; }
+  __syncthreads();
+
+  unsigned long long my_survivors = 0;
+
+  if (!p.force_exact) {
+    // ---- warm-up: approximate keys of the first tile give every reduction a finite tau
+    {
+      const int g = g_begin + tid;
+      float a_min[KT + 1];
+#pragma unroll
+      for (int kk = 0; kk <= KT; ++kk) a_min[kk] = __builtin_huge_valf();
+      if (g < g_end) {
+        float vq[4];
+        load4<T>(trow, g * 4, V, vec, fill, vq);
+#pragma unroll
+        for (int kk = 0; kk < KT; ++kk) {
+          if (kbase + kk < p.K) {
+            float vd[4];
+            load4<T>(drow0 + (SHARED ? 0 : (long long)(kbase + kk) * p.draft_stride_k), g * 4, V, vec,
+                     fill, vd);
+            uint32_t x[4];
+            philox_block((uint32_t)g, (uint32_t)(kbase + kk), row_lo, row_hi, p.seed_lo, p.seed_hi, x);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const float l2S = approx_log2_race_time(x[j]);
+              float ell;
+              if (kok[kk] && approx_log2_mass<PROBS>(vd[j], cd[kk], ell))
+                a_min[kk] = fminf(a_min[kk], l2S - ell);
+              if (approx_log2_mass<PROBS>(vq[j], cq, ell)) a_min[KT] = fminf(a_min[KT], l2S - ell);
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int kk = 0; kk <= KT; ++kk) {
+        int o = ord32(a_min[kk]);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) o = min(o, __shfl_xor(o, d));
+        if ((tid & 63) == 0 && o < 0x7F800000) atomicMin(&s.tau[kk], o);
+      }
+      __syncthreads();
+      if (tid <= KT) {
+        const float tau = unord32(s.tau[tid]);
+        const bool used = (tid == KT) || (kbase + tid < p.K);
+        if (used && tau < __builtin_huge_valf() && !(fabsf(tau) <= kTauLimit)) s.unsafe = 1;
+      }
+      if (tid == 0) {
+        if (SHARED) {
+          int m = s.tau[0];
+#pragma unroll
+          for (int kk = 1; kk < KT; ++kk) m = max(m, s.tau[kk]);
+          store_offset(&s.O[0], make_offset<PROBS>(unord32(m)));
+        } else {
+#pragma unroll
+          for (int kk = 0; kk < KT; ++kk) store_offset(&s.O[kk], make_offset<PROBS>(unord32(s.tau[kk])));
+        }
+        store_offset(&s.O[KT], make_offset<PROBS>(unord32(s.tau[KT])));
+      }
+      __syncthreads();
+    }
+
+    // ---- main loop: level 1 on every element, level 2 on survivors
+    if (!s.unsafe) {
+      constexpr int KD = SHARED ? 1 : KT;
+      float nq[4], nd[KD][4];  // next tile (prefetch)
+      {
+        const int g = g_begin + tid;
+        if (g < g_end) {
+          load4<T>(trow, g * 4, V, vec, fill, nq);
+#pragma unroll
+          for (int kk = 0; kk < KD; ++kk)
+            if (SHARED || kbase + kk < p.K)
+              load4<T>(drow0 + (SHARED ? 0 : (long long)(kbase + kk) * p.draft_stride_k), g * 4, V,
+                       vec, fill, nd[kk]);
+        }
+      }
+      for (int it = 0; it < iters; ++it) {
+        const int g = g_begin + it * kBlock + tid;
+        float vq[4], vd[KD][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) vq[j] = nq[j];
+#pragma unroll
+        for (int kk = 0; kk < KD; ++kk)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) vd[kk][j] = nd[kk][j];
+        {
+          const int gn = g + kBlock;
+          if (it + 1 < iters && gn < g_end) {
+            load4<T>(trow, gn * 4, V, vec, fill, nq);
+#pragma unroll
+            for (int kk = 0; kk < KD; ++kk)
+              if (SHARED || kbase + kk < p.K)
+                load4<T>(drow0 + (SHARED ? 0 : (long long)(kbase + kk) * p.draft_stride_k), gn * 4,
+                         V, vec, fill, nd[kk]);
+          }
+        }
+        if (g >= g_end) continue;
+
+        const float OY = load_offset(&s.O[KT]);
+        float FY[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          FY[j] = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vq[j]), cq23, OY), 0.0f, kCap);
+
+        uint32_t nts[4];  // shared layout: one threshold per index serves every draft
+        if (SHARED) {
+          const float OX = load_offset(&s.O[0]);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) nts[j] = element_not_threshold<PROBS>(vd[0][j], cd23[0], OX, FY[j]);
+        }
+
+        uint32_t x[KT][4];
+        bool hit[KT];
+        bool any = false;
+#pragma unroll
+        for (int kk = 0; kk < KT; ++kk) {
+          hit[kk] = false;
+          if (kbase + kk < p.K) {
+            philox_block((uint32_t)g, (uint32_t)(kbase + kk), row_lo, row_hi, p.seed_lo, p.seed_hi,
+                         x[kk]);
+            uint32_t nt[4];
+            if (SHARED) {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) nt[j] = nts[j];
+            } else {
+              const float OX = kok[kk] ? load_offset(&s.O[kk]) : -__builtin_huge_valf();
+#pragma unroll
+              for (int j = 0; j < 4; ++j) nt[j] = element_not_threshold<PROBS>(vd[kk][j], cd23[kk], OX, FY[j]);
+            }
+            hit[kk] = (x[kk][0] >= nt[0]) | (x[kk][1] >= nt[1]) | (x[kk][2] >= nt[2]) | (x[kk][3] >= nt[3]);
+            any |= hit[kk];
+          }
+        }
+        if (any) {
+#pragma unroll
+          for (int kk = 0; kk < KT; ++kk) {
+            if (hit[kk]) {
+              const int kd = SHARED ? 0 : kk;
+              uint32_t nt[4];
+              if (SHARED) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) nt[j] = nts[j];
+              } else {
+                // recomputed rather than kept live; a fresher (tighter) offset is equally valid
+                const float OX = kok[kk] ? load_offset(&s.O[kk]) : -__builtin_huge_valf();
+#pragma unroll
+                for (int j = 0; j < 4; ++j) nt[j] = element_not_threshold<PROBS>(vd[kk][j], cd23[kk], OX, FY[j]);
+              }
+              unsigned m = (x[kk][0] >= nt[0] ? 1u : 0u) | (x[kk][1] >= nt[1] ? 2u : 0u) |
+                           (x[kk][2] >= nt[2] ? 4u : 0u) | (x[kk][3] >= nt[3] ? 8u : 0u);
+              while (m) {
+                const int j = __ffs(m) - 1;
+                m &= m - 1;
+                const uint32_t xs = j == 0 ? x[kk][0] : j == 1 ? x[kk][1] : j == 2 ? x[kk][2] : x[kk][3];
+                const float ds = j == 0 ? vd[kd][0] : j == 1 ? vd[kd][1] : j == 2 ? vd[kd][2] : vd[kd][3];
+                const float qs = j == 0 ? vq[0] : j == 1 ? vq[1] : j == 2 ? vq[2] : vq[3];
+                const int i = g * 4 + j;
+                if (i < V) {
+                  ++my_survivors;
+                  level2<KT, SHARED, PROBS>(s, xs, ds, qs, i, kk, kok[kk], cd[kk], cq);
+                }
+              }
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();
+    if (tid == 0 && s.count > kListCap) s.unsafe = 1;
+    __syncthreads();
+  }
+
+  unsigned long long my_exact = 0;
+  const bool exact_all = s.unsafe != 0;  // uniform: read after the barrier
+
+  if (!exact_all) {
+    // ---- level 3: exact keys of the records that are still within the band
+    const int n = s.count;
+    constexpr int kPer = kListCap / kBlock;
+    double key[kPer];
+    int ri[kPer], rslot[kPer], rk[kPer];
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) {
+      key[e] = __builtin_huge_val();
+      ri[e] = 0; rslot[e] = 0; rk[e] = 0;
+      const int r = e * kBlock + tid;
+      if (r < n) {
+        const int tag = s.rec_tag[r];
+        const bool pool = tag >= KT;
+        const int kk = pool ? tag - KT : tag;
+        const int slot = pool ? KT : kk;
+        const float tau = unord32(s.tau[slot]);
+        if (s.rec_a[r] <= tau + kEps2) {
+          const int i = s.rec_i[r];
+          const int k = kbase + kk;
+          uint32_t x[4];
+          philox_block((uint32_t)(i >> 2), (uint32_t)k, row_lo, row_hi, p.seed_lo, p.seed_hi, x);
+          const uint32_t xs = (i & 3) == 0 ? x[0] : (i & 3) == 1 ? x[1] : (i & 3) == 2 ? x[2] : x[3];
+          const double S = exact_race_time(xs);
+          float temp = Tq;
+          float v;
+          if (pool) {
+            v = load1<T>(trow, i);
+          } else {
+            v = load1<T>(drow0 + (SHARED ? 0 : (long long)k * p.draft_stride_k), i);
+            temp = p.temp_draft != nullptr ? p.temp_draft[k] : p.temp_draft_all;
+          }
+          key[e] = exact_key<PROBS>(S, v, (double)temp);
+          ri[e] = i; rslot[e] = slot; rk[e] = pool ? k : 0;
+          ++my_exact;
+          offer_key(s, slot, key[e]);
+        }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) offer_where(s, rslot[e], key[e], ri[e], rk[e]);
+  } else {
+    // ---- fallback: every element of the chunk in fp64 (debug flag, out-of-range tau, list overflow)
+    if (tid < 9) { s.best[tid] = kOrdInf64; s.where[tid] = ~0ull; }
+    __syncthreads();
+    double best[KT + 1];
+    int bi[KT + 1], bk = 0;
+#pragma unroll
+    for (int kk = 0; kk <= KT; ++kk) { best[kk] = __builtin_huge_val(); bi[kk] = -1; }
+    for (int it = 0; it < iters; ++it) {
+      const int g = g_begin + it * kBlock + tid;
+      if (g >= g_end) continue;
+      float vq[4];
+      load4<T>(trow, g * 4, V, false, fill, vq);
+#pragma unroll 1
+      for (int kk = 0; kk < KT; ++kk) {
+        const int k = kbase + kk;
+        if (k >= p.K) break;
+        float vd[4];
+        load4<T>(drow0 + (SHARED ? 0 : (long long)k * p.draft_stride_k), g * 4, V, false, fill, vd);
+        uint32_t x[4];
+        philox_block((uint32_t)g, (uint32_t)k, row_lo, row_hi, p.seed_lo, p.seed_hi, x);
+        const float tk = p.temp_draft != nullptr ? p.temp_draft[k] : p.temp_draft_all;
+        const bool ok = (tk > 0.0f) && (tk < __builtin_huge_valf());
+        double bx = __builtin_huge_val();
+        int bxi = -1;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int i = g * 4 + j;
+          if (i >= V) continue;
+          const double S = exact_race_time(x[j]);
+          const double kx = ok ? exact_key<PROBS>(S, vd[j], (double)tk) : __builtin_huge_val();
+          const double ky = exact_key<PROBS>(S, vq[j], (double)Tq);
+          my_exact += 2;
+          if (kx < bx) { bx = kx; bxi = i; }
+          if (ky < best[KT] || (ky == best[KT] && ky < __builtin_huge_val() &&
+                                (i < bi[KT] || (i == bi[KT] && k < bk)))) {
+            best[KT] = ky; bi[KT] = i; bk = k;
+          }
+        }
+        // fold (bx, bxi) into draft kk's running best without dynamic register indexing
+#pragma unroll
+        for (int q = 0; q < KT; ++q)
+          if (q == kk && (bx < best[q] || (bx == best[q] && bx < __builtin_huge_val() && bxi < bi[q]))) {
+            best[q] = bx; bi[q] = bxi;
+          }
+      }
+    }
+#pragma unroll
+    for (int kk = 0; kk <= KT; ++kk) offer_key(s, kk, best[kk]);
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk <= KT; ++kk) offer_where(s, kk, best[kk], bi[kk], kk == KT ? bk : 0);
+  }
+  __syncthreads();
+
+  // ---- partial results of this (row, draft group, chunk)
+  if (tid <= KT) {
+    const bool has = s.where[tid] != ~0ull;
+    const double key = has ? unord64(s.best[tid]) : __builtin_huge_val();
+    const int idx = has ? (int)(s.where[tid] >> 32) : -1;
+    if (tid < KT) {
+      const int k = kbase + tid;
+      if (k < p.K) {
+        const long long o = (b * p.K + k) * p.n_chunks + chunk;
+        p.out.keyX[o] = key;
+        p.out.idxX[o] = idx;
+      }
+    } else {
+      const long long o = (b * p.n_kgroups + kg) * p.n_chunks + chunk;
+      p.out.keyY[o] = key;
+      p.out.idxY[o] = idx;
+      p.out.kY[o] = has ? (int)(uint32_t)s.where[tid] : -1;
+    }
+  }
+  if (p.stats != nullptr) {
+    if (my_survivors) atomicAdd(&s.n_survivors, my_survivors);
+    if (my_exact) atomicAdd(&s.n_exact, my_exact);
+    __syncthreads();
+    if (tid == 0) {
+      if (s.n_survivors) atomicAdd(&p.stats->survivors, s.n_survivors);
+      if (s.n_exact) atomicAdd(&p.stats->exact_evals, s.n_exact);
+      if (exact_all && !p.force_exact) atomicAdd(&p.stats->slow_blocks, 1ull);
+    }
+  }
+}
+
+template <typename T, bool SHARED>
+hipError_t launch_scan(int kt, bool probs, unsigned grid, hipStream_t st, const ScanParams &p) {
+#define LLC_LAUNCH(KT_, PR_)                                                                \
+  hipLaunchKernelGGL((scan_kernel<T, KT_, SHARED, PR_>), dim3(grid), dim3(kBlock), 0, st, p); \
+  return hipGetLastError();
+  if (!probs) {
+    switch (kt) {
+      case 1: LLC_LAUNCH(1, false)
+      case 2: LLC_LAUNCH(2, false)
+      case 4: LLC_LAUNCH(4, false)
+      case 8: LLC_LAUNCH(8, false)
+    }
+  } else {
+    switch (kt) {
+      case 1: LLC_LAUNCH(1, true)
+      case 2: LLC_LAUNCH(2, true)
+      case 4: LLC_LAUNCH(4, true)
+      case 8: LLC_LAUNCH(8, true)
+    }
+  }
+#undef LLC_LAUNCH
+  return hipErrorInvalidValue;
+}
+
+}  // namespace llc

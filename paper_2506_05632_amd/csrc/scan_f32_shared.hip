@@ -1,0 +1,8 @@
+// Instantiates the scan kernel for one (element type, draft layout) pair.
+#include "scan.hpp"
+
+namespace llc {
+hipError_t launch_scan_f32_shared(int kt, bool probs, unsigned grid, hipStream_t s, const ScanParams &p) {
+  return launch_scan<F32In, true>(kt, probs, grid, s, p);
+}
+}  // namespace llc
