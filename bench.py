@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Throughput of the list Gumbel-max coupling hot path on one MI355X.
+
+One step = one llc_couple call (scan + finalize) over one synthetic batch that
+is already resident in HBM.  Default workload: the large-vocabulary
+configuration (B=1024, V=128256, K=8 i.i.d. drafts, fp32 logits, T=0.7) that
+the headline metric is quoted on.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5]
+                    [--materialised] [--keys] [--no-cpu-baseline]
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# MI355X published figures used as denominators.
+HBM_PEAK_GBS = 8000.0
+# 256 CUs x 64 lanes x 2.4 GHz: 32-bit integer / fp32 lane-operations issued per second.
+ALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12
+# Issue cycles per element the method cannot avoid (derivation in the design doc): a quarter of a
+# Philox4x32-10 block (20 32x32->64 products at 4 issue cycles each + 20 three-input xors = 100
+# per 4 words) + 1 integer compare against the prefilter threshold.
+ALG_LANE_CYCLES_PER_ELEM = 26.0
+# HBM bytes per scan launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
+# copy kernel of known size); None until measured for that workload.  See profiles/.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+class HipEvents:
+    """hipEvent pairs created through the HIP runtime that torch has already loaded."""
+
+    def __init__(self, n):
+        path = "libamdhip64.so"
+        with open("/proc/self/maps") as fh:  # the copy of the runtime this process already uses
+            for line in fh:
+                if "libamdhip64" in line:
+                    path = line.split()[-1]
+                    break
+        self.hip = ctypes.CDLL(path)
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p,
+                                                 ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.pairs = []
+        for _ in range(n):
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0
+            assert self.hip.hipEventCreate(ctypes.byref(b)) == 0
+            self.pairs.append((a, b))
+
+    def elapsed_ms(self, i):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.pairs[i][0], self.pairs[i][1])
+        assert rc == 0, rc
+        return ms.value
+
+    def close(self):
+        for a, b in self.pairs:
+            self.hip.hipEventDestroy(a)
+            self.hip.hipEventDestroy(b)
+
+
+def algorithmic_bytes(w, materialised):
+    """Input bytes one call must read (outputs are negligible): the design doc, 'algorithmic bytes'."""
+    es = 4 if str(w.dtype).endswith("float32") else 2
+    draft_rows = w.B * (w.K if (materialised or not w.shared_draft) else 1)
+    return (draft_rows + w.B) * w.V * es
+
+
+def _to_host(t):
+    import numpy as np
+    import torch
+    import oracle
+    t = t.detach().cpu()
+    if t.dtype == torch.bfloat16:
+        return t.contiguous().view(torch.int16).numpy().view(np.uint16), oracle.BF16
+    return t.contiguous().numpy(), oracle.F32
+
+
+def run_cpu_baseline(w, budget_s=12.0):
+    import oracle
+    kinds = {"logits": oracle.LOGITS, "probs": oracle.PROBS, "logw": oracle.LOGW}
+    cores = oracle.threads()
+
+    def run(rows):
+        d, dt = _to_host(w.draft[:rows])
+        t, _ = _to_host(w.target[:rows])
+        t0 = time.perf_counter()
+        oracle.couple(d, t, w.K, dtype=dt, kind=kinds[w.kind], temp_target=w.temp_target,
+                      temp_draft_all=w.temp_draft, seed=w.seed, row_offset=w.row_offset)
+        return time.perf_counter() - t0
+
+    probe_rows = min(w.B, cores)
+    t_probe = run(probe_rows)
+    per_row = t_probe / probe_rows
+    rows = int(max(probe_rows, min(w.B, budget_s / max(per_row, 1e-9))))
+    rows = max(cores, rows - rows % cores) if rows >= cores else rows
+    rows = min(rows, w.B)
+    dt = run(rows)
+    elems = rows * w.K * w.V
+    return {"value": elems / dt / 1e9, "unit": "Gelem/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {rows} of {w.B} rows of the same workload, {elems} elements, "
+                      f"{dt:.2f} s wall, OpenMP over rows"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--materialised", action="store_true",
+                    help="give the K i.i.d. drafts as a [B,K,V] tensor instead of one shared [B,V] row")
+    ap.add_argument("--keys", action="store_true", help="also produce the winning keys (adds the normaliser pass)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--v-chunks", type=int, default=0)
+    ap.add_argument("--k-tile", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (rows shard across GPUs with no "
+              "communication; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2506_05632_amd as llc
+    from paper_2506_05632_amd import workloads
+
+    dev = "cuda:0"
+    w = workloads.make(args.config, dev)
+    draft = w.draft
+    if args.materialised and w.shared_draft:
+        draft = w.draft[:, None, :].expand(w.B, w.K, w.V).contiguous()
+    ws = llc.new_workspace(w.B, w.K, w.V, dev, v_chunks=args.v_chunks)
+    out = {"X": torch.empty(w.B, w.K, dtype=torch.int32, device=dev),
+           "Y": torch.empty(w.B, dtype=torch.int32, device=dev),
+           "accept": torch.empty(w.B, dtype=torch.uint8, device=dev),
+           "match_k": torch.empty(w.B, dtype=torch.int32, device=dev)}
+    if args.keys:
+        out["keyX"] = torch.empty(w.B, w.K, dtype=torch.float32, device=dev)
+        out["keyY"] = torch.empty(w.B, dtype=torch.float32, device=dev)
+    ev = HipEvents(args.steps)
+
+    def step(i=None):
+        llc.llc_couple(draft, w.target, w.K, kind=w.kind, temp_target=w.temp_target,
+                       temp_draft=w.temp_draft, seed=w.seed + (0 if i is None else i),
+                       row_offset=w.row_offset, workspace=ws, out=out,
+                       v_chunks=args.v_chunks, k_tile=args.k_tile,
+                       scan_events=None if i is None else ev.pairs[i])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    scan_ms = [ev.elapsed_ms(i) for i in range(args.steps)]
+    ev.close()
+    scan_avg_s = sum(scan_ms) / len(scan_ms) / 1e3
+    ms_per_step = wall / args.steps * 1e3
+    elems = w.elems
+    value = elems / (wall / args.steps) / 1e9
+    alg_bytes = algorithmic_bytes(w, args.materialised)
+    lane_cycles = ALG_LANE_CYCLES_PER_ELEM * elems
+    achieved = lane_cycles / scan_avg_s / 1e12
+    name = w.name + ("_materialised" if args.materialised and w.shared_draft else "")
+    roofline = {
+        "bound": "alu", "kernel": "scan_kernel",
+        "achieved": achieved, "peak": ALU_PEAK_TLANEOPS, "unit": "Tlane-op/s",
+        "frac": achieved / ALU_PEAK_TLANEOPS,
+        "traffic": MEASURED_TRAFFIC_BYTES.get(name),
+        "kernel_ms": scan_avg_s * 1e3, "kernel_ms_min": min(scan_ms),
+        "algorithmic_lane_cycles_per_elem": ALG_LANE_CYCLES_PER_ELEM,
+        "algorithmic_bytes": alg_bytes,
+        "hbm_achieved_GBs": alg_bytes / scan_avg_s / 1e9,
+        "hbm_frac": alg_bytes / scan_avg_s / 1e9 / HBM_PEAK_GBS,
+    }
+    result = {
+        "metric": "Gelem/s (B*K*V) of list Gumbel-max coupling",
+        "value": value, "unit": "Gelem/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u32+f32 (Philox words, fp32 thresholds, fp64 tie resolution)",
+        "data": "synthetic",
+        "config": {"workload": name, "B": w.B, "K": w.K, "V": w.V, "input_dtype": str(w.dtype),
+                   "temperature": w.temp_target,
+                   "draft_layout": "[B,K,V]" if (args.materialised or not w.shared_draft) else "[B,V] shared by the K drafts",
+                   "outputs": "X,Y,accept,match_k" + (",keyX,keyY" if args.keys else ""),
+                   "accept_rate": float(out["accept"].float().mean())},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = run_cpu_baseline(w)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -104,6 +104,8 @@ typedef struct llc_couple_args {
                                Results do not depend on it.                              */
   int32_t k_tile;           /* 0 = choose; else drafts per workgroup pass: 1, 2, 4 or 8.
                                Results do not depend on it.                              */
+  void *ev_scan_begin;      /* optional hipEvent_t pair, recorded on `stream` right before */
+  void *ev_scan_end;        /* and right after the scan kernel (for timing it alone)      */
 } llc_couple_args;
 
 /* Importance-weight form (Appendix C: lossy compression with K decoders, here L).
@@ -131,6 +133,7 @@ typedef struct llc_couple_is_args {
   size_t workspace_bytes;
   void *stream;
   int32_t flags, v_chunks, k_tile;
+  void *ev_scan_begin, *ev_scan_end; /* as in llc_couple_args */
 } llc_couple_is_args;
 
 /* Algorithm 1 on a batch (Section 3).  Asynchronous on a->stream. */

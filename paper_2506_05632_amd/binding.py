@@ -43,6 +43,7 @@ class CoupleArgs(ctypes.Structure):
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("stream", ctypes.c_void_p),
         ("flags", ctypes.c_int32), ("v_chunks", ctypes.c_int32), ("k_tile", ctypes.c_int32),
+        ("ev_scan_begin", ctypes.c_void_p), ("ev_scan_end", ctypes.c_void_p),
     ]
 
 
@@ -59,6 +60,7 @@ class CoupleIsArgs(ctypes.Structure):
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("stream", ctypes.c_void_p),
         ("flags", ctypes.c_int32), ("v_chunks", ctypes.c_int32), ("k_tile", ctypes.c_int32),
+        ("ev_scan_begin", ctypes.c_void_p), ("ev_scan_end", ctypes.c_void_p),
     ]
 
 
@@ -122,7 +124,7 @@ def llc_couple(draft: torch.Tensor, target: torch.Tensor, K: int, *, kind="logit
                temp_draft_per_k: Optional[torch.Tensor] = None, seed: int = 0, row_offset: int = 0,
                want_keys: bool = False, want_match: bool = True, stats: Optional[torch.Tensor] = None,
                workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None,
-               flags: int = 0, v_chunks: int = 0, k_tile: int = 0) -> dict:
+               flags: int = 0, v_chunks: int = 0, k_tile: int = 0, scan_events=None) -> dict:
     """Algorithm 1 on device tensors.
 
     draft: [B,V] (the K drafts of a row share it) or [B,K,V]; target: [B,V]; both
@@ -177,6 +179,8 @@ def llc_couple(draft: torch.Tensor, target: torch.Tensor, K: int, *, kind="logit
     a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
     a.stream = _stream_handle(dev)
     a.flags, a.v_chunks, a.k_tile = flags, v_chunks, k_tile
+    if scan_events is not None:
+        a.ev_scan_begin, a.ev_scan_end = scan_events
     rc = lib.llc_couple(ctypes.byref(a))
     if rc != 0:
         raise LlcError(rc)
@@ -186,7 +190,7 @@ def llc_couple(draft: torch.Tensor, target: torch.Tensor, K: int, *, kind="logit
 def llc_couple_is(logw_enc: torch.Tensor, logw_dec: torch.Tensor, *, seed: int = 0,
                   row_offset: int = 0, want_keys: bool = False,
                   stats: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                  flags: int = 0, v_chunks: int = 0, k_tile: int = 0) -> dict:
+                  flags: int = 0, v_chunks: int = 0, k_tile: int = 0, scan_events=None) -> dict:
     """Importance-weight form: logw_enc [B,N], logw_dec [B,L,N], float32 device tensors."""
     lib = load()
     if not (logw_enc.is_cuda and logw_dec.is_cuda):
@@ -219,6 +223,8 @@ def llc_couple_is(logw_enc: torch.Tensor, logw_dec: torch.Tensor, *, seed: int =
     a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
     a.stream = _stream_handle(dev)
     a.flags, a.v_chunks, a.k_tile = flags, v_chunks, k_tile
+    if scan_events is not None:
+        a.ev_scan_begin, a.ev_scan_end = scan_events
     rc = lib.llc_couple_is(ctypes.byref(a))
     if rc != 0:
         raise LlcError(rc)

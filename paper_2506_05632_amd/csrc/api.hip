@@ -186,6 +186,8 @@ int llc_couple(const llc_couple_args *a) {
   sp.stats = a->stats;
 
   const bool probs = a->kind == LLC_PROBS;
+  if (a->ev_scan_begin != nullptr && hipEventRecord((hipEvent_t)a->ev_scan_begin, st) != hipSuccess)
+    return LLC_E_LAUNCH;
   hipError_t e;
   if (a->dtype == LLC_F32)
     e = shared ? launch_scan_f32_shared(pl.kt, probs, (unsigned)blocks, st, sp)
@@ -194,6 +196,8 @@ int llc_couple(const llc_couple_args *a) {
     e = shared ? launch_scan_bf16_shared(pl.kt, probs, (unsigned)blocks, st, sp)
                : launch_scan_bf16_perk(pl.kt, probs, (unsigned)blocks, st, sp);
   if (e != hipSuccess) return LLC_E_LAUNCH;
+  if (a->ev_scan_end != nullptr && hipEventRecord((hipEvent_t)a->ev_scan_end, st) != hipSuccess)
+    return LLC_E_LAUNCH;
 
   FinalizeParams fp;
   fp.B = a->B; fp.K = (int)a->K; fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
@@ -220,6 +224,7 @@ int llc_couple_is(const llc_couple_is_args *a) {
   c.keyX = a->keyX; c.keyY = a->keyY; c.stats = a->stats;
   c.workspace = a->workspace; c.workspace_bytes = a->workspace_bytes; c.stream = a->stream;
   c.flags = a->flags; c.v_chunks = a->v_chunks; c.k_tile = a->k_tile;
+  c.ev_scan_begin = a->ev_scan_begin; c.ev_scan_end = a->ev_scan_end;
   return llc_couple(&c);
 }
 
