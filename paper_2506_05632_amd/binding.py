@@ -71,10 +71,11 @@ def load():
     """Load the HIP library (built by paper_2506_05632_amd/build.py); raise if it is not there."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2506_05632_amd.build` "
+        path = os.environ.get("LLC_HIP_LIB", LIB_PATH)  # override: try another build of the library
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is missing: run `python -m paper_2506_05632_amd.build` "
                                "(there is no CPU fallback)")
-        lib = ctypes.CDLL(LIB_PATH)
+        lib = ctypes.CDLL(path)
         lib.llc_couple.argtypes = [ctypes.POINTER(CoupleArgs)]
         lib.llc_couple.restype = ctypes.c_int
         lib.llc_couple_is.argtypes = [ctypes.POINTER(CoupleIsArgs)]

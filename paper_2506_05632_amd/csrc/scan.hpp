@@ -42,6 +42,11 @@ constexpr float kCap = 1333788672.0f;  // 159 * 2^23: bit pattern of 2^32
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLog2Ln2 = -0.5287663729448977f;  // log2(ln 2)
 
+// a ^ b ^ c in one instruction (gfx950's three-input bitwise op, truth table 0x96).
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+  return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 // ---- Philox4x32, ten rounds (Salmon et al., SC'11) ----------------------------
 __device__ __forceinline__ void philox_block(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4]) {
@@ -49,8 +54,8 @@ __device__ __forceinline__ void philox_block(uint32_t c0, uint32_t c1, uint32_t 
   for (int r = 0; r < 10; ++r) {
     const uint64_t pa = (uint64_t)c0 * 0xD2511F53ull;
     const uint64_t pb = (uint64_t)c2 * 0xCD9E8D57ull;
-    const uint32_t n0 = (uint32_t)(pb >> 32) ^ c1 ^ k0;
-    const uint32_t n2 = (uint32_t)(pa >> 32) ^ c3 ^ k1;
+    const uint32_t n0 = xor3((uint32_t)(pb >> 32), c1, k0);
+    const uint32_t n2 = xor3((uint32_t)(pa >> 32), c3, k1);
     c1 = (uint32_t)pb;
     c3 = (uint32_t)pa;
     c0 = n0;
@@ -59,6 +64,37 @@ __device__ __forceinline__ void philox_block(uint32_t c0, uint32_t c1, uint32_t 
     k1 += 0xBB67AE85u;
   }
   out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// KT blocks that differ only in counter word 1 (the draft index), advanced round by round
+// so that the KT dependency chains interleave.  The rounds before the draft index has
+// reached both multiplicands are identical for all KT blocks and are computed once by
+// the compiler's common-subexpression elimination.
+template <int KT>
+__device__ __forceinline__ void philox_blocks(uint32_t g, uint32_t kbase, uint32_t row_lo,
+                                              uint32_t row_hi, uint32_t k0, uint32_t k1,
+                                              uint32_t (&out)[KT][4]) {
+  uint32_t c0[KT], c1[KT], c2[KT], c3[KT];
+#pragma unroll
+  for (int kk = 0; kk < KT; ++kk) { c0[kk] = g; c1[kk] = kbase + kk; c2[kk] = row_lo; c3[kk] = row_hi; }
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+#pragma unroll
+    for (int kk = 0; kk < KT; ++kk) {
+      const uint64_t pa = (uint64_t)c0[kk] * 0xD2511F53ull;
+      const uint64_t pb = (uint64_t)c2[kk] * 0xCD9E8D57ull;
+      const uint32_t n0 = xor3((uint32_t)(pb >> 32), c1[kk], k0);
+      const uint32_t n2 = xor3((uint32_t)(pa >> 32), c3[kk], k1);
+      c1[kk] = (uint32_t)pb;
+      c3[kk] = (uint32_t)pa;
+      c0[kk] = n0;
+      c2[kk] = n2;
+    }
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+#pragma unroll
+  for (int kk = 0; kk < KT; ++kk) { out[kk][0] = c0[kk]; out[kk][1] = c1[kk]; out[kk][2] = c2[kk]; out[kk][3] = c3[kk]; }
 }
 
 // ---- small helpers ------------------------------------------------------------
@@ -140,10 +176,10 @@ __device__ __forceinline__ float approx_log2_race_time(uint32_t x) {
   if (xt < (1u << 25)) {
     const float W = ((float)xt + 0.5f) * 0x1p-32f;
     const float S = W * fmaf(W, fmaf(W, 0.33333334f, 0.5f), 1.0f);
-    return log2f(S);
+    return __log2f(S);  // arguments here are never subnormal: the bare hardware log2 suffices
   }
   const float U = ((float)x + 0.5f) * 0x1p-32f;
-  return log2f(-log2f(U)) + kLog2Ln2;
+  return __log2f(-__log2f(U)) + kLog2Ln2;
 }
 
 // The race time S = -ln U in fp64.
@@ -264,8 +300,11 @@ __device__ __forceinline__ void offer_where(Lds &s, int slot, double key, int i,
     atomicMin(&s.where[slot], ((unsigned long long)(uint32_t)i << 32) | (uint32_t)k);
 }
 
+#ifndef LLC_MIN_WAVES
+#define LLC_MIN_WAVES 1
+#endif
 template <typename T, int KT, bool SHARED, bool PROBS>
-__global__ void __launch_bounds__(kBlock) scan_kernel(const ScanParams p) {
+__global__ void __launch_bounds__(kBlock, LLC_MIN_WAVES) scan_kernel(const ScanParams p) {
   using elem = typename T::elem;
   __shared__ Lds s;
 
@@ -375,19 +414,22 @@ __global__ void __launch_bounds__(kBlock) scan_kernel(const ScanParams p) {
       __syncthreads();
     }
 
-    // ---- main loop: level 1 on every element, level 2 on survivors
+    // ---- main loop: level 1 on every element, level 2 on survivors.  No branch depends on
+    // the draft index: a padded draft (kbase + kk >= K) reads the last real row and runs its
+    // Philox chain like the others, and only its hits are masked off.
     if (!s.unsafe) {
       constexpr int KD = SHARED ? 1 : KT;
+      const elem *drow[KD];
+#pragma unroll
+      for (int kk = 0; kk < KD; ++kk)
+        drow[kk] = drow0 + (SHARED ? 0 : (long long)min(kbase + kk, p.K - 1) * p.draft_stride_k);
       float nq[4], nd[KD][4];  // next tile (prefetch)
       {
         const int g = g_begin + tid;
         if (g < g_end) {
           load4<T>(trow, g * 4, V, vec, fill, nq);
 #pragma unroll
-          for (int kk = 0; kk < KD; ++kk)
-            if (SHARED || kbase + kk < p.K)
-              load4<T>(drow0 + (SHARED ? 0 : (long long)(kbase + kk) * p.draft_stride_k), g * 4, V,
-                       vec, fill, nd[kk]);
+          for (int kk = 0; kk < KD; ++kk) load4<T>(drow[kk], g * 4, V, vec, fill, nd[kk]);
         }
       }
       for (int it = 0; it < iters; ++it) {
@@ -404,10 +446,7 @@ __global__ void __launch_bounds__(kBlock) scan_kernel(const ScanParams p) {
           if (it + 1 < iters && gn < g_end) {
             load4<T>(trow, gn * 4, V, vec, fill, nq);
 #pragma unroll
-            for (int kk = 0; kk < KD; ++kk)
-              if (SHARED || kbase + kk < p.K)
-                load4<T>(drow0 + (SHARED ? 0 : (long long)(kbase + kk) * p.draft_stride_k), gn * 4,
-                         V, vec, fill, nd[kk]);
+            for (int kk = 0; kk < KD; ++kk) load4<T>(drow[kk], gn * 4, V, vec, fill, nd[kk]);
           }
         }
         if (g >= g_end) continue;
@@ -418,63 +457,44 @@ __global__ void __launch_bounds__(kBlock) scan_kernel(const ScanParams p) {
         for (int j = 0; j < 4; ++j)
           FY[j] = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vq[j]), cq23, OY), 0.0f, kCap);
 
-        uint32_t nts[4];  // shared layout: one threshold per index serves every draft
-        if (SHARED) {
-          const float OX = load_offset(&s.O[0]);
+        uint32_t nt[KD][4];  // shared layout: one threshold per index serves every draft
 #pragma unroll
-          for (int j = 0; j < 4; ++j) nts[j] = element_not_threshold<PROBS>(vd[0][j], cd23[0], OX, FY[j]);
+        for (int kk = 0; kk < KD; ++kk) {
+          const float OX = (SHARED || kok[kk]) ? load_offset(&s.O[kk]) : -__builtin_huge_valf();
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            nt[kk][j] = element_not_threshold<PROBS>(vd[kk][j], cd23[kk], OX, FY[j]);
         }
 
         uint32_t x[KT][4];
+        philox_blocks<KT>((uint32_t)g, (uint32_t)kbase, row_lo, row_hi, p.seed_lo, p.seed_hi, x);
         bool hit[KT];
         bool any = false;
 #pragma unroll
         for (int kk = 0; kk < KT; ++kk) {
-          hit[kk] = false;
-          if (kbase + kk < p.K) {
-            philox_block((uint32_t)g, (uint32_t)(kbase + kk), row_lo, row_hi, p.seed_lo, p.seed_hi,
-                         x[kk]);
-            uint32_t nt[4];
-            if (SHARED) {
-#pragma unroll
-              for (int j = 0; j < 4; ++j) nt[j] = nts[j];
-            } else {
-              const float OX = kok[kk] ? load_offset(&s.O[kk]) : -__builtin_huge_valf();
-#pragma unroll
-              for (int j = 0; j < 4; ++j) nt[j] = element_not_threshold<PROBS>(vd[kk][j], cd23[kk], OX, FY[j]);
-            }
-            hit[kk] = (x[kk][0] >= nt[0]) | (x[kk][1] >= nt[1]) | (x[kk][2] >= nt[2]) | (x[kk][3] >= nt[3]);
-            any |= hit[kk];
-          }
+          const int kd = SHARED ? 0 : kk;
+          hit[kk] = (x[kk][0] >= nt[kd][0]) | (x[kk][1] >= nt[kd][1]) | (x[kk][2] >= nt[kd][2]) |
+                    (x[kk][3] >= nt[kd][3]);
+          any |= hit[kk];
         }
         if (any) {
 #pragma unroll
           for (int kk = 0; kk < KT; ++kk) {
-            if (hit[kk]) {
-              const int kd = SHARED ? 0 : kk;
-              uint32_t nt[4];
-              if (SHARED) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) nt[j] = nts[j];
-              } else {
-                // recomputed rather than kept live; a fresher (tighter) offset is equally valid
-                const float OX = kok[kk] ? load_offset(&s.O[kk]) : -__builtin_huge_valf();
-#pragma unroll
-                for (int j = 0; j < 4; ++j) nt[j] = element_not_threshold<PROBS>(vd[kk][j], cd23[kk], OX, FY[j]);
-              }
-              unsigned m = (x[kk][0] >= nt[0] ? 1u : 0u) | (x[kk][1] >= nt[1] ? 2u : 0u) |
-                           (x[kk][2] >= nt[2] ? 4u : 0u) | (x[kk][3] >= nt[3] ? 8u : 0u);
-              while (m) {
-                const int j = __ffs(m) - 1;
-                m &= m - 1;
-                const uint32_t xs = j == 0 ? x[kk][0] : j == 1 ? x[kk][1] : j == 2 ? x[kk][2] : x[kk][3];
-                const float ds = j == 0 ? vd[kd][0] : j == 1 ? vd[kd][1] : j == 2 ? vd[kd][2] : vd[kd][3];
-                const float qs = j == 0 ? vq[0] : j == 1 ? vq[1] : j == 2 ? vq[2] : vq[3];
-                const int i = g * 4 + j;
-                if (i < V) {
-                  ++my_survivors;
-                  level2<KT, SHARED, PROBS>(s, xs, ds, qs, i, kk, kok[kk], cd[kk], cq);
-                }
+            if (!hit[kk]) continue;
+            const int kd = SHARED ? 0 : kk;
+            unsigned m = (x[kk][0] >= nt[kd][0] ? 1u : 0u) | (x[kk][1] >= nt[kd][1] ? 2u : 0u) |
+                         (x[kk][2] >= nt[kd][2] ? 4u : 0u) | (x[kk][3] >= nt[kd][3] ? 8u : 0u);
+            if (kbase + kk >= p.K) m = 0;
+            while (m) {
+              const int j = __ffs(m) - 1;
+              m &= m - 1;
+              const uint32_t xs = j == 0 ? x[kk][0] : j == 1 ? x[kk][1] : j == 2 ? x[kk][2] : x[kk][3];
+              const float ds = j == 0 ? vd[kd][0] : j == 1 ? vd[kd][1] : j == 2 ? vd[kd][2] : vd[kd][3];
+              const float qs = j == 0 ? vq[0] : j == 1 ? vq[1] : j == 2 ? vq[2] : vq[3];
+              const int i = g * 4 + j;
+              if (i < V) {
+                ++my_survivors;
+                level2<KT, SHARED, PROBS>(s, xs, ds, qs, i, kk, kok[kk], cd[kk], cq);
               }
             }
           }
