@@ -160,6 +160,23 @@ __device__ __forceinline__ void load4<BF16In>(const uint16_t *row, int i0, int V
   }
 }
 
+// Four in-range elements from a row aligned for vector loads: no bounds checks.
+template <typename T>
+__device__ __forceinline__ void load4_vec(const typename T::elem *row, int i0, float (&v)[4]);
+template <>
+__device__ __forceinline__ void load4_vec<F32In>(const float *row, int i0, float (&v)[4]) {
+  const float4 t = *reinterpret_cast<const float4 *>(row + i0);
+  v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+}
+template <>
+__device__ __forceinline__ void load4_vec<BF16In>(const uint16_t *row, int i0, float (&v)[4]) {
+  const uint2 t = *reinterpret_cast<const uint2 *>(row + i0);
+  v[0] = __uint_as_float(t.x << 16);
+  v[1] = __uint_as_float(t.x & 0xFFFF0000u);
+  v[2] = __uint_as_float(t.y << 16);
+  v[3] = __uint_as_float(t.y & 0xFFFF0000u);
+}
+
 template <typename T>
 __device__ __forceinline__ float load1(const typename T::elem *row, int i);
 template <>
@@ -423,33 +440,21 @@ __global__ void __launch_bounds__(kBlock, LLC_MIN_WAVES) scan_kernel(const ScanP
 #pragma unroll
       for (int kk = 0; kk < KD; ++kk)
         drow[kk] = drow0 + (SHARED ? 0 : (long long)min(kbase + kk, p.K - 1) * p.draft_stride_k);
-      float nq[4], nd[KD][4];  // next tile (prefetch)
-      {
-        const int g = g_begin + tid;
-        if (g < g_end) {
-          load4<T>(trow, g * 4, V, vec, fill, nq);
-#pragma unroll
-          for (int kk = 0; kk < KD; ++kk) load4<T>(drow[kk], g * 4, V, vec, fill, nd[kk]);
-        }
-      }
-      for (int it = 0; it < iters; ++it) {
-        const int g = g_begin + it * kBlock + tid;
+      // One tile (kBlock groups): loads are issued first, the Philox chains (which do not
+      // depend on them) run while they are in flight, thresholds and compares come last.
+      auto process_tile = [&](const int g, const bool interior) {
         float vq[4], vd[KD][4];
+        if (interior) {
+          load4_vec<T>(trow, g * 4, vq);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) vq[j] = nq[j];
+          for (int kk = 0; kk < KD; ++kk) load4_vec<T>(drow[kk], g * 4, vd[kk]);
+        } else {
+          load4<T>(trow, g * 4, V, vec, fill, vq);
 #pragma unroll
-        for (int kk = 0; kk < KD; ++kk)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) vd[kk][j] = nd[kk][j];
-        {
-          const int gn = g + kBlock;
-          if (it + 1 < iters && gn < g_end) {
-            load4<T>(trow, gn * 4, V, vec, fill, nq);
-#pragma unroll
-            for (int kk = 0; kk < KD; ++kk) load4<T>(drow[kk], gn * 4, V, vec, fill, nd[kk]);
-          }
+          for (int kk = 0; kk < KD; ++kk) load4<T>(drow[kk], g * 4, V, vec, fill, vd[kk]);
         }
-        if (g >= g_end) continue;
+        uint32_t x[KT][4];
+        philox_blocks<KT>((uint32_t)g, (uint32_t)kbase, row_lo, row_hi, p.seed_lo, p.seed_hi, x);
 
         const float OY = load_offset(&s.O[KT]);
         float FY[4];
@@ -466,8 +471,6 @@ __global__ void __launch_bounds__(kBlock, LLC_MIN_WAVES) scan_kernel(const ScanP
             nt[kk][j] = element_not_threshold<PROBS>(vd[kk][j], cd23[kk], OX, FY[j]);
         }
 
-        uint32_t x[KT][4];
-        philox_blocks<KT>((uint32_t)g, (uint32_t)kbase, row_lo, row_hi, p.seed_lo, p.seed_hi, x);
         bool hit[KT];
         bool any = false;
 #pragma unroll
@@ -499,6 +502,16 @@ __global__ void __launch_bounds__(kBlock, LLC_MIN_WAVES) scan_kernel(const ScanP
             }
           }
         }
+      };
+      // A tile is interior when every lane's group is complete and inside the chunk: all rows
+      // are then read with unconditional vector loads.
+      const int interior_end = vec ? min(g_end, V >> 2) : g_begin;
+      const int n_interior = max(0, (interior_end - g_begin) / kBlock);
+      int it = 0;
+      for (; it < n_interior; ++it) process_tile(g_begin + it * kBlock + tid, true);
+      for (; it < iters; ++it) {
+        const int g = g_begin + it * kBlock + tid;
+        if (g < g_end) process_tile(g, false);
       }
     }
     __syncthreads();
