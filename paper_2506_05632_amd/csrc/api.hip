@@ -17,7 +17,13 @@ struct Plan {
   int kt, n_kgroups, n_chunks, groups_per_chunk;
 };
 
-int auto_ktile(long long K) { return K >= 8 ? 8 : K >= 3 ? 4 : K == 2 ? 2 : 1; }
+// Drafts per workgroup pass.  With one shared proposal the per-index work is amortised over the
+// drafts of a pass, so wider is better; with per-draft rows each draft brings its own loads and
+// thresholds and four keep the kernel within 128 VGPRs.
+int auto_ktile(long long K, bool shared) {
+  if (K >= 8 && shared) return 8;
+  return K >= 3 ? 4 : K == 2 ? 2 : 1;
+}
 
 // Split the G four-element groups of a row into chunks of a multiple of kBlock groups.
 void plan_chunks(long long G, int want, int *n_chunks, int *groups_per_chunk) {
@@ -122,7 +128,7 @@ int llc_couple(const llc_couple_args *a) {
   const bool shared = a->draft_stride_k == 0 && temp_draft == nullptr;
 
   Plan pl;
-  pl.kt = a->k_tile != 0 ? a->k_tile : auto_ktile(a->K);
+  pl.kt = a->k_tile != 0 ? a->k_tile : auto_ktile(a->K, shared);
   pl.n_kgroups = (int)((a->K + pl.kt - 1) / pl.kt);
   const long long G = (a->V + 3) / 4;
   plan_chunks(G, a->v_chunks != 0 ? a->v_chunks : auto_chunks(a->B, pl.n_kgroups), &pl.n_chunks,

@@ -317,11 +317,10 @@ __device__ __forceinline__ void offer_where(Lds &s, int slot, double key, int i,
     atomicMin(&s.where[slot], ((unsigned long long)(uint32_t)i << 32) | (uint32_t)k);
 }
 
-#ifndef LLC_MIN_WAVES
-#define LLC_MIN_WAVES 1
-#endif
+// Four workgroups per CU (at most 128 VGPRs) wherever that costs no spills: with B a
+// multiple of 1024 rows every CU then holds a whole number of rows at a time.
 template <typename T, int KT, bool SHARED, bool PROBS>
-__global__ void __launch_bounds__(kBlock, LLC_MIN_WAVES) scan_kernel(const ScanParams p) {
+__global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kernel(const ScanParams p) {
   using elem = typename T::elem;
   __shared__ Lds s;
 
