@@ -23,10 +23,17 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # 256 CUs x 64 lanes x 2.4 GHz: 32-bit integer / fp32 lane-operations issued per second.
 ALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12
-# Issue cycles per element the method cannot avoid (derivation in the design doc): a quarter of a
-# Philox4x32-10 block (20 32x32->64 products at 4 issue cycles each + 20 three-input xors = 100
-# per 4 words) + 1 integer compare against the prefilter threshold.
-ALG_LANE_CYCLES_PER_ELEM = 26.0
+
+
+def algorithmic_lane_ops(K):
+    """Vector-ALU lane operations per element that the method cannot avoid (derivation in
+    the design doc): per Philox4x32-10 block of 4 words, 15 32x32->64 products and 15 three-input
+    xors depend on both the index and the draft, 3 + 3 more are shared by the K drafts of a row
+    (32-bit multiplies and three-input xors both issue at full rate on gfx950: measured), plus
+    one integer compare per element.  Threshold construction and everything else the kernel
+    executes counts as overhead, not as algorithmic work."""
+    return (30.0 + 6.0 / K) / 4.0 + 1.0
+
 # HBM bytes per scan launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
 # copy kernel of known size); None until measured for that workload.  See profiles/.
 MEASURED_TRAFFIC_BYTES = {}
@@ -121,6 +128,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--v-chunks", type=int, default=0)
     ap.add_argument("--k-tile", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region run three plain 1 GiB device copies (a known-size "
+                         "reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (rows shard across GPUs with no "
@@ -164,25 +174,35 @@ def main():
 
     scan_ms = [ev.elapsed_ms(i) for i in range(args.steps)]
     ev.close()
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     scan_avg_s = sum(scan_ms) / len(scan_ms) / 1e3
     ms_per_step = wall / args.steps * 1e3
     elems = w.elems
     value = elems / (wall / args.steps) / 1e9
     alg_bytes = algorithmic_bytes(w, args.materialised)
-    lane_cycles = ALG_LANE_CYCLES_PER_ELEM * elems
-    achieved = lane_cycles / scan_avg_s / 1e12
+    alg_ops = algorithmic_lane_ops(w.K)
+    alu_achieved = alg_ops * elems / scan_avg_s / 1e12
+    hbm_achieved = alg_bytes / scan_avg_s / 1e9
+    alu_frac, hbm_frac = alu_achieved / ALU_PEAK_TLANEOPS, hbm_achieved / HBM_PEAK_GBS
     name = w.name + ("_materialised" if args.materialised and w.shared_draft else "")
-    roofline = {
-        "bound": "alu", "kernel": "scan_kernel",
-        "achieved": achieved, "peak": ALU_PEAK_TLANEOPS, "unit": "Tlane-op/s",
-        "frac": achieved / ALU_PEAK_TLANEOPS,
-        "traffic": MEASURED_TRAFFIC_BYTES.get(name),
+    # the ceiling that binds this workload is the one it sits closer to
+    if hbm_frac >= alu_frac:
+        roofline = {"bound": "hbm", "achieved": hbm_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": hbm_frac}
+    else:
+        roofline = {"bound": "alu", "achieved": alu_achieved, "peak": ALU_PEAK_TLANEOPS,
+                    "unit": "Tlane-op/s", "frac": alu_frac}
+    roofline.update({
+        "kernel": "scan_kernel", "traffic": MEASURED_TRAFFIC_BYTES.get(name),
         "kernel_ms": scan_avg_s * 1e3, "kernel_ms_min": min(scan_ms),
-        "algorithmic_lane_cycles_per_elem": ALG_LANE_CYCLES_PER_ELEM,
-        "algorithmic_bytes": alg_bytes,
-        "hbm_achieved_GBs": alg_bytes / scan_avg_s / 1e9,
-        "hbm_frac": alg_bytes / scan_avg_s / 1e9 / HBM_PEAK_GBS,
-    }
+        "algorithmic_bytes": alg_bytes, "algorithmic_lane_ops_per_elem": alg_ops,
+        "hbm_frac": hbm_frac, "alu_frac": alu_frac,
+    })
     result = {
         "metric": "Gelem/s (B*K*V) of list Gumbel-max coupling",
         "value": value, "unit": "Gelem/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -325,7 +325,15 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
   __shared__ Lds s;
 
   const int tid = threadIdx.x;
-  const unsigned bid = blockIdx.x;
+  // Workgroups are handed to the 8 XCDs round-robin by index.  Renumber them so that the
+  // workgroups of one row (its draft groups and chunks, which share the target row and, in the
+  // shared layout, the draft row) get indices that are congruent modulo 8: they then run on one
+  // XCD, close in time, and the second reader finds the row in that XCD's L2.
+  unsigned bid = blockIdx.x;
+  {
+    const unsigned per_xcd = gridDim.x >> 3;
+    if (bid < (per_xcd << 3)) bid = (bid & 7u) * per_xcd + (bid >> 3);
+  }
   const int chunk = (int)(bid % (unsigned)p.n_chunks);
   const int kg = (int)((bid / (unsigned)p.n_chunks) % (unsigned)p.n_kgroups);
   const long long b = (long long)(bid / ((unsigned)p.n_chunks * (unsigned)p.n_kgroups));
