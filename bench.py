@@ -34,9 +34,15 @@ def algorithmic_lane_ops(K):
     executes counts as overhead, not as algorithmic work."""
     return (30.0 + 6.0 / K) / 4.0 + 1.0
 
-# HBM bytes per scan launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
-# copy kernel of known size); None until measured for that workload.  See profiles/.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per scan launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# each scaled by what the counter reads for a plain 1 GiB copy (x2.0 and x1.0); the summaries are
+# under profiles/.  None for workloads that have not been measured.
+MEASURED_TRAFFIC_BYTES = {
+    "largevocab_v128256_k8_f32": 1062.5e6 + 0.3e6,
+    "largevocab_v128256_k8_f32_materialised": 4921.3e6 + 0.2e6,
+    "distinct_v152064_k16_bf16": 2664.4e6 + 0.1e6,
+    "is_n65536_l4_f32": 5431.0e6 + 0.4e6,
+}
 
 
 class HipEvents:

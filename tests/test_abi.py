@@ -1,0 +1,111 @@
+"""Host-side checks of the C ABI that need no GPU: symbols, struct layout, argument errors."""
+import ctypes
+import os
+import re
+import subprocess
+import sys
+
+import pytest
+
+import paper_2506_05632_amd as llc
+from paper_2506_05632_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "llc.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(llc_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = llc.load()
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+    assert llc.llc_version() == 100
+    assert llc.llc_status_string(0) == "ok"
+    assert "workspace" in llc.llc_status_string(-6)
+
+
+def test_header_is_plain_c_and_matches_the_binding_layout(tmp_path):
+    src = tmp_path / "layout.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <stddef.h>\n#include "llc.h"\n'
+        "int main(void){printf(\"%zu %zu %zu %zu %zu %zu %zu\\n\", sizeof(llc_couple_args),"
+        " sizeof(llc_couple_is_args), sizeof(llc_stats), offsetof(llc_couple_args, temp_draft),"
+        " offsetof(llc_couple_args, workspace), offsetof(llc_couple_args, ev_scan_begin),"
+        " offsetof(llc_couple_is_args, workspace)); return 0;}\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    got = [int(v) for v in subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.split()]
+    want = [ctypes.sizeof(binding.CoupleArgs), ctypes.sizeof(binding.CoupleIsArgs),
+            ctypes.sizeof(binding.LlcStats), binding.CoupleArgs.temp_draft.offset,
+            binding.CoupleArgs.workspace.offset, binding.CoupleArgs.ev_scan_begin.offset,
+            binding.CoupleIsArgs.workspace.offset]
+    assert got == want
+
+
+def _args(**kw):
+    a = binding.CoupleArgs()
+    a.B, a.K, a.V = 4, 2, 64
+    a.dtype, a.kind = binding.F32, binding.LOGITS
+    a.draft = a.target = 0x1000
+    a.draft_stride_b = a.target_stride_b = 64
+    a.temp_target = a.temp_draft_all = 1.0
+    a.X = a.Y = a.accept = 0x2000
+    a.workspace, a.workspace_bytes = 0x4000, 1 << 30
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(draft=None), -1), (dict(Y=None), -1),
+    (dict(K=0), -2), (dict(V=0), -2), (dict(B=-1), -2), (dict(K=70000), -2), (dict(V=1 << 31), -2),
+    (dict(draft_stride_b=-1), -2),
+    (dict(temp_target=0.0), -3), (dict(temp_target=float("nan")), -3), (dict(temp_draft_all=-1.0), -3),
+    (dict(dtype=7), -4), (dict(kind=5), -4),
+    (dict(draft=0x1002), -5),
+    (dict(workspace=None), -6), (dict(workspace=0x4010), -6), (dict(workspace_bytes=16), -6),
+    (dict(flags=64), -8), (dict(v_chunks=5000), -8), (dict(k_tile=3), -8),
+])
+def test_argument_errors_are_reported_before_any_launch(kw, code):
+    # every one of these returns on the host: no kernel runs, no GPU is needed
+    lib = llc.load()
+    assert lib.llc_couple(ctypes.byref(_args(**kw))) == code
+
+
+def test_null_struct_and_empty_batch():
+    lib = llc.load()
+    assert lib.llc_couple(None) == -1
+    assert lib.llc_couple_is(None) == -1
+    assert lib.llc_couple(ctypes.byref(_args(B=0, draft=None, X=None))) == 0
+    assert llc.llc_couple_workspace_size(0, 1, 1) > 0
+    assert llc.llc_couple_workspace_size(4, 0, 64) == 0
+    big = llc.llc_couple_workspace_size(1024, 8, 128256)
+    assert 0 < big < 64 << 20
+
+
+def test_probability_kind_ignores_temperatures():
+    # temperatures are not validated for kinds that do not use them; a bad workspace then is the first error
+    lib = llc.load()
+    assert lib.llc_couple(ctypes.byref(_args(kind=binding.PROBS, temp_target=0.0, workspace=None))) == -6
+
+
+def test_product_does_not_import_the_oracle():
+    code = ("import sys; import paper_2506_05632_amd; "
+            "assert not any(m == 'oracle' or m.startswith('oracle.') for m in sys.modules), 'oracle imported'")
+    subprocess.run([sys.executable, "-c", code], check=True, cwd=ROOT)
+
+
+def test_missing_library_fails_loudly(tmp_path, monkeypatch):
+    code = ("import os; os.environ['LLC_HIP_LIB'] = '/nonexistent/libllc_hip.so';"
+            "import paper_2506_05632_amd as m\n"
+            "try:\n    m.load()\nexcept RuntimeError as e:\n    print('raised')\n")
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, cwd=ROOT)
+    assert "raised" in out.stdout
