@@ -478,19 +478,28 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
             nt[kk][j] = element_not_threshold<PROBS>(vd[kk][j], cd23[kk], OX, FY[j]);
         }
 
-        bool hit[KT];
         bool any = false;
+        if (SHARED && KT > 1) {
+          // one threshold per index serves every draft: any_k (x_k >= nt) == (max_k x_k >= nt),
+          // and the maxima stay in the vector unit (a compare into a scalar mask costs more)
 #pragma unroll
-        for (int kk = 0; kk < KT; ++kk) {
-          const int kd = SHARED ? 0 : kk;
-          hit[kk] = (x[kk][0] >= nt[kd][0]) | (x[kk][1] >= nt[kd][1]) | (x[kk][2] >= nt[kd][2]) |
-                    (x[kk][3] >= nt[kd][3]);
-          any |= hit[kk];
+          for (int j = 0; j < 4; ++j) {
+            uint32_t mx = x[0][j];
+#pragma unroll
+            for (int kk = 1; kk < KT; ++kk) mx = max(mx, x[kk][j]);
+            any |= mx >= nt[0][j];
+          }
+        } else {
+#pragma unroll
+          for (int kk = 0; kk < KT; ++kk) {
+            const int kd = SHARED ? 0 : kk;
+            any |= (x[kk][0] >= nt[kd][0]) | (x[kk][1] >= nt[kd][1]) | (x[kk][2] >= nt[kd][2]) |
+                   (x[kk][3] >= nt[kd][3]);
+          }
         }
         if (any) {
 #pragma unroll
           for (int kk = 0; kk < KT; ++kk) {
-            if (!hit[kk]) continue;
             const int kd = SHARED ? 0 : kk;
             unsigned m = (x[kk][0] >= nt[kd][0] ? 1u : 0u) | (x[kk][1] >= nt[kd][1] ? 2u : 0u) |
                          (x[kk][2] >= nt[kd][2] ? 4u : 0u) | (x[kk][3] >= nt[kd][3] ? 8u : 0u);
