@@ -9,7 +9,8 @@ namespace {
 
 constexpr int kMaxChunks = 4096;
 constexpr int kPlannedChunkFloor = 16;  // the workspace always covers this many chunks
-constexpr long long kTargetBlocks = 2048;
+constexpr long long kTargetBlocks = 1024;  // four resident workgroups on each of 256 CUs
+constexpr long long kMinTilesPerChunk = 8; // a chunk pays its own warm-up: keep it worth it
 
 inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 
@@ -36,10 +37,14 @@ void plan_chunks(long long G, int want, int *n_chunks, int *groups_per_chunk) {
   *n_chunks = (int)((tiles + tiles_per_chunk - 1) / tiles_per_chunk);
 }
 
-int auto_chunks(long long B, long long n_kgroups) {
+int auto_chunks(long long B, long long n_kgroups, long long G) {
   const long long rows = B * n_kgroups;
   if (rows >= kTargetBlocks || rows <= 0) return 1;
   long long c = (kTargetBlocks + rows - 1) / rows;
+  const long long tiles = (G + kBlock - 1) / kBlock;
+  const long long most = tiles / kMinTilesPerChunk;
+  if (c > most) c = most;
+  if (c < 1) c = 1;
   return (int)(c > kMaxChunks ? kMaxChunks : c);
 }
 
@@ -96,7 +101,7 @@ size_t llc_couple_workspace_size(int64_t B, int64_t K, int64_t V) {
   // worst case over k_tile (one draft per group) and over v_chunks up to the planned floor
   const long long G = (V + 3) / 4;
   int nc, gpc;
-  int want = auto_chunks(B, 1);
+  int want = auto_chunks(B, 1, G);
   if (want < kPlannedChunkFloor) want = kPlannedChunkFloor;
   plan_chunks(G, want, &nc, &gpc);
   return layout_for(B, K, K, nc).total + 256;
@@ -131,7 +136,7 @@ int llc_couple(const llc_couple_args *a) {
   pl.kt = a->k_tile != 0 ? a->k_tile : auto_ktile(a->K, shared);
   pl.n_kgroups = (int)((a->K + pl.kt - 1) / pl.kt);
   const long long G = (a->V + 3) / 4;
-  plan_chunks(G, a->v_chunks != 0 ? a->v_chunks : auto_chunks(a->B, pl.n_kgroups), &pl.n_chunks,
+  plan_chunks(G, a->v_chunks != 0 ? a->v_chunks : auto_chunks(a->B, pl.n_kgroups, G), &pl.n_chunks,
               &pl.groups_per_chunk);
   const long long blocks = a->B * pl.n_kgroups * pl.n_chunks;
   if (blocks > 0x7FFFFFFFLL) return LLC_E_SHAPE;
