@@ -39,6 +39,24 @@ class _Args(ctypes.Structure):
     ]
 
 
+class _VerifyArgs(ctypes.Structure):
+    _fields_ = [
+        ("S", ctypes.c_int64), ("L", ctypes.c_int64), ("K", ctypes.c_int64), ("V", ctypes.c_int64),
+        ("dtype", ctypes.c_int32), ("kind", ctypes.c_int32),
+        ("target", ctypes.c_void_p),
+        ("stride_s", ctypes.c_int64), ("stride_j", ctypes.c_int64), ("stride_k", ctypes.c_int64),
+        ("temp_target", ctypes.c_float),
+        ("tokens", ctypes.c_void_p),
+        ("tok_stride_s", ctypes.c_int64), ("tok_stride_j", ctypes.c_int64),
+        ("seed", ctypes.c_uint64), ("row_offset", ctypes.c_uint64),
+        ("row_stride_s", ctypes.c_int64), ("row_stride_j", ctypes.c_int64),
+        ("strong", ctypes.c_int32),
+        ("Y", ctypes.c_void_p), ("n_out", ctypes.c_void_p), ("active", ctypes.c_void_p),
+        ("key", ctypes.c_void_p), ("gap", ctypes.c_void_p),
+        ("threads", ctypes.c_int32),
+    ]
+
+
 def lib():
     global _lib
     if _lib is None:
@@ -59,6 +77,8 @@ def lib():
                                     ctypes.c_int64, ctypes.c_int64, ctypes.c_uint64,
                                     ctypes.c_uint64] + [ctypes.c_void_p] * 8 + [ctypes.c_int32])
         _lib.llc_couple_is_ref.restype = ctypes.c_int
+        _lib.llc_verify_ref.argtypes = [ctypes.POINTER(_VerifyArgs)]
+        _lib.llc_verify_ref.restype = ctypes.c_int
     return _lib
 
 
@@ -163,4 +183,40 @@ def couple_is(logw_enc, logw_dec, *, seed=0, row_offset=0, threads=0):
         out["keyY"].ctypes.data, out["gapX"].ctypes.data, out["gapY"].ctypes.data, threads)
     if rc != 0:
         raise ValueError("llc_couple_is_ref rejected its arguments")
+    return out
+
+
+def verify(target, tokens, *, dtype=F32, kind=LOGITS, temp_target=1.0, seed=0, row_offset=0,
+           row_stride_s=None, row_stride_j=1, strong=False, threads=0):
+    """Algorithm 2's verification loop on host arrays.
+
+    target: [S, L+1, K, V] (q^(j,k), position L is the bonus position); tokens: [S, L, K] int32
+    draft tokens.  Position j of sequence s uses the stream of row
+    row_offset + s*row_stride_s + j*row_stride_j (default row_stride_s = L+1).
+    Returns Y [S, L+1] (-1 where not reached), n_out [S], active [S, K], key, gap [S, L+1].
+    """
+    target = _check_input(target, dtype)
+    S, L1, K, V = target.shape
+    L = L1 - 1
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32).reshape(S, L, K)
+    it = target.itemsize
+    out = {"Y": np.full((S, L1), -2, np.int32), "n_out": np.zeros(S, np.int32),
+           "active": np.zeros((S, K), np.uint8), "key": np.zeros((S, L1)), "gap": np.zeros((S, L1))}
+    a = _VerifyArgs()
+    a.S, a.L, a.K, a.V = S, L, K, V
+    a.dtype, a.kind = dtype, kind
+    a.target = target.ctypes.data
+    a.stride_s, a.stride_j, a.stride_k = (target.strides[0] // it, target.strides[1] // it,
+                                          target.strides[2] // it)
+    a.temp_target = temp_target
+    a.tokens, a.tok_stride_s, a.tok_stride_j = tokens.ctypes.data, L * K, K
+    a.seed, a.row_offset = seed, row_offset
+    a.row_stride_s = L1 if row_stride_s is None else row_stride_s
+    a.row_stride_j = row_stride_j
+    a.strong = 1 if strong else 0
+    for name in out:
+        setattr(a, name, out[name].ctypes.data)
+    a.threads = threads
+    if lib().llc_verify_ref(ctypes.byref(a)) != 0:
+        raise ValueError("llc_verify_ref rejected its arguments")
     return out

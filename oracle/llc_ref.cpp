@@ -11,6 +11,9 @@
 //   * X^(k)   = argmin_i S_i^(k) / p_i^(k)                            (Alg. 1, step 4;
 //               distinct proposals p^(k): Appendix A.3)
 //   * accept  = [ Y in {X^(1..K)} ]                                   (Alg. 1, step 5)
+// llc_verify_ref is Algorithm 2's verification loop (Section 4.2): position by
+// position the target token is the pool argmin over the drafts that are still
+// viable, and drafts whose token differs are dropped.
 // The importance-weight form (Appendix C, the normalised weights lambda_q,
 // lambda_p^(k) and the selection rule below them) is the same computation with
 // p, q proportional to exp(log-weight).
@@ -292,6 +295,90 @@ int llc_couple_is_ref(int64_t B, int64_t L, int64_t N,
   a.keyX = keyX; a.keyY = keyY; a.gapX = gapX; a.gapY = gapY;
   a.threads = threads;
   return llc_couple_ref(&a);
+}
+
+// Algorithm 2 (Section 4.2), the verification loop, for S independent sequences.
+// target[s, j, k, :] denotes q^(j,k) = M_b(. | X_{1:j-1}^(k), c) for j = 0..L (L is the
+// bonus position), tokens[s, j, k] = X_j^(k) for j = 0..L-1.  Randomness of position j of
+// sequence s is the stream of row  row_offset + s*row_stride_s + j*row_stride_j.
+// strong != 0: the pool runs over all K drafts' randomness, viable or not (Appendix B, strong
+// drafter invariance); dropped drafts are priced with a viable draft's target row.  Y[s, j] = -1 for positions that are not reached.
+struct llc_verify_ref_args {
+  int64_t S, L, K, V;
+  int32_t dtype, kind;
+  const void *target;
+  int64_t stride_s, stride_j, stride_k;
+  float temp_target;
+  const int32_t *tokens;
+  int64_t tok_stride_s, tok_stride_j;
+  uint64_t seed, row_offset;
+  int64_t row_stride_s, row_stride_j;
+  int32_t strong;
+  int32_t *Y;        // [S, L+1]
+  int32_t *n_out;    // [S]
+  uint8_t *active;   // [S, K] optional: drafts still viable when the loop ends
+  double *key;       // [S, L+1] optional: winning S/q (normalised q)
+  double *gap;       // [S, L+1] optional: relative gap to the best entry with another index
+  int32_t threads;
+};
+
+int llc_verify_ref(const llc_verify_ref_args *a) {
+  if (!a || !a->target || !a->Y || !a->n_out) return -1;
+  if (a->S < 0 || a->L < 0 || a->K < 1 || a->V < 1) return -1;
+  if (a->L > 0 && !a->tokens) return -1;
+  if (a->kind == KIND_PROBS) return -1;  // keys of different drafts are compared: needs normalised q
+  const int64_t S = a->S, L = a->L, K = a->K, V = a->V;
+  int nthreads = a->threads;
+#ifdef _OPENMP
+  if (nthreads <= 0) nthreads = omp_get_max_threads();
+#else
+  nthreads = 1;
+#endif
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+  for (int64_t s = 0; s < S; ++s) {
+    std::vector<uint8_t> viable((size_t)K, 1);
+    std::vector<double> q;
+    int32_t n = 0;
+    for (int64_t j = 0; j <= L; ++j) {
+      a->Y[s * (L + 1) + j] = -1;
+      if (a->key) a->key[s * (L + 1) + j] = kInf;
+      if (a->gap) a->gap[s * (L + 1) + j] = kInf;
+    }
+    for (int64_t j = 0; j <= L; ++j) {
+      const uint64_t row = a->row_offset + (uint64_t)(s * a->row_stride_s + j * a->row_stride_j);
+      Race pool;
+      int64_t kref = 0;  // the first viable draft: its prefix equals the output so far
+      while (kref < K && !viable[kref]) ++kref;
+      for (int64_t k = 0; k < K; ++k) {
+        if (!a->strong && !viable[k]) continue;
+        // A dropped draft's own row is conditioned on a prefix that is not the output; the
+        // strong variant keeps its randomness in the pool but prices it with the target
+        // distribution given the output prefix, i.e. the row of a viable draft.
+        const int64_t krow = viable[k] ? k : kref;
+        row_distribution(a->target, a->dtype, s * a->stride_s + j * a->stride_j + krow * a->stride_k, V,
+                         a->kind, (double)a->temp_target, q);
+        for (int64_t i = 0; i < V; ++i) {
+          const double St = race_time(shared_word(a->seed, row, (uint32_t)k, (uint64_t)i));
+          pool.offer(q[i] > 0.0 ? St / q[i] : kInf, i, k);
+        }
+      }
+      a->Y[s * (L + 1) + j] = (int32_t)pool.idx;
+      if (a->key) a->key[s * (L + 1) + j] = pool.best;
+      if (a->gap) a->gap[s * (L + 1) + j] = pool.rel_gap();
+      n = (int32_t)(j + 1);
+      if (j == L) break;
+      bool any = false;
+      for (int64_t k = 0; k < K; ++k) {
+        if (viable[k] && a->tokens[s * a->tok_stride_s + j * a->tok_stride_j + k] != (int32_t)pool.idx)
+          viable[k] = 0;
+        any = any || viable[k];
+      }
+      if (!any) break;
+    }
+    a->n_out[s] = n;
+    if (a->active) for (int64_t k = 0; k < K; ++k) a->active[s * K + k] = viable[k];
+  }
+  return 0;
 }
 
 }  // extern "C"
