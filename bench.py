@@ -8,6 +8,7 @@ the headline metric is quoted on.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5]
                     [--materialised] [--keys] [--no-cpu-baseline]
+    python bench.py --workload verify     (Algorithm 2's verification loop, llc_verify)
 """
 import argparse
 import ctypes
@@ -96,6 +97,87 @@ def _to_host(t):
     return t.contiguous().numpy(), oracle.F32
 
 
+def run_cpu_baseline_verify(w, budget_s=12.0):
+    import oracle
+    cores = oracle.threads()
+
+    def run(n):
+        t, dt = _to_host(w.target[:n])
+        tok = w.tokens[:n].cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.verify(t, tok, dtype=dt, temp_target=w.temp_target, seed=w.seed)
+        return time.perf_counter() - t0
+
+    probe = min(w.S, cores)
+    per_seq = run(probe) / probe
+    n = int(max(probe, min(w.S, budget_s / max(per_seq, 1e-9))))
+    n = min(w.S, max(cores, n - n % cores) if n >= cores else n)
+    dt = run(n)
+    elems = n * (w.L + 1) * w.K * w.V
+    return {"value": elems / dt / 1e9, "unit": "Gelem/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {n} of {w.S} sequences of the same workload, {elems} elements, "
+                      f"{dt:.2f} s wall, OpenMP over sequences (the oracle stops a sequence at its "
+                      f"first rejection, the GPU path evaluates every position)"}
+
+
+def bench_verify(args):
+    import torch
+    import paper_2506_05632_amd as llc
+    from paper_2506_05632_amd import workloads
+
+    dev = "cuda:0"
+    w = workloads.make_verify("largevocab", dev)
+    ws = torch.empty(llc.llc_verify_workspace_size(w.S, w.L, w.K, w.V), dtype=torch.uint8, device=dev)
+    out = {"Y": torch.empty(w.S, w.L + 1, dtype=torch.int32, device=dev),
+           "n_out": torch.empty(w.S, dtype=torch.int32, device=dev),
+           "active": torch.empty(w.S, w.K, dtype=torch.uint8, device=dev)}
+    ev = HipEvents(args.steps)
+
+    def step(i=None):
+        llc.llc_verify(w.target, w.tokens, temp_target=w.temp_target, seed=w.seed + (0 if i is None else i),
+                       workspace=ws, out=out, v_chunks=args.v_chunks, k_tile=args.k_tile,
+                       scan_events=None if i is None else ev.pairs[i])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    scan_ms = [ev.elapsed_ms(i) for i in range(args.steps)]
+    ev.close()
+    scan_avg_s = sum(scan_ms) / len(scan_ms) / 1e3
+    elems = w.elems
+    es = 4 if w.dtype == torch.float32 else 2
+    alg_bytes = elems * es                      # every target row read once
+    alg_ops = algorithmic_lane_ops(1) - 0.0     # no sharing of Philox rounds is assumed across rows
+    hbm_achieved = alg_bytes / scan_avg_s / 1e9
+    alu_achieved = alg_ops * elems / scan_avg_s / 1e12
+    hbm_frac, alu_frac = hbm_achieved / HBM_PEAK_GBS, alu_achieved / ALU_PEAK_TLANEOPS
+    roofline = {"bound": "hbm", "achieved": hbm_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": hbm_frac, "kernel": "scan_kernel", "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+                "kernel_ms": scan_avg_s * 1e3, "kernel_ms_min": min(scan_ms),
+                "algorithmic_bytes": alg_bytes, "hbm_frac": hbm_frac, "alu_frac": alu_frac}
+    result = {
+        "metric": "Gelem/s (S*(L+1)*K*V) of Algorithm 2's verification loop",
+        "value": elems / (wall / args.steps) / 1e9, "unit": "Gelem/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32+f32 (Philox words, fp32 thresholds, fp64 tie resolution and normalisers)",
+        "data": "synthetic",
+        "config": {"workload": w.name, "S": w.S, "L": w.L, "K": w.K, "V": w.V,
+                   "input_dtype": str(w.dtype), "temperature": w.temp_target,
+                   "outputs": "Y,n_out,active",
+                   "mean_tokens_per_block": float(out["n_out"].float().mean())},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = run_cpu_baseline_verify(w)
+    print(json.dumps(result))
+
+
 def run_cpu_baseline(w, budget_s=12.0):
     import oracle
     kinds = {"logits": oracle.LOGITS, "probs": oracle.PROBS, "logw": oracle.LOGW}
@@ -128,6 +210,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--workload", choices=["couple", "verify"], default="couple")
     ap.add_argument("--materialised", action="store_true",
                     help="give the K i.i.d. drafts as a [B,K,V] tensor instead of one shared [B,V] row")
     ap.add_argument("--keys", action="store_true", help="also produce the winning keys (adds the normaliser pass)")
@@ -142,6 +225,10 @@ def main():
         print("bench.py: this build measures one GPU only (rows shard across GPUs with no "
               "communication; see DESIGN.md); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.workload == "verify":
+        bench_verify(args)
+        return
 
     import torch
     import paper_2506_05632_amd as llc

@@ -25,7 +25,7 @@
 extern "C" {
 #endif
 
-#define LLC_VERSION 100
+#define LLC_VERSION 101
 
 enum {
   LLC_OK = 0,
@@ -136,14 +136,67 @@ typedef struct llc_couple_is_args {
   void *ev_scan_begin, *ev_scan_end; /* as in llc_couple_args */
 } llc_couple_is_args;
 
+/* Arguments of llc_verify: the verification loop of Algorithm 2 (Section 4.2,
+ * drafter-invariant multi-draft speculative decoding) for S independent sequences, each
+ * with K drafts of L tokens.
+ *
+ * Inputs.  target[s,j,k,:] denotes q^(j,k), the target model's next-token distribution
+ * after draft k's first j tokens, j = 0..L (j = L is the bonus position); addressed as
+ * target[s*stride_s + j*stride_j + k*stride_k + i], last dimension contiguous, kind
+ * LLC_LOGITS (with temp_target) or LLC_LOGW (the keys of different rows are compared, so
+ * rows must be normalisable: LLC_PROBS is refused).  tokens[s*tok_stride_s + j*tok_stride_j
+ * + k] = X_j^(k), j = 0..L-1, the draft tokens (from llc_couple's X, or anywhere else).
+ * Randomness: position j of sequence s uses the stream of row
+ * row_offset + s*row_stride_s + j*row_stride_j, draft k uses counter word k, exactly as
+ * llc_couple does, so a drafting call on the same row and this call are coupled.
+ *
+ * Outputs.  Position by position, Y[s,j] = argmin_i min_{k viable} S_i^(j,k) / q_i^(j,k)
+ * with q normalised; every draft whose token differs from Y[s,j] stops being viable; the
+ * loop ends after the first position at which no draft is viable, or after the bonus
+ * position.  n_out[s] = number of tokens emitted (accepted + 1), Y[s,j] = -1 for
+ * j >= n_out[s].  active[s,k] = 1 iff draft k is still viable at the end (all L tokens
+ * accepted).  keyY[s,j] = the winning S/q.  Yk / keyYk[s,j,k] = draft k's own
+ * argmin_i S_i^(j,k)/q_i^(j,k) and its key, whether or not k was viable.
+ */
+typedef struct llc_verify_args {
+  int64_t S, L, K, V;       /* S >= 0, L >= 0, K in 1..64, V >= 1                       */
+  int32_t dtype;            /* LLC_F32 | LLC_BF16                                        */
+  int32_t kind;             /* LLC_LOGITS | LLC_LOGW                                     */
+  const void *target;       /* device [S, L+1, K, V]                                     */
+  int64_t stride_s, stride_j, stride_k;
+  float temp_target;        /* > 0; LLC_LOGITS only                                      */
+  const int32_t *tokens;    /* device [S, L, K]; may be NULL when L == 0                 */
+  int64_t tok_stride_s, tok_stride_j;
+  uint64_t seed, row_offset;
+  int64_t row_stride_s, row_stride_j; /* >= 0                                            */
+  int32_t *Y;               /* [S, L+1] required                                         */
+  int32_t *n_out;           /* [S]      required                                         */
+  uint8_t *active;          /* [S, K]   optional                                         */
+  float *keyY;              /* [S, L+1] optional                                         */
+  int32_t *Yk;              /* [S, L+1, K] optional                                      */
+  float *keyYk;             /* [S, L+1, K] optional                                      */
+  llc_stats *stats;
+  void *workspace;          /* device, 256-byte aligned, >= llc_verify_workspace_size()  */
+  size_t workspace_bytes;
+  void *stream;
+  int32_t flags, v_chunks, k_tile;   /* as in llc_couple_args                            */
+  void *ev_scan_begin, *ev_scan_end; /* as in llc_couple_args                            */
+} llc_verify_args;
+
 /* Algorithm 1 on a batch (Section 3).  Asynchronous on a->stream. */
 int llc_couple(const llc_couple_args *a);
 
 /* Appendix C's index selection at the encoder and the L decoders.  Asynchronous. */
 int llc_couple_is(const llc_couple_is_args *a);
 
+/* Algorithm 2's verification loop (Section 4.2) on S sequences.  Asynchronous. */
+int llc_verify(const llc_verify_args *a);
+
 /* Bytes of device scratch either call needs for this shape (any options); 0 on bad shapes. */
 size_t llc_couple_workspace_size(int64_t B, int64_t K, int64_t V);
+
+/* Bytes of device scratch llc_verify needs for this shape (any options); 0 on bad shapes. */
+size_t llc_verify_workspace_size(int64_t S, int64_t L, int64_t K, int64_t V);
 
 /* Text for a return code (static storage). */
 const char *llc_status_string(int code);

@@ -18,8 +18,8 @@ LOGITS, PROBS, LOGW = 0, 1, 2
 FLAG_EXACT_SCAN = 1
 
 _KINDS = {"logits": LOGITS, "probs": PROBS, "logw": LOGW}
-EXPORTS = ["llc_couple", "llc_couple_is", "llc_couple_workspace_size", "llc_status_string",
-           "llc_version"]
+EXPORTS = ["llc_couple", "llc_couple_is", "llc_verify", "llc_couple_workspace_size",
+           "llc_verify_workspace_size", "llc_status_string", "llc_version"]
 
 
 class LlcStats(ctypes.Structure):
@@ -64,6 +64,27 @@ class CoupleIsArgs(ctypes.Structure):
     ]
 
 
+class VerifyArgs(ctypes.Structure):
+    _fields_ = [
+        ("S", ctypes.c_int64), ("L", ctypes.c_int64), ("K", ctypes.c_int64), ("V", ctypes.c_int64),
+        ("dtype", ctypes.c_int32), ("kind", ctypes.c_int32),
+        ("target", ctypes.c_void_p),
+        ("stride_s", ctypes.c_int64), ("stride_j", ctypes.c_int64), ("stride_k", ctypes.c_int64),
+        ("temp_target", ctypes.c_float),
+        ("tokens", ctypes.c_void_p),
+        ("tok_stride_s", ctypes.c_int64), ("tok_stride_j", ctypes.c_int64),
+        ("seed", ctypes.c_uint64), ("row_offset", ctypes.c_uint64),
+        ("row_stride_s", ctypes.c_int64), ("row_stride_j", ctypes.c_int64),
+        ("Y", ctypes.c_void_p), ("n_out", ctypes.c_void_p), ("active", ctypes.c_void_p),
+        ("keyY", ctypes.c_void_p), ("Yk", ctypes.c_void_p), ("keyYk", ctypes.c_void_p),
+        ("stats", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("stream", ctypes.c_void_p),
+        ("flags", ctypes.c_int32), ("v_chunks", ctypes.c_int32), ("k_tile", ctypes.c_int32),
+        ("ev_scan_begin", ctypes.c_void_p), ("ev_scan_end", ctypes.c_void_p),
+    ]
+
+
 _lib = None
 
 
@@ -80,8 +101,12 @@ def load():
         lib.llc_couple.restype = ctypes.c_int
         lib.llc_couple_is.argtypes = [ctypes.POINTER(CoupleIsArgs)]
         lib.llc_couple_is.restype = ctypes.c_int
+        lib.llc_verify.argtypes = [ctypes.POINTER(VerifyArgs)]
+        lib.llc_verify.restype = ctypes.c_int
         lib.llc_couple_workspace_size.argtypes = [ctypes.c_int64] * 3
         lib.llc_couple_workspace_size.restype = ctypes.c_size_t
+        lib.llc_verify_workspace_size.argtypes = [ctypes.c_int64] * 4
+        lib.llc_verify_workspace_size.restype = ctypes.c_size_t
         lib.llc_status_string.argtypes = [ctypes.c_int]
         lib.llc_status_string.restype = ctypes.c_char_p
         lib.llc_version.restype = ctypes.c_int
@@ -105,6 +130,10 @@ def llc_status_string(code: int) -> str:
 
 def llc_couple_workspace_size(B: int, K: int, V: int) -> int:
     return load().llc_couple_workspace_size(B, K, V)
+
+
+def llc_verify_workspace_size(S: int, L: int, K: int, V: int) -> int:
+    return load().llc_verify_workspace_size(S, L, K, V)
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -227,6 +256,71 @@ def llc_couple_is(logw_enc: torch.Tensor, logw_dec: torch.Tensor, *, seed: int =
     if scan_events is not None:
         a.ev_scan_begin, a.ev_scan_end = scan_events
     rc = lib.llc_couple_is(ctypes.byref(a))
+    if rc != 0:
+        raise LlcError(rc)
+    return out
+
+
+def llc_verify(target: torch.Tensor, tokens: torch.Tensor, *, kind="logits", temp_target: float = 1.0,
+               seed: int = 0, row_offset: int = 0, row_stride_s: Optional[int] = None,
+               row_stride_j: int = 1, want_keys: bool = False, want_partials: bool = False,
+               stats: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+               out: Optional[dict] = None, flags: int = 0, v_chunks: int = 0, k_tile: int = 0,
+               scan_events=None) -> dict:
+    """Algorithm 2's verification loop on device tensors.
+
+    target: [S, L+1, K, V] float32 or bfloat16 (q^(j,k); position L is the bonus position),
+    tokens: [S, L, K] int32 draft tokens.  Position j of sequence s uses the random stream of
+    row row_offset + s*row_stride_s + j*row_stride_j (default row_stride_s = L+1).  Returns
+    device tensors Y [S, L+1] int32 (-1 where not reached), n_out [S] int32, active [S, K]
+    uint8 and, if asked, keyY [S, L+1], Yk and keyYk [S, L+1, K].  Asynchronous on torch's
+    current stream.
+    """
+    lib = load()
+    if not target.is_cuda:
+        raise ValueError("llc_verify needs device tensors (there is no CPU path)")
+    if target.dtype not in (torch.float32, torch.bfloat16) or target.dim() != 4 or target.stride(-1) != 1:
+        raise ValueError("target must be [S, L+1, K, V], float32 or bfloat16, last dimension contiguous")
+    S, L1, K, V = target.shape
+    L = L1 - 1
+    dev = target.device
+    if L > 0:
+        if (not tokens.is_cuda or tokens.dtype != torch.int32 or tuple(tokens.shape) != (S, L, K)
+                or tokens.stride(2) != 1):
+            raise ValueError("tokens must be [S, L, K] int32 on the device, last dimension contiguous")
+    if out is None:
+        out = {"Y": torch.empty(S, L1, dtype=torch.int32, device=dev),
+               "n_out": torch.empty(S, dtype=torch.int32, device=dev),
+               "active": torch.empty(S, K, dtype=torch.uint8, device=dev)}
+        if want_keys:
+            out["keyY"] = torch.empty(S, L1, dtype=torch.float32, device=dev)
+        if want_partials:
+            out["Yk"] = torch.empty(S, L1, K, dtype=torch.int32, device=dev)
+            out["keyYk"] = torch.empty(S, L1, K, dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(llc_verify_workspace_size(S, L, K, V), 256), dtype=torch.uint8, device=dev)
+    a = VerifyArgs()
+    a.S, a.L, a.K, a.V = S, L, K, V
+    a.dtype = F32 if target.dtype == torch.float32 else BF16
+    a.kind = _KINDS[kind]
+    a.target = target.data_ptr()
+    a.stride_s, a.stride_j, a.stride_k = target.stride(0), target.stride(1), target.stride(2)
+    a.temp_target = temp_target
+    if L > 0:
+        a.tokens, a.tok_stride_s, a.tok_stride_j = tokens.data_ptr(), tokens.stride(0), tokens.stride(1)
+    a.seed, a.row_offset = seed, row_offset
+    a.row_stride_s = L1 if row_stride_s is None else row_stride_s
+    a.row_stride_j = row_stride_j
+    a.Y, a.n_out = out["Y"].data_ptr(), out["n_out"].data_ptr()
+    a.active, a.keyY = _ptr(out.get("active")), _ptr(out.get("keyY"))
+    a.Yk, a.keyYk = _ptr(out.get("Yk")), _ptr(out.get("keyYk"))
+    a.stats = _ptr(stats)
+    a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
+    a.stream = _stream_handle(dev)
+    a.flags, a.v_chunks, a.k_tile = flags, v_chunks, k_tile
+    if scan_events is not None:
+        a.ev_scan_begin, a.ev_scan_end = scan_events
+    rc = lib.llc_verify(ctypes.byref(a))
     if rc != 0:
         raise LlcError(rc)
     return out

@@ -72,6 +72,143 @@ bool shape_ok(long long B, long long K, long long V) {
 
 bool good_temp(float t) { return std::isfinite(t) && t > 0.0f; }
 
+RowMap plain_rows(long long draft_stride_b, long long target_stride_b) {
+  RowMap m;
+  m.inner_count = 1;
+  m.draft_outer = draft_stride_b; m.draft_inner = 0;
+  m.target_outer = target_stride_b; m.target_inner = 0;
+  m.row_outer = 1; m.row_inner = 0;
+  return m;
+}
+
+// llc_verify keeps, beyond the scan's partials, ln(key) [B][K] fp64 and the index [B][K].
+size_t verify_extra_bytes(long long B, long long K) {
+  return align256((size_t)(B * K) * sizeof(double)) + align256((size_t)(B * K) * sizeof(int32_t));
+}
+
+// One scan over B rows: what llc_couple and llc_verify have in common.
+struct ScanJob {
+  long long B, K, V;
+  int dtype, kind;
+  const void *draft, *target;
+  RowMap map;
+  long long draft_stride_k;
+  float temp_target, temp_draft_all;
+  const float *temp_draft;
+  uint64_t seed, row_offset;
+  bool no_pool;      // draft-side reductions only
+  bool need_lse;     // also compute the row normalisers (log kinds)
+  bool force_perk = false;  // every draft has its own row even if draft_stride_k == 0
+  int flags, v_chunks, k_tile;
+  llc_stats *stats;
+  void *workspace;
+  size_t workspace_bytes, extra_bytes;  // extra_bytes: caller's own region behind the partials
+  void *stream, *ev_begin, *ev_end;
+};
+
+// Checks the options, plans the launch, carves the workspace and enqueues the normaliser pass
+// (if asked) and the scan kernel.  *extra (if given) receives the caller's region.
+int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
+  if (j.dtype != LLC_F32 && j.dtype != LLC_BF16) return LLC_E_DTYPE;
+  if (j.kind != LLC_LOGITS && j.kind != LLC_PROBS && j.kind != LLC_LOGW) return LLC_E_DTYPE;
+  if (j.flags & ~LLC_FLAG_EXACT_SCAN) return LLC_E_OPTION;
+  if (j.v_chunks < 0 || j.v_chunks > kMaxChunks) return LLC_E_OPTION;
+  if (j.k_tile != 0 && j.k_tile != 1 && j.k_tile != 2 && j.k_tile != 4 && j.k_tile != 8)
+    return LLC_E_OPTION;
+  const bool logits = j.kind == LLC_LOGITS;
+  if (logits) {
+    if (!good_temp(j.temp_target)) return LLC_E_TEMP;
+    if (j.temp_draft == nullptr && !good_temp(j.temp_draft_all)) return LLC_E_TEMP;
+  }
+  const size_t esize = j.dtype == LLC_F32 ? 4 : 2;
+  if (((uintptr_t)j.draft % esize) != 0 || ((uintptr_t)j.target % esize) != 0) return LLC_E_ALIGN;
+
+  const float *temp_draft = logits ? j.temp_draft : nullptr;
+  const bool shared = j.draft_stride_k == 0 && temp_draft == nullptr && !j.force_perk;
+
+  Plan pl;
+  pl.kt = j.k_tile != 0 ? j.k_tile : auto_ktile(j.K, shared);
+  pl.n_kgroups = (int)((j.K + pl.kt - 1) / pl.kt);
+  const long long G = (j.V + 3) / 4;
+  plan_chunks(G, j.v_chunks != 0 ? j.v_chunks : auto_chunks(j.B, pl.n_kgroups, G), &pl.n_chunks,
+              &pl.groups_per_chunk);
+  const long long blocks = j.B * pl.n_kgroups * pl.n_chunks;
+  if (blocks > 0x7FFFFFFFLL) return LLC_E_SHAPE;
+
+  const Layout lay = layout_for(j.B, j.K, pl.n_kgroups, pl.n_chunks);
+  if (j.workspace == nullptr || ((uintptr_t)j.workspace & 255) != 0 ||
+      j.workspace_bytes < lay.total + j.extra_bytes)
+    return LLC_E_WORKSPACE;
+  char *ws = (char *)j.workspace;
+  if (extra != nullptr) *extra = ws + lay.total;
+
+  // vector loads need every row to start on a 4-element boundary of a 16-byte (fp32) or
+  // 8-byte (bf16) aligned base
+  const size_t vbytes = 4 * esize;
+  const RowMap &m = j.map;
+  const bool vec = ((uintptr_t)j.draft % vbytes) == 0 && ((uintptr_t)j.target % vbytes) == 0 &&
+                   (m.draft_outer % 4) == 0 && (m.draft_inner % 4) == 0 && (j.draft_stride_k % 4) == 0 &&
+                   (m.target_outer % 4) == 0 && (m.target_inner % 4) == 0;
+
+  hipStream_t st = (hipStream_t)j.stream;
+  Partials part;
+  part.keyX = (double *)(ws + lay.keyX);
+  part.idxX = (int32_t *)(ws + lay.idxX);
+  part.keyY = (double *)(ws + lay.keyY);
+  part.idxY = (int32_t *)(ws + lay.idxY);
+  part.kY = (int32_t *)(ws + lay.kY);
+  part.lse = (double *)(ws + lay.lse);
+
+  if (j.need_lse && j.kind != LLC_PROBS) {
+    LseParams lp;
+    lp.draft = j.draft; lp.target = j.target;
+    lp.map = j.map; lp.draft_stride_k = j.draft_stride_k;
+    lp.B = j.B; lp.K = (int)j.K; lp.V = (int)j.V; lp.dtype = j.dtype;
+    lp.temp_target = logits ? j.temp_target : 1.0f;
+    lp.temp_draft_all = logits ? j.temp_draft_all : 1.0f;
+    lp.temp_draft = temp_draft;
+    lp.is_logits = logits ? 1 : 0;
+    lp.per_k = shared ? 0 : 1;
+    lp.with_target = j.no_pool ? 0 : 1;
+    lp.vector_loads = vec ? 1 : 0;
+    lp.lse = part.lse;
+    if (launch_lse(st, lp) != hipSuccess) return LLC_E_LAUNCH;
+  }
+
+  ScanParams sp;
+  sp.draft = j.draft; sp.target = j.target;
+  sp.map = j.map; sp.draft_stride_k = j.draft_stride_k;
+  sp.B = j.B; sp.K = (int)j.K; sp.V = (int)j.V;
+  sp.n_chunks = pl.n_chunks; sp.groups_per_chunk = pl.groups_per_chunk; sp.n_kgroups = pl.n_kgroups;
+  sp.seed_lo = (unsigned)j.seed; sp.seed_hi = (unsigned)(j.seed >> 32);
+  sp.row_offset = j.row_offset;
+  sp.temp_target = logits ? j.temp_target : 1.0f;
+  sp.temp_draft_all = logits ? j.temp_draft_all : 1.0f;
+  sp.temp_draft = temp_draft;
+  sp.vector_loads = vec ? 1 : 0;
+  sp.force_exact = (j.flags & LLC_FLAG_EXACT_SCAN) ? 1 : 0;
+  sp.no_pool = j.no_pool ? 1 : 0;
+  sp.out = part;
+  sp.stats = j.stats;
+
+  const bool probs = j.kind == LLC_PROBS;
+  if (j.ev_begin != nullptr && hipEventRecord((hipEvent_t)j.ev_begin, st) != hipSuccess)
+    return LLC_E_LAUNCH;
+  hipError_t e;
+  if (j.dtype == LLC_F32)
+    e = shared ? launch_scan_f32_shared(pl.kt, probs, (unsigned)blocks, st, sp)
+               : launch_scan_f32_perk(pl.kt, probs, (unsigned)blocks, st, sp);
+  else
+    e = shared ? launch_scan_bf16_shared(pl.kt, probs, (unsigned)blocks, st, sp)
+               : launch_scan_bf16_perk(pl.kt, probs, (unsigned)blocks, st, sp);
+  if (e != hipSuccess) return LLC_E_LAUNCH;
+  if (j.ev_end != nullptr && hipEventRecord((hipEvent_t)j.ev_end, st) != hipSuccess)
+    return LLC_E_LAUNCH;
+  *plan = pl;
+  *partials = part;
+  return LLC_OK;
+}
+
 }  // namespace
 }  // namespace llc
 
@@ -114,110 +251,103 @@ int llc_couple(const llc_couple_args *a) {
   if (a->draft == nullptr || a->target == nullptr || a->X == nullptr || a->Y == nullptr ||
       a->accept == nullptr)
     return LLC_E_NULL;
-  if (a->dtype != LLC_F32 && a->dtype != LLC_BF16) return LLC_E_DTYPE;
-  if (a->kind != LLC_LOGITS && a->kind != LLC_PROBS && a->kind != LLC_LOGW) return LLC_E_DTYPE;
   if (a->draft_stride_b < 0 || a->draft_stride_k < 0 || a->target_stride_b < 0) return LLC_E_SHAPE;
-  if (a->flags & ~LLC_FLAG_EXACT_SCAN) return LLC_E_OPTION;
-  if (a->v_chunks < 0 || a->v_chunks > kMaxChunks) return LLC_E_OPTION;
-  if (a->k_tile != 0 && a->k_tile != 1 && a->k_tile != 2 && a->k_tile != 4 && a->k_tile != 8)
-    return LLC_E_OPTION;
-  if (a->kind == LLC_LOGITS) {
-    if (!good_temp(a->temp_target)) return LLC_E_TEMP;
-    if (a->temp_draft == nullptr && !good_temp(a->temp_draft_all)) return LLC_E_TEMP;
-  }
-  const size_t esize = a->dtype == LLC_F32 ? 4 : 2;
-  if (((uintptr_t)a->draft % esize) != 0 || ((uintptr_t)a->target % esize) != 0) return LLC_E_ALIGN;
 
-  const bool logits = a->kind == LLC_LOGITS;
-  const float *temp_draft = logits ? a->temp_draft : nullptr;
-  const bool shared = a->draft_stride_k == 0 && temp_draft == nullptr;
+  ScanJob j;
+  j.B = a->B; j.K = a->K; j.V = a->V; j.dtype = a->dtype; j.kind = a->kind;
+  j.draft = a->draft; j.target = a->target;
+  j.map = plain_rows(a->draft_stride_b, a->target_stride_b);
+  j.draft_stride_k = a->draft_stride_k;
+  j.temp_target = a->temp_target; j.temp_draft_all = a->temp_draft_all; j.temp_draft = a->temp_draft;
+  j.seed = a->seed; j.row_offset = a->row_offset;
+  j.no_pool = false;
+  j.need_lse = a->keyX != nullptr || a->keyY != nullptr;
+  j.flags = a->flags; j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;
+  j.stats = a->stats; j.workspace = a->workspace; j.workspace_bytes = a->workspace_bytes;
+  j.stream = a->stream; j.ev_begin = a->ev_scan_begin; j.ev_end = a->ev_scan_end;
+  j.extra_bytes = 0;
 
   Plan pl;
-  pl.kt = a->k_tile != 0 ? a->k_tile : auto_ktile(a->K, shared);
-  pl.n_kgroups = (int)((a->K + pl.kt - 1) / pl.kt);
-  const long long G = (a->V + 3) / 4;
-  plan_chunks(G, a->v_chunks != 0 ? a->v_chunks : auto_chunks(a->B, pl.n_kgroups, G), &pl.n_chunks,
-              &pl.groups_per_chunk);
-  const long long blocks = a->B * pl.n_kgroups * pl.n_chunks;
-  if (blocks > 0x7FFFFFFFLL) return LLC_E_SHAPE;
-
-  const Layout lay = layout_for(a->B, a->K, pl.n_kgroups, pl.n_chunks);
-  if (a->workspace == nullptr || ((uintptr_t)a->workspace & 255) != 0 ||
-      a->workspace_bytes < lay.total)
-    return LLC_E_WORKSPACE;
-  char *ws = (char *)a->workspace;
-
-  // vector loads need every row to start on a 4-element boundary of a 16-byte (fp32) or
-  // 8-byte (bf16) aligned base
-  const size_t vbytes = 4 * esize;
-  const bool vec = ((uintptr_t)a->draft % vbytes) == 0 && ((uintptr_t)a->target % vbytes) == 0 &&
-                   (a->draft_stride_b % 4) == 0 && (a->draft_stride_k % 4) == 0 &&
-                   (a->target_stride_b % 4) == 0;
-
-  hipStream_t st = (hipStream_t)a->stream;
-  const bool want_keys = a->keyX != nullptr || a->keyY != nullptr;
-  const bool log_kind = a->kind != LLC_PROBS;
-
   Partials part;
-  part.keyX = (double *)(ws + lay.keyX);
-  part.idxX = (int32_t *)(ws + lay.idxX);
-  part.keyY = (double *)(ws + lay.keyY);
-  part.idxY = (int32_t *)(ws + lay.idxY);
-  part.kY = (int32_t *)(ws + lay.kY);
-  part.lse = (double *)(ws + lay.lse);
-
-  if (want_keys && log_kind) {
-    LseParams lp;
-    lp.draft = a->draft; lp.target = a->target;
-    lp.draft_stride_b = a->draft_stride_b; lp.draft_stride_k = a->draft_stride_k;
-    lp.target_stride_b = a->target_stride_b;
-    lp.B = a->B; lp.K = (int)a->K; lp.V = (int)a->V; lp.dtype = a->dtype;
-    lp.temp_target = logits ? a->temp_target : 1.0f;
-    lp.temp_draft_all = logits ? a->temp_draft_all : 1.0f;
-    lp.temp_draft = temp_draft;
-    lp.is_logits = logits ? 1 : 0;
-    lp.lse = part.lse;
-    if (launch_lse(st, lp) != hipSuccess) return LLC_E_LAUNCH;
-  }
-
-  ScanParams sp;
-  sp.draft = a->draft; sp.target = a->target;
-  sp.draft_stride_b = a->draft_stride_b; sp.draft_stride_k = a->draft_stride_k;
-  sp.target_stride_b = a->target_stride_b;
-  sp.B = a->B; sp.K = (int)a->K; sp.V = (int)a->V;
-  sp.n_chunks = pl.n_chunks; sp.groups_per_chunk = pl.groups_per_chunk; sp.n_kgroups = pl.n_kgroups;
-  sp.seed_lo = (unsigned)a->seed; sp.seed_hi = (unsigned)(a->seed >> 32);
-  sp.row_offset = a->row_offset;
-  sp.temp_target = logits ? a->temp_target : 1.0f;
-  sp.temp_draft_all = logits ? a->temp_draft_all : 1.0f;
-  sp.temp_draft = temp_draft;
-  sp.vector_loads = vec ? 1 : 0;
-  sp.force_exact = (a->flags & LLC_FLAG_EXACT_SCAN) ? 1 : 0;
-  sp.out = part;
-  sp.stats = a->stats;
-
-  const bool probs = a->kind == LLC_PROBS;
-  if (a->ev_scan_begin != nullptr && hipEventRecord((hipEvent_t)a->ev_scan_begin, st) != hipSuccess)
-    return LLC_E_LAUNCH;
-  hipError_t e;
-  if (a->dtype == LLC_F32)
-    e = shared ? launch_scan_f32_shared(pl.kt, probs, (unsigned)blocks, st, sp)
-               : launch_scan_f32_perk(pl.kt, probs, (unsigned)blocks, st, sp);
-  else
-    e = shared ? launch_scan_bf16_shared(pl.kt, probs, (unsigned)blocks, st, sp)
-               : launch_scan_bf16_perk(pl.kt, probs, (unsigned)blocks, st, sp);
-  if (e != hipSuccess) return LLC_E_LAUNCH;
-  if (a->ev_scan_end != nullptr && hipEventRecord((hipEvent_t)a->ev_scan_end, st) != hipSuccess)
-    return LLC_E_LAUNCH;
+  const int rc = run_scan(j, &pl, &part, nullptr);
+  if (rc != LLC_OK) return rc;
 
   FinalizeParams fp;
   fp.B = a->B; fp.K = (int)a->K; fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
-  fp.log_kind = log_kind ? 1 : 0;
+  fp.log_kind = a->kind != LLC_PROBS ? 1 : 0;
   fp.in = part;
   fp.X = a->X; fp.Y = a->Y; fp.match_k = a->match_k; fp.accept = a->accept;
-  fp.keyX = a->keyX; fp.keyY = a->keyY;
+  fp.keyX = a->keyX; fp.keyY = a->keyY; fp.log_keyX = nullptr;
+  fp.stats = a->stats;
+  if (launch_finalize((hipStream_t)a->stream, fp) != hipSuccess) return LLC_E_LAUNCH;
+  return LLC_OK;
+}
+
+size_t llc_verify_workspace_size(int64_t S, int64_t L, int64_t K, int64_t V) {
+  if (S < 0 || L < 0 || L > (1 << 20) || K > 64) return 0;
+  const long long B = S * (L + 1);
+  const size_t base = llc_couple_workspace_size(B, K, V);
+  if (base == 0) return 0;
+  return base + verify_extra_bytes(B, K);
+}
+
+int llc_verify(const llc_verify_args *a) {
+  if (a == nullptr) return LLC_E_NULL;
+  if (a->S < 0 || a->L < 0 || a->L > (1 << 20) || a->K > 64) return LLC_E_SHAPE;
+  const long long B = a->S * (a->L + 1);
+  if (!shape_ok(B, a->K, a->V)) return LLC_E_SHAPE;
+  if (a->S == 0) return LLC_OK;
+  if (a->target == nullptr || a->Y == nullptr || a->n_out == nullptr) return LLC_E_NULL;
+  if (a->L > 0 && a->tokens == nullptr) return LLC_E_NULL;
+  if (a->kind != LLC_LOGITS && a->kind != LLC_LOGW) return LLC_E_DTYPE;
+  if (a->stride_s < 0 || a->stride_j < 0 || a->stride_k < 0 || a->tok_stride_s < 0 ||
+      a->tok_stride_j < 0 || a->row_stride_s < 0 || a->row_stride_j < 0)
+    return LLC_E_SHAPE;
+
+  ScanJob j;
+  j.B = B; j.K = a->K; j.V = a->V; j.dtype = a->dtype; j.kind = a->kind;
+  // the draft side of the scan is the reduction Algorithm 2 needs per (position, draft):
+  // argmin_i S_i^(j,k) / q_i^(j,k); there is no pool over a common row
+  j.draft = a->target; j.target = a->target;
+  j.map.inner_count = a->L + 1;
+  j.map.draft_outer = a->stride_s; j.map.draft_inner = a->stride_j;
+  j.map.target_outer = a->stride_s; j.map.target_inner = a->stride_j;
+  j.map.row_outer = a->row_stride_s; j.map.row_inner = a->row_stride_j;
+  j.draft_stride_k = a->stride_k;
+  j.temp_target = a->temp_target; j.temp_draft_all = a->temp_target; j.temp_draft = nullptr;
+  j.seed = a->seed; j.row_offset = a->row_offset;
+  j.no_pool = true;
+  j.need_lse = true;  // keys of different rows are compared: they must be normalised
+  j.force_perk = true;
+  j.flags = a->flags; j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;
+  j.stats = a->stats; j.workspace = a->workspace; j.workspace_bytes = a->workspace_bytes;
+  j.stream = a->stream; j.ev_begin = a->ev_scan_begin; j.ev_end = a->ev_scan_end;
+  j.extra_bytes = verify_extra_bytes(B, a->K);
+
+  Plan pl;
+  Partials part;
+  char *extra = nullptr;
+  const int rc = run_scan(j, &pl, &part, &extra);
+  if (rc != LLC_OK) return rc;
+  double *cand_key = (double *)extra;
+  int32_t *cand = a->Yk != nullptr ? a->Yk : (int32_t *)(extra + align256((size_t)(B * a->K) * sizeof(double)));
+
+  hipStream_t st = (hipStream_t)a->stream;
+  FinalizeParams fp;
+  fp.B = B; fp.K = (int)a->K; fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
+  fp.log_kind = 1;
+  fp.in = part;
+  fp.X = cand; fp.Y = nullptr; fp.match_k = nullptr; fp.accept = nullptr;
+  fp.keyX = a->keyYk; fp.keyY = nullptr; fp.log_keyX = cand_key;
   fp.stats = a->stats;
   if (launch_finalize(st, fp) != hipSuccess) return LLC_E_LAUNCH;
+
+  VerifyParams vp;
+  vp.S = a->S; vp.L = (int)a->L; vp.K = (int)a->K;
+  vp.cand = cand; vp.cand_key = cand_key;
+  vp.tokens = a->tokens; vp.tok_stride_s = a->tok_stride_s; vp.tok_stride_j = a->tok_stride_j;
+  vp.Y = a->Y; vp.n_out = a->n_out; vp.active = a->active; vp.keyY = a->keyY;
+  if (launch_verify(st, vp) != hipSuccess) return LLC_E_LAUNCH;
   return LLC_OK;
 }
 

@@ -23,10 +23,29 @@ struct Partials {
   double *lse;    // [B][K+1]: ln sum exp(x/T) of draft k (k < K) and of the target (k == K)
 };
 
+// Rows may be a two-level index b = outer * inner_count + inner (sequences x positions in
+// the verifier); plain batches have inner_count = 1.
+struct RowMap {
+  long long inner_count;
+  long long draft_outer, draft_inner;    // element strides of the draft tensor
+  long long target_outer, target_inner;  // element strides of the target tensor
+  long long row_outer, row_inner;        // strides of the random stream's row number
+  __host__ __device__ long long draft_off(long long b) const {
+    return (b / inner_count) * draft_outer + (b % inner_count) * draft_inner;
+  }
+  __host__ __device__ long long target_off(long long b) const {
+    return (b / inner_count) * target_outer + (b % inner_count) * target_inner;
+  }
+  __host__ __device__ unsigned long long row_of(long long b) const {
+    return (unsigned long long)((b / inner_count) * row_outer + (b % inner_count) * row_inner);
+  }
+};
+
 struct ScanParams {
   const void *draft;
   const void *target;
-  long long draft_stride_b, draft_stride_k, target_stride_b;  // elements
+  RowMap map;
+  long long draft_stride_k;  // elements
   long long B;
   int K, V;
   int n_chunks;          // workgroups a row's V is split over
@@ -38,6 +57,7 @@ struct ScanParams {
   const float *temp_draft;  // device, K entries, or nullptr
   int vector_loads;         // rows are aligned for 4-element vector loads
   int force_exact;
+  int no_pool;              // draft-side reductions only: the target is never read
   Partials out;
   llc_stats *stats;
 };
@@ -47,22 +67,41 @@ struct FinalizeParams {
   int K, n_chunks, n_kgroups;
   int log_kind;        // keys are in the log domain and need the normaliser
   Partials in;
-  int32_t *X, *Y, *match_k;
+  int32_t *X, *Y, *match_k;  // Y, accept may be null (draft side only)
   uint8_t *accept;
   float *keyX, *keyY;  // optional
+  double *log_keyX;    // optional [B][K]: ln of the normalised winning key (log kinds)
   llc_stats *stats;
+};
+
+// Algorithm 2's sequential epilogue over the per-(position, draft) target-side argmins.
+struct VerifyParams {
+  long long S;
+  int L, K;
+  const int32_t *cand;       // [S][L+1][K] argmin_i S_i^(j,k) / q_i^(j,k)
+  const double *cand_key;    // [S][L+1][K] ln of its normalised key
+  const int32_t *tokens;     // draft tokens
+  long long tok_stride_s, tok_stride_j;
+  int32_t *Y;                // [S][L+1]
+  int32_t *n_out;            // [S]
+  uint8_t *active;           // [S][K] optional
+  float *keyY;               // [S][L+1] optional
 };
 
 struct LseParams {
   const void *draft;
   const void *target;
-  long long draft_stride_b, draft_stride_k, target_stride_b;
+  RowMap map;
+  long long draft_stride_k;
   long long B;
   int K, V;
   int dtype;
   float temp_target, temp_draft_all;
   const float *temp_draft;
   int is_logits;  // divide by the temperature
+  int per_k;      // every draft has its own row (else one row serves the K drafts)
+  int with_target;  // also the target row's normaliser
+  int vector_loads; // rows are aligned for 4-element vector loads
   double *lse;    // [B][K+1]
 };
 
@@ -75,5 +114,6 @@ hipError_t launch_scan_bf16_perk(int kt, bool probs, unsigned grid, hipStream_t 
 
 hipError_t launch_finalize(hipStream_t s, const FinalizeParams &p);
 hipError_t launch_lse(hipStream_t s, const LseParams &p);
+hipError_t launch_verify(hipStream_t s, const VerifyParams &p);
 
 }  // namespace llc

@@ -38,11 +38,17 @@ __global__ void __launch_bounds__(64) finalize_kernel(const FinalizeParams p) {
     }
     p.X[b * p.K + k] = bidx;
     if (bidx < 0) ++degenerate;
+    if (p.log_keyX != nullptr)
+      p.log_keyX[b * p.K + k] = bidx >= 0 ? bkey + p.in.lse[b * (p.K + 1) + k] : __builtin_huge_val();
     if (p.keyX != nullptr) {
       double out = __builtin_huge_val();
       if (bidx >= 0) out = p.log_kind ? exp(bkey + p.in.lse[b * (p.K + 1) + k]) : bkey;
       p.keyX[b * p.K + k] = (float)out;
     }
+  }
+  if (p.Y == nullptr) {  // draft side only
+    if (p.stats != nullptr && degenerate) atomicAdd(&p.stats->degenerate, degenerate);
+    return;
   }
   // target side: the pool over draft groups and chunks
   if (tid == 0) {
@@ -79,70 +85,105 @@ __global__ void __launch_bounds__(64) finalize_kernel(const FinalizeParams p) {
   if (p.stats != nullptr && degenerate) atomicAdd(&p.stats->degenerate, degenerate);
 }
 
-// ln sum_i exp(x_i / T) of one input row; fp32 terms relative to the row maximum,
-// fp64 accumulation.  NaN and +inf entries carry no mass.
+// ln sum_i exp(x_i / T) of one input row, in one pass over the row: every thread keeps a
+// running maximum and the sum of exp relative to it (fp32 terms, four at a time, into an fp64
+// running sum that is rescaled when the maximum moves).  NaN and +inf entries carry no mass.
 template <typename E>
-__device__ __forceinline__ float widen(const E *row, int i);
+__device__ __forceinline__ void load_group(const E *row, int i0, int V, bool vec, float (&v)[4]);
 template <>
-__device__ __forceinline__ float widen<float>(const float *row, int i) { return row[i]; }
+__device__ __forceinline__ void load_group<float>(const float *row, int i0, int V, bool vec, float (&v)[4]) {
+  if (vec && i0 + 3 < V) {
+    const float4 t = *reinterpret_cast<const float4 *>(row + i0);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = (i0 + j < V) ? row[i0 + j] : -__builtin_huge_valf();
+  }
+}
 template <>
-__device__ __forceinline__ float widen<uint16_t>(const uint16_t *row, int i) {
-  return __uint_as_float((uint32_t)row[i] << 16);
+__device__ __forceinline__ void load_group<uint16_t>(const uint16_t *row, int i0, int V, bool vec, float (&v)[4]) {
+  if (vec && i0 + 3 < V) {
+    const uint2 t = *reinterpret_cast<const uint2 *>(row + i0);
+    v[0] = __uint_as_float(t.x << 16);
+    v[1] = __uint_as_float(t.x & 0xFFFF0000u);
+    v[2] = __uint_as_float(t.y << 16);
+    v[3] = __uint_as_float(t.y & 0xFFFF0000u);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      v[j] = (i0 + j < V) ? __uint_as_float((uint32_t)row[i0 + j] << 16) : -__builtin_huge_valf();
+  }
 }
 
 template <typename E>
 __global__ void __launch_bounds__(256) lse_kernel(const LseParams p) {
   __shared__ float s_max[4];
   __shared__ double s_sum[4];
-  const int kd = p.draft_stride_k == 0 && p.temp_draft == nullptr ? 1 : p.K;  // distinct draft rows
-  const long long b = blockIdx.x / (unsigned)(kd + 1);
-  const int which = (int)(blockIdx.x % (unsigned)(kd + 1));  // kd = the target row
+  const int kd = p.per_k ? p.K : 1;  // distinct draft rows
+  const int per_b = kd + (p.with_target ? 1 : 0);
+  const long long b = blockIdx.x / (unsigned)per_b;
+  const int which = (int)(blockIdx.x % (unsigned)per_b);  // kd = the target row
   const int tid = threadIdx.x;
   const E *row;
   float T;
   if (which == kd) {
-    row = reinterpret_cast<const E *>(p.target) + b * p.target_stride_b;
+    row = reinterpret_cast<const E *>(p.target) + p.map.target_off(b);
     T = p.temp_target;
   } else {
-    row = reinterpret_cast<const E *>(p.draft) + b * p.draft_stride_b + (long long)which * p.draft_stride_k;
+    row = reinterpret_cast<const E *>(p.draft) + p.map.draft_off(b) + (long long)which * p.draft_stride_k;
     T = p.temp_draft != nullptr ? p.temp_draft[which] : p.temp_draft_all;
   }
   if (!p.is_logits) T = 1.0f;
   const float inf = __builtin_huge_valf();
+  const bool vec = p.vector_loads != 0;
+  // log2(e)/T as a two-float sum, so that the exponent carries no systematic rounding of 1/T
+  const double c64 = 1.4426950408889634 / (double)T;
+  const float c_hi = (float)c64;
+  const float c_lo = (float)(c64 - (double)c_hi);
 
-  float m = -inf;
-  for (int i = tid; i < p.V; i += 256) {
-    const float v = widen<E>(row, i);
-    if (v < inf) m = fmaxf(m, v);
-  }
-  for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d));
-  if ((tid & 63) == 0) s_max[tid >> 6] = m;
-  __syncthreads();
-  m = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
-
-  double sum = 0.0;
-  if (m > -inf) {
-    const float c = 1.4426950408889634f / T;
-    for (int i0 = tid; i0 < p.V; i0 += 256 * 8) {
-      float part = 0.0f;  // eight terms in fp32, then into the fp64 running sum
+  float m = -inf;     // running maximum of the entries that carry mass
+  double sum = 0.0;   // sum of exp((x - m)/T) over the entries seen
+  const int G = (p.V + 3) >> 2;
+  for (int g = tid; g < G; g += 256) {
+    float v[4];
+    load_group<E>(row, g * 4, p.V, vec, v);
+    float gm = -inf;
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int i = i0 + u * 256;
-        if (i < p.V) {
-          const float v = widen<E>(row, i);
-          if (v < inf) part += exp2f((v - m) * c);
-        }
+    for (int j = 0; j < 4; ++j) {
+      if (!(v[j] < inf)) v[j] = -inf;  // NaN, +inf: no mass
+      gm = fmaxf(gm, v[j]);
+    }
+    if (gm > m) {
+      if (m > -inf) {
+        const float d = m - gm;
+        sum *= (double)exp2f(fmaf(d, c_hi, d * c_lo));
+      }
+      m = gm;
+    }
+    if (m > -inf) {
+      float part = 0.0f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float d = v[j] - m;  // <= 0, -inf for entries without mass
+        part += exp2f(fmaf(d, c_hi, d * c_lo));
       }
       sum += (double)part;
     }
   }
+  float bm = m;
+  for (int d = 32; d >= 1; d >>= 1) bm = fmaxf(bm, __shfl_xor(bm, d));
+  if ((tid & 63) == 0) s_max[tid >> 6] = bm;
+  __syncthreads();
+  bm = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+  if (m > -inf && m < bm) sum *= exp2(((double)m - (double)bm) * c64);
+  if (!(m > -inf)) sum = 0.0;
   for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d);
   if ((tid & 63) == 0) s_sum[tid >> 6] = sum;
   __syncthreads();
   if (tid == 0) {
     sum = (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]);
-    const bool ok = (m > -inf) && (T > 0.0f) && (T < inf);
-    const double lse = ok ? (double)m / (double)T + log(sum) : -__builtin_huge_val();
+    const bool ok = (bm > -inf) && (T > 0.0f) && (T < inf);
+    const double lse = ok ? (double)bm / (double)T + log(sum) : -__builtin_huge_val();
     double *out = p.lse + b * (p.K + 1);
     if (which == kd) {
       out[p.K] = lse;
@@ -154,7 +195,53 @@ __global__ void __launch_bounds__(256) lse_kernel(const LseParams p) {
   }
 }
 
+// Algorithm 2, the loop over positions (Section 4.2): Y_j is the candidate of the viable draft
+// with the smallest key (ties: smaller index, then smaller k); drafts whose token differs from
+// Y_j stop being viable; the loop ends when none is left or after the bonus position.
+__global__ void __launch_bounds__(64) verify_kernel(const VerifyParams p) {
+  const long long s = (long long)blockIdx.x * 64 + threadIdx.x;
+  if (s >= p.S) return;
+  const int L = p.L, K = p.K;  // K <= 64: the viable set is a bit mask
+  const int32_t *cand = p.cand + s * (L + 1) * K;
+  const double *ckey = p.cand_key + s * (L + 1) * K;
+  int32_t *Y = p.Y + s * (L + 1);
+  unsigned long long viable = K >= 64 ? ~0ull : ((1ull << K) - 1ull);
+  int n = 0;
+  for (int j = 0; j <= L; ++j) {
+    double bkey = __builtin_huge_val();
+    int bidx = -1;
+    for (int k = 0; k < K; ++k) {
+      if (!((viable >> k) & 1ull)) continue;
+      const double key = ckey[j * K + k];
+      const int idx = cand[j * K + k];
+      if (idx < 0) continue;
+      if (bidx < 0 || key < bkey || (key == bkey && idx < bidx)) { bkey = key; bidx = idx; }
+    }
+    Y[j] = bidx;
+    if (p.keyY != nullptr) p.keyY[s * (L + 1) + j] = bidx >= 0 ? (float)exp(bkey) : __builtin_huge_valf();
+    n = j + 1;
+    if (j == L) break;
+    const int32_t *tok = p.tokens + s * p.tok_stride_s + (long long)j * p.tok_stride_j;
+    for (int k = 0; k < K; ++k)
+      if (((viable >> k) & 1ull) && tok[k] != bidx) viable &= ~(1ull << k);
+    if (viable == 0) break;
+  }
+  for (int j = n; j <= L; ++j) {
+    Y[j] = -1;
+    if (p.keyY != nullptr) p.keyY[s * (L + 1) + j] = __builtin_huge_valf();
+  }
+  p.n_out[s] = n;
+  if (p.active != nullptr)
+    for (int k = 0; k < K; ++k) p.active[s * K + k] = (uint8_t)((viable >> k) & 1ull);
+}
+
 }  // namespace
+
+hipError_t launch_verify(hipStream_t s, const VerifyParams &p) {
+  if (p.S == 0) return hipSuccess;
+  hipLaunchKernelGGL(verify_kernel, dim3((unsigned)((p.S + 63) / 64)), dim3(64), 0, s, p);
+  return hipGetLastError();
+}
 
 hipError_t launch_finalize(hipStream_t s, const FinalizeParams &p) {
   if (p.B == 0) return hipSuccess;
@@ -164,8 +251,8 @@ hipError_t launch_finalize(hipStream_t s, const FinalizeParams &p) {
 
 hipError_t launch_lse(hipStream_t s, const LseParams &p) {
   if (p.B == 0) return hipSuccess;
-  const int kd = p.draft_stride_k == 0 && p.temp_draft == nullptr ? 1 : p.K;
-  const unsigned grid = (unsigned)(p.B * (kd + 1));
+  const int kd = p.per_k ? p.K : 1;
+  const unsigned grid = (unsigned)(p.B * (kd + (p.with_target ? 1 : 0)));
   if (p.dtype == LLC_F32)
     hipLaunchKernelGGL(lse_kernel<float>, dim3(grid), dim3(256), 0, s, p);
   else

@@ -284,7 +284,7 @@ __device__ __forceinline__ void publish(Lds &s, int slot, float a) {
 // Level 2 for one survivor of level 1.
 template <int KT, bool SHARED, bool PROBS>
 __device__ __forceinline__ void level2(Lds &s, uint32_t x, float vd, float vq, int i, int kk,
-                                       bool draft_ok, float cd, float cq) {
+                                       bool draft_ok, bool pool_ok, float cd, float cq) {
   const float l2S = approx_log2_race_time(x);
   float ell;
   if (draft_ok && approx_log2_mass<PROBS>(vd, cd, ell)) {
@@ -296,7 +296,7 @@ __device__ __forceinline__ void level2(Lds &s, uint32_t x, float vd, float vq, i
       if (a < tau) publish<KT, SHARED, PROBS>(s, kk, a);
     }
   }
-  if (approx_log2_mass<PROBS>(vq, cq, ell)) {
+  if (pool_ok && approx_log2_mass<PROBS>(vq, cq, ell)) {
     const float a = l2S - ell;
     const float tau = unord32(__atomic_load_n(&s.tau[KT], __ATOMIC_RELAXED));
     if (a <= tau + kEps2) {
@@ -344,13 +344,14 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
   const int g_end = min(g_begin + p.groups_per_chunk, G);
   const int iters = (g_end - g_begin + kBlock - 1) / kBlock;
   const bool vec = p.vector_loads != 0;
+  const bool with_pool = p.no_pool == 0;  // false: draft-side reductions only, the target is not read
   const float fill = PROBS ? 0.0f : -__builtin_huge_valf();
 
-  const unsigned long long row = p.row_offset + (unsigned long long)b;
+  const unsigned long long row = p.row_offset + p.map.row_of(b);
   const uint32_t row_lo = (uint32_t)row, row_hi = (uint32_t)(row >> 32);
 
-  const elem *trow = reinterpret_cast<const elem *>(p.target) + b * p.target_stride_b;
-  const elem *drow0 = reinterpret_cast<const elem *>(p.draft) + b * p.draft_stride_b;
+  const elem *trow = reinterpret_cast<const elem *>(p.target) + p.map.target_off(b);
+  const elem *drow0 = reinterpret_cast<const elem *>(p.draft) + p.map.draft_off(b);
 
   // per-draft constants (wave-uniform)
   float cd[KT], cd23[KT];
@@ -389,8 +390,8 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
 #pragma unroll
       for (int kk = 0; kk <= KT; ++kk) a_min[kk] = __builtin_huge_valf();
       if (g < g_end) {
-        float vq[4];
-        load4<T>(trow, g * 4, V, vec, fill, vq);
+        float vq[4] = {fill, fill, fill, fill};
+        if (with_pool) load4<T>(trow, g * 4, V, vec, fill, vq);
 #pragma unroll
         for (int kk = 0; kk < KT; ++kk) {
           if (kbase + kk < p.K) {
@@ -405,7 +406,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
               float ell;
               if (kok[kk] && approx_log2_mass<PROBS>(vd[j], cd[kk], ell))
                 a_min[kk] = fminf(a_min[kk], l2S - ell);
-              if (approx_log2_mass<PROBS>(vq[j], cq, ell)) a_min[KT] = fminf(a_min[KT], l2S - ell);
+              if (with_pool && approx_log2_mass<PROBS>(vq[j], cq, ell)) a_min[KT] = fminf(a_min[KT], l2S - ell);
             }
           }
         }
@@ -450,20 +451,21 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
       // One tile (kBlock groups): loads are issued first, the Philox chains (which do not
       // depend on them) run while they are in flight, thresholds and compares come last.
       auto process_tile = [&](const int g, const bool interior) {
-        float vq[4], vd[KD][4];
+        // without a pool the target-side exponent is pinned at 0 (threshold 0: never a hit)
+        float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f}, vd[KD][4];
         if (interior) {
-          load4_vec<T>(trow, g * 4, vq);
+          if (with_pool) load4_vec<T>(trow, g * 4, vq);
 #pragma unroll
           for (int kk = 0; kk < KD; ++kk) load4_vec<T>(drow[kk], g * 4, vd[kk]);
         } else {
-          load4<T>(trow, g * 4, V, vec, fill, vq);
+          if (with_pool) load4<T>(trow, g * 4, V, vec, fill, vq);
 #pragma unroll
           for (int kk = 0; kk < KD; ++kk) load4<T>(drow[kk], g * 4, V, vec, fill, vd[kk]);
         }
         uint32_t x[KT][4];
         philox_blocks<KT>((uint32_t)g, (uint32_t)kbase, row_lo, row_hi, p.seed_lo, p.seed_hi, x);
 
-        const float OY = load_offset(&s.O[KT]);
+        const float OY = with_pool ? load_offset(&s.O[KT]) : -__builtin_huge_valf();
         float FY[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -513,7 +515,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
               const int i = g * 4 + j;
               if (i < V) {
                 ++my_survivors;
-                level2<KT, SHARED, PROBS>(s, xs, ds, qs, i, kk, kok[kk], cd[kk], cq);
+                level2<KT, SHARED, PROBS>(s, xs, ds, qs, i, kk, kok[kk], with_pool, cd[kk], cq);
               }
             }
           }
@@ -591,8 +593,8 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
     for (int it = 0; it < iters; ++it) {
       const int g = g_begin + it * kBlock + tid;
       if (g >= g_end) continue;
-      float vq[4];
-      load4<T>(trow, g * 4, V, false, fill, vq);
+      float vq[4] = {fill, fill, fill, fill};
+      if (with_pool) load4<T>(trow, g * 4, V, false, fill, vq);
 #pragma unroll 1
       for (int kk = 0; kk < KT; ++kk) {
         const int k = kbase + kk;
@@ -611,7 +613,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
           if (i >= V) continue;
           const double S = exact_race_time(x[j]);
           const double kx = ok ? exact_key<PROBS>(S, vd[j], (double)tk) : __builtin_huge_val();
-          const double ky = exact_key<PROBS>(S, vq[j], (double)Tq);
+          const double ky = with_pool ? exact_key<PROBS>(S, vq[j], (double)Tq) : __builtin_huge_val();
           my_exact += 2;
           if (kx < bx) { bx = kx; bxi = i; }
           if (ky < best[KT] || (ky == best[KT] && ky < __builtin_huge_val() &&

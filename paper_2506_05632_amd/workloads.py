@@ -62,14 +62,14 @@ def _gen(device, cfg):
     return g
 
 
-def _zipf_logits(B, V, noise_sigma, g, device):
-    """-1.1 ln(rank) + N(0, sigma^2), ranks a fresh random permutation of 1..V per row."""
+def _zipf_logits(B, V, noise_sigma, g, device, alpha=1.1):
+    """-alpha ln(rank) + N(0, sigma^2), ranks a fresh random permutation of 1..V per row."""
     out = torch.empty(B, V, dtype=torch.float32, device=device)
     step = max(1, min(B, (1 << 25) // V))
     for b0 in range(0, B, step):
         n = min(step, B - b0)
         ranks = torch.rand(n, V, generator=g, device=device).argsort(dim=1).argsort(dim=1) + 1
-        out[b0:b0 + n] = -1.1 * torch.log(ranks.to(torch.float32))
+        out[b0:b0 + n] = -alpha * torch.log(ranks.to(torch.float32))
         out[b0:b0 + n] += noise_sigma * torch.randn(n, V, generator=g, device=device)
     return out
 
@@ -128,3 +128,72 @@ def make(cfg: int, device="cpu", rows: Optional[int] = None) -> Workload:
                         1.0, 1.0, seed, shared_draft=False,
                         extra={"x": x, "y": y, "u": u})
     raise ValueError(f"unknown config {cfg}")
+
+
+@dataclass
+class VerifyWorkload:
+    name: str
+    S: int
+    L: int
+    K: int
+    V: int
+    dtype: torch.dtype
+    kind: str
+    target: torch.Tensor           # [S, L+1, K, V]
+    tokens: torch.Tensor           # [S, L, K] int32
+    temp_target: float = 1.0
+    seed: int = 0
+    row_offset: int = 0
+
+    @property
+    def elems(self) -> int:
+        return self.S * (self.L + 1) * self.K * self.V
+
+
+VERIFY_SHAPES = {
+    # name: S sequences, L draft tokens, K drafts, V vocabulary
+    "tiny": dict(S=24, L=3, K=4, V=1000, dtype=torch.float32, temp=1.0),
+    "small_bf16": dict(S=12, L=4, K=6, V=32000, dtype=torch.bfloat16, temp=1.0),
+    "largevocab": dict(S=128, L=7, K=8, V=128256, dtype=torch.float32, temp=0.7),
+}
+
+
+def make_verify(name: str, device="cpu", sequences: Optional[int] = None) -> VerifyWorkload:
+    """Inputs of Algorithm 2's verification loop, shaped like a batched target-model pass over
+    K drafts of L tokens (Section 4.2): target[s, j, k, :] are Zipf-like logits (rank exponent
+    1.8: a peaked next-token law, so that blocks of several tokens occur); drafts of one
+    sequence whose first j tokens coincide see the same row at position j (the target model is
+    conditioned on the same prefix), so all K rows coincide at j = 0.  Draft tokens are the
+    row's most likely token with probability 0.85 and a uniform token otherwise, so that some
+    drafts stay viable for several positions.  The draw uses no sampler arithmetic."""
+    shp = VERIFY_SHAPES[name]
+    S = sequences if sequences is not None else shp["S"]
+    L, K, V = shp["L"], shp["K"], shp["V"]
+    device = torch.device(device)
+    g = torch.Generator(device=device)
+    g.manual_seed(INPUT_SEED_BASE + 100 + sorted(VERIFY_SHAPES).index(name))
+    target = torch.empty(S, L + 1, K, V, dtype=shp["dtype"], device=device)
+    for j in range(L + 1):
+        for k in range(K):
+            target[:, j, k, :] = _zipf_logits(S, V, 0.5, g, device, alpha=1.8).to(shp["dtype"])
+    tokens = torch.empty(S, L, K, dtype=torch.int32, device=device)
+    same_prefix = torch.ones(S, K, K, dtype=torch.bool, device=device)  # [s, k, k']: prefixes equal so far
+    first = torch.arange(K, device=device)
+    for j in range(L + 1):
+        # the first draft with the same prefix supplies the row
+        cand = torch.where(same_prefix, first.view(1, 1, K), K)
+        src = cand.min(dim=2).values                                    # [S, K], src <= k
+        for k in range(1, K):
+            rows = torch.nonzero(src[:, k] != k).flatten()
+            if rows.numel():
+                target[rows, j, k, :] = target[rows, j, src[rows, k], :]
+        if j == L:
+            break
+        top = target[:, j].float().argmax(dim=2).to(torch.int32)        # [S, K]
+        rnd = torch.randint(0, V, (S, K), generator=g, device=device, dtype=torch.int32)
+        pick = torch.rand(S, K, generator=g, device=device) < 0.85
+        # drafts that share a prefix and a coin keep sharing; others diverge
+        tokens[:, j] = torch.where(pick, top, rnd)
+        same_prefix &= tokens[:, j].view(S, K, 1) == tokens[:, j].view(S, 1, K)
+    return VerifyWorkload(f"verify_{name}_s{S}_l{L}_k{K}_v{V}", S, L, K, V, shp["dtype"], "logits",
+                          target, tokens, shp["temp"], SAMPLER_SEED_BASE + 64, 0)

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(binding.EXPORTS)
     for name in names:
         assert getattr(lib, name) is not None
-    assert llc.llc_version() == 100
+    assert llc.llc_version() == 101
     assert llc.llc_status_string(0) == "ok"
     assert "workspace" in llc.llc_status_string(-6)
 
@@ -35,10 +35,11 @@ def test_header_is_plain_c_and_matches_the_binding_layout(tmp_path):
     src = tmp_path / "layout.c"
     src.write_text(
         '#include <stdio.h>\n#include <stddef.h>\n#include "llc.h"\n'
-        "int main(void){printf(\"%zu %zu %zu %zu %zu %zu %zu\\n\", sizeof(llc_couple_args),"
+        "int main(void){printf(\"%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\\n\", sizeof(llc_couple_args),"
         " sizeof(llc_couple_is_args), sizeof(llc_stats), offsetof(llc_couple_args, temp_draft),"
         " offsetof(llc_couple_args, workspace), offsetof(llc_couple_args, ev_scan_begin),"
-        " offsetof(llc_couple_is_args, workspace)); return 0;}\n")
+        " offsetof(llc_couple_is_args, workspace), sizeof(llc_verify_args),"
+        " offsetof(llc_verify_args, tokens), offsetof(llc_verify_args, workspace)); return 0;}\n")
     exe = tmp_path / "layout"
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
                     str(src), "-o", str(exe)], check=True)
@@ -46,7 +47,8 @@ def test_header_is_plain_c_and_matches_the_binding_layout(tmp_path):
     want = [ctypes.sizeof(binding.CoupleArgs), ctypes.sizeof(binding.CoupleIsArgs),
             ctypes.sizeof(binding.LlcStats), binding.CoupleArgs.temp_draft.offset,
             binding.CoupleArgs.workspace.offset, binding.CoupleArgs.ev_scan_begin.offset,
-            binding.CoupleIsArgs.workspace.offset]
+            binding.CoupleIsArgs.workspace.offset, ctypes.sizeof(binding.VerifyArgs),
+            binding.VerifyArgs.tokens.offset, binding.VerifyArgs.workspace.offset]
     assert got == want
 
 
@@ -109,3 +111,42 @@ def test_missing_library_fails_loudly(tmp_path, monkeypatch):
             "try:\n    m.load()\nexcept RuntimeError as e:\n    print('raised')\n")
     out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, cwd=ROOT)
     assert "raised" in out.stdout
+
+
+def _verify_args(**kw):
+    a = binding.VerifyArgs()
+    a.S, a.L, a.K, a.V = 3, 2, 2, 64
+    a.dtype, a.kind = binding.F32, binding.LOGITS
+    a.target = 0x1000
+    a.stride_s, a.stride_j, a.stride_k = 3 * 2 * 64, 2 * 64, 64
+    a.temp_target = 1.0
+    a.tokens, a.tok_stride_s, a.tok_stride_j = 0x3000, 4, 2
+    a.row_stride_s, a.row_stride_j = 3, 1
+    a.Y = a.n_out = 0x2000
+    a.workspace, a.workspace_bytes = 0x4000, 1 << 30
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(target=None), -1), (dict(Y=None), -1), (dict(n_out=None), -1), (dict(tokens=None), -1),
+    (dict(K=65), -2), (dict(K=0), -2), (dict(L=-1), -2), (dict(S=-1), -2), (dict(V=0), -2),
+    (dict(stride_j=-1), -2), (dict(row_stride_s=-1), -2),
+    (dict(temp_target=0.0), -3),
+    (dict(kind=binding.PROBS), -4), (dict(dtype=9), -4),
+    (dict(target=0x1002), -5),
+    (dict(workspace=None), -6), (dict(workspace_bytes=1024), -6),
+    (dict(k_tile=5), -8),
+])
+def test_verify_argument_errors_are_reported_before_any_launch(kw, code):
+    lib = llc.load()
+    assert lib.llc_verify(ctypes.byref(_verify_args(**kw))) == code
+
+
+def test_verify_null_struct_empty_batch_and_workspace_size():
+    lib = llc.load()
+    assert lib.llc_verify(None) == -1
+    assert lib.llc_verify(ctypes.byref(_verify_args(S=0, target=None, Y=None))) == 0
+    assert llc.llc_verify_workspace_size(3, 2, 2, 64) > llc.llc_couple_workspace_size(9, 2, 64)
+    assert llc.llc_verify_workspace_size(3, 2, 65, 64) == 0

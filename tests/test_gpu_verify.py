@@ -1,0 +1,204 @@
+"""GPU parity of llc_verify (Algorithm 2's verification loop) against the CPU oracle (needs an MI355X).
+
+The bar: Y, n_out, active bit-exact.  A sequence is excused from the first position at which the
+oracle's own relative gap between the best and the runner-up key is below 1e-6 (a near-tie; what
+follows depends on which of the two is taken).  Winning keys within 1e-6 relative.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2506_05632_amd as llc
+from paper_2506_05632_amd import workloads
+from parity_util import KEY_RTOL, NEAR_TIE, to_host
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+_KIND = {"logits": oracle.LOGITS, "logw": oracle.LOGW}
+
+
+def oracle_verify(target, tokens, seqs, *, kind="logits", temp_target=1.0, seed=0, row_offset=0,
+                  row_stride_s=None, row_stride_j=1):
+    """Oracle on sequences [s0, s1), keyed as the same global rows."""
+    s0, s1 = seqs
+    t, dt = to_host(target[s0:s1])
+    L1 = target.shape[1]
+    rs = L1 if row_stride_s is None else row_stride_s
+    tok = tokens[s0:s1].detach().cpu().numpy() if L1 > 1 else np.zeros((s1 - s0, 0, target.shape[2]), np.int32)
+    return oracle.verify(t, tok, dtype=dt, kind=_KIND[kind], temp_target=temp_target, seed=seed,
+                         row_offset=row_offset + s0 * rs, row_stride_s=rs, row_stride_j=row_stride_j)
+
+
+def compare_verify(gpu, ref, seqs=None):
+    g = {k: v.detach().cpu().numpy() for k, v in gpu.items()}
+    if seqs is not None:
+        g = {k: v[seqs[0]:seqs[1]] for k, v in g.items()}
+    S, L1 = ref["Y"].shape
+    near = 0
+    for s in range(S):
+        clean = True
+        for j in range(L1):
+            if ref["Y"][s, j] >= 0 and ref["gap"][s, j] < NEAR_TIE:
+                near += 1
+                clean = False
+                break
+            assert g["Y"][s, j] == ref["Y"][s, j], f"Y[{s},{j}] gpu {g['Y'][s, j]} ref {ref['Y'][s, j]} gap {ref['gap'][s, j]}"
+            if "keyY" in g:
+                if ref["Y"][s, j] >= 0:
+                    np.testing.assert_allclose(g["keyY"][s, j], ref["key"][s, j], rtol=KEY_RTOL)
+                else:
+                    assert np.isinf(g["keyY"][s, j])
+        if clean:
+            assert g["n_out"][s] == ref["n_out"][s]
+            assert np.array_equal(g["active"][s], ref["active"][s])
+    return near
+
+
+def run_verify(w, **kw):
+    return llc.llc_verify(w.target, w.tokens, kind=w.kind, temp_target=w.temp_target, seed=w.seed,
+                          row_offset=w.row_offset, **kw)
+
+
+def test_verify_tiny_full_with_partials():
+    w = workloads.make_verify("tiny", DEV)
+    gpu = run_verify(w, want_keys=True, want_partials=True)
+    torch.cuda.synchronize()
+    ref = oracle_verify(w.target, w.tokens, (0, w.S), temp_target=w.temp_target, seed=w.seed)
+    compare_verify({k: gpu[k] for k in ("Y", "n_out", "active", "keyY")}, ref)
+    assert ref["n_out"].max() == w.L + 1 and ref["n_out"].min() == 1      # both ends of the loop occur
+    # the per-(position, draft) reductions are Algorithm 1's draft-side argmins on the same rows
+    rows, dt = to_host(w.target.reshape(w.S * (w.L + 1), w.K, w.V))
+    part = oracle.couple(rows, rows[:, 0], w.K, dtype=dt, temp_target=w.temp_target,
+                         temp_draft_all=w.temp_target, seed=w.seed)
+    Yk = gpu["Yk"].cpu().numpy().reshape(-1, w.K)
+    ok = part["gapX"] >= NEAR_TIE
+    assert np.array_equal(Yk[ok], part["X"][ok])
+    np.testing.assert_allclose(gpu["keyYk"].cpu().numpy().reshape(-1, w.K)[ok], part["keyX"][ok], rtol=KEY_RTOL)
+
+
+def test_verify_with_drafts_coupled_by_algorithm_1():
+    # draft tokens drawn by the oracle's Algorithm 1 on the same rows: the realistic, coupled case
+    g = torch.Generator(device="cpu").manual_seed(31)
+    S, L, K, V = 40, 3, 3, 6000
+    seed, base = 91, 1 << 33
+    tq = 2.5 * torch.randn(S, L + 1, K, V, generator=g)
+    tq[:, 0, 1:] = tq[:, 0, :1]
+    tokens = np.zeros((S, L, K), np.int32)
+    for j in range(L):
+        draft = (tq[:, j] + 0.7 * torch.randn(S, K, V, generator=g)).numpy()
+        res = oracle.couple(draft, draft[:, 0], K, seed=seed, row_offset=base + j * S)
+        tokens[:, j] = res["X"]
+        if j + 1 <= L:
+            # drafts that chose the same token keep seeing the same target row
+            for s in range(S):
+                for k in range(1, K):
+                    for k2 in range(k):
+                        if (tokens[s, :j + 1, k] == tokens[s, :j + 1, k2]).all():
+                            tq[s, j + 1, k] = tq[s, j + 1, k2]
+                            break
+    target, tok = tq.to(DEV), torch.from_numpy(tokens).to(DEV)
+    gpu = llc.llc_verify(target, tok, seed=seed, row_offset=base, row_stride_s=1, row_stride_j=S,
+                         want_keys=True)
+    torch.cuda.synchronize()
+    ref = oracle.verify(tq.numpy(), tokens, seed=seed, row_offset=base, row_stride_s=1, row_stride_j=S)
+    compare_verify(gpu, ref)
+    assert ref["n_out"].mean() > 1.5      # coupled drafts are accepted often
+
+
+def test_verify_bf16_full():
+    w = workloads.make_verify("small_bf16", DEV)
+    stats = llc.new_stats(DEV)
+    gpu = run_verify(w, want_keys=True, stats=stats)
+    torch.cuda.synchronize()
+    ref = oracle_verify(w.target, w.tokens, (0, w.S), temp_target=w.temp_target, seed=w.seed)
+    near = compare_verify(gpu, ref)
+    s = stats.cpu().numpy()
+    print(f"verify bf16: near-ties {near}, survivors {s[0]} of {w.elems}, exact {s[1]}, slow blocks {s[2]}")
+    assert s[2] == 0
+
+
+def test_verify_large_vocab_sampled_sequences():
+    w = workloads.make_verify("largevocab", DEV)          # the shape bench.py --workload verify times
+    stats = llc.new_stats(DEV)
+    gpu = run_verify(w, want_keys=True, stats=stats)
+    torch.cuda.synchronize()
+    near = 0
+    for seqs in [(0, 2), (63, 65), (126, 128)]:
+        ref = oracle_verify(w.target, w.tokens, seqs, temp_target=w.temp_target, seed=w.seed)
+        near += compare_verify(gpu, ref, seqs)
+    s = stats.cpu().numpy()
+    print(f"verify large: near-ties {near}, survivors {s[0]} of {w.elems}, exact {s[1]}, slow blocks {s[2]}")
+    assert s[2] == 0
+    Y, n = gpu["Y"].cpu().numpy(), gpu["n_out"].cpu().numpy()
+    assert n.min() >= 1 and n.max() <= w.L + 1
+    for srow in range(w.S):
+        assert (Y[srow, :n[srow]] >= 0).all() and (Y[srow, :n[srow]] < w.V).all() and (Y[srow, n[srow]:] == -1).all()
+    # the first token is position 0's pool argmin, where all K rows coincide: Algorithm 1's Y on that row
+    # (rows of llc_couple are consecutive; position 0 of sequence s is row s*(L+1))
+    for srow in range(0, w.S, 17):
+        one = llc.llc_couple(w.target[srow:srow + 1, 0, 0], w.target[srow:srow + 1, 0, 0], w.K,
+                             temp_target=w.temp_target, temp_draft=w.temp_target, seed=w.seed,
+                             row_offset=srow * (w.L + 1))
+        assert one["Y"].item() == Y[srow, 0]
+
+
+def test_verify_results_do_not_depend_on_launch_shape():
+    w = workloads.make_verify("small_bf16", DEV, sequences=5)
+    base = run_verify(w, want_keys=True, want_partials=True)
+    for vc, kt in ((1, 1), (3, 2), (9, 4), (2, 8)):
+        other = run_verify(w, want_keys=True, want_partials=True, v_chunks=vc, k_tile=kt)
+        torch.cuda.synchronize()
+        for name in base:
+            assert torch.equal(base[name], other[name]), name
+    exact = run_verify(w, want_keys=True, want_partials=True, flags=llc.FLAG_EXACT_SCAN)
+    torch.cuda.synchronize()
+    for name in ("Y", "n_out", "active", "Yk"):
+        assert torch.equal(base[name], exact[name]), name
+
+
+@pytest.mark.parametrize("L,K,V", [(0, 1, 777), (0, 5, 1025), (1, 1, 4099), (5, 2, 333), (2, 64, 517)])
+def test_verify_edge_shapes(L, K, V):
+    g = torch.Generator(device=DEV).manual_seed(L * 1000 + K * 10 + V)
+    S = 7
+    target = 3 * torch.randn(S, L + 1, K, V, generator=g, device=DEV)
+    target[:, 0, 1:] = target[:, 0, :1]
+    tokens = target[:, :L].argmax(dim=3).to(torch.int32)
+    gpu = llc.llc_verify(target, tokens, temp_target=0.6, seed=17, row_offset=5, want_keys=True)
+    torch.cuda.synchronize()
+    ref = oracle_verify(target, tokens, (0, S), temp_target=0.6, seed=17, row_offset=5)
+    compare_verify(gpu, ref)
+
+
+def test_verify_strided_views_log_weights_and_rows_without_mass():
+    g = torch.Generator(device=DEV).manual_seed(41)
+    S, L, K, V = 6, 3, 4, 2051
+    store = 2 * torch.randn(S, K, L + 1, V + 3, generator=g, device=DEV)   # [S, K, L+1, V'] permuted, odd rows
+    target = store.permute(0, 2, 1, 3)[:, :, :, 1:1 + V]
+    target[:, 0, 1:] = target[:, 0, :1]
+    ninf = float("-inf")
+    target[1, 1, 2, :] = ninf                     # one (position, draft) row without mass
+    target[2, 0, :, :] = ninf                     # position 0 without mass at all: Y = -1, loop ends
+    target[3, 2, 0, 5] = float("nan")
+    big_tok = torch.randint(0, V, (S, L, K + 2), generator=g, device=DEV, dtype=torch.int32)
+    tokens = big_tok[:, :, :K]
+    tokens[:, :, 0] = target[:, :L, 0].argmax(dim=2).to(torch.int32)
+    gpu = llc.llc_verify(target, tokens, kind="logw", seed=19, want_keys=True)
+    torch.cuda.synchronize()
+    t, dt = to_host(target)
+    ref = oracle.verify(t, tokens.cpu().numpy(), dtype=dt, kind=oracle.LOGW, seed=19)
+    compare_verify(gpu, ref)
+    assert gpu["Y"][2, 0].item() == -1 and gpu["n_out"][2].item() == 1
+
+
+def test_verify_error_codes_on_device():
+    t = torch.randn(2, 3, 2, 64, device=DEV)
+    tok = torch.zeros(2, 2, 2, dtype=torch.int32, device=DEV)
+    with pytest.raises(llc.LlcError) as e:
+        llc.llc_verify(t, tok, kind="probs")
+    assert e.value.code == -4
+    with pytest.raises(llc.LlcError) as e:
+        llc.llc_verify(t, tok, workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
+    assert e.value.code == -6
+    out = llc.llc_verify(torch.empty(0, 3, 2, 64, device=DEV), torch.empty(0, 2, 2, dtype=torch.int32, device=DEV))
+    assert out["Y"].shape == (0, 3)
