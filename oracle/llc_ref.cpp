@@ -20,8 +20,8 @@
 //
 // Readings the paper leaves open (each is also listed in the design notes):
 //   * generator: Philox4x32 with 10 rounds (Salmon et al., SC'11); key = the
-//     two halves of `seed`; counter = (i >> 2, k, lo32(row), hi32(row)); element
-//     i uses output word (i & 3).  row = row_offset + b.
+//     two halves of `seed`; the 32-bit word of element (row, k, i) is made of two
+//     16-bit halves taken from two blocks (see shared_word).  row = row_offset + b.
 //   * U on the open interval: U = (x + 1/2) / 2^32 for the 32-bit word x.
 //   * argmin ties: smallest key, then smallest i, then (pool only) smallest k.
 //   * entries that are NaN or +inf (logit kinds) / NaN, +inf or negative
@@ -73,13 +73,22 @@ void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]
   for (int j = 0; j < 4; ++j) out[j] = c[j];
 }
 
-// 32-bit word for element (row, k, i).
+// 32-bit word for element (row, k, i): two 16-bit halves from two Philox blocks.
+// Four consecutive indices and two consecutive drafts share a block: counter
+// (i >> 2, k >> 1, lo32(row), hi32(row)) gives the high halves, the same counter with bit 31
+// of its second word set gives the low halves; element (k, i) reads output word (i & 3) of
+// each, its lower 16 bits for even k and its upper 16 bits for odd k.
 uint32_t shared_word(uint64_t seed, uint64_t row, uint32_t k, uint64_t i) {
-  const uint32_t ctr[4] = {(uint32_t)(i >> 2), k, (uint32_t)row, (uint32_t)(row >> 32)};
   const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
-  uint32_t out[4];
-  philox4x32_10(ctr, key, out);
-  return out[i & 3];
+  const uint32_t ctr_hi[4] = {(uint32_t)(i >> 2), k >> 1, (uint32_t)row, (uint32_t)(row >> 32)};
+  const uint32_t ctr_lo[4] = {(uint32_t)(i >> 2), (k >> 1) | 0x80000000u, (uint32_t)row, (uint32_t)(row >> 32)};
+  uint32_t out_hi[4], out_lo[4];
+  philox4x32_10(ctr_hi, key, out_hi);
+  philox4x32_10(ctr_lo, key, out_lo);
+  const unsigned shift = (k & 1u) ? 16u : 0u;
+  const uint32_t hi16 = (out_hi[i & 3] >> shift) & 0xFFFFu;
+  const uint32_t lo16 = (out_lo[i & 3] >> shift) & 0xFFFFu;
+  return (hi16 << 16) | lo16;
 }
 
 // S = -ln U with U = (x + 1/2) 2^-32 (exact in fp64).  Section 3: S_i^(k) = -ln U_i^(k).

@@ -164,7 +164,9 @@ __global__ void __launch_bounds__(256) lse_kernel(const LseParams p) {
       float part = 0.0f;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const float d = v[j] - m;  // <= 0, -inf for entries without mass
+        // <= 0; entries without mass are clamped to a finite distance whose term is exactly 0
+        // (an infinite one would meet c_lo's sign in the two-float product)
+        const float d = fmaxf(v[j] - m, -65536.0f);
         part += exp2f(fmaf(d, c_hi, d * c_lo));
       }
       sum += (double)part;

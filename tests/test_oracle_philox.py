@@ -39,14 +39,28 @@ def test_cpp_matches_python_on_random_inputs():
 
 
 def test_element_keying_layout():
-    # four consecutive indices share one block; k, row and seed enter where the design says
+    # four consecutive indices and two consecutive drafts share a block; the upper and lower
+    # half-words come from two blocks that differ in bit 31 of the second counter word
     seed, row = 0x0123456789ABCDEF, (5 << 32) | 77
-    for k in (0, 3):
+    key = [seed & 0xFFFFFFFF, seed >> 32]
+    for k in (0, 1, 2, 3, 7, 65534, 65535):
         for i in (0, 1, 2, 3, 4, 1023, 128255):
-            blk = philox_py.philox4x32([i >> 2, k, row & 0xFFFFFFFF, row >> 32],
-                                       [seed & 0xFFFFFFFF, seed >> 32])
-            assert oracle.shared_word(seed, row, k, i) == blk[i & 3]
-            assert philox_py.shared_word(seed, row, k, i) == blk[i & 3]
+            hi = philox_py.philox4x32([i >> 2, k >> 1, row & 0xFFFFFFFF, row >> 32], key)[i & 3]
+            lo = philox_py.philox4x32([i >> 2, (k >> 1) + 2 ** 31, row & 0xFFFFFFFF, row >> 32], key)[i & 3]
+            if k % 2:
+                hi, lo = hi >> 16, lo >> 16
+            want = ((hi & 0xFFFF) << 16) | (lo & 0xFFFF)
+            assert oracle.shared_word(seed, row, k, i) == want
+            assert philox_py.shared_word(seed, row, k, i) == want
+
+
+def test_words_of_distinct_elements_do_not_repeat():
+    # every (k, i) gets its own 32 bits: neighbours in k and in i are distinct words
+    seed, row = 99, 3
+    words = {(k, i): oracle.shared_word(seed, row, k, i) for k in range(6) for i in range(64)}
+    assert len(set(words.values())) == len(words)
+    # and they do not depend on the neighbour: the same word from the Python generator
+    assert all(philox_py.shared_word(seed, row, k, i) == w for (k, i), w in words.items())
 
 
 def test_race_time_mapping():
@@ -59,13 +73,17 @@ def test_race_time_mapping():
 
 
 def test_uniformity_of_stream():
-    # chi-square of the top byte over 2^18 words drawn the way the sampler draws them
-    n = 1 << 18
-    counts = np.zeros(256, dtype=np.int64)
-    for blk in range(n // 4):
-        for w in oracle.philox4x32_10([blk, 1, 9, 0], [42, 0]):
-            counts[int(w) >> 24] += 1
-    expected = n / 256
-    chi2 = float(((counts - expected) ** 2 / expected).sum())
+    # chi-square of the top byte and of the byte that straddles the two half-words, over 2^16
+    # words drawn the way the sampler draws them
+    n = 1 << 16
+    top = np.zeros(256, dtype=np.int64)
+    mid = np.zeros(256, dtype=np.int64)
+    for e in range(n):
+        w = oracle.shared_word(42, 9, e & 3, e >> 2)
+        top[w >> 24] += 1
+        mid[(w >> 12) & 0xFF] += 1
     from scipy import stats
-    assert stats.chi2.sf(chi2, 255) > 1e-4
+    for counts in (top, mid):
+        expected = n / 256
+        chi2 = float(((counts - expected) ** 2 / expected).sum())
+        assert stats.chi2.sf(chi2, 255) > 1e-4
