@@ -22,8 +22,8 @@ struct Plan {
 // drafts of a pass, so wider is better; with per-draft rows each draft brings its own loads and
 // thresholds and four keep the kernel within 128 VGPRs.
 int auto_ktile(long long K, bool shared) {
-  if (K >= 8 && shared) return 8;
-  return K >= 3 ? 4 : K == 2 ? 2 : 1;
+  if (K >= 5 && shared) return 8;
+  return K >= 3 ? 4 : 2;
 }
 
 // Split the G four-element groups of a row into chunks of a multiple of kBlock groups.
@@ -127,7 +127,7 @@ int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
   const bool shared = j.draft_stride_k == 0 && temp_draft == nullptr && !j.force_perk;
 
   Plan pl;
-  pl.kt = j.k_tile != 0 ? j.k_tile : auto_ktile(j.K, shared);
+  pl.kt = j.k_tile != 0 ? (j.k_tile == 1 ? 2 : j.k_tile) : auto_ktile(j.K, shared);
   pl.n_kgroups = (int)((j.K + pl.kt - 1) / pl.kt);
   const long long G = (j.V + 3) / 4;
   plan_chunks(G, j.v_chunks != 0 ? j.v_chunks : auto_chunks(j.B, pl.n_kgroups, G), &pl.n_chunks,

@@ -12,6 +12,12 @@
 //    fused multiply-add into the exponent/mantissa field of a float (a
 //    piecewise-linear 2^y that never under-estimates) and one conversion.
 //    The draft-side and target-side thresholds are merged by a median-of-three.
+//    The word's upper and lower 16 bits come from two different Philox blocks, and
+//    the upper half alone decides almost every element (x >= ~t needs
+//    hi16(x) >= hi16(~t)): only the "upper" block is generated in the main loop,
+//    its eight half-words (four indices x two drafts) are tested two at a time
+//    with packed 16-bit operations, and the "lower" block is generated only for
+//    the few lanes whose upper half passes.
 //  level 2 (survivors, fp32): an approximate key a = log2 S - log2 p; survivors
 //    within a band of the running best are recorded in an LDS list and lower tau.
 //  level 3 (end of the scan, fp64): records still within the band of the final
@@ -38,7 +44,11 @@ constexpr float kEps1 = 0x1p-7f;       // slack of the integer prefilter
 constexpr float kPseudoLog = 0.0861f;  // max of log2(1+f) - f: slack when log2 p is read off the bits
 constexpr float kTauLimit = 1024.0f;
 constexpr float kTwo23 = 8388608.0f;
-constexpr float kCap = 1333788672.0f;  // 159 * 2^23: bit pattern of 2^32
+// Cap of the scaled exponent in the main loop: the bit pattern of the float 0xFFFE8000, so
+// that hi16(t) <= 0xFFFE.  An element whose exponent reaches the cap is "hot": it goes to
+// level 2 whatever its random word is.
+constexpr float kCapHot = 1333788288.0f;
+constexpr uint32_t kLowBlock = 0x80000000u;  // bit 31 of counter word 1 marks the lower-half block
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLog2Ln2 = -0.5287663729448977f;  // log2(ln 2)
 
@@ -66,35 +76,54 @@ __device__ __forceinline__ void philox_block(uint32_t c0, uint32_t c1, uint32_t 
   out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// KT blocks that differ only in counter word 1 (the draft index), advanced round by round
-// so that the KT dependency chains interleave.  The rounds before the draft index has
-// reached both multiplicands are identical for all KT blocks and are computed once by
+// KB blocks that differ only in counter word 1 (the draft pair), advanced round by round
+// so that the KB dependency chains interleave.  The rounds before the pair index has
+// reached both multiplicands are identical for all KB blocks and are computed once by
 // the compiler's common-subexpression elimination.
-template <int KT>
-__device__ __forceinline__ void philox_blocks(uint32_t g, uint32_t kbase, uint32_t row_lo,
+template <int KB>
+__device__ __forceinline__ void philox_blocks(uint32_t g, uint32_t pair_base, uint32_t row_lo,
                                               uint32_t row_hi, uint32_t k0, uint32_t k1,
-                                              uint32_t (&out)[KT][4]) {
-  uint32_t c0[KT], c1[KT], c2[KT], c3[KT];
+                                              uint32_t (&out)[KB][4]) {
+  uint32_t c0[KB], c1[KB], c2[KB], c3[KB];
 #pragma unroll
-  for (int kk = 0; kk < KT; ++kk) { c0[kk] = g; c1[kk] = kbase + kk; c2[kk] = row_lo; c3[kk] = row_hi; }
+  for (int m = 0; m < KB; ++m) { c0[m] = g; c1[m] = pair_base + m; c2[m] = row_lo; c3[m] = row_hi; }
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
 #pragma unroll
-    for (int kk = 0; kk < KT; ++kk) {
-      const uint64_t pa = (uint64_t)c0[kk] * 0xD2511F53ull;
-      const uint64_t pb = (uint64_t)c2[kk] * 0xCD9E8D57ull;
-      const uint32_t n0 = xor3((uint32_t)(pb >> 32), c1[kk], k0);
-      const uint32_t n2 = xor3((uint32_t)(pa >> 32), c3[kk], k1);
-      c1[kk] = (uint32_t)pb;
-      c3[kk] = (uint32_t)pa;
-      c0[kk] = n0;
-      c2[kk] = n2;
+    for (int m = 0; m < KB; ++m) {
+      const uint64_t pa = (uint64_t)c0[m] * 0xD2511F53ull;
+      const uint64_t pb = (uint64_t)c2[m] * 0xCD9E8D57ull;
+      const uint32_t n0 = xor3((uint32_t)(pb >> 32), c1[m], k0);
+      const uint32_t n2 = xor3((uint32_t)(pa >> 32), c3[m], k1);
+      c1[m] = (uint32_t)pb;
+      c3[m] = (uint32_t)pa;
+      c0[m] = n0;
+      c2[m] = n2;
     }
     k0 += 0x9E3779B9u;
     k1 += 0xBB67AE85u;
   }
 #pragma unroll
-  for (int kk = 0; kk < KT; ++kk) { out[kk][0] = c0[kk]; out[kk][1] = c1[kk]; out[kk][2] = c2[kk]; out[kk][3] = c3[kk]; }
+  for (int m = 0; m < KB; ++m) { out[m][0] = c0[m]; out[m][1] = c1[m]; out[m][2] = c2[m]; out[m][3] = c3[m]; }
+}
+
+// The 32-bit word of one element from the words its index selects in the upper-half and the
+// lower-half block of its draft pair: even drafts read the lower 16 bits, odd drafts the upper.
+__device__ __forceinline__ uint32_t element_word(uint32_t upper_word, uint32_t lower_word, int odd) {
+  const uint32_t hi = odd ? (upper_word >> 16) : (upper_word & 0xFFFFu);
+  const uint32_t lo = odd ? (lower_word >> 16) : (lower_word & 0xFFFFu);
+  return (hi << 16) | lo;
+}
+
+// Packed unsigned 16-bit maximum and saturating difference of two half-word pairs.
+typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2v, a),
+                                                                __builtin_bit_cast(ushort2v, b)));
+}
+__device__ __forceinline__ uint32_t pk_sub_sat_u16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_sub_sat(__builtin_bit_cast(ushort2v, a),
+                                                                    __builtin_bit_cast(ushort2v, b)));
 }
 
 // ---- small helpers ------------------------------------------------------------
@@ -119,13 +148,6 @@ __device__ __forceinline__ uint32_t cvt_u32_saturating(float f) {
   uint32_t r;  // hardware conversion: clamps to [0, 2^32 - 1], NaN -> 0
   asm("v_cvt_u32_f32 %0, %1" : "=v"(r) : "v"(f));
   return r;
-}
-
-// Integer threshold from a scaled exponent F in [0, kCap]: the float whose bit
-// pattern is int(F) is >= 2^(F/2^23 - 127); its integer part is t, and the test
-// xt <= t is carried out on x as x >= ~t.
-__device__ __forceinline__ uint32_t not_threshold(float F) {
-  return ~cvt_u32_saturating(__int_as_float((int)F));
 }
 
 template <typename T>
@@ -261,9 +283,19 @@ __device__ __forceinline__ void store_offset(int *slot, float O) {
 __device__ __forceinline__ float load_offset(const int *slot) {
   return __int_as_float(__atomic_load_n(slot, __ATOMIC_RELAXED));
 }
+// Scaled exponent of one element's threshold, merged with the target side's (FY) and capped.
 template <bool PROBS>
-__device__ __forceinline__ uint32_t element_not_threshold(float v, float c23, float O, float FY) {
-  return not_threshold(__builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(v), c23, O), FY, kCap));
+__device__ __forceinline__ float merged_exponent(float v, float c23, float O, float FY) {
+  return __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(v), c23, O), FY, kCapHot);
+}
+// The threshold t on ~x that a scaled exponent stands for (t <= 0xFFFE8000).
+__device__ __forceinline__ uint32_t threshold_of(float F) {
+  return cvt_u32_saturating(__int_as_float((int)F));
+}
+// Half-word test value for a pair of thresholds (even draft in the lower half): the upper 16
+// bits h of a word can only pass x >= ~t if h >= 0xFFFF - hi16(t), i.e. if h > 0xFFFE - hi16(t).
+__device__ __forceinline__ uint32_t coarse_pair(uint32_t t_even, uint32_t t_odd) {
+  return 0xFFFEFFFEu - ((t_odd & 0xFFFF0000u) | (t_even >> 16));
 }
 
 // Lower tau[slot] to `a` and refresh the level-1 offset that depends on it.
@@ -317,11 +349,12 @@ __device__ __forceinline__ void offer_where(Lds &s, int slot, double key, int i,
     atomicMin(&s.where[slot], ((unsigned long long)(uint32_t)i << 32) | (uint32_t)k);
 }
 
-// Four workgroups per CU (at most 128 VGPRs) wherever that costs no spills: with B a
-// multiple of 1024 rows every CU then holds a whole number of rows at a time.
-template <typename T, int KT, bool SHARED, bool PROBS>
-__global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kernel(const ScanParams p) {
+// One workgroup scans one (row, draft group, chunk).  KB = draft pairs per pass (KT = 2 KB
+// drafts): each pair of drafts shares its Philox blocks.
+template <typename T, int KB, bool SHARED, bool PROBS>
+__global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kernel(const ScanParams p) {
   using elem = typename T::elem;
+  constexpr int KT = 2 * KB;
   __shared__ Lds s;
 
   const int tid = threadIdx.x;
@@ -338,6 +371,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
   const int kg = (int)((bid / (unsigned)p.n_chunks) % (unsigned)p.n_kgroups);
   const long long b = (long long)(bid / ((unsigned)p.n_chunks * (unsigned)p.n_kgroups));
   const int kbase = kg * KT;
+  const uint32_t pair_base = (uint32_t)(kg * KB);
   const int V = p.V;
   const int G = (V + 3) >> 2;
   const int g_begin = chunk * p.groups_per_chunk;
@@ -393,20 +427,27 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
         float vq[4] = {fill, fill, fill, fill};
         if (with_pool) load4<T>(trow, g * 4, V, vec, fill, vq);
 #pragma unroll
-        for (int kk = 0; kk < KT; ++kk) {
-          if (kbase + kk < p.K) {
-            float vd[4];
-            load4<T>(drow0 + (SHARED ? 0 : (long long)(kbase + kk) * p.draft_stride_k), g * 4, V, vec,
-                     fill, vd);
-            uint32_t x[4];
-            philox_block((uint32_t)g, (uint32_t)(kbase + kk), row_lo, row_hi, p.seed_lo, p.seed_hi, x);
+        for (int m = 0; m < KB; ++m) {
+          if (kbase + 2 * m < p.K) {
+            uint32_t up[4], lo[4];
+            philox_block((uint32_t)g, pair_base + m, row_lo, row_hi, p.seed_lo, p.seed_hi, up);
+            philox_block((uint32_t)g, (pair_base + m) | kLowBlock, row_lo, row_hi, p.seed_lo, p.seed_hi, lo);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const float l2S = approx_log2_race_time(x[j]);
-              float ell;
-              if (kok[kk] && approx_log2_mass<PROBS>(vd[j], cd[kk], ell))
-                a_min[kk] = fminf(a_min[kk], l2S - ell);
-              if (with_pool && approx_log2_mass<PROBS>(vq[j], cq, ell)) a_min[KT] = fminf(a_min[KT], l2S - ell);
+            for (int h = 0; h < 2; ++h) {
+              const int kk = 2 * m + h;
+              if (kbase + kk < p.K) {
+                float vd[4];
+                load4<T>(drow0 + (SHARED ? 0 : (long long)(kbase + kk) * p.draft_stride_k), g * 4, V, vec,
+                         fill, vd);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                  const float l2S = approx_log2_race_time(element_word(up[j], lo[j], h));
+                  float ell;
+                  if (kok[kk] && approx_log2_mass<PROBS>(vd[j], cd[kk], ell))
+                    a_min[kk] = fminf(a_min[kk], l2S - ell);
+                  if (with_pool && approx_log2_mass<PROBS>(vq[j], cq, ell)) a_min[KT] = fminf(a_min[KT], l2S - ell);
+                }
+              }
             }
           }
         }
@@ -439,9 +480,9 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
       __syncthreads();
     }
 
-    // ---- main loop: level 1 on every element, level 2 on survivors.  No branch depends on
-    // the draft index: a padded draft (kbase + kk >= K) reads the last real row and runs its
-    // Philox chain like the others, and only its hits are masked off.
+    // ---- main loop: level 1 on the upper half-words of every element, the rest on survivors.
+    // No branch depends on the draft index: a padded draft (kbase + kk >= K) reads the last
+    // real row and its half-words are tested like the others; only its hits are masked off.
     if (!s.unsafe) {
       constexpr int KD = SHARED ? 1 : KT;
       const elem *drow[KD];
@@ -462,60 +503,91 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
 #pragma unroll
           for (int kk = 0; kk < KD; ++kk) load4<T>(drow[kk], g * 4, V, vec, fill, vd[kk]);
         }
-        uint32_t x[KT][4];
-        philox_blocks<KT>((uint32_t)g, (uint32_t)kbase, row_lo, row_hi, p.seed_lo, p.seed_hi, x);
+        uint32_t up[KB][4];  // upper half-words: word j of block m = (index 4g+j, drafts 2m | 2m+1)
+        philox_blocks<KB>((uint32_t)g, pair_base, row_lo, row_hi, p.seed_lo, p.seed_hi, up);
 
         const float OY = with_pool ? load_offset(&s.O[KT]) : -__builtin_huge_valf();
         float FY[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-          FY[j] = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vq[j]), cq23, OY), 0.0f, kCap);
-
-        uint32_t nt[KD][4];  // shared layout: one threshold per index serves every draft
-#pragma unroll
-        for (int kk = 0; kk < KD; ++kk) {
-          const float OX = (SHARED || kok[kk]) ? load_offset(&s.O[kk]) : -__builtin_huge_valf();
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            nt[kk][j] = element_not_threshold<PROBS>(vd[kk][j], cd23[kk], OX, FY[j]);
-        }
+          FY[j] = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vq[j]), cq23, OY), 0.0f, kCapHot);
 
         bool any = false;
-        if (SHARED && KT > 1) {
-          // one threshold per index serves every draft: any_k (x_k >= nt) == (max_k x_k >= nt),
-          // and the maxima stay in the vector unit (a compare into a scalar mask costs more)
+        uint32_t cp[SHARED ? 1 : KB][4];  // packed half-word test values
+        if (SHARED) {
+          // one threshold per index serves every draft: any_k (h_k > c) == (max_k h_k > c)
+          const float OX = load_offset(&s.O[0]);
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            uint32_t mx = x[0][j];
+            const float F = merged_exponent<PROBS>(vd[0][j], cd23[0], OX, FY[j]);
+            any |= F >= kCapHot;
+            const uint32_t t = threshold_of(F);
+            cp[0][j] = coarse_pair(t, t);
+            uint32_t mx = up[0][j];
 #pragma unroll
-            for (int kk = 1; kk < KT; ++kk) mx = max(mx, x[kk][j]);
-            any |= mx >= nt[0][j];
+            for (int m = 1; m < KB; ++m) mx = pk_max_u16(mx, up[m][j]);
+            any |= pk_sub_sat_u16(mx, cp[0][j]) != 0u;
           }
         } else {
 #pragma unroll
-          for (int kk = 0; kk < KT; ++kk) {
-            const int kd = SHARED ? 0 : kk;
-            any |= (x[kk][0] >= nt[kd][0]) | (x[kk][1] >= nt[kd][1]) | (x[kk][2] >= nt[kd][2]) |
-                   (x[kk][3] >= nt[kd][3]);
+          for (int m = 0; m < KB; ++m) {
+            const float OX0 = kok[2 * m] ? load_offset(&s.O[2 * m]) : -__builtin_huge_valf();
+            const float OX1 = kok[2 * m + 1] ? load_offset(&s.O[2 * m + 1]) : -__builtin_huge_valf();
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const float F0 = merged_exponent<PROBS>(vd[SHARED ? 0 : 2 * m][j], cd23[2 * m], OX0, FY[j]);
+              const float F1 = merged_exponent<PROBS>(vd[SHARED ? 0 : 2 * m + 1][j], cd23[2 * m + 1], OX1, FY[j]);
+              any |= fmaxf(F0, F1) >= kCapHot;
+              cp[SHARED ? 0 : m][j] = coarse_pair(threshold_of(F0), threshold_of(F1));
+              any |= pk_sub_sat_u16(up[m][j], cp[SHARED ? 0 : m][j]) != 0u;
+            }
           }
         }
         if (any) {
+          // Rare: some half-word of this lane passed (or an element is hot).  Find the pairs
+          // concerned, draw their lower half-words, and run the full-word test.  Offsets are
+          // read again here: they only ever tighten, and a tighter threshold is still valid.
 #pragma unroll
-          for (int kk = 0; kk < KT; ++kk) {
-            const int kd = SHARED ? 0 : kk;
-            unsigned m = (x[kk][0] >= nt[kd][0] ? 1u : 0u) | (x[kk][1] >= nt[kd][1] ? 2u : 0u) |
-                         (x[kk][2] >= nt[kd][2] ? 4u : 0u) | (x[kk][3] >= nt[kd][3] ? 8u : 0u);
-            if (kbase + kk >= p.K) m = 0;
-            while (m) {
-              const int j = __ffs(m) - 1;
-              m &= m - 1;
-              const uint32_t xs = j == 0 ? x[kk][0] : j == 1 ? x[kk][1] : j == 2 ? x[kk][2] : x[kk][3];
-              const float ds = j == 0 ? vd[kd][0] : j == 1 ? vd[kd][1] : j == 2 ? vd[kd][2] : vd[kd][3];
-              const float qs = j == 0 ? vq[0] : j == 1 ? vq[1] : j == 2 ? vq[2] : vq[3];
-              const int i = g * 4 + j;
-              if (i < V) {
-                ++my_survivors;
-                level2<KT, SHARED, PROBS>(s, xs, ds, qs, i, kk, kok[kk], with_pool, cd[kk], cq);
+          for (int m = 0; m < KB; ++m) {
+            const int ke = 2 * m, ko = 2 * m + 1;        // slots of the pair's even and odd draft
+            const int de = SHARED ? 0 : ke, dk = SHARED ? 0 : ko;
+            const float OXe = (SHARED || kok[ke]) ? load_offset(&s.O[SHARED ? 0 : ke]) : -__builtin_huge_valf();
+            const float OXo = (SHARED || kok[ko]) ? load_offset(&s.O[SHARED ? 0 : ko]) : -__builtin_huge_valf();
+            unsigned hm = 0;  // bit 2j + h: element (index 4g + j, draft 2m + h) is a candidate
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const uint32_t d = pk_sub_sat_u16(up[m][j], cp[SHARED ? 0 : m][j]);
+              const float Fe = merged_exponent<PROBS>(vd[de][j], cd23[ke], OXe, FY[j]);
+              const float Fo = merged_exponent<PROBS>(vd[dk][j], cd23[ko], OXo, FY[j]);
+              if ((d & 0xFFFFu) != 0u || Fe >= kCapHot) hm |= 1u << (2 * j);
+              if ((d >> 16) != 0u || Fo >= kCapHot) hm |= 2u << (2 * j);
+            }
+            if (kbase + ko >= p.K) hm &= 0x55u;  // the odd draft of this pair is padding
+            if (kbase + ke >= p.K) hm = 0;
+            if (hm) {
+              uint32_t lo[4];
+              philox_block((uint32_t)g, (pair_base + m) | kLowBlock, row_lo, row_hi, p.seed_lo, p.seed_hi, lo);
+              while (hm) {
+                const int bit = __ffs(hm) - 1;
+                hm &= hm - 1;
+                const int j = bit >> 1, h = bit & 1;
+                const uint32_t uw = j == 0 ? up[m][0] : j == 1 ? up[m][1] : j == 2 ? up[m][2] : up[m][3];
+                const uint32_t lw = j == 0 ? lo[0] : j == 1 ? lo[1] : j == 2 ? lo[2] : lo[3];
+                const float dse = j == 0 ? vd[de][0] : j == 1 ? vd[de][1] : j == 2 ? vd[de][2] : vd[de][3];
+                const float dso = j == 0 ? vd[dk][0] : j == 1 ? vd[dk][1] : j == 2 ? vd[dk][2] : vd[dk][3];
+                const float ds = h ? dso : dse;
+                const float qs = j == 0 ? vq[0] : j == 1 ? vq[1] : j == 2 ? vq[2] : vq[3];
+                const float fy = j == 0 ? FY[0] : j == 1 ? FY[1] : j == 2 ? FY[2] : FY[3];
+                const int i = g * 4 + j;
+                if (i < V) {
+                  const float F = merged_exponent<PROBS>(ds, h ? cd23[ko] : cd23[ke], h ? OXo : OXe, fy);
+                  const uint32_t x = element_word(uw, lw, h);
+                  if (F >= kCapHot || x >= ~threshold_of(F)) {
+                    ++my_survivors;
+                    level2<KT, SHARED, PROBS>(s, x, ds, qs, i, 2 * m + h, h ? kok[ko] : kok[ke], with_pool,
+                                              h ? cd[ko] : cd[ke], cq);
+                  }
+                }
               }
             }
           }
@@ -560,10 +632,13 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
         if (s.rec_a[r] <= tau + kEps2) {
           const int i = s.rec_i[r];
           const int k = kbase + kk;
-          uint32_t x[4];
-          philox_block((uint32_t)(i >> 2), (uint32_t)k, row_lo, row_hi, p.seed_lo, p.seed_hi, x);
-          const uint32_t xs = (i & 3) == 0 ? x[0] : (i & 3) == 1 ? x[1] : (i & 3) == 2 ? x[2] : x[3];
-          const double S = exact_race_time(xs);
+          uint32_t up[4], lo[4];
+          philox_block((uint32_t)(i >> 2), (uint32_t)(k >> 1), row_lo, row_hi, p.seed_lo, p.seed_hi, up);
+          philox_block((uint32_t)(i >> 2), (uint32_t)(k >> 1) | kLowBlock, row_lo, row_hi, p.seed_lo, p.seed_hi, lo);
+          const int j = i & 3;
+          const uint32_t uw = j == 0 ? up[0] : j == 1 ? up[1] : j == 2 ? up[2] : up[3];
+          const uint32_t lw = j == 0 ? lo[0] : j == 1 ? lo[1] : j == 2 ? lo[2] : lo[3];
+          const double S = exact_race_time(element_word(uw, lw, k & 1));
           float temp = Tq;
           float v;
           if (pool) {
@@ -601,8 +676,9 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
         if (k >= p.K) break;
         float vd[4];
         load4<T>(drow0 + (SHARED ? 0 : (long long)k * p.draft_stride_k), g * 4, V, false, fill, vd);
-        uint32_t x[4];
-        philox_block((uint32_t)g, (uint32_t)k, row_lo, row_hi, p.seed_lo, p.seed_hi, x);
+        uint32_t up[4], lo[4];
+        philox_block((uint32_t)g, (uint32_t)(k >> 1), row_lo, row_hi, p.seed_lo, p.seed_hi, up);
+        philox_block((uint32_t)g, (uint32_t)(k >> 1) | kLowBlock, row_lo, row_hi, p.seed_lo, p.seed_hi, lo);
         const float tk = p.temp_draft != nullptr ? p.temp_draft[k] : p.temp_draft_all;
         const bool ok = (tk > 0.0f) && (tk < __builtin_huge_valf());
         double bx = __builtin_huge_val();
@@ -611,7 +687,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
         for (int j = 0; j < 4; ++j) {
           const int i = g * 4 + j;
           if (i >= V) continue;
-          const double S = exact_race_time(x[j]);
+          const double S = exact_race_time(element_word(up[j], lo[j], k & 1));
           const double kx = ok ? exact_key<PROBS>(S, vd[j], (double)tk) : __builtin_huge_val();
           const double ky = with_pool ? exact_key<PROBS>(S, vq[j], (double)Tq) : __builtin_huge_val();
           my_exact += 2;
@@ -668,24 +744,23 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KT <= 4) ? 4 : 2) scan_kern
   }
 }
 
+// kt: drafts per workgroup pass (2, 4 or 8; 1 runs as 2: a draft pair shares its blocks).
 template <typename T, bool SHARED>
 hipError_t launch_scan(int kt, bool probs, unsigned grid, hipStream_t st, const ScanParams &p) {
-#define LLC_LAUNCH(KT_, PR_)                                                                \
-  hipLaunchKernelGGL((scan_kernel<T, KT_, SHARED, PR_>), dim3(grid), dim3(kBlock), 0, st, p); \
+#define LLC_LAUNCH(KB_, PR_)                                                                \
+  hipLaunchKernelGGL((scan_kernel<T, KB_, SHARED, PR_>), dim3(grid), dim3(kBlock), 0, st, p); \
   return hipGetLastError();
   if (!probs) {
     switch (kt) {
-      case 1: LLC_LAUNCH(1, false)
-      case 2: LLC_LAUNCH(2, false)
-      case 4: LLC_LAUNCH(4, false)
-      case 8: LLC_LAUNCH(8, false)
+      case 2: LLC_LAUNCH(1, false)
+      case 4: LLC_LAUNCH(2, false)
+      case 8: LLC_LAUNCH(4, false)
     }
   } else {
     switch (kt) {
-      case 1: LLC_LAUNCH(1, true)
-      case 2: LLC_LAUNCH(2, true)
-      case 4: LLC_LAUNCH(4, true)
-      case 8: LLC_LAUNCH(8, true)
+      case 2: LLC_LAUNCH(1, true)
+      case 4: LLC_LAUNCH(2, true)
+      case 8: LLC_LAUNCH(4, true)
     }
   }
 #undef LLC_LAUNCH
