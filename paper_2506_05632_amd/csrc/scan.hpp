@@ -352,7 +352,13 @@ __device__ __forceinline__ void offer_where(Lds &s, int slot, double key, int i,
 // One workgroup scans one (row, draft group, chunk).  KB = draft pairs per pass (KT = 2 KB
 // drafts): each pair of drafts shares its Philox blocks.
 template <typename T, int KB, bool SHARED, bool PROBS>
-__global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kernel(const ScanParams p) {
+#ifndef LLC_OCC_SHARED
+#define LLC_OCC_SHARED 4
+#endif
+#ifndef LLC_OCC_PERK
+#define LLC_OCC_PERK 4
+#endif
+__global__ void __launch_bounds__(kBlock, SHARED ? LLC_OCC_SHARED : (KB <= 2 ? LLC_OCC_PERK : 2)) scan_kernel(const ScanParams p) {
   using elem = typename T::elem;
   constexpr int KT = 2 * KB;
   __shared__ Lds s;
@@ -489,11 +495,10 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
 #pragma unroll
       for (int kk = 0; kk < KD; ++kk)
         drow[kk] = drow0 + (SHARED ? 0 : (long long)min(kbase + kk, p.K - 1) * p.draft_stride_k);
-      // One tile (kBlock groups): loads are issued first, the Philox chains (which do not
-      // depend on them) run while they are in flight, thresholds and compares come last.
-      auto process_tile = [&](const int g, const bool interior) {
-        // without a pool the target-side exponent is pinned at 0 (threshold 0: never a hit)
-        float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f}, vd[KD][4];
+      // One tile (kBlock groups).  The next tile's loads are issued before this tile's Philox
+      // chains, thresholds and compares, so they have a whole tile of arithmetic to arrive.
+      // Without a pool the target-side exponent is pinned at 0 (threshold 0: never a hit).
+      auto load_tile = [&](const int g, const bool interior, float (&vq)[4], float (&vd)[KD][4]) {
         if (interior) {
           if (with_pool) load4_vec<T>(trow, g * 4, vq);
 #pragma unroll
@@ -503,6 +508,8 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
 #pragma unroll
           for (int kk = 0; kk < KD; ++kk) load4<T>(drow[kk], g * 4, V, vec, fill, vd[kk]);
         }
+      };
+      auto process_tile = [&](const int g, const float (&vq)[4], const float (&vd)[KD][4]) {
         uint32_t up[KB][4];  // upper half-words: word j of block m = (index 4g+j, drafts 2m | 2m+1)
         philox_blocks<KB>((uint32_t)g, pair_base, row_lo, row_hi, p.seed_lo, p.seed_hi, up);
 
@@ -512,7 +519,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         for (int j = 0; j < 4; ++j)
           FY[j] = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vq[j]), cq23, OY), 0.0f, kCapHot);
 
-        bool any = false;
+        bool any = false, hot = false;
         uint32_t cp[SHARED ? 1 : KB][4];  // packed half-word test values
         if (SHARED) {
           // one threshold per index serves every draft: any_k (h_k > c) == (max_k h_k > c)
@@ -520,7 +527,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             const float F = merged_exponent<PROBS>(vd[0][j], cd23[0], OX, FY[j]);
-            any |= F >= kCapHot;
+            hot |= F >= kCapHot;
             const uint32_t t = threshold_of(F);
             cp[0][j] = coarse_pair(t, t);
             uint32_t mx = up[0][j];
@@ -537,13 +544,13 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             for (int j = 0; j < 4; ++j) {
               const float F0 = merged_exponent<PROBS>(vd[SHARED ? 0 : 2 * m][j], cd23[2 * m], OX0, FY[j]);
               const float F1 = merged_exponent<PROBS>(vd[SHARED ? 0 : 2 * m + 1][j], cd23[2 * m + 1], OX1, FY[j]);
-              any |= fmaxf(F0, F1) >= kCapHot;
+              hot |= fmaxf(F0, F1) >= kCapHot;
               cp[SHARED ? 0 : m][j] = coarse_pair(threshold_of(F0), threshold_of(F1));
               any |= pk_sub_sat_u16(up[m][j], cp[SHARED ? 0 : m][j]) != 0u;
             }
           }
         }
-        if (any) {
+        if (any || hot) {
           // Rare: some half-word of this lane passed (or an element is hot).  Find the pairs
           // concerned, draw their lower half-words, and run the full-word test.  Offsets are
           // read again here: they only ever tighten, and a tighter threshold is still valid.
@@ -551,16 +558,25 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
           for (int m = 0; m < KB; ++m) {
             const int ke = 2 * m, ko = 2 * m + 1;        // slots of the pair's even and odd draft
             const int de = SHARED ? 0 : ke, dk = SHARED ? 0 : ko;
-            const float OXe = (SHARED || kok[ke]) ? load_offset(&s.O[SHARED ? 0 : ke]) : -__builtin_huge_valf();
-            const float OXo = (SHARED || kok[ko]) ? load_offset(&s.O[SHARED ? 0 : ko]) : -__builtin_huge_valf();
+            // (the shared layout's main loop uses the loosest draft's offset; here each draft
+            // gets its own, so most of the other drafts' candidates end before the lower block)
+            const float OXe = SHARED ? make_offset<PROBS>(unord32(__atomic_load_n(&s.tau[ke], __ATOMIC_RELAXED)))
+                                     : (kok[ke] ? load_offset(&s.O[ke]) : -__builtin_huge_valf());
+            const float OXo = SHARED ? make_offset<PROBS>(unord32(__atomic_load_n(&s.tau[ko], __ATOMIC_RELAXED)))
+                                     : (kok[ko] ? load_offset(&s.O[ko]) : -__builtin_huge_valf());
             unsigned hm = 0;  // bit 2j + h: element (index 4g + j, draft 2m + h) is a candidate
+            uint32_t d[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const uint32_t d = pk_sub_sat_u16(up[m][j], cp[SHARED ? 0 : m][j]);
-              const float Fe = merged_exponent<PROBS>(vd[de][j], cd23[ke], OXe, FY[j]);
-              const float Fo = merged_exponent<PROBS>(vd[dk][j], cd23[ko], OXo, FY[j]);
-              if ((d & 0xFFFFu) != 0u || Fe >= kCapHot) hm |= 1u << (2 * j);
-              if ((d >> 16) != 0u || Fo >= kCapHot) hm |= 2u << (2 * j);
+            for (int j = 0; j < 4; ++j) d[j] = pk_sub_sat_u16(up[m][j], cp[SHARED ? 0 : m][j]);
+            if ((d[0] | d[1] | d[2] | d[3]) != 0u || hot) {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                const float Fe = merged_exponent<PROBS>(vd[de][j], cd23[ke], OXe, FY[j]);
+                const float Fo = merged_exponent<PROBS>(vd[dk][j], cd23[ko], OXo, FY[j]);
+                const uint32_t dd = pk_sub_sat_u16(up[m][j], coarse_pair(threshold_of(Fe), threshold_of(Fo)));
+                if ((dd & 0xFFFFu) != 0u || Fe >= kCapHot) hm |= 1u << (2 * j);
+                if ((dd >> 16) != 0u || Fo >= kCapHot) hm |= 2u << (2 * j);
+              }
             }
             if (kbase + ko >= p.K) hm &= 0x55u;  // the odd draft of this pair is padding
             if (kbase + ke >= p.K) hm = 0;
@@ -598,10 +614,29 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
       const int interior_end = vec ? min(g_end, V >> 2) : g_begin;
       const int n_interior = max(0, (interior_end - g_begin) / kBlock);
       int it = 0;
-      for (; it < n_interior; ++it) process_tile(g_begin + it * kBlock + tid, true);
+      if (n_interior > 0) {
+        float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f}, vd[KD][4];
+        load_tile(g_begin + tid, true, vq, vd);
+        for (; it < n_interior; ++it) {
+          float nq[4] = {0.0f, 0.0f, 0.0f, 0.0f}, nd[KD][4];
+          // the last interior tile prefetches itself again (in bounds, result unused)
+          load_tile(g_begin + min(it + 1, n_interior - 1) * kBlock + tid, true, nq, nd);
+          process_tile(g_begin + it * kBlock + tid, vq, vd);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            vq[j] = nq[j];
+#pragma unroll
+            for (int kk = 0; kk < KD; ++kk) vd[kk][j] = nd[kk][j];
+          }
+        }
+      }
       for (; it < iters; ++it) {
         const int g = g_begin + it * kBlock + tid;
-        if (g < g_end) process_tile(g, false);
+        if (g < g_end) {
+          float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f}, vd[KD][4];
+          load_tile(g, false, vq, vd);
+          process_tile(g, vq, vd);
+        }
       }
     }
     __syncthreads();
