@@ -9,10 +9,7 @@ namespace {
 
 constexpr int kMaxChunks = 4096;
 constexpr int kPlannedChunkFloor = 16;  // the workspace always covers this many chunks
-#ifndef LLC_TARGET_BLOCKS
-#define LLC_TARGET_BLOCKS 1024
-#endif
-constexpr long long kTargetBlocks = LLC_TARGET_BLOCKS;  // four resident workgroups on each of 256 CUs
+constexpr long long kTargetBlocks = 1024;  // four resident workgroups on each of 256 CUs
 constexpr long long kMinTilesPerChunk = 8; // a chunk pays its own warm-up: keep it worth it
 
 inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }

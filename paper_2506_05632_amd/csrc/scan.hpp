@@ -33,8 +33,9 @@
 
 namespace llc {
 
-struct F32In { using elem = float; };
-struct BF16In { using elem = uint16_t; };
+// raw: four consecutive elements as they sit in memory (what a prefetched tile keeps per lane)
+struct F32In { using elem = float; using raw = float4; };
+struct BF16In { using elem = uint16_t; using raw = uint2; };
 
 // ---- margins (log2 units) ---------------------------------------------------
 // |tau| <= kTauLimit is enforced (else the workgroup redoes its chunk in fp64).
@@ -182,21 +183,41 @@ __device__ __forceinline__ void load4<BF16In>(const uint16_t *row, int i0, int V
   }
 }
 
-// Four in-range elements from a row aligned for vector loads: no bounds checks.
+// Four in-range elements of an aligned row, kept as loaded; unpack() widens them to fp32.
 template <typename T>
-__device__ __forceinline__ void load4_vec(const typename T::elem *row, int i0, float (&v)[4]);
+__device__ __forceinline__ typename T::raw load_raw(const typename T::elem *row, int i0) {
+  return *reinterpret_cast<const typename T::raw *>(row + i0);
+}
+// The same four elements with bounds checks (ragged tails, unaligned rows); `fill` stands for
+// elements past the end.
+template <typename T>
+__device__ __forceinline__ typename T::raw load_raw_checked(const typename T::elem *row, int i0, int V, bool vec, float fill);
 template <>
-__device__ __forceinline__ void load4_vec<F32In>(const float *row, int i0, float (&v)[4]) {
-  const float4 t = *reinterpret_cast<const float4 *>(row + i0);
-  v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+__device__ __forceinline__ float4 load_raw_checked<F32In>(const float *row, int i0, int V, bool vec, float fill) {
+  if (vec && i0 + 3 < V) return *reinterpret_cast<const float4 *>(row + i0);
+  float4 r;
+  r.x = (i0 + 0 < V) ? row[i0 + 0] : fill;
+  r.y = (i0 + 1 < V) ? row[i0 + 1] : fill;
+  r.z = (i0 + 2 < V) ? row[i0 + 2] : fill;
+  r.w = (i0 + 3 < V) ? row[i0 + 3] : fill;
+  return r;
 }
 template <>
-__device__ __forceinline__ void load4_vec<BF16In>(const uint16_t *row, int i0, float (&v)[4]) {
-  const uint2 t = *reinterpret_cast<const uint2 *>(row + i0);
-  v[0] = __uint_as_float(t.x << 16);
-  v[1] = __uint_as_float(t.x & 0xFFFF0000u);
-  v[2] = __uint_as_float(t.y << 16);
-  v[3] = __uint_as_float(t.y & 0xFFFF0000u);
+__device__ __forceinline__ uint2 load_raw_checked<BF16In>(const uint16_t *row, int i0, int V, bool vec, float fill) {
+  if (vec && i0 + 3 < V) return *reinterpret_cast<const uint2 *>(row + i0);
+  const uint32_t f = __float_as_uint(fill) >> 16;  // 0 and -inf are exact in bf16
+  const uint32_t e0 = (i0 + 0 < V) ? row[i0 + 0] : f, e1 = (i0 + 1 < V) ? row[i0 + 1] : f;
+  const uint32_t e2 = (i0 + 2 < V) ? row[i0 + 2] : f, e3 = (i0 + 3 < V) ? row[i0 + 3] : f;
+  return make_uint2(e0 | (e1 << 16), e2 | (e3 << 16));
+}
+__device__ __forceinline__ void unpack(const float4 &r, float (&v)[4]) {
+  v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
+}
+__device__ __forceinline__ void unpack(const uint2 &r, float (&v)[4]) {
+  v[0] = __uint_as_float(r.x << 16);
+  v[1] = __uint_as_float(r.x & 0xFFFF0000u);
+  v[2] = __uint_as_float(r.y << 16);
+  v[3] = __uint_as_float(r.y & 0xFFFF0000u);
 }
 
 template <typename T>
@@ -352,13 +373,7 @@ __device__ __forceinline__ void offer_where(Lds &s, int slot, double key, int i,
 // One workgroup scans one (row, draft group, chunk).  KB = draft pairs per pass (KT = 2 KB
 // drafts): each pair of drafts shares its Philox blocks.
 template <typename T, int KB, bool SHARED, bool PROBS>
-#ifndef LLC_OCC_SHARED
-#define LLC_OCC_SHARED 4
-#endif
-#ifndef LLC_OCC_PERK
-#define LLC_OCC_PERK 4
-#endif
-__global__ void __launch_bounds__(kBlock, SHARED ? LLC_OCC_SHARED : (KB <= 2 ? LLC_OCC_PERK : 2)) scan_kernel(const ScanParams p) {
+__global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kernel(const ScanParams p) {
   using elem = typename T::elem;
   constexpr int KT = 2 * KB;
   __shared__ Lds s;
@@ -498,55 +513,64 @@ __global__ void __launch_bounds__(kBlock, SHARED ? LLC_OCC_SHARED : (KB <= 2 ? L
       // One tile (kBlock groups).  The next tile's loads are issued before this tile's Philox
       // chains, thresholds and compares, so they have a whole tile of arithmetic to arrive.
       // Without a pool the target-side exponent is pinned at 0 (threshold 0: never a hit).
-      auto load_tile = [&](const int g, const bool interior, float (&vq)[4], float (&vd)[KD][4]) {
+      using raw = typename T::raw;
+      auto load_tile = [&](const int g, const bool interior, raw &rq, raw (&rd)[KD]) {
         if (interior) {
-          if (with_pool) load4_vec<T>(trow, g * 4, vq);
+          if (with_pool) rq = load_raw<T>(trow, g * 4);
 #pragma unroll
-          for (int kk = 0; kk < KD; ++kk) load4_vec<T>(drow[kk], g * 4, vd[kk]);
+          for (int kk = 0; kk < KD; ++kk) rd[kk] = load_raw<T>(drow[kk], g * 4);
         } else {
-          if (with_pool) load4<T>(trow, g * 4, V, vec, fill, vq);
+          if (with_pool) rq = load_raw_checked<T>(trow, g * 4, V, vec, fill);
 #pragma unroll
-          for (int kk = 0; kk < KD; ++kk) load4<T>(drow[kk], g * 4, V, vec, fill, vd[kk]);
+          for (int kk = 0; kk < KD; ++kk) rd[kk] = load_raw_checked<T>(drow[kk], g * 4, V, vec, fill);
         }
       };
-      auto process_tile = [&](const int g, const float (&vq)[4], const float (&vd)[KD][4]) {
+      // The tile is kept in its raw form and widened where it is used, so that few registers
+      // are live across the (rare) branch to the survivors' path, which widens it again.
+      auto process_tile = [&](const int g, const raw &rq, const raw (&rd)[KD]) {
         uint32_t up[KB][4];  // upper half-words: word j of block m = (index 4g+j, drafts 2m | 2m+1)
         philox_blocks<KB>((uint32_t)g, pair_base, row_lo, row_hi, p.seed_lo, p.seed_hi, up);
 
         const float OY = with_pool ? load_offset(&s.O[KT]) : -__builtin_huge_valf();
         float FY[4];
+        {
+          float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+          if (with_pool) unpack(rq, vq);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          FY[j] = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vq[j]), cq23, OY), 0.0f, kCapHot);
+          for (int j = 0; j < 4; ++j)
+            FY[j] = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vq[j]), cq23, OY), 0.0f, kCapHot);
+        }
 
         bool any = false, hot = false;
-        uint32_t cp[SHARED ? 1 : KB][4];  // packed half-word test values
         if (SHARED) {
           // one threshold per index serves every draft: any_k (h_k > c) == (max_k h_k > c)
           const float OX = load_offset(&s.O[0]);
+          float vd[4];
+          unpack(rd[0], vd);
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const float F = merged_exponent<PROBS>(vd[0][j], cd23[0], OX, FY[j]);
+            const float F = merged_exponent<PROBS>(vd[j], cd23[0], OX, FY[j]);
             hot |= F >= kCapHot;
             const uint32_t t = threshold_of(F);
-            cp[0][j] = coarse_pair(t, t);
             uint32_t mx = up[0][j];
 #pragma unroll
             for (int m = 1; m < KB; ++m) mx = pk_max_u16(mx, up[m][j]);
-            any |= pk_sub_sat_u16(mx, cp[0][j]) != 0u;
+            any |= pk_sub_sat_u16(mx, coarse_pair(t, t)) != 0u;
           }
         } else {
 #pragma unroll
           for (int m = 0; m < KB; ++m) {
             const float OX0 = kok[2 * m] ? load_offset(&s.O[2 * m]) : -__builtin_huge_valf();
             const float OX1 = kok[2 * m + 1] ? load_offset(&s.O[2 * m + 1]) : -__builtin_huge_valf();
+            float v0[4], v1[4];
+            unpack(rd[SHARED ? 0 : 2 * m], v0);
+            unpack(rd[SHARED ? 0 : 2 * m + 1], v1);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-              const float F0 = merged_exponent<PROBS>(vd[SHARED ? 0 : 2 * m][j], cd23[2 * m], OX0, FY[j]);
-              const float F1 = merged_exponent<PROBS>(vd[SHARED ? 0 : 2 * m + 1][j], cd23[2 * m + 1], OX1, FY[j]);
+              const float F0 = merged_exponent<PROBS>(v0[j], cd23[2 * m], OX0, FY[j]);
+              const float F1 = merged_exponent<PROBS>(v1[j], cd23[2 * m + 1], OX1, FY[j]);
               hot |= fmaxf(F0, F1) >= kCapHot;
-              cp[SHARED ? 0 : m][j] = coarse_pair(threshold_of(F0), threshold_of(F1));
-              any |= pk_sub_sat_u16(up[m][j], cp[SHARED ? 0 : m][j]) != 0u;
+              any |= pk_sub_sat_u16(up[m][j], coarse_pair(threshold_of(F0), threshold_of(F1))) != 0u;
             }
           }
         }
@@ -554,29 +578,43 @@ __global__ void __launch_bounds__(kBlock, SHARED ? LLC_OCC_SHARED : (KB <= 2 ? L
           // Rare: some half-word of this lane passed (or an element is hot).  Find the pairs
           // concerned, draw their lower half-words, and run the full-word test.  Offsets are
           // read again here: they only ever tighten, and a tighter threshold is still valid.
+          float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+          if (with_pool) unpack(rq, vq);
+          uint32_t cps[4] = {0u, 0u, 0u, 0u};  // shared layout: the main loop's test values again
+          if (SHARED) {
+            const float OX = load_offset(&s.O[0]);
+            float vd[4];
+            unpack(rd[0], vd);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const uint32_t t = threshold_of(merged_exponent<PROBS>(vd[j], cd23[0], OX, FY[j]));
+              cps[j] = coarse_pair(t, t);
+            }
+          }
 #pragma unroll
           for (int m = 0; m < KB; ++m) {
             const int ke = 2 * m, ko = 2 * m + 1;        // slots of the pair's even and odd draft
-            const int de = SHARED ? 0 : ke, dk = SHARED ? 0 : ko;
             // (the shared layout's main loop uses the loosest draft's offset; here each draft
             // gets its own, so most of the other drafts' candidates end before the lower block)
             const float OXe = SHARED ? make_offset<PROBS>(unord32(__atomic_load_n(&s.tau[ke], __ATOMIC_RELAXED)))
                                      : (kok[ke] ? load_offset(&s.O[ke]) : -__builtin_huge_valf());
             const float OXo = SHARED ? make_offset<PROBS>(unord32(__atomic_load_n(&s.tau[ko], __ATOMIC_RELAXED)))
                                      : (kok[ko] ? load_offset(&s.O[ko]) : -__builtin_huge_valf());
+            float ve[4], vo[4];
+            unpack(rd[SHARED ? 0 : ke], ve);
+            unpack(rd[SHARED ? 0 : ko], vo);
             unsigned hm = 0;  // bit 2j + h: element (index 4g + j, draft 2m + h) is a candidate
-            uint32_t d[4];
+            if (SHARED && !hot &&
+                (pk_sub_sat_u16(up[m][0], cps[0]) | pk_sub_sat_u16(up[m][1], cps[1]) |
+                 pk_sub_sat_u16(up[m][2], cps[2]) | pk_sub_sat_u16(up[m][3], cps[3])) == 0u)
+              continue;  // this pair had no part in the hit
 #pragma unroll
-            for (int j = 0; j < 4; ++j) d[j] = pk_sub_sat_u16(up[m][j], cp[SHARED ? 0 : m][j]);
-            if ((d[0] | d[1] | d[2] | d[3]) != 0u || hot) {
-#pragma unroll
-              for (int j = 0; j < 4; ++j) {
-                const float Fe = merged_exponent<PROBS>(vd[de][j], cd23[ke], OXe, FY[j]);
-                const float Fo = merged_exponent<PROBS>(vd[dk][j], cd23[ko], OXo, FY[j]);
-                const uint32_t dd = pk_sub_sat_u16(up[m][j], coarse_pair(threshold_of(Fe), threshold_of(Fo)));
-                if ((dd & 0xFFFFu) != 0u || Fe >= kCapHot) hm |= 1u << (2 * j);
-                if ((dd >> 16) != 0u || Fo >= kCapHot) hm |= 2u << (2 * j);
-              }
+            for (int j = 0; j < 4; ++j) {
+              const float Fe = merged_exponent<PROBS>(ve[j], cd23[ke], OXe, FY[j]);
+              const float Fo = merged_exponent<PROBS>(vo[j], cd23[ko], OXo, FY[j]);
+              const uint32_t dd = pk_sub_sat_u16(up[m][j], coarse_pair(threshold_of(Fe), threshold_of(Fo)));
+              if ((dd & 0xFFFFu) != 0u || Fe >= kCapHot) hm |= 1u << (2 * j);
+              if ((dd >> 16) != 0u || Fo >= kCapHot) hm |= 2u << (2 * j);
             }
             if (kbase + ko >= p.K) hm &= 0x55u;  // the odd draft of this pair is padding
             if (kbase + ke >= p.K) hm = 0;
@@ -589,8 +627,8 @@ __global__ void __launch_bounds__(kBlock, SHARED ? LLC_OCC_SHARED : (KB <= 2 ? L
                 const int j = bit >> 1, h = bit & 1;
                 const uint32_t uw = j == 0 ? up[m][0] : j == 1 ? up[m][1] : j == 2 ? up[m][2] : up[m][3];
                 const uint32_t lw = j == 0 ? lo[0] : j == 1 ? lo[1] : j == 2 ? lo[2] : lo[3];
-                const float dse = j == 0 ? vd[de][0] : j == 1 ? vd[de][1] : j == 2 ? vd[de][2] : vd[de][3];
-                const float dso = j == 0 ? vd[dk][0] : j == 1 ? vd[dk][1] : j == 2 ? vd[dk][2] : vd[dk][3];
+                const float dse = j == 0 ? ve[0] : j == 1 ? ve[1] : j == 2 ? ve[2] : ve[3];
+                const float dso = j == 0 ? vo[0] : j == 1 ? vo[1] : j == 2 ? vo[2] : vo[3];
                 const float ds = h ? dso : dse;
                 const float qs = j == 0 ? vq[0] : j == 1 ? vq[1] : j == 2 ? vq[2] : vq[3];
                 const float fy = j == 0 ? FY[0] : j == 1 ? FY[1] : j == 2 ? FY[2] : FY[3];
@@ -615,27 +653,24 @@ __global__ void __launch_bounds__(kBlock, SHARED ? LLC_OCC_SHARED : (KB <= 2 ? L
       const int n_interior = max(0, (interior_end - g_begin) / kBlock);
       int it = 0;
       if (n_interior > 0) {
-        float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f}, vd[KD][4];
-        load_tile(g_begin + tid, true, vq, vd);
+        raw rq = raw(), rd[KD];
+        load_tile(g_begin + tid, true, rq, rd);
         for (; it < n_interior; ++it) {
-          float nq[4] = {0.0f, 0.0f, 0.0f, 0.0f}, nd[KD][4];
+          raw nq = raw(), nd[KD];
           // the last interior tile prefetches itself again (in bounds, result unused)
           load_tile(g_begin + min(it + 1, n_interior - 1) * kBlock + tid, true, nq, nd);
-          process_tile(g_begin + it * kBlock + tid, vq, vd);
+          process_tile(g_begin + it * kBlock + tid, rq, rd);
+          rq = nq;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            vq[j] = nq[j];
-#pragma unroll
-            for (int kk = 0; kk < KD; ++kk) vd[kk][j] = nd[kk][j];
-          }
+          for (int kk = 0; kk < KD; ++kk) rd[kk] = nd[kk];
         }
       }
       for (; it < iters; ++it) {
         const int g = g_begin + it * kBlock + tid;
         if (g < g_end) {
-          float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f}, vd[KD][4];
-          load_tile(g, false, vq, vd);
-          process_tile(g, vq, vd);
+          raw rq = raw(), rd[KD];
+          load_tile(g, false, rq, rd);
+          process_tile(g, rq, rd);
         }
       }
     }
