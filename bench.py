@@ -213,6 +213,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--workload", choices=["couple", "verify"], default="couple")
+    ap.add_argument("--rows", type=int, default=0, help="use only the first ROWS rows of the configuration")
     ap.add_argument("--materialised", action="store_true",
                     help="give the K i.i.d. drafts as a [B,K,V] tensor instead of one shared [B,V] row")
     ap.add_argument("--keys", action="store_true", help="also produce the winning keys (adds the normaliser pass)")
@@ -237,7 +238,7 @@ def main():
     from paper_2506_05632_amd import workloads
 
     dev = "cuda:0"
-    w = workloads.make(args.config, dev)
+    w = workloads.make(args.config, dev, rows=args.rows or None)
     draft = w.draft
     if args.materialised and w.shared_draft:
         draft = w.draft[:, None, :].expand(w.B, w.K, w.V).contiguous()
@@ -285,6 +286,8 @@ def main():
     hbm_achieved = alg_bytes / scan_avg_s / 1e9
     alu_frac, hbm_frac = alu_achieved / ALU_PEAK_TLANEOPS, hbm_achieved / HBM_PEAK_GBS
     name = w.name + ("_materialised" if args.materialised and w.shared_draft else "")
+    if args.rows:
+        name += f"_rows{w.B}"
     # the ceiling that binds this workload is the one it sits closer to
     if hbm_frac >= alu_frac:
         roofline = {"bound": "hbm", "achieved": hbm_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

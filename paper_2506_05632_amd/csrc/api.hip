@@ -49,7 +49,7 @@ int auto_chunks(long long B, long long n_kgroups, long long G) {
 }
 
 struct Layout {
-  size_t keyX, idxX, keyY, idxY, kY, lse, total;
+  size_t keyX, idxX, keyY, idxY, kY, lse, shared_tau, total;
 };
 
 Layout layout_for(long long B, long long K, long long n_kgroups, long long n_chunks) {
@@ -61,6 +61,7 @@ Layout layout_for(long long B, long long K, long long n_kgroups, long long n_chu
   l.idxY = off; off += align256((size_t)(B * n_kgroups * n_chunks) * sizeof(int32_t));
   l.kY = off;   off += align256((size_t)(B * n_kgroups * n_chunks) * sizeof(int32_t));
   l.lse = off;  off += align256((size_t)(B * (K + 1)) * sizeof(double));
+  l.shared_tau = off; off += align256((size_t)(B * (K + 1)) * sizeof(int32_t));
   l.total = off;
   return l;
 }
@@ -175,7 +176,15 @@ int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
     if (launch_lse(st, lp) != hipSuccess) return LLC_E_LAUNCH;
   }
 
+  // a row spread over several workgroups shares its running bests through the workspace
+  int32_t *shared_tau = nullptr;
+  if (pl.n_chunks * pl.n_kgroups > 1) {
+    shared_tau = (int32_t *)(ws + lay.shared_tau);
+    if (launch_fill(st, shared_tau, j.B * (j.K + 1), 0x7F800000) != hipSuccess) return LLC_E_LAUNCH;
+  }
+
   ScanParams sp;
+  sp.shared_tau = shared_tau;
   sp.draft = j.draft; sp.target = j.target;
   sp.map = j.map; sp.draft_stride_k = j.draft_stride_k;
   sp.B = j.B; sp.K = (int)j.K; sp.V = (int)j.V;

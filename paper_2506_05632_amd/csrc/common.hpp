@@ -58,6 +58,8 @@ struct ScanParams {
   int vector_loads;         // rows are aligned for 4-element vector loads
   int force_exact;
   int no_pool;              // draft-side reductions only: the target is never read
+  int *shared_tau;          // [B][K+1] running bests shared by a row's workgroups, preset to
+                            // the ordered image of +inf; nullptr when a row is one workgroup
   Partials out;
   llc_stats *stats;
 };
@@ -115,5 +117,6 @@ hipError_t launch_scan_bf16_perk(int kt, bool probs, unsigned grid, hipStream_t 
 hipError_t launch_finalize(hipStream_t s, const FinalizeParams &p);
 hipError_t launch_lse(hipStream_t s, const LseParams &p);
 hipError_t launch_verify(hipStream_t s, const VerifyParams &p);
+hipError_t launch_fill(hipStream_t s, int32_t *dst, long long n, int32_t value);
 
 }  // namespace llc

@@ -237,7 +237,18 @@ __global__ void __launch_bounds__(64) verify_kernel(const VerifyParams p) {
     for (int k = 0; k < K; ++k) p.active[s * K + k] = (uint8_t)((viable >> k) & 1ull);
 }
 
+__global__ void __launch_bounds__(256) fill_kernel(int32_t *dst, long long n, int32_t value) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = value;
+}
+
 }  // namespace
+
+hipError_t launch_fill(hipStream_t s, int32_t *dst, long long n, int32_t value) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, n, value);
+  return hipGetLastError();
+}
 
 hipError_t launch_verify(hipStream_t s, const VerifyParams &p) {
   if (p.S == 0) return hipSuccess;

@@ -287,6 +287,8 @@ struct Lds {
   unsigned long long best[9];
   unsigned long long where[9];
   unsigned long long n_survivors, n_exact;
+  int *shared_tau;       // the row's running bests shared by all its workgroups (or null)
+  int shared_base, shared_pool;  // where this workgroup's draft 0 and the pool sit in it
   float rec_a[kListCap];
   int rec_i[kListCap];
   int rec_tag[kListCap];
@@ -319,10 +321,14 @@ __device__ __forceinline__ uint32_t coarse_pair(uint32_t t_even, uint32_t t_odd)
   return 0xFFFEFFFEu - ((t_odd & 0xFFFF0000u) | (t_even >> 16));
 }
 
-// Lower tau[slot] to `a` and refresh the level-1 offset that depends on it.
+// Lower tau[slot] to `a` and refresh the level-1 offset that depends on it.  When the row is
+// spread over several workgroups the new best is also posted to the row's shared array, from
+// which the others pick it up (a bound found in one chunk prunes all of them).
 template <int KT, bool SHARED, bool PROBS>
-__device__ __forceinline__ void publish(Lds &s, int slot, float a) {
+__device__ __forceinline__ void publish(Lds &s, int slot, float a, bool post = true) {
   atomicMin(&s.tau[slot], ord32(a));
+  if (post && s.shared_tau != nullptr)
+    atomicMin(&s.shared_tau[slot < KT ? s.shared_base + slot : s.shared_pool], ord32(a));
   if (!(fabsf(a) <= kTauLimit)) s.unsafe = 1;
   if (SHARED && slot < KT) {
     int m = s.tau[0];
@@ -334,28 +340,28 @@ __device__ __forceinline__ void publish(Lds &s, int slot, float a) {
   }
 }
 
-// Level 2 for one survivor of level 1.
+// Level 2 for one survivor of level 1.  tau_d / tau_p: the draft's and the pool's running best
+// as read a little earlier (a stale, larger value only lets more candidates through).
 template <int KT, bool SHARED, bool PROBS>
 __device__ __forceinline__ void level2(Lds &s, uint32_t x, float vd, float vq, int i, int kk,
-                                       bool draft_ok, bool pool_ok, float cd, float cq) {
+                                       bool draft_ok, bool pool_ok, float cd, float cq,
+                                       float tau_d, float tau_p) {
   const float l2S = approx_log2_race_time(x);
   float ell;
   if (draft_ok && approx_log2_mass<PROBS>(vd, cd, ell)) {
     const float a = l2S - ell;
-    const float tau = unord32(__atomic_load_n(&s.tau[kk], __ATOMIC_RELAXED));
-    if (a <= tau + kEps2) {
+    if (a <= tau_d + kEps2) {
       const int pos = atomicAdd(&s.count, 1);
       if (pos < kListCap) { s.rec_a[pos] = a; s.rec_i[pos] = i; s.rec_tag[pos] = kk; }
-      if (a < tau) publish<KT, SHARED, PROBS>(s, kk, a);
+      if (a < tau_d) publish<KT, SHARED, PROBS>(s, kk, a);
     }
   }
   if (pool_ok && approx_log2_mass<PROBS>(vq, cq, ell)) {
     const float a = l2S - ell;
-    const float tau = unord32(__atomic_load_n(&s.tau[KT], __ATOMIC_RELAXED));
-    if (a <= tau + kEps2) {
+    if (a <= tau_p + kEps2) {
       const int pos = atomicAdd(&s.count, 1);
       if (pos < kListCap) { s.rec_a[pos] = a; s.rec_i[pos] = i; s.rec_tag[pos] = KT + kk; }
-      if (a < tau) publish<KT, SHARED, PROBS>(s, KT, a);
+      if (a < tau_p) publish<KT, SHARED, PROBS>(s, KT, a);
     }
   }
 }
@@ -432,60 +438,80 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
     s.best[tid] = kOrdInf64;
     s.where[tid] = ~0ull;
   }
-  if (tid == 0) { s.count = 0; s.unsafe = p.force_exact ? 1 : 0; s.n_survivors = 0; s.n_exact = 0; }
+  if (tid == 0) {
+    s.count = 0; s.unsafe = p.force_exact ? 1 : 0; s.n_survivors = 0; s.n_exact = 0;
+    s.shared_tau = p.shared_tau != nullptr ? p.shared_tau + b * (p.K + 1) : nullptr;
+    s.shared_base = kbase;
+    s.shared_pool = p.K;
+  }
   __syncthreads();
 
   unsigned long long my_survivors = 0;
 
   if (!p.force_exact) {
-    // ---- warm-up: approximate keys of the first tile give every reduction a finite tau
+    // ---- warm-up: approximate keys of a few hundred elements give every reduction a finite
+    // tau.  Each wave takes one draft pair (wave w: pair w mod KB) and 64 groups of the chunk's
+    // first tile, so a lane evaluates 8 elements on both sides.
     {
-      const int g = g_begin + tid;
-      float a_min[KT + 1];
-#pragma unroll
-      for (int kk = 0; kk <= KT; ++kk) a_min[kk] = __builtin_huge_valf();
-      if (g < g_end) {
+      const int wv = tid >> 6;
+      const int m = wv % KB;
+      const int g = g_begin + (wv / KB) * 64 + (tid & 63);
+      float a_even = __builtin_huge_valf(), a_odd = __builtin_huge_valf(), a_pool = __builtin_huge_valf();
+      if (g < g_end && kbase + 2 * m < p.K) {
         float vq[4] = {fill, fill, fill, fill};
         if (with_pool) load4<T>(trow, g * 4, V, vec, fill, vq);
+        uint32_t up[4], lo[4];
+        philox_block((uint32_t)g, pair_base + m, row_lo, row_hi, p.seed_lo, p.seed_hi, up);
+        philox_block((uint32_t)g, (pair_base + m) | kLowBlock, row_lo, row_hi, p.seed_lo, p.seed_hi, lo);
 #pragma unroll
-        for (int m = 0; m < KB; ++m) {
-          if (kbase + 2 * m < p.K) {
-            uint32_t up[4], lo[4];
-            philox_block((uint32_t)g, pair_base + m, row_lo, row_hi, p.seed_lo, p.seed_hi, up);
-            philox_block((uint32_t)g, (pair_base + m) | kLowBlock, row_lo, row_hi, p.seed_lo, p.seed_hi, lo);
+        for (int h = 0; h < 2; ++h) {
+          const int k = kbase + 2 * m + h;
+          if (k < p.K) {
+            float tk = p.temp_draft_all;
+            if (p.temp_draft != nullptr) tk = p.temp_draft[k];
+            const bool ok = (tk > 0.0f) && (tk < __builtin_huge_valf());
+            const float ck = PROBS ? 1.0f : kLog2e / tk;
+            float vd[4];
+            load4<T>(drow0 + (SHARED ? 0 : (long long)k * p.draft_stride_k), g * 4, V, vec, fill, vd);
+            float a_k = __builtin_huge_valf();
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-              const int kk = 2 * m + h;
-              if (kbase + kk < p.K) {
-                float vd[4];
-                load4<T>(drow0 + (SHARED ? 0 : (long long)(kbase + kk) * p.draft_stride_k), g * 4, V, vec,
-                         fill, vd);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                  const float l2S = approx_log2_race_time(element_word(up[j], lo[j], h));
-                  float ell;
-                  if (kok[kk] && approx_log2_mass<PROBS>(vd[j], cd[kk], ell))
-                    a_min[kk] = fminf(a_min[kk], l2S - ell);
-                  if (with_pool && approx_log2_mass<PROBS>(vq[j], cq, ell)) a_min[KT] = fminf(a_min[KT], l2S - ell);
-                }
-              }
+            for (int j = 0; j < 4; ++j) {
+              const float l2S = approx_log2_race_time(element_word(up[j], lo[j], h));
+              float ell;
+              if (ok && approx_log2_mass<PROBS>(vd[j], ck, ell)) a_k = fminf(a_k, l2S - ell);
+              if (with_pool && approx_log2_mass<PROBS>(vq[j], cq, ell)) a_pool = fminf(a_pool, l2S - ell);
             }
+            if (h == 0) a_even = a_k; else a_odd = a_k;
           }
         }
       }
+      int oe = ord32(a_even), oo = ord32(a_odd), op = ord32(a_pool);
 #pragma unroll
-      for (int kk = 0; kk <= KT; ++kk) {
-        int o = ord32(a_min[kk]);
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) o = min(o, __shfl_xor(o, d));
-        if ((tid & 63) == 0 && o < 0x7F800000) atomicMin(&s.tau[kk], o);
+      for (int d = 32; d >= 1; d >>= 1) {
+        oe = min(oe, __shfl_xor(oe, d));
+        oo = min(oo, __shfl_xor(oo, d));
+        op = min(op, __shfl_xor(op, d));
+      }
+      if ((tid & 63) == 0) {
+        if (oe < 0x7F800000) atomicMin(&s.tau[2 * m], oe);
+        if (oo < 0x7F800000) atomicMin(&s.tau[2 * m + 1], oo);
+        if (op < 0x7F800000) atomicMin(&s.tau[KT], op);
       }
       __syncthreads();
       if (tid <= KT) {
+        const bool used = tid == KT ? with_pool : (kbase + tid < p.K);
+        if (used && p.shared_tau != nullptr) {
+          // post this chunk's first bound and take what the row's other workgroups have posted
+          int *slot = p.shared_tau + b * (p.K + 1) + (tid < KT ? kbase + tid : p.K);
+          const int mine = s.tau[tid];
+          const int theirs = mine < 0x7F800000 ? atomicMin(slot, mine)
+                                               : __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (theirs < mine) s.tau[tid] = theirs;
+        }
         const float tau = unord32(s.tau[tid]);
-        const bool used = (tid == KT) || (kbase + tid < p.K);
         if (used && tau < __builtin_huge_valf() && !(fabsf(tau) <= kTauLimit)) s.unsafe = 1;
       }
+      __syncthreads();
       if (tid == 0) {
         if (SHARED) {
           int m = s.tau[0];
@@ -580,6 +606,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
           // read again here: they only ever tighten, and a tighter threshold is still valid.
           float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
           if (with_pool) unpack(rq, vq);
+          const float tau_y = unord32(__atomic_load_n(&s.tau[KT], __ATOMIC_RELAXED));
           uint32_t cps[4] = {0u, 0u, 0u, 0u};  // shared layout: the main loop's test values again
           if (SHARED) {
             const float OX = load_offset(&s.O[0]);
@@ -596,9 +623,11 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             const int ke = 2 * m, ko = 2 * m + 1;        // slots of the pair's even and odd draft
             // (the shared layout's main loop uses the loosest draft's offset; here each draft
             // gets its own, so most of the other drafts' candidates end before the lower block)
-            const float OXe = SHARED ? make_offset<PROBS>(unord32(__atomic_load_n(&s.tau[ke], __ATOMIC_RELAXED)))
+            const float tau_e = unord32(__atomic_load_n(&s.tau[ke], __ATOMIC_RELAXED));
+            const float tau_o = unord32(__atomic_load_n(&s.tau[ko], __ATOMIC_RELAXED));
+            const float OXe = SHARED ? make_offset<PROBS>(tau_e)
                                      : (kok[ke] ? load_offset(&s.O[ke]) : -__builtin_huge_valf());
-            const float OXo = SHARED ? make_offset<PROBS>(unord32(__atomic_load_n(&s.tau[ko], __ATOMIC_RELAXED)))
+            const float OXo = SHARED ? make_offset<PROBS>(tau_o)
                                      : (kok[ko] ? load_offset(&s.O[ko]) : -__builtin_huge_valf());
             float ve[4], vo[4];
             unpack(rd[SHARED ? 0 : ke], ve);
@@ -639,7 +668,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
                   if (F >= kCapHot || x >= ~threshold_of(F)) {
                     ++my_survivors;
                     level2<KT, SHARED, PROBS>(s, x, ds, qs, i, 2 * m + h, h ? kok[ko] : kok[ke], with_pool,
-                                              h ? cd[ko] : cd[ke], cq);
+                                              h ? cd[ko] : cd[ke], cq, h ? tau_o : tau_e, tau_y);
                   }
                 }
               }
@@ -655,7 +684,18 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
       if (n_interior > 0) {
         raw rq = raw(), rd[KD];
         load_tile(g_begin + tid, true, rq, rd);
+        // lanes 0..KT of the first wave follow the row's shared bounds: read every fourth
+        // iteration, merged four iterations later (the load never has to be waited for)
+        const bool follows = p.shared_tau != nullptr && tid <= KT &&
+                             (tid == KT ? with_pool : (kbase + tid < p.K));
+        const int *follow_slot = follows ? p.shared_tau + b * (p.K + 1) + (tid < KT ? kbase + tid : p.K) : nullptr;
+        int seen = 0x7F800000;
         for (; it < n_interior; ++it) {
+          if (follows && (it & 3) == 0) {
+            if (seen < __atomic_load_n(&s.tau[tid], __ATOMIC_RELAXED))
+              publish<KT, SHARED, PROBS>(s, tid, unord32(seen), false);
+            seen = __hip_atomic_load(follow_slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
           raw nq = raw(), nd[KD];
           // the last interior tile prefetches itself again (in bounds, result unused)
           load_tile(g_begin + min(it + 1, n_interior - 1) * kBlock + tid, true, nq, nd);
