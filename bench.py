@@ -41,10 +41,12 @@ def algorithmic_lane_ops(K):
 # each scaled by what the counter reads for a plain 1 GiB copy (x2.0 and x1.0); the summaries are
 # under profiles/.  None for workloads that have not been measured.
 MEASURED_TRAFFIC_BYTES = {
-    "largevocab_v128256_k8_f32": 1062.5e6 + 0.3e6,
-    "largevocab_v128256_k8_f32_materialised": 4921.3e6 + 0.2e6,
-    "distinct_v152064_k16_bf16": 2664.4e6 + 0.1e6,
-    "is_n65536_l4_f32": 5431.0e6 + 0.4e6,
+    "largevocab_v128256_k8_f32": 1052.5e6 + 0.1e6,
+    "largevocab_v128256_k8_f32_materialised": 4981.2e6 + 2.5e6,
+    "distinct_v152064_k16_bf16": 2706.8e6 + 2.3e6,
+    "is_n65536_l4_f32": 5398.7e6 + 0.4e6,
+    "specdec_v32000_k4_bf16": 33.5e6 + 0.5e6,
+    "verify_largevocab_s128_l7_k8_v128256": 4214.7e6 + 1.9e6,
 }
 
 
@@ -150,6 +152,12 @@ def bench_verify(args):
     wall = time.perf_counter() - t0
     scan_ms = [ev.elapsed_ms(i) for i in range(args.steps)]
     ev.close()
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     scan_avg_s = sum(scan_ms) / len(scan_ms) / 1e3
     elems = w.elems
     es = 4 if w.dtype == torch.float32 else 2
@@ -161,7 +169,8 @@ def bench_verify(args):
     roofline = {"bound": "hbm", "achieved": hbm_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": hbm_frac, "kernel": "scan_kernel", "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
                 "kernel_ms": scan_avg_s * 1e3, "kernel_ms_min": min(scan_ms),
-                "algorithmic_bytes": alg_bytes, "hbm_frac": hbm_frac, "alu_frac": alu_frac}
+                "algorithmic_bytes": alg_bytes, "algorithmic_lane_ops_per_elem": alg_ops,
+                "hbm_frac": hbm_frac, "alu_frac": alu_frac}
     result = {
         "metric": "Gelem/s (S*(L+1)*K*V) of Algorithm 2's verification loop",
         "value": elems / (wall / args.steps) / 1e9, "unit": "Gelem/s", "n_gpus": 1,

@@ -200,41 +200,62 @@ __global__ void __launch_bounds__(256) lse_kernel(const LseParams p) {
 // Algorithm 2, the loop over positions (Section 4.2): Y_j is the candidate of the viable draft
 // with the smallest key (ties: smaller index, then smaller k); drafts whose token differs from
 // Y_j stop being viable; the loop ends when none is left or after the bonus position.
+// One wavefront per sequence, lane k holds draft k (K <= 64); positions are fetched eight at a
+// time so that the loop itself only waits for memory once per eight positions.
 __global__ void __launch_bounds__(64) verify_kernel(const VerifyParams p) {
-  const long long s = (long long)blockIdx.x * 64 + threadIdx.x;
-  if (s >= p.S) return;
-  const int L = p.L, K = p.K;  // K <= 64: the viable set is a bit mask
+  const long long s = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int L = p.L, K = p.K;
   const int32_t *cand = p.cand + s * (L + 1) * K;
   const double *ckey = p.cand_key + s * (L + 1) * K;
   int32_t *Y = p.Y + s * (L + 1);
-  unsigned long long viable = K >= 64 ? ~0ull : ((1ull << K) - 1ull);
+  float *keyY = p.keyY != nullptr ? p.keyY + s * (L + 1) : nullptr;
+  bool viable = lane < K;
+  bool done = false;
   int n = 0;
-  for (int j = 0; j <= L; ++j) {
-    double bkey = __builtin_huge_val();
-    int bidx = -1;
-    for (int k = 0; k < K; ++k) {
-      if (!((viable >> k) & 1ull)) continue;
-      const double key = ckey[j * K + k];
-      const int idx = cand[j * K + k];
-      if (idx < 0) continue;
-      if (bidx < 0 || key < bkey || (key == bkey && idx < bidx)) { bkey = key; bidx = idx; }
+  for (int j0 = 0; j0 <= L && !done; j0 += 8) {
+    double key[8];
+    int idx[8], tok[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int j = j0 + u;
+      key[u] = __builtin_huge_val(); idx[u] = -1; tok[u] = -2;
+      if (j <= L && lane < K) {
+        key[u] = ckey[(long long)j * K + lane];
+        idx[u] = cand[(long long)j * K + lane];
+        if (j < L) tok[u] = p.tokens[s * p.tok_stride_s + (long long)j * p.tok_stride_j + lane];
+      }
     }
-    Y[j] = bidx;
-    if (p.keyY != nullptr) p.keyY[s * (L + 1) + j] = bidx >= 0 ? (float)exp(bkey) : __builtin_huge_valf();
-    n = j + 1;
-    if (j == L) break;
-    const int32_t *tok = p.tokens + s * p.tok_stride_s + (long long)j * p.tok_stride_j;
-    for (int k = 0; k < K; ++k)
-      if (((viable >> k) & 1ull) && tok[k] != bidx) viable &= ~(1ull << k);
-    if (viable == 0) break;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int j = j0 + u;
+      if (j > L || done) break;  // uniform
+      double bkey = (viable && idx[u] >= 0) ? key[u] : __builtin_huge_val();
+      int bidx = (viable && idx[u] >= 0) ? idx[u] : -1;
+      int bk = lane;
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) {
+        const double okey = __shfl_xor(bkey, d);
+        const int oidx = __shfl_xor(bidx, d);
+        const int ok = __shfl_xor(bk, d);
+        if (beats(okey, oidx, ok, bkey, bidx, bk)) { bkey = okey; bidx = oidx; bk = ok; }
+      }
+      if (lane == 0) {
+        Y[j] = bidx;
+        if (keyY != nullptr) keyY[j] = bidx >= 0 ? (float)exp(bkey) : __builtin_huge_valf();
+      }
+      n = j + 1;
+      if (j == L) { done = true; break; }
+      viable = viable && tok[u] == bidx;
+      if (__ballot(viable) == 0ull) done = true;
+    }
   }
-  for (int j = n; j <= L; ++j) {
+  for (int j = n + lane; j <= L; j += 64) {
     Y[j] = -1;
-    if (p.keyY != nullptr) p.keyY[s * (L + 1) + j] = __builtin_huge_valf();
+    if (keyY != nullptr) keyY[j] = __builtin_huge_valf();
   }
-  p.n_out[s] = n;
-  if (p.active != nullptr)
-    for (int k = 0; k < K; ++k) p.active[s * K + k] = (uint8_t)((viable >> k) & 1ull);
+  if (lane == 0) p.n_out[s] = n;
+  if (p.active != nullptr && lane < K) p.active[s * K + lane] = viable ? 1 : 0;
 }
 
 __global__ void __launch_bounds__(256) fill_kernel(int32_t *dst, long long n, int32_t value) {
@@ -252,7 +273,7 @@ hipError_t launch_fill(hipStream_t s, int32_t *dst, long long n, int32_t value) 
 
 hipError_t launch_verify(hipStream_t s, const VerifyParams &p) {
   if (p.S == 0) return hipSuccess;
-  hipLaunchKernelGGL(verify_kernel, dim3((unsigned)((p.S + 63) / 64)), dim3(64), 0, s, p);
+  hipLaunchKernelGGL(verify_kernel, dim3((unsigned)p.S), dim3(64), 0, s, p);
   return hipGetLastError();
 }
 

@@ -415,7 +415,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
   const elem *drow0 = reinterpret_cast<const elem *>(p.draft) + p.map.draft_off(b);
 
   // per-draft constants (wave-uniform)
-  float cd[KT], cd23[KT];
+  float cd23[KT];  // log2(e) / T_k scaled by 2^23 (an exact scaling: the plain factor is cd23 * 2^-23)
   bool kok[KT];
 #pragma unroll
   for (int kk = 0; kk < KT; ++kk) {
@@ -423,8 +423,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
     float t = p.temp_draft_all;
     if (p.temp_draft != nullptr && k < p.K) t = p.temp_draft[k];
     kok[kk] = (k < p.K) && (t > 0.0f) && (t < __builtin_huge_valf());
-    cd[kk] = PROBS ? 1.0f : kLog2e / t;
-    cd23[kk] = PROBS ? 1.0f : cd[kk] * kTwo23;
+    cd23[kk] = PROBS ? 1.0f : (kLog2e / t) * kTwo23;
   }
   const float Tq = p.temp_target;
   const float cq = PROBS ? 1.0f : kLog2e / Tq;
@@ -663,12 +662,13 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
                 const float fy = j == 0 ? FY[0] : j == 1 ? FY[1] : j == 2 ? FY[2] : FY[3];
                 const int i = g * 4 + j;
                 if (i < V) {
-                  const float F = merged_exponent<PROBS>(ds, h ? cd23[ko] : cd23[ke], h ? OXo : OXe, fy);
+                  const float c23 = h ? cd23[ko] : cd23[ke];
+                  const float F = merged_exponent<PROBS>(ds, c23, h ? OXo : OXe, fy);
                   const uint32_t x = element_word(uw, lw, h);
                   if (F >= kCapHot || x >= ~threshold_of(F)) {
                     ++my_survivors;
                     level2<KT, SHARED, PROBS>(s, x, ds, qs, i, 2 * m + h, h ? kok[ko] : kok[ke], with_pool,
-                                              h ? cd[ko] : cd[ke], cq, h ? tau_o : tau_e, tau_y);
+                                              PROBS ? 1.0f : c23 * (1.0f / kTwo23), cq, h ? tau_o : tau_e, tau_y);
                   }
                 }
               }
