@@ -10,9 +10,12 @@
  * -1 (and accept = 0 for the row).
  *
  * Shared randomness (a reading, the paper only asks for i.i.d. uniforms):
- * Philox4x32 with 10 rounds, key = (lo32(seed), hi32(seed)), counter =
- * (i >> 2, k, lo32(row), hi32(row)) with row = row_offset + b; element i takes
- * output word (i & 3); U = (word + 1/2) / 2^32 and S = -ln U.
+ * Philox4x32 with 10 rounds, key = (lo32(seed), hi32(seed)), row = row_offset + b.
+ * The 32-bit word x of element (row, k, i) is two 16-bit halves from two blocks:
+ * counter (i >> 2, k >> 1, lo32(row), hi32(row)) gives the upper half, the same
+ * counter with bit 31 of its second word set gives the lower half; both read
+ * output word (i & 3), its lower 16 bits for even k, its upper 16 bits for odd k.
+ * U = (x + 1/2) / 2^32 and S = -ln U.
  * Ties in an argmin go to the smaller index, then (pool) to the smaller k.
  */
 #ifndef LLC_H_
@@ -102,8 +105,8 @@ typedef struct llc_couple_args {
   int32_t flags;            /* LLC_FLAG_*                                                */
   int32_t v_chunks;         /* 0 = choose; else split V over this many workgroups (1..4096).
                                Results do not depend on it.                              */
-  int32_t k_tile;           /* 0 = choose; else drafts per workgroup pass: 1, 2, 4 or 8.
-                               Results do not depend on it.                              */
+  int32_t k_tile;           /* 0 = choose; else drafts per workgroup pass: 2, 4 or 8 (1 is
+                               accepted and runs as 2).  Results do not depend on it.    */
   void *ev_scan_begin;      /* optional hipEvent_t pair, recorded on `stream` right before */
   void *ev_scan_end;        /* and right after the scan kernel (for timing it alone)      */
 } llc_couple_args;
