@@ -28,7 +28,7 @@
 extern "C" {
 #endif
 
-#define LLC_VERSION 101
+#define LLC_VERSION 102
 
 enum {
   LLC_OK = 0,
@@ -186,11 +186,56 @@ typedef struct llc_verify_args {
   void *ev_scan_begin, *ev_scan_end; /* as in llc_couple_args                            */
 } llc_verify_args;
 
+/* Arguments of llc_couple_topm: Algorithm 1 on candidate lists (Section 4.4: with top-K
+ * sampling all but M << N high-probability tokens are thrown away before the coupling).
+ *
+ * Inputs.  Each distribution is a list of (token id, value) pairs: draft k of row b has
+ * entries e = 0..Md-1 at draft_ids / draft_val[b*draft_stride_b + k*draft_stride_k + e]
+ * (draft_stride_k == 0: the K drafts are i.i.d. from one list), the target has Mt entries
+ * at target_ids / target_val[b*target_stride_b + e].  Values denote the distribution
+ * restricted to the list (softmax over the list for logits, normalised over the list for
+ * log-weights, as given for probabilities).  Ids must lie in [0, 2^31 - 4); an entry with a
+ * negative id is an empty slot.  An id that occurs twice in a list competes twice with the
+ * same race time (the larger probability wins).  The lists of the two sides need not hold
+ * the same ids: the uniforms are keyed by the token id, exactly as in llc_couple, so the
+ * result equals llc_couple on the dense rows that carry no mass outside the lists.
+ *
+ * Outputs are token ids: X[b,k] = id of argmin_e S_id^(k) / p_e^(k), Y[b] = id of the pool
+ * argmin over (k, target entry); ties go to the smaller id, then the smaller k; accept,
+ * match_k, keyX, keyY as in llc_couple.  No workspace is needed.
+ */
+typedef struct llc_couple_topm_args {
+  int64_t B, K, Md, Mt;     /* B >= 0, K in 1..1024, Md, Mt in 1..65536                   */
+  int32_t dtype;            /* LLC_F32 | LLC_BF16 (both value arrays)                     */
+  int32_t kind;             /* LLC_LOGITS | LLC_PROBS | LLC_LOGW                          */
+  const int32_t *draft_ids; /* device */
+  const void *draft_val;    /* device */
+  int64_t draft_stride_b, draft_stride_k;   /* elements, shared by ids and values         */
+  const int32_t *target_ids;/* device */
+  const void *target_val;   /* device */
+  int64_t target_stride_b;
+  float temp_target;        /* > 0; LLC_LOGITS only                                       */
+  float temp_draft_all;     /* > 0; used when temp_draft == NULL                          */
+  const float *temp_draft;  /* device, K entries, or NULL                                 */
+  uint64_t seed, row_offset;
+  int32_t *X;               /* [B,K] required */
+  int32_t *Y;               /* [B]   required */
+  uint8_t *accept;          /* [B]   required */
+  int32_t *match_k;         /* [B]   optional */
+  float *keyX;              /* [B,K] optional */
+  float *keyY;              /* [B]   optional */
+  llc_stats *stats;         /* optional: exact_evals and degenerate are counted           */
+  void *stream;
+} llc_couple_topm_args;
+
 /* Algorithm 1 on a batch (Section 3).  Asynchronous on a->stream. */
 int llc_couple(const llc_couple_args *a);
 
 /* Appendix C's index selection at the encoder and the L decoders.  Asynchronous. */
 int llc_couple_is(const llc_couple_is_args *a);
+
+/* Algorithm 1 on top-M candidate lists (Section 4.4).  Asynchronous. */
+int llc_couple_topm(const llc_couple_topm_args *a);
 
 /* Algorithm 2's verification loop (Section 4.2) on S sequences.  Asynchronous. */
 int llc_verify(const llc_verify_args *a);

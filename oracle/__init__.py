@@ -57,6 +57,26 @@ class _VerifyArgs(ctypes.Structure):
     ]
 
 
+class _TopmArgs(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int64), ("K", ctypes.c_int64), ("Md", ctypes.c_int64), ("Mt", ctypes.c_int64),
+        ("dtype", ctypes.c_int32), ("kind", ctypes.c_int32),
+        ("draft_ids", ctypes.c_void_p), ("draft_val", ctypes.c_void_p),
+        ("draft_stride_b", ctypes.c_int64), ("draft_stride_k", ctypes.c_int64),
+        ("target_ids", ctypes.c_void_p), ("target_val", ctypes.c_void_p),
+        ("target_stride_b", ctypes.c_int64),
+        ("temp_target", ctypes.c_float),
+        ("temp_draft", ctypes.c_void_p),
+        ("temp_draft_all", ctypes.c_float),
+        ("seed", ctypes.c_uint64), ("row_offset", ctypes.c_uint64),
+        ("X", ctypes.c_void_p), ("Y", ctypes.c_void_p), ("accept", ctypes.c_void_p),
+        ("match_k", ctypes.c_void_p),
+        ("keyX", ctypes.c_void_p), ("keyY", ctypes.c_void_p),
+        ("gapX", ctypes.c_void_p), ("gapY", ctypes.c_void_p),
+        ("threads", ctypes.c_int32),
+    ]
+
+
 def lib():
     global _lib
     if _lib is None:
@@ -79,6 +99,8 @@ def lib():
         _lib.llc_couple_is_ref.restype = ctypes.c_int
         _lib.llc_verify_ref.argtypes = [ctypes.POINTER(_VerifyArgs)]
         _lib.llc_verify_ref.restype = ctypes.c_int
+        _lib.llc_couple_topm_ref.argtypes = [ctypes.POINTER(_TopmArgs)]
+        _lib.llc_couple_topm_ref.restype = ctypes.c_int
     return _lib
 
 
@@ -219,4 +241,58 @@ def verify(target, tokens, *, dtype=F32, kind=LOGITS, temp_target=1.0, seed=0, r
     a.threads = threads
     if lib().llc_verify_ref(ctypes.byref(a)) != 0:
         raise ValueError("llc_verify_ref rejected its arguments")
+    return out
+
+
+def couple_topm(draft_ids, draft_val, target_ids, target_val, K, *, dtype=F32, kind=LOGITS,
+                temp_target=1.0, temp_draft=None, temp_draft_all=1.0, seed=0, row_offset=0, threads=0):
+    """Algorithm 1 on candidate lists (Section 4.4).
+
+    draft_ids / draft_val: [B,Md] (one list per row, shared by the K drafts) or [B,K,Md];
+    target_ids / target_val: [B,Mt].  ids are int32 token ids (negative = empty slot).  Returns
+    X [B,K], Y [B] (token ids), accept, match_k, keyX, keyY, gapX, gapY.
+    """
+    draft_val, target_val = _check_input(draft_val, dtype), _check_input(target_val, dtype)
+    draft_ids = np.asarray(draft_ids)
+    target_ids = np.asarray(target_ids)
+    assert draft_ids.dtype == np.int32 and target_ids.dtype == np.int32
+    assert draft_ids.shape == draft_val.shape and target_ids.shape == target_val.shape
+    B, Mt = target_val.shape
+    Md = draft_val.shape[-1]
+    it = draft_val.itemsize
+    assert draft_ids.strides[-1] == 4 and target_ids.strides[-1] == 4
+    if draft_val.ndim == 2:
+        sb, sk = draft_val.strides[0] // it, 0
+        assert draft_ids.strides[0] // 4 == sb
+    else:
+        assert draft_val.shape[:2] == (B, K)
+        sb, sk = draft_val.strides[0] // it, draft_val.strides[1] // it
+        assert (draft_ids.strides[0] // 4, draft_ids.strides[1] // 4) == (sb, sk)
+    assert target_ids.strides[0] // 4 == target_val.strides[0] // it
+    out = {
+        "X": np.full((B, K), -2, np.int32), "Y": np.full(B, -2, np.int32),
+        "accept": np.zeros(B, np.uint8), "match_k": np.full(B, -2, np.int32),
+        "keyX": np.zeros((B, K)), "keyY": np.zeros(B),
+        "gapX": np.zeros((B, K)), "gapY": np.zeros(B),
+    }
+    a = _TopmArgs()
+    a.B, a.K, a.Md, a.Mt = B, K, Md, Mt
+    a.dtype, a.kind = dtype, kind
+    a.draft_ids, a.draft_val = draft_ids.ctypes.data, draft_val.ctypes.data
+    a.draft_stride_b, a.draft_stride_k = sb, sk
+    a.target_ids, a.target_val = target_ids.ctypes.data, target_val.ctypes.data
+    a.target_stride_b = target_val.strides[0] // it
+    a.temp_target = temp_target
+    td = None
+    if temp_draft is not None:
+        td = np.ascontiguousarray(temp_draft, dtype=np.float32)
+        assert td.shape == (K,)
+        a.temp_draft = td.ctypes.data
+    a.temp_draft_all = temp_draft_all
+    a.seed, a.row_offset = seed, row_offset
+    for name in out:
+        setattr(a, name, out[name].ctypes.data)
+    a.threads = threads
+    if lib().llc_couple_topm_ref(ctypes.byref(a)) != 0:
+        raise ValueError("llc_couple_topm_ref rejected its arguments")
     return out

@@ -14,6 +14,9 @@
 // llc_verify_ref is Algorithm 2's verification loop (Section 4.2): position by
 // position the target token is the pool argmin over the drafts that are still
 // viable, and drafts whose token differs are dropped.
+// llc_couple_topm_ref is Algorithm 1 on candidate lists (Section 4.4: top-K sampling
+// keeps M << N tokens): every distribution is a list of (token id, value) pairs,
+// normalised over the list, and the uniforms are keyed by the token id.
 // The importance-weight form (Appendix C, the normalised weights lambda_q,
 // lambda_p^(k) and the selection rule below them) is the same computation with
 // p, q proportional to exp(log-weight).
@@ -142,6 +145,36 @@ void row_distribution(const void *base, int dtype, int64_t off, int64_t V, int k
   for (int64_t i = 0; i < V; ++i) sum += std::exp(prob[i] - zmax);
   const double lse = zmax + std::log(sum);
   for (int64_t i = 0; i < V; ++i) prob[i] = std::exp(prob[i] - lse);
+}
+
+// The distribution a candidate list denotes, on its own entries (Section 4.4: all but the M listed
+// tokens are thrown away).  An entry with a negative id is an empty slot and carries nothing.
+void list_distribution(const int32_t *ids, const void *val, int dtype, int64_t off, int64_t M,
+                       int kind, double T, std::vector<double> &prob) {
+  prob.assign((size_t)M, 0.0);
+  if (kind == KIND_PROBS) {
+    for (int64_t e = 0; e < M; ++e) {
+      const double v = load_elem(val, dtype, off + e);
+      prob[e] = (ids[e] >= 0 && std::isfinite(v) && v > 0.0) ? v : 0.0;
+    }
+    return;
+  }
+  const double temp = (kind == KIND_LOGITS) ? T : 1.0;
+  double zmax = -kInf;
+  for (int64_t e = 0; e < M; ++e) {
+    double z = load_elem(val, dtype, off + e) / temp;
+    if (ids[e] < 0 || std::isnan(z) || z == kInf) z = -kInf;
+    prob[e] = z;
+    if (z > zmax) zmax = z;
+  }
+  if (zmax == -kInf) {
+    for (int64_t e = 0; e < M; ++e) prob[e] = 0.0;
+    return;
+  }
+  double sum = 0.0;
+  for (int64_t e = 0; e < M; ++e) sum += std::exp(prob[e] - zmax);
+  const double lse = zmax + std::log(sum);
+  for (int64_t e = 0; e < M; ++e) prob[e] = std::exp(prob[e] - lse);
 }
 
 // Running (smallest, runner-up) of a race; `second` is the smallest key among
@@ -304,6 +337,89 @@ int llc_couple_is_ref(int64_t B, int64_t L, int64_t N,
   a.keyX = keyX; a.keyY = keyY; a.gapX = gapX; a.gapY = gapY;
   a.threads = threads;
   return llc_couple_ref(&a);
+}
+
+// Algorithm 1 on candidate lists (Section 4.4).  draft_ids / draft_val: [B,K,Md] (stride_k == 0:
+// one list per row), target_ids / target_val: [B,Mt].  A negative id marks an empty slot.  The
+// distribution a list denotes lives on its entries only: softmax of the listed logits, the
+// listed log-weights normalised, or the listed probabilities as given.  Outputs are token ids.
+struct llc_topm_ref_args {
+  int64_t B, K, Md, Mt;
+  int32_t dtype, kind;
+  const int32_t *draft_ids;
+  const void *draft_val;
+  int64_t draft_stride_b, draft_stride_k;
+  const int32_t *target_ids;
+  const void *target_val;
+  int64_t target_stride_b;
+  float temp_target;
+  const float *temp_draft;
+  float temp_draft_all;
+  uint64_t seed, row_offset;
+  int32_t *X;        // [B,K] token ids
+  int32_t *Y;        // [B]
+  uint8_t *accept;   // [B]
+  int32_t *match_k;  // [B]   optional
+  double *keyX;      // [B,K] optional
+  double *keyY;      // [B]   optional
+  double *gapX;      // [B,K] optional: relative gap to the best entry with another id
+  double *gapY;      // [B]   optional
+  int32_t threads;
+};
+
+int llc_couple_topm_ref(const llc_topm_ref_args *a) {
+  if (!a || !a->draft_ids || !a->draft_val || !a->target_ids || !a->target_val || !a->X || !a->Y ||
+      !a->accept)
+    return -1;
+  if (a->B < 0 || a->K < 1 || a->Md < 1 || a->Mt < 1) return -1;
+  const int64_t B = a->B, K = a->K, Md = a->Md, Mt = a->Mt;
+  int nthreads = a->threads;
+#ifdef _OPENMP
+  if (nthreads <= 0) nthreads = omp_get_max_threads();
+#else
+  nthreads = 1;
+#endif
+#pragma omp parallel for schedule(dynamic, 4) num_threads(nthreads)
+  for (int64_t b = 0; b < B; ++b) {
+    const uint64_t row = a->row_offset + (uint64_t)b;
+    std::vector<double> q, p;
+    const int32_t *tid = a->target_ids + b * a->target_stride_b;
+    list_distribution(tid, a->target_val, a->dtype, b * a->target_stride_b, Mt, a->kind,
+                      (double)a->temp_target, q);
+    Race pool;
+    std::vector<int64_t> xs((size_t)K);
+    for (int64_t k = 0; k < K; ++k) {
+      const int64_t off = b * a->draft_stride_b + k * a->draft_stride_k;
+      const int32_t *did = a->draft_ids + off;
+      const double Tk = a->temp_draft ? (double)a->temp_draft[k] : (double)a->temp_draft_all;
+      list_distribution(did, a->draft_val, a->dtype, off, Md, a->kind, Tk, p);
+      Race draft;
+      for (int64_t e = 0; e < Md; ++e) {
+        if (did[e] < 0) continue;
+        const double S = race_time(shared_word(a->seed, row, (uint32_t)k, (uint64_t)did[e]));
+        draft.offer(p[e] > 0.0 ? S / p[e] : kInf, did[e], k);
+      }
+      for (int64_t e = 0; e < Mt; ++e) {
+        if (tid[e] < 0) continue;
+        const double S = race_time(shared_word(a->seed, row, (uint32_t)k, (uint64_t)tid[e]));
+        pool.offer(q[e] > 0.0 ? S / q[e] : kInf, tid[e], k);
+      }
+      xs[k] = draft.idx;
+      a->X[b * K + k] = (int32_t)draft.idx;
+      if (a->keyX) a->keyX[b * K + k] = draft.best;
+      if (a->gapX) a->gapX[b * K + k] = draft.rel_gap();
+    }
+    a->Y[b] = (int32_t)pool.idx;
+    if (a->keyY) a->keyY[b] = pool.best;
+    if (a->gapY) a->gapY[b] = pool.rel_gap();
+    int64_t match = -1;
+    if (pool.idx >= 0)
+      for (int64_t k = 0; k < K; ++k)
+        if (xs[k] == pool.idx) { match = k; break; }
+    a->accept[b] = (uint8_t)(match >= 0);
+    if (a->match_k) a->match_k[b] = (int32_t)match;
+  }
+  return 0;
 }
 
 // Algorithm 2 (Section 4.2), the verification loop, for S independent sequences.
