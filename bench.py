@@ -9,6 +9,7 @@ the headline metric is quoted on.  Prints ONE JSON line.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5]
                     [--materialised] [--keys] [--no-cpu-baseline]
     python bench.py --workload verify     (Algorithm 2's verification loop, llc_verify)
+    python bench.py --workload topm       (Algorithm 1 on top-50 candidate lists, llc_couple_topm)
 """
 import argparse
 import ctypes
@@ -189,6 +190,79 @@ def bench_verify(args):
     print(json.dumps(result))
 
 
+def bench_topm(args):
+    import torch
+    import oracle
+    import paper_2506_05632_amd as llc
+    from paper_2506_05632_amd import workloads
+
+    dev = "cuda:0"
+    w = workloads.make_topm("top50", dev)
+    out = {"X": torch.empty(w.B, w.K, dtype=torch.int32, device=dev),
+           "Y": torch.empty(w.B, dtype=torch.int32, device=dev),
+           "accept": torch.empty(w.B, dtype=torch.uint8, device=dev),
+           "match_k": torch.empty(w.B, dtype=torch.int32, device=dev)}
+    ev = HipEvents(args.steps)
+
+    def step(i=None):
+        llc.llc_couple_topm(w.draft_ids, w.draft_val, w.target_ids, w.target_val, w.K,
+                            seed=w.seed + (0 if i is None else i), out=out,
+                            events=None if i is None else ev.pairs[i])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = [ev.elapsed_ms(i) for i in range(args.steps)]
+    ev.close()
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+    kern_s = sum(kern_ms) / len(kern_ms) / 1e3
+    elems = w.elems
+    # every key is evaluated exactly: per (k, entry) and side two Philox blocks (40 multiplies,
+    # 40 three-input xors) and two fp64 logarithms; the lists (id + value) are read once
+    alg_bytes = (w.draft_ids.numel() + w.target_ids.numel()) * (4 + w.draft_val.element_size())
+    alg_ops = 2 * 80.0
+    alu = alg_ops * elems / kern_s / 1e12
+    hbm = alg_bytes / kern_s / 1e9
+    roofline = {"bound": "alu", "achieved": alu, "peak": ALU_PEAK_TLANEOPS, "unit": "Tlane-op/s",
+                "frac": alu / ALU_PEAK_TLANEOPS, "kernel": "topm_kernel", "traffic": None,
+                "kernel_ms": kern_s * 1e3, "kernel_ms_min": min(kern_ms), "algorithmic_bytes": alg_bytes,
+                "algorithmic_lane_ops_per_elem": alg_ops, "hbm_frac": hbm / HBM_PEAK_GBS,
+                "alu_frac": alu / ALU_PEAK_TLANEOPS,
+                "note": "a few hundred candidates per row: the call is bound by launch latency, not by a roofline"}
+    result = {
+        "metric": "Gelem/s (B*K*M) of list Gumbel-max coupling on top-M candidate lists",
+        "value": elems / (wall / args.steps) / 1e9, "unit": "Gelem/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32+f64 (Philox words, every key in fp64)", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "K": w.K, "M": w.M, "V": w.V,
+                   "input_dtype": str(w.dtype), "outputs": "X,Y,accept,match_k",
+                   "accept_rate": float(out["accept"].float().mean())},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        cores = oracle.threads()
+        args_cpu = [t.cpu().numpy() for t in (w.draft_ids, w.draft_val, w.target_ids, w.target_val)]
+        reps, t0 = 0, time.perf_counter()
+        while time.perf_counter() - t0 < 5.0:
+            oracle.couple_topm(*args_cpu, w.K, seed=w.seed + reps)
+            reps += 1
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": reps * elems / dt / 1e9, "unit": "Gelem/s", "cores": cores,
+                                  "kind": "oracle", "sample": f"{reps} passes over the whole workload, {dt:.2f} s wall, OpenMP over rows"}
+    print(json.dumps(result))
+
+
 def run_cpu_baseline(w, budget_s=12.0):
     import oracle
     kinds = {"logits": oracle.LOGITS, "probs": oracle.PROBS, "logw": oracle.LOGW}
@@ -221,7 +295,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=3)
-    ap.add_argument("--workload", choices=["couple", "verify"], default="couple")
+    ap.add_argument("--workload", choices=["couple", "verify", "topm"], default="couple")
     ap.add_argument("--rows", type=int, default=0, help="use only the first ROWS rows of the configuration")
     ap.add_argument("--materialised", action="store_true",
                     help="give the K i.i.d. drafts as a [B,K,V] tensor instead of one shared [B,V] row")
@@ -240,6 +314,9 @@ def main():
 
     if args.workload == "verify":
         bench_verify(args)
+        return
+    if args.workload == "topm":
+        bench_topm(args)
         return
 
     import torch

@@ -226,6 +226,7 @@ typedef struct llc_couple_topm_args {
   float *keyY;              /* [B]   optional */
   llc_stats *stats;         /* optional: exact_evals and degenerate are counted           */
   void *stream;
+  void *ev_begin, *ev_end;  /* optional hipEvent_t pair recorded around the kernel        */
 } llc_couple_topm_args;
 
 /* Algorithm 1 on a batch (Section 3).  Asynchronous on a->stream. */

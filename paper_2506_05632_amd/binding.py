@@ -18,7 +18,7 @@ LOGITS, PROBS, LOGW = 0, 1, 2
 FLAG_EXACT_SCAN = 1
 
 _KINDS = {"logits": LOGITS, "probs": PROBS, "logw": LOGW}
-EXPORTS = ["llc_couple", "llc_couple_is", "llc_verify", "llc_couple_workspace_size",
+EXPORTS = ["llc_couple", "llc_couple_is", "llc_couple_topm", "llc_verify", "llc_couple_workspace_size",
            "llc_verify_workspace_size", "llc_status_string", "llc_version"]
 
 
@@ -64,6 +64,24 @@ class CoupleIsArgs(ctypes.Structure):
     ]
 
 
+class TopmArgs(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int64), ("K", ctypes.c_int64), ("Md", ctypes.c_int64), ("Mt", ctypes.c_int64),
+        ("dtype", ctypes.c_int32), ("kind", ctypes.c_int32),
+        ("draft_ids", ctypes.c_void_p), ("draft_val", ctypes.c_void_p),
+        ("draft_stride_b", ctypes.c_int64), ("draft_stride_k", ctypes.c_int64),
+        ("target_ids", ctypes.c_void_p), ("target_val", ctypes.c_void_p),
+        ("target_stride_b", ctypes.c_int64),
+        ("temp_target", ctypes.c_float), ("temp_draft_all", ctypes.c_float),
+        ("temp_draft", ctypes.c_void_p),
+        ("seed", ctypes.c_uint64), ("row_offset", ctypes.c_uint64),
+        ("X", ctypes.c_void_p), ("Y", ctypes.c_void_p), ("accept", ctypes.c_void_p),
+        ("match_k", ctypes.c_void_p), ("keyX", ctypes.c_void_p), ("keyY", ctypes.c_void_p),
+        ("stats", ctypes.c_void_p), ("stream", ctypes.c_void_p),
+        ("ev_begin", ctypes.c_void_p), ("ev_end", ctypes.c_void_p),
+    ]
+
+
 class VerifyArgs(ctypes.Structure):
     _fields_ = [
         ("S", ctypes.c_int64), ("L", ctypes.c_int64), ("K", ctypes.c_int64), ("V", ctypes.c_int64),
@@ -101,6 +119,8 @@ def load():
         lib.llc_couple.restype = ctypes.c_int
         lib.llc_couple_is.argtypes = [ctypes.POINTER(CoupleIsArgs)]
         lib.llc_couple_is.restype = ctypes.c_int
+        lib.llc_couple_topm.argtypes = [ctypes.POINTER(TopmArgs)]
+        lib.llc_couple_topm.restype = ctypes.c_int
         lib.llc_verify.argtypes = [ctypes.POINTER(VerifyArgs)]
         lib.llc_verify.restype = ctypes.c_int
         lib.llc_couple_workspace_size.argtypes = [ctypes.c_int64] * 3
@@ -256,6 +276,79 @@ def llc_couple_is(logw_enc: torch.Tensor, logw_dec: torch.Tensor, *, seed: int =
     if scan_events is not None:
         a.ev_scan_begin, a.ev_scan_end = scan_events
     rc = lib.llc_couple_is(ctypes.byref(a))
+    if rc != 0:
+        raise LlcError(rc)
+    return out
+
+
+def llc_couple_topm(draft_ids: torch.Tensor, draft_val: torch.Tensor, target_ids: torch.Tensor,
+                    target_val: torch.Tensor, K: int, *, kind="logits", temp_target: float = 1.0,
+                    temp_draft: float = 1.0, temp_draft_per_k: Optional[torch.Tensor] = None,
+                    seed: int = 0, row_offset: int = 0, want_keys: bool = False,
+                    stats: Optional[torch.Tensor] = None, out: Optional[dict] = None,
+                    events=None) -> dict:
+    """Algorithm 1 on candidate lists (top-M form) on device tensors.
+
+    draft_ids / draft_val: [B,Md] (one list per row, shared by the K drafts) or [B,K,Md];
+    target_ids / target_val: [B,Mt]; ids int32 (negative = empty slot), values float32 or
+    bfloat16, ids and values of one side with identical strides.  Returns token ids X [B,K],
+    Y [B], accept [B] uint8, match_k [B] and, if asked, keyX, keyY.  Asynchronous.
+    """
+    lib = load()
+    for t in (draft_ids, draft_val, target_ids, target_val):
+        if not t.is_cuda:
+            raise ValueError("llc_couple_topm needs device tensors (there is no CPU path)")
+    if draft_ids.dtype != torch.int32 or target_ids.dtype != torch.int32:
+        raise ValueError("ids must be int32")
+    if draft_val.dtype != target_val.dtype or draft_val.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("values must both be float32 or both bfloat16")
+    if draft_ids.shape != draft_val.shape or target_ids.shape != target_val.shape or target_val.dim() != 2:
+        raise ValueError("ids and values must have the same shape; the target side is [B,Mt]")
+    if draft_ids.stride() != draft_val.stride() or target_ids.stride() != target_val.stride():
+        raise ValueError("ids and values of one side must have identical strides")
+    if draft_val.stride(-1) != 1 or target_val.stride(-1) != 1:
+        raise ValueError("last dimension must be contiguous")
+    B, Mt = target_val.shape
+    Md = draft_val.shape[-1]
+    if draft_val.dim() == 2:
+        if draft_val.shape[0] != B:
+            raise ValueError("draft lists must be [B,Md] or [B,K,Md]")
+        sb, sk = draft_val.stride(0), 0
+    else:
+        if tuple(draft_val.shape[:2]) != (B, K):
+            raise ValueError("draft lists must be [B,Md] or [B,K,Md]")
+        sb, sk = draft_val.stride(0), draft_val.stride(1)
+    dev = target_val.device
+    if out is None:
+        out = {"X": torch.empty(B, K, dtype=torch.int32, device=dev),
+               "Y": torch.empty(B, dtype=torch.int32, device=dev),
+               "accept": torch.empty(B, dtype=torch.uint8, device=dev),
+               "match_k": torch.empty(B, dtype=torch.int32, device=dev)}
+        if want_keys:
+            out["keyX"] = torch.empty(B, K, dtype=torch.float32, device=dev)
+            out["keyY"] = torch.empty(B, dtype=torch.float32, device=dev)
+    a = TopmArgs()
+    a.B, a.K, a.Md, a.Mt = B, K, Md, Mt
+    a.dtype = F32 if draft_val.dtype == torch.float32 else BF16
+    a.kind = _KINDS[kind]
+    a.draft_ids, a.draft_val = draft_ids.data_ptr(), draft_val.data_ptr()
+    a.draft_stride_b, a.draft_stride_k = sb, sk
+    a.target_ids, a.target_val = target_ids.data_ptr(), target_val.data_ptr()
+    a.target_stride_b = target_val.stride(0)
+    a.temp_target, a.temp_draft_all = temp_target, temp_draft
+    if temp_draft_per_k is not None:
+        if temp_draft_per_k.dtype != torch.float32 or temp_draft_per_k.numel() != K or not temp_draft_per_k.is_cuda:
+            raise ValueError("temp_draft_per_k must be K float32 values on the device")
+        a.temp_draft = temp_draft_per_k.data_ptr()
+    a.seed, a.row_offset = seed, row_offset
+    a.X, a.Y, a.accept = out["X"].data_ptr(), out["Y"].data_ptr(), out["accept"].data_ptr()
+    a.match_k = _ptr(out.get("match_k"))
+    a.keyX, a.keyY = _ptr(out.get("keyX")), _ptr(out.get("keyY"))
+    a.stats = _ptr(stats)
+    a.stream = _stream_handle(dev)
+    if events is not None:
+        a.ev_begin, a.ev_end = events
+    rc = lib.llc_couple_topm(ctypes.byref(a))
     if rc != 0:
         raise LlcError(rc)
     return out

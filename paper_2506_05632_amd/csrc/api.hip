@@ -292,6 +292,45 @@ int llc_couple(const llc_couple_args *a) {
   return LLC_OK;
 }
 
+int llc_couple_topm(const llc_couple_topm_args *a) {
+  if (a == nullptr) return LLC_E_NULL;
+  if (a->B < 0 || a->B > 0x7FFFFFFFLL || a->K < 1 || a->K > 1024 || a->Md < 1 || a->Md > 65536 ||
+      a->Mt < 1 || a->Mt > 65536)
+    return LLC_E_SHAPE;
+  if (a->B == 0) return LLC_OK;
+  if (a->draft_ids == nullptr || a->draft_val == nullptr || a->target_ids == nullptr ||
+      a->target_val == nullptr || a->X == nullptr || a->Y == nullptr || a->accept == nullptr)
+    return LLC_E_NULL;
+  if (a->draft_stride_b < 0 || a->draft_stride_k < 0 || a->target_stride_b < 0) return LLC_E_SHAPE;
+  if (a->dtype != LLC_F32 && a->dtype != LLC_BF16) return LLC_E_DTYPE;
+  if (a->kind != LLC_LOGITS && a->kind != LLC_PROBS && a->kind != LLC_LOGW) return LLC_E_DTYPE;
+  if (a->kind == LLC_LOGITS) {
+    if (!good_temp(a->temp_target)) return LLC_E_TEMP;
+    if (a->temp_draft == nullptr && !good_temp(a->temp_draft_all)) return LLC_E_TEMP;
+  }
+  const size_t esize = a->dtype == LLC_F32 ? 4 : 2;
+  if (((uintptr_t)a->draft_val % esize) != 0 || ((uintptr_t)a->target_val % esize) != 0 ||
+      ((uintptr_t)a->draft_ids % 4) != 0 || ((uintptr_t)a->target_ids % 4) != 0)
+    return LLC_E_ALIGN;
+  TopmParams p;
+  p.B = a->B; p.K = (int)a->K; p.Md = (int)a->Md; p.Mt = (int)a->Mt;
+  p.dtype = a->dtype; p.kind = a->kind;
+  p.draft_ids = a->draft_ids; p.draft_val = a->draft_val;
+  p.draft_stride_b = a->draft_stride_b; p.draft_stride_k = a->draft_stride_k;
+  p.target_ids = a->target_ids; p.target_val = a->target_val; p.target_stride_b = a->target_stride_b;
+  p.temp_target = a->temp_target; p.temp_draft_all = a->temp_draft_all;
+  p.temp_draft = a->kind == LLC_LOGITS ? a->temp_draft : nullptr;
+  p.seed_lo = (unsigned)a->seed; p.seed_hi = (unsigned)(a->seed >> 32);
+  p.row_offset = a->row_offset;
+  p.X = a->X; p.Y = a->Y; p.match_k = a->match_k; p.accept = a->accept;
+  p.keyX = a->keyX; p.keyY = a->keyY; p.stats = a->stats;
+  hipStream_t st = (hipStream_t)a->stream;
+  if (a->ev_begin != nullptr && hipEventRecord((hipEvent_t)a->ev_begin, st) != hipSuccess) return LLC_E_LAUNCH;
+  if (launch_topm(st, p) != hipSuccess) return LLC_E_LAUNCH;
+  if (a->ev_end != nullptr && hipEventRecord((hipEvent_t)a->ev_end, st) != hipSuccess) return LLC_E_LAUNCH;
+  return LLC_OK;
+}
+
 size_t llc_verify_workspace_size(int64_t S, int64_t L, int64_t K, int64_t V) {
   if (S < 0 || L < 0 || L > (1 << 20) || K > 64) return 0;
   const long long B = S * (L + 1);

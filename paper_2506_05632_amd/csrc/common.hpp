@@ -107,6 +107,27 @@ struct LseParams {
   double *lse;    // [B][K+1]
 };
 
+// Algorithm 1 on candidate lists: one workgroup per row, every key exact.
+struct TopmParams {
+  long long B;
+  int K, Md, Mt;
+  int dtype, kind;
+  const int32_t *draft_ids;
+  const void *draft_val;
+  long long draft_stride_b, draft_stride_k;
+  const int32_t *target_ids;
+  const void *target_val;
+  long long target_stride_b;
+  float temp_target, temp_draft_all;
+  const float *temp_draft;
+  unsigned seed_lo, seed_hi;
+  unsigned long long row_offset;
+  int32_t *X, *Y, *match_k;
+  uint8_t *accept;
+  float *keyX, *keyY;
+  llc_stats *stats;
+};
+
 // One launcher per (element type, draft layout); defined in scan_*.hip.
 // kt: drafts per workgroup pass (1, 2, 4, 8); probs: inputs are probabilities.
 hipError_t launch_scan_f32_shared(int kt, bool probs, unsigned grid, hipStream_t s, const ScanParams &p);
@@ -118,5 +139,6 @@ hipError_t launch_finalize(hipStream_t s, const FinalizeParams &p);
 hipError_t launch_lse(hipStream_t s, const LseParams &p);
 hipError_t launch_verify(hipStream_t s, const VerifyParams &p);
 hipError_t launch_fill(hipStream_t s, int32_t *dst, long long n, int32_t value);
+hipError_t launch_topm(hipStream_t s, const TopmParams &p);
 
 }  // namespace llc

@@ -197,3 +197,59 @@ def make_verify(name: str, device="cpu", sequences: Optional[int] = None) -> Ver
         same_prefix &= tokens[:, j].view(S, K, 1) == tokens[:, j].view(S, 1, K)
     return VerifyWorkload(f"verify_{name}_s{S}_l{L}_k{K}_v{V}", S, L, K, V, shp["dtype"], "logits",
                           target, tokens, shp["temp"], SAMPLER_SEED_BASE + 64, 0)
+
+
+@dataclass
+class TopmWorkload:
+    name: str
+    B: int
+    K: int
+    M: int
+    V: int
+    dtype: torch.dtype
+    draft_ids: torch.Tensor        # [B,M] int32 (one list per row) or [B,K,M]
+    draft_val: torch.Tensor
+    target_ids: torch.Tensor       # [B,M] int32
+    target_val: torch.Tensor
+    temp_target: float = 1.0
+    temp_draft: float = 1.0
+    seed: int = 0
+
+    @property
+    def elems(self) -> int:
+        return self.B * self.K * self.M
+
+
+TOPM_SHAPES = {
+    # the paper's deployment setting keeps the 50 most likely tokens of each model (Appendix D.1)
+    "top50": dict(B=1024, V=128256, K=8, M=50, dtype=torch.float32, distinct=False),
+    "top50_distinct_bf16": dict(B=256, V=32000, K=4, M=50, dtype=torch.bfloat16, distinct=True),
+    "top256": dict(B=64, V=32000, K=5, M=256, dtype=torch.float32, distinct=True),
+}
+
+
+def make_topm(name: str, device="cpu", rows: Optional[int] = None) -> TopmWorkload:
+    """Candidate lists: the M largest logits of Zipf-like target and draft rows (draft = target +
+    N(0, 0.5^2) per entry), with their token ids, in descending order of the logit."""
+    shp = TOPM_SHAPES[name]
+    B = rows if rows is not None else shp["B"]
+    V, K, M = shp["V"], shp["K"], shp["M"]
+    device = torch.device(device)
+    g = torch.Generator(device=device)
+    g.manual_seed(INPUT_SEED_BASE + 200 + sorted(TOPM_SHAPES).index(name))
+    tq = _zipf_logits(B, V, 0.5, g, device)
+    t_val, t_ids = tq.topk(M, dim=1)
+    if shp["distinct"]:
+        d_val = torch.empty(B, K, M, dtype=torch.float32, device=device)
+        d_ids = torch.empty(B, K, M, dtype=torch.int64, device=device)
+        for k in range(K):
+            td = tq + 0.5 * torch.randn(B, V, generator=g, device=device)
+            d_val[:, k], d_ids[:, k] = td.topk(M, dim=1)
+    else:
+        td = tq + 0.5 * torch.randn(B, V, generator=g, device=device)
+        d_val, d_ids = td.topk(M, dim=1)
+    dt = shp["dtype"]
+    return TopmWorkload(f"topm_{name}_b{B}_k{K}_m{M}", B, K, M, V, dt,
+                        d_ids.to(torch.int32).contiguous(), d_val.to(dt).contiguous(),
+                        t_ids.to(torch.int32).contiguous(), t_val.to(dt).contiguous(),
+                        1.0, 1.0, SAMPLER_SEED_BASE + 80)

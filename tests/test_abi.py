@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(binding.EXPORTS)
     for name in names:
         assert getattr(lib, name) is not None
-    assert llc.llc_version() == 101
+    assert llc.llc_version() == 102
     assert llc.llc_status_string(0) == "ok"
     assert "workspace" in llc.llc_status_string(-6)
 
@@ -39,7 +39,9 @@ def test_header_is_plain_c_and_matches_the_binding_layout(tmp_path):
         " sizeof(llc_couple_is_args), sizeof(llc_stats), offsetof(llc_couple_args, temp_draft),"
         " offsetof(llc_couple_args, workspace), offsetof(llc_couple_args, ev_scan_begin),"
         " offsetof(llc_couple_is_args, workspace), sizeof(llc_verify_args),"
-        " offsetof(llc_verify_args, tokens), offsetof(llc_verify_args, workspace)); return 0;}\n")
+        " offsetof(llc_verify_args, tokens), offsetof(llc_verify_args, workspace));"
+        " printf(\"%zu %zu %zu\\n\", sizeof(llc_couple_topm_args), offsetof(llc_couple_topm_args, temp_draft),"
+        " offsetof(llc_couple_topm_args, stream)); return 0;}\n")
     exe = tmp_path / "layout"
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
                     str(src), "-o", str(exe)], check=True)
@@ -48,7 +50,8 @@ def test_header_is_plain_c_and_matches_the_binding_layout(tmp_path):
             ctypes.sizeof(binding.LlcStats), binding.CoupleArgs.temp_draft.offset,
             binding.CoupleArgs.workspace.offset, binding.CoupleArgs.ev_scan_begin.offset,
             binding.CoupleIsArgs.workspace.offset, ctypes.sizeof(binding.VerifyArgs),
-            binding.VerifyArgs.tokens.offset, binding.VerifyArgs.workspace.offset]
+            binding.VerifyArgs.tokens.offset, binding.VerifyArgs.workspace.offset,
+            ctypes.sizeof(binding.TopmArgs), binding.TopmArgs.temp_draft.offset, binding.TopmArgs.stream.offset]
     assert got == want
 
 
@@ -150,3 +153,32 @@ def test_verify_null_struct_empty_batch_and_workspace_size():
     assert lib.llc_verify(ctypes.byref(_verify_args(S=0, target=None, Y=None))) == 0
     assert llc.llc_verify_workspace_size(3, 2, 2, 64) > llc.llc_couple_workspace_size(9, 2, 64)
     assert llc.llc_verify_workspace_size(3, 2, 65, 64) == 0
+
+
+def _topm_args(**kw):
+    a = binding.TopmArgs()
+    a.B, a.K, a.Md, a.Mt = 4, 2, 8, 8
+    a.dtype, a.kind = binding.F32, binding.LOGITS
+    a.draft_ids = a.target_ids = 0x1000
+    a.draft_val = a.target_val = 0x3000
+    a.draft_stride_b = a.target_stride_b = 8
+    a.temp_target = a.temp_draft_all = 1.0
+    a.X = a.Y = a.accept = 0x2000
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(draft_ids=None), -1), (dict(target_val=None), -1), (dict(accept=None), -1),
+    (dict(K=0), -2), (dict(K=1025), -2), (dict(Md=0), -2), (dict(Mt=70000), -2), (dict(B=-1), -2),
+    (dict(target_stride_b=-8), -2),
+    (dict(temp_draft_all=0.0), -3), (dict(temp_target=float("inf")), -3),
+    (dict(dtype=3), -4), (dict(kind=-1), -4),
+    (dict(draft_val=0x3002), -5), (dict(target_ids=0x1001), -5),
+])
+def test_topm_argument_errors_are_reported_before_any_launch(kw, code):
+    lib = llc.load()
+    assert lib.llc_couple_topm(ctypes.byref(_topm_args(**kw))) == code
+    assert lib.llc_couple_topm(None) == -1
+    assert lib.llc_couple_topm(ctypes.byref(_topm_args(B=0, draft_ids=None, X=None))) == 0

@@ -1,0 +1,112 @@
+"""GPU parity of llc_couple_topm (Algorithm 1 on candidate lists) against the CPU oracle (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2506_05632_amd as llc
+from paper_2506_05632_amd import workloads
+from parity_util import compare, to_host
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+_KIND = {"logits": oracle.LOGITS, "probs": oracle.PROBS, "logw": oracle.LOGW}
+
+
+def oracle_topm(d_ids, d_val, t_ids, t_val, K, **kw):
+    dv, dt = to_host(d_val)
+    tv, _ = to_host(t_val)
+    tk = kw.pop("temp_draft_per_k", None)
+    kind = _KIND[kw.pop("kind", "logits")]
+    return oracle.couple_topm(d_ids.cpu().contiguous().numpy(), dv, t_ids.cpu().contiguous().numpy(), tv, K,
+                              dtype=dt, kind=kind, temp_draft=None if tk is None else tk.cpu().numpy(),
+                              temp_draft_all=kw.pop("temp_draft", 1.0), **kw)
+
+
+@pytest.mark.parametrize("name", ["top50", "top50_distinct_bf16", "top256"])
+def test_topm_workloads_full(name):
+    w = workloads.make_topm(name, DEV)
+    stats = llc.new_stats(DEV)
+    gpu = llc.llc_couple_topm(w.draft_ids, w.draft_val, w.target_ids, w.target_val, w.K, seed=w.seed,
+                              want_keys=True, stats=stats)
+    torch.cuda.synchronize()
+    ref = oracle_topm(w.draft_ids, w.draft_val, w.target_ids, w.target_val, w.K, seed=w.seed)
+    near = compare(gpu, ref)
+    s = stats.cpu().numpy()
+    print(f"{w.name}: near-ties {near}, exact evaluations {s[1]}, accept rate {ref['accept'].mean():.3f}")
+    assert s[1] == 2 * w.elems and s[3] == 0
+    assert ref["accept"].mean() > 0.5
+    # the same answer as the dense sampler on rows that carry no mass off the lists (first rows)
+    n = min(w.B, 6)
+    dense_t = torch.full((n, w.V), float("-inf"), device=DEV)
+    dense_t.scatter_(1, w.target_ids[:n].long(), w.target_val[:n].float())
+    if w.draft_ids.dim() == 2:
+        dense_d = torch.full((n, w.V), float("-inf"), device=DEV)
+        dense_d.scatter_(1, w.draft_ids[:n].long(), w.draft_val[:n].float())
+    else:
+        dense_d = torch.full((n, w.K, w.V), float("-inf"), device=DEV)
+        dense_d.scatter_(2, w.draft_ids[:n].long(), w.draft_val[:n].float())
+    dense = llc.llc_couple(dense_d, dense_t, w.K, seed=w.seed)
+    for key in ("X", "Y", "accept"):
+        assert torch.equal(dense[key], gpu[key][:n]), key
+
+
+@pytest.mark.parametrize("kind", ["logits", "probs", "logw"])
+@pytest.mark.parametrize("K,Md,Mt", [(1, 1, 1), (3, 7, 130), (64, 65, 3), (1024, 2, 5)])
+def test_topm_shapes_kinds_and_temperatures(kind, K, Md, Mt):
+    g = torch.Generator(device=DEV).manual_seed(K * 7 + Md)
+    B, V = 9, 5000
+    t_ids = torch.randint(0, V, (B, Mt), generator=g, device=DEV, dtype=torch.int32)
+    d_ids = torch.randint(0, V, (B, K, Md), generator=g, device=DEV, dtype=torch.int32)
+    d_ids[:, :, 0] = t_ids[:, :1]                       # some overlap between the sides
+    t_val = 2 * torch.randn(B, Mt, generator=g, device=DEV)
+    d_val = 2 * torch.randn(B, K, Md, generator=g, device=DEV)
+    if kind == "probs":
+        t_val, d_val = t_val.exp(), d_val.exp()
+    temps = (0.5 + torch.rand(K, generator=g, device=DEV)).float()
+    kw = dict(kind=kind, temp_target=0.8, seed=31, row_offset=(1 << 40) + 5)
+    gpu = llc.llc_couple_topm(d_ids, d_val, t_ids, t_val, K, temp_draft_per_k=temps, want_keys=True, **kw)
+    torch.cuda.synchronize()
+    ref = oracle_topm(d_ids, d_val, t_ids, t_val, K, temp_draft_per_k=temps, **kw)
+    compare(gpu, ref)
+
+
+def test_topm_empty_slots_duplicates_strided_views_and_lists_without_mass():
+    g = torch.Generator(device=DEV).manual_seed(5)
+    B, K, Md, Mt, V = 12, 3, 33, 40, 900
+    big_ids = torch.randint(0, V, (B, K, Md + 5), generator=g, device=DEV, dtype=torch.int32)
+    big_val = torch.randn(B, K, Md + 5, generator=g, device=DEV)
+    d_ids, d_val = big_ids[:, :, 2:2 + Md], big_val[:, :, 2:2 + Md]      # odd offsets, padded rows
+    t_ids = torch.randint(0, V, (B, Mt), generator=g, device=DEV, dtype=torch.int32)
+    t_val = torch.randn(B, Mt, generator=g, device=DEV)
+    d_ids[:, :, 5] = -1; d_val[:, :, 5] = 80.0                            # empty slot with a huge value
+    d_ids[:, 0, 7] = d_ids[:, 0, 8]                                       # duplicate ids
+    t_ids[0, :] = -1                                                      # target list without entries
+    d_val[1, 1, :] = float("-inf")                                        # draft list without mass
+    t_val[2, 3] = float("nan"); d_val[2, 0, 1] = float("inf")
+    stats = llc.new_stats(DEV)
+    gpu = llc.llc_couple_topm(d_ids, d_val, t_ids, t_val, K, seed=8, want_keys=True, stats=stats)
+    torch.cuda.synchronize()
+    ref = oracle_topm(d_ids, d_val, t_ids, t_val, K, seed=8)
+    compare(gpu, ref)
+    assert gpu["Y"][0].item() == -1 and gpu["accept"][0].item() == 0 and gpu["X"][1, 1].item() == -1
+    assert stats.cpu().numpy()[3] == 2
+    # bf16 values, one list per row shared by the K drafts
+    ids0 = d_ids[:, 0].contiguous()
+    val0 = d_val[:, 0].contiguous().to(torch.bfloat16)
+    gpu = llc.llc_couple_topm(ids0, val0, t_ids, t_val.to(torch.bfloat16), K, seed=8, want_keys=True)
+    torch.cuda.synchronize()
+    ref = oracle_topm(ids0, val0, t_ids, t_val.to(torch.bfloat16), K, seed=8)
+    compare(gpu, ref)
+
+
+def test_topm_error_codes_and_empty_batch_on_device():
+    ids = torch.zeros(2, 4, dtype=torch.int32, device=DEV)
+    val = torch.zeros(2, 4, device=DEV)
+    with pytest.raises(llc.LlcError) as e:
+        llc.llc_couple_topm(ids, val, ids, val, 2000)
+    assert e.value.code == -2
+    with pytest.raises(ValueError):
+        llc.llc_couple_topm(ids.long(), val, ids, val, 2)
+    out = llc.llc_couple_topm(ids[:0], val[:0], ids[:0], val[:0], 3)
+    assert out["X"].shape == (0, 3)
