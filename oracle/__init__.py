@@ -99,6 +99,11 @@ def lib():
         _lib.llc_couple_is_ref.restype = ctypes.c_int
         _lib.llc_verify_ref.argtypes = [ctypes.POINTER(_VerifyArgs)]
         _lib.llc_verify_ref.restype = ctypes.c_int
+        _lib.llc_compress_select_ref.argtypes = (
+            [ctypes.c_int64] * 3 + [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
+                                    ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64,
+                                    ctypes.c_uint64] + [ctypes.c_void_p] * 9 + [ctypes.c_int32])
+        _lib.llc_compress_select_ref.restype = ctypes.c_int
         _lib.llc_couple_topm_ref.argtypes = [ctypes.POINTER(_TopmArgs)]
         _lib.llc_couple_topm_ref.restype = ctypes.c_int
     return _lib
@@ -295,4 +300,34 @@ def couple_topm(draft_ids, draft_val, target_ids, target_val, K, *, dtype=F32, k
     a.threads = threads
     if lib().llc_couple_topm_ref(ctypes.byref(a)) != 0:
         raise ValueError("llc_couple_topm_ref rejected its arguments")
+    return out
+
+
+def compress_select(logw_enc, logw_dec, bins, *, seed=0, row_offset=0, threads=0):
+    """Index selection of the compression scheme with bins (Section 5.1 / Appendix C).
+
+    logw_enc [B,N], logw_dec [B,L,N] fp32, bins [B,N] uint8.  Returns Y, message (the bin of Y),
+    X [B,L] (drawn among the candidates of that bin), accept, match_k, keys and gaps."""
+    enc = _check_input(logw_enc, F32)
+    dec = _check_input(logw_dec, F32)
+    bins = np.asarray(bins)
+    assert bins.dtype == np.uint8 and bins.strides[-1] == 1
+    B, N = enc.shape
+    L = dec.shape[1]
+    assert dec.shape == (B, L, N) and bins.shape == (B, N)
+    out = {
+        "X": np.full((B, L), -2, np.int32), "Y": np.full(B, -2, np.int32),
+        "message": np.full(B, -2, np.int32),
+        "accept": np.zeros(B, np.uint8), "match_k": np.full(B, -2, np.int32),
+        "keyX": np.zeros((B, L)), "keyY": np.zeros(B),
+        "gapX": np.zeros((B, L)), "gapY": np.zeros(B),
+    }
+    rc = lib().llc_compress_select_ref(
+        B, L, N, enc.ctypes.data, enc.strides[0] // 4, dec.ctypes.data, dec.strides[0] // 4,
+        dec.strides[1] // 4, bins.ctypes.data, bins.strides[0], seed, row_offset,
+        out["X"].ctypes.data, out["Y"].ctypes.data, out["message"].ctypes.data,
+        out["accept"].ctypes.data, out["match_k"].ctypes.data, out["keyX"].ctypes.data,
+        out["keyY"].ctypes.data, out["gapX"].ctypes.data, out["gapY"].ctypes.data, threads)
+    if rc != 0:
+        raise ValueError("llc_compress_select_ref rejected its arguments")
     return out

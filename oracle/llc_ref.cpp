@@ -339,6 +339,76 @@ int llc_couple_is_ref(int64_t B, int64_t L, int64_t N,
   return llc_couple_ref(&a);
 }
 
+// Index selection of the list-decoding compression scheme with bins (Section 5.1; Appendix C for
+// importance weights).  Candidate i carries a bin l_i.  The encoder draws Y = argmin_i min_l
+// S_i^(l) / lambda_q,i over all candidates and sends the message M = l_Y; decoder l draws
+// X^(l) = argmin_i S_i^(l) / lambda_p,i^(l) over the candidates with l_i = M only (its weights
+// carry the indicator 1{l_i = M} and are normalised over those candidates).  bins: [B,N] uint8.
+int llc_compress_select_ref(int64_t B, int64_t L, int64_t N,
+                            const float *logw_enc, int64_t enc_stride_b,
+                            const float *logw_dec, int64_t dec_stride_b, int64_t dec_stride_l,
+                            const uint8_t *bins, int64_t bins_stride_b,
+                            uint64_t seed, uint64_t row_offset,
+                            int32_t *X, int32_t *Y, int32_t *message, uint8_t *accept, int32_t *match_l,
+                            double *keyX, double *keyY, double *gapX, double *gapY, int32_t threads) {
+  if (!logw_enc || !logw_dec || !bins || !X || !Y || !accept) return -1;
+  if (B < 0 || L < 1 || N < 1) return -1;
+  int nthreads = threads;
+#ifdef _OPENMP
+  if (nthreads <= 0) nthreads = omp_get_max_threads();
+#else
+  nthreads = 1;
+#endif
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+  for (int64_t b = 0; b < B; ++b) {
+    const uint64_t row = row_offset + (uint64_t)b;
+    const uint8_t *bin = bins + b * bins_stride_b;
+    std::vector<double> q, p;
+    // encoder: lambda_q over all N candidates, pool over the L sets of race times
+    row_distribution(logw_enc, DT_F32, b * enc_stride_b, N, KIND_LOGW, 1.0, q);
+    Race pool;
+    for (int64_t l = 0; l < L; ++l)
+      for (int64_t i = 0; i < N; ++i) {
+        const double S = race_time(shared_word(seed, row, (uint32_t)l, (uint64_t)i));
+        pool.offer(q[i] > 0.0 ? S / q[i] : kInf, i, l);
+      }
+    Y[b] = (int32_t)pool.idx;
+    if (keyY) keyY[b] = pool.best;
+    if (gapY) gapY[b] = pool.rel_gap();
+    const int msg = pool.idx >= 0 ? (int)bin[pool.idx] : -1;
+    if (message) message[b] = msg;
+    // decoders: lambda_p^(l) lives on the candidates of the announced bin
+    int64_t match = -1;
+    for (int64_t l = 0; l < L; ++l) {
+      p.assign((size_t)N, 0.0);
+      double zmax = -kInf;
+      for (int64_t i = 0; i < N; ++i) {
+        double z = (double)logw_dec[b * dec_stride_b + l * dec_stride_l + i];
+        if (msg < 0 || (int)bin[i] != msg || std::isnan(z) || z == kInf) z = -kInf;
+        p[i] = z;
+        if (z > zmax) zmax = z;
+      }
+      double sum = 0.0;
+      if (zmax > -kInf)
+        for (int64_t i = 0; i < N; ++i) sum += std::exp(p[i] - zmax);
+      Race dec;
+      for (int64_t i = 0; i < N; ++i) {
+        const double w = zmax > -kInf ? std::exp(p[i] - zmax - std::log(sum)) : 0.0;
+        if (!(w > 0.0)) continue;
+        const double S = race_time(shared_word(seed, row, (uint32_t)l, (uint64_t)i));
+        dec.offer(S / w, i, l);
+      }
+      X[b * L + l] = (int32_t)dec.idx;
+      if (keyX) keyX[b * L + l] = dec.best;
+      if (gapX) gapX[b * L + l] = dec.rel_gap();
+      if (match < 0 && dec.idx >= 0 && dec.idx == pool.idx) match = l;
+    }
+    accept[b] = (uint8_t)(match >= 0);
+    if (match_l) match_l[b] = (int32_t)match;
+  }
+  return 0;
+}
+
 // Algorithm 1 on candidate lists (Section 4.4).  draft_ids / draft_val: [B,K,Md] (stride_k == 0:
 // one list per row), target_ids / target_val: [B,Mt].  A negative id marks an empty slot.  The
 // distribution a list denotes lives on its entries only: softmax of the listed logits, the
