@@ -263,7 +263,7 @@ def bench_topm(args):
     print(json.dumps(result))
 
 
-def run_cpu_baseline(w, budget_s=12.0):
+def run_cpu_baseline(w, budget_s=12.0, bins=None):
     import oracle
     kinds = {"logits": oracle.LOGITS, "probs": oracle.PROBS, "logw": oracle.LOGW}
     cores = oracle.threads()
@@ -271,6 +271,11 @@ def run_cpu_baseline(w, budget_s=12.0):
     def run(rows):
         d, dt = _to_host(w.draft[:rows])
         t, _ = _to_host(w.target[:rows])
+        if bins is not None:
+            bb = bins[:rows].cpu().numpy()
+            t0 = time.perf_counter()
+            oracle.compress_select(t, d, bb, seed=w.seed, row_offset=w.row_offset)
+            return time.perf_counter() - t0
         t0 = time.perf_counter()
         oracle.couple(d, t, w.K, dtype=dt, kind=kinds[w.kind], temp_target=w.temp_target,
                       temp_draft_all=w.temp_draft, seed=w.seed, row_offset=w.row_offset)
@@ -296,6 +301,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--workload", choices=["couple", "verify", "topm"], default="couple")
+    ap.add_argument("--bins", type=int, default=0,
+                    help="with --config 5: give every candidate one of BINS bins and run the compression "
+                         "scheme's binned selection (llc_compress_select) instead of llc_couple_is")
     ap.add_argument("--rows", type=int, default=0, help="use only the first ROWS rows of the configuration")
     ap.add_argument("--materialised", action="store_true",
                     help="give the K i.i.d. drafts as a [B,K,V] tensor instead of one shared [B,V] row")
@@ -338,7 +346,20 @@ def main():
         out["keyY"] = torch.empty(w.B, dtype=torch.float32, device=dev)
     ev = HipEvents(args.steps)
 
+    bins = None
+    if args.bins:
+        assert args.config == 5 and 1 <= args.bins <= 256, "--bins goes with --config 5"
+        gb = torch.Generator(device=dev)
+        gb.manual_seed(4242)
+        bins = torch.randint(0, args.bins, (w.B, w.V), generator=gb, device=dev, dtype=torch.uint8)
+        out["message"] = torch.empty(w.B, dtype=torch.int32, device=dev)
+
     def step(i=None):
+        if bins is not None:
+            llc.llc_compress_select(w.target, w.draft, bins, seed=w.seed + (0 if i is None else i),
+                                    row_offset=w.row_offset, workspace=ws, out=out, v_chunks=args.v_chunks,
+                                    k_tile=args.k_tile, scan_events=None if i is None else ev.pairs[i])
+            return
         llc.llc_couple(draft, w.target, w.K, kind=w.kind, temp_target=w.temp_target,
                        temp_draft=w.temp_draft, seed=w.seed + (0 if i is None else i),
                        row_offset=w.row_offset, workspace=ws, out=out,
@@ -369,11 +390,16 @@ def main():
     alg_bytes = algorithmic_bytes(w, args.materialised)
     alg_ops = algorithmic_lane_ops(w.K)
     alu_achieved = alg_ops * elems / scan_avg_s / 1e12
-    hbm_achieved = alg_bytes / scan_avg_s / 1e9
-    alu_frac, hbm_frac = alu_achieved / ALU_PEAK_TLANEOPS, hbm_achieved / HBM_PEAK_GBS
     name = w.name + ("_materialised" if args.materialised and w.shared_draft else "")
+    if bins is not None:
+        name += f"_bins{args.bins}"
+        # the timed kernel is the decoders' scan: their rows and one byte per candidate (the
+        # encoder's pass before it reads its row once more and is part of the step, not of this figure)
+        alg_bytes = w.B * w.K * w.V * 4 + w.B * w.V
     if args.rows:
         name += f"_rows{w.B}"
+    hbm_achieved = alg_bytes / scan_avg_s / 1e9
+    alu_frac, hbm_frac = alu_achieved / ALU_PEAK_TLANEOPS, hbm_achieved / HBM_PEAK_GBS
     # the ceiling that binds this workload is the one it sits closer to
     if hbm_frac >= alu_frac:
         roofline = {"bound": "hbm", "achieved": hbm_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -401,7 +427,7 @@ def main():
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = run_cpu_baseline(w)
+        result["cpu_baseline"] = run_cpu_baseline(w, bins=bins)
     print(json.dumps(result))
 
 

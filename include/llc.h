@@ -28,7 +28,7 @@
 extern "C" {
 #endif
 
-#define LLC_VERSION 102
+#define LLC_VERSION 103
 
 enum {
   LLC_OK = 0,
@@ -139,6 +139,40 @@ typedef struct llc_couple_is_args {
   void *ev_scan_begin, *ev_scan_end; /* as in llc_couple_args */
 } llc_couple_is_args;
 
+/* Arguments of llc_compress_select: the index selection of the list-decoding compression
+ * scheme with bins (Section 5.1; Appendix C for importance weights).  Candidate i of row b
+ * carries the bin bins[b*bins_stride_b + i] (one byte, so L_max <= 256).  The encoder draws
+ * Y[b] = argmin_i min_l S_i^(l) / lambda_q,i over all N candidates and announces
+ * message[b] = the bin of Y[b]; decoder l draws X[b,l] = argmin_i S_i^(l) / lambda_p,i^(l)
+ * over the candidates of that bin only (its weights hold the indicator 1{l_i = message} and
+ * are normalised over that bin).  accept[b] = 1 iff some decoder recovers Y[b].  Two passes
+ * over the inputs (encoder, then decoders) on the same stream; otherwise as llc_couple_is,
+ * with which it coincides when all candidates share one bin.
+ */
+typedef struct llc_compress_select_args {
+  int64_t B, L, N;
+  const float *logw_enc;    /* device [B,N]   */
+  int64_t enc_stride_b;
+  const float *logw_dec;    /* device [B,L,N] */
+  int64_t dec_stride_b, dec_stride_l;
+  const uint8_t *bins;      /* device [B,N]   */
+  int64_t bins_stride_b;
+  uint64_t seed, row_offset;
+  int32_t *X;               /* [B,L] required */
+  int32_t *Y;               /* [B]   required */
+  uint8_t *accept;          /* [B]   required */
+  int32_t *message;         /* [B]   optional */
+  int32_t *match_l;         /* [B]   optional */
+  float *keyX;              /* [B,L] optional: S / lambda_p with lambda_p normalised over the bin */
+  float *keyY;              /* [B]   optional */
+  llc_stats *stats;
+  void *workspace;          /* >= llc_couple_workspace_size(B, L, N) */
+  size_t workspace_bytes;
+  void *stream;
+  int32_t flags, v_chunks, k_tile;
+  void *ev_scan_begin, *ev_scan_end; /* recorded around the decoders' scan */
+} llc_compress_select_args;
+
 /* Arguments of llc_verify: the verification loop of Algorithm 2 (Section 4.2,
  * drafter-invariant multi-draft speculative decoding) for S independent sequences, each
  * with K drafts of L tokens.
@@ -234,6 +268,9 @@ int llc_couple(const llc_couple_args *a);
 
 /* Appendix C's index selection at the encoder and the L decoders.  Asynchronous. */
 int llc_couple_is(const llc_couple_is_args *a);
+
+/* Binned index selection of the compression scheme (Section 5.1, Appendix C).  Asynchronous. */
+int llc_compress_select(const llc_compress_select_args *a);
 
 /* Algorithm 1 on top-M candidate lists (Section 4.4).  Asynchronous. */
 int llc_couple_topm(const llc_couple_topm_args *a);

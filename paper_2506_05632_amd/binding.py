@@ -18,7 +18,7 @@ LOGITS, PROBS, LOGW = 0, 1, 2
 FLAG_EXACT_SCAN = 1
 
 _KINDS = {"logits": LOGITS, "probs": PROBS, "logw": LOGW}
-EXPORTS = ["llc_couple", "llc_couple_is", "llc_couple_topm", "llc_verify", "llc_couple_workspace_size",
+EXPORTS = ["llc_couple", "llc_couple_is", "llc_couple_topm", "llc_compress_select", "llc_verify", "llc_couple_workspace_size",
            "llc_verify_workspace_size", "llc_status_string", "llc_version"]
 
 
@@ -56,6 +56,25 @@ class CoupleIsArgs(ctypes.Structure):
         ("seed", ctypes.c_uint64), ("row_offset", ctypes.c_uint64),
         ("X", ctypes.c_void_p), ("Y", ctypes.c_void_p), ("accept", ctypes.c_void_p),
         ("match_l", ctypes.c_void_p), ("keyX", ctypes.c_void_p), ("keyY", ctypes.c_void_p),
+        ("stats", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("stream", ctypes.c_void_p),
+        ("flags", ctypes.c_int32), ("v_chunks", ctypes.c_int32), ("k_tile", ctypes.c_int32),
+        ("ev_scan_begin", ctypes.c_void_p), ("ev_scan_end", ctypes.c_void_p),
+    ]
+
+
+class CompressSelectArgs(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int64), ("L", ctypes.c_int64), ("N", ctypes.c_int64),
+        ("logw_enc", ctypes.c_void_p), ("enc_stride_b", ctypes.c_int64),
+        ("logw_dec", ctypes.c_void_p),
+        ("dec_stride_b", ctypes.c_int64), ("dec_stride_l", ctypes.c_int64),
+        ("bins", ctypes.c_void_p), ("bins_stride_b", ctypes.c_int64),
+        ("seed", ctypes.c_uint64), ("row_offset", ctypes.c_uint64),
+        ("X", ctypes.c_void_p), ("Y", ctypes.c_void_p), ("accept", ctypes.c_void_p),
+        ("message", ctypes.c_void_p), ("match_l", ctypes.c_void_p),
+        ("keyX", ctypes.c_void_p), ("keyY", ctypes.c_void_p),
         ("stats", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("stream", ctypes.c_void_p),
@@ -119,6 +138,8 @@ def load():
         lib.llc_couple.restype = ctypes.c_int
         lib.llc_couple_is.argtypes = [ctypes.POINTER(CoupleIsArgs)]
         lib.llc_couple_is.restype = ctypes.c_int
+        lib.llc_compress_select.argtypes = [ctypes.POINTER(CompressSelectArgs)]
+        lib.llc_compress_select.restype = ctypes.c_int
         lib.llc_couple_topm.argtypes = [ctypes.POINTER(TopmArgs)]
         lib.llc_couple_topm.restype = ctypes.c_int
         lib.llc_verify.argtypes = [ctypes.POINTER(VerifyArgs)]
@@ -276,6 +297,57 @@ def llc_couple_is(logw_enc: torch.Tensor, logw_dec: torch.Tensor, *, seed: int =
     if scan_events is not None:
         a.ev_scan_begin, a.ev_scan_end = scan_events
     rc = lib.llc_couple_is(ctypes.byref(a))
+    if rc != 0:
+        raise LlcError(rc)
+    return out
+
+
+def llc_compress_select(logw_enc: torch.Tensor, logw_dec: torch.Tensor, bins: torch.Tensor, *,
+                        seed: int = 0, row_offset: int = 0, want_keys: bool = False,
+                        stats: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                        out: Optional[dict] = None, flags: int = 0, v_chunks: int = 0, k_tile: int = 0,
+                        scan_events=None) -> dict:
+    """Binned index selection of the compression scheme: logw_enc [B,N], logw_dec [B,L,N]
+    float32, bins [B,N] uint8, all on the device.  Returns Y, message, X [B,L], accept, match_k
+    and, if asked, keyX, keyY.  Asynchronous on torch's current stream."""
+    lib = load()
+    if not (logw_enc.is_cuda and logw_dec.is_cuda and bins.is_cuda):
+        raise ValueError("llc_compress_select needs device tensors (there is no CPU path)")
+    if logw_enc.dtype != torch.float32 or logw_dec.dtype != torch.float32 or bins.dtype != torch.uint8:
+        raise ValueError("log-weights must be float32, bins uint8")
+    B, N = logw_enc.shape
+    L = logw_dec.shape[1]
+    if (tuple(logw_dec.shape) != (B, L, N) or tuple(bins.shape) != (B, N) or logw_enc.stride(-1) != 1
+            or logw_dec.stride(-1) != 1 or bins.stride(-1) != 1):
+        raise ValueError("logw_dec must be [B,L,N], bins [B,N], last dimensions contiguous")
+    dev = logw_enc.device
+    if out is None:
+        out = {"X": torch.empty(B, L, dtype=torch.int32, device=dev),
+               "Y": torch.empty(B, dtype=torch.int32, device=dev),
+               "message": torch.empty(B, dtype=torch.int32, device=dev),
+               "accept": torch.empty(B, dtype=torch.uint8, device=dev),
+               "match_k": torch.empty(B, dtype=torch.int32, device=dev)}
+        if want_keys:
+            out["keyX"] = torch.empty(B, L, dtype=torch.float32, device=dev)
+            out["keyY"] = torch.empty(B, dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = new_workspace(B, L, N, dev)
+    a = CompressSelectArgs()
+    a.B, a.L, a.N = B, L, N
+    a.logw_enc, a.enc_stride_b = logw_enc.data_ptr(), logw_enc.stride(0)
+    a.logw_dec, a.dec_stride_b, a.dec_stride_l = logw_dec.data_ptr(), logw_dec.stride(0), logw_dec.stride(1)
+    a.bins, a.bins_stride_b = bins.data_ptr(), bins.stride(0)
+    a.seed, a.row_offset = seed, row_offset
+    a.X, a.Y, a.accept = out["X"].data_ptr(), out["Y"].data_ptr(), out["accept"].data_ptr()
+    a.message, a.match_l = _ptr(out.get("message")), _ptr(out.get("match_k"))
+    a.keyX, a.keyY = _ptr(out.get("keyX")), _ptr(out.get("keyY"))
+    a.stats = _ptr(stats)
+    a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
+    a.stream = _stream_handle(dev)
+    a.flags, a.v_chunks, a.k_tile = flags, v_chunks, k_tile
+    if scan_events is not None:
+        a.ev_scan_begin, a.ev_scan_end = scan_events
+    rc = lib.llc_compress_select(ctypes.byref(a))
     if rc != 0:
         raise LlcError(rc)
     return out

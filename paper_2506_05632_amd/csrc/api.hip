@@ -99,7 +99,11 @@ struct ScanJob {
   uint64_t seed, row_offset;
   bool no_pool;      // draft-side reductions only
   bool need_lse;     // also compute the row normalisers (log kinds)
+  bool no_draft = false;    // pool only
   bool force_perk = false;  // every draft has its own row even if draft_stride_k == 0
+  const uint8_t *bins = nullptr;  // binned candidates: mask of the draft rows (see ScanParams)
+  long long bins_stride_b = 0;
+  const int32_t *bin_of = nullptr;
   int flags, v_chunks, k_tile;
   llc_stats *stats;
   void *workspace;
@@ -172,6 +176,7 @@ int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
     lp.per_k = shared ? 0 : 1;
     lp.with_target = j.no_pool ? 0 : 1;
     lp.vector_loads = vec ? 1 : 0;
+    lp.bins = j.bins; lp.bins_stride_b = j.bins_stride_b; lp.bin_of = j.bin_of;
     lp.lse = part.lse;
     if (launch_lse(st, lp) != hipSuccess) return LLC_E_LAUNCH;
   }
@@ -185,6 +190,7 @@ int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
 
   ScanParams sp;
   sp.shared_tau = shared_tau;
+  sp.bins = j.bins; sp.bins_stride_b = j.bins_stride_b; sp.bin_of = j.bin_of;
   sp.draft = j.draft; sp.target = j.target;
   sp.map = j.map; sp.draft_stride_k = j.draft_stride_k;
   sp.B = j.B; sp.K = (int)j.K; sp.V = (int)j.V;
@@ -197,6 +203,7 @@ int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
   sp.vector_loads = vec ? 1 : 0;
   sp.force_exact = (j.flags & LLC_FLAG_EXACT_SCAN) ? 1 : 0;
   sp.no_pool = j.no_pool ? 1 : 0;
+  sp.no_draft = j.no_draft ? 1 : 0;
   sp.out = part;
   sp.stats = j.stats;
 
@@ -287,8 +294,71 @@ int llc_couple(const llc_couple_args *a) {
   fp.in = part;
   fp.X = a->X; fp.Y = a->Y; fp.match_k = a->match_k; fp.accept = a->accept;
   fp.keyX = a->keyX; fp.keyY = a->keyY; fp.log_keyX = nullptr;
+  fp.y_given = 0; fp.bins = nullptr; fp.bins_stride_b = 0; fp.message = nullptr;
   fp.stats = a->stats;
   if (launch_finalize((hipStream_t)a->stream, fp) != hipSuccess) return LLC_E_LAUNCH;
+  return LLC_OK;
+}
+
+int llc_compress_select(const llc_compress_select_args *a) {
+  if (a == nullptr) return LLC_E_NULL;
+  if (!shape_ok(a->B, a->L, a->N)) return LLC_E_SHAPE;
+  if (a->B == 0) return LLC_OK;
+  if (a->logw_enc == nullptr || a->logw_dec == nullptr || a->bins == nullptr || a->X == nullptr ||
+      a->Y == nullptr || a->accept == nullptr)
+    return LLC_E_NULL;
+  if (a->enc_stride_b < 0 || a->dec_stride_b < 0 || a->dec_stride_l < 0 || a->bins_stride_b < 0)
+    return LLC_E_SHAPE;
+  hipStream_t st = (hipStream_t)a->stream;
+
+  // pass 1, the encoder: Y = the pool argmin under lambda_q over the L sets of race times (the
+  // shared-proposal scan without a draft side; its X comes out as -1 and pass 2 overwrites it)
+  ScanJob j;
+  j.B = a->B; j.K = a->L; j.V = a->N; j.dtype = LLC_F32; j.kind = LLC_LOGW;
+  j.draft = a->logw_enc; j.target = a->logw_enc;
+  j.map = plain_rows(a->enc_stride_b, a->enc_stride_b);
+  j.draft_stride_k = 0;
+  j.temp_target = 1.0f; j.temp_draft_all = 1.0f; j.temp_draft = nullptr;
+  j.seed = a->seed; j.row_offset = a->row_offset;
+  j.no_pool = false;
+  j.no_draft = true;
+  j.need_lse = a->keyY != nullptr;
+  j.flags = a->flags; j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;
+  j.stats = a->stats; j.workspace = a->workspace; j.workspace_bytes = a->workspace_bytes;
+  j.stream = a->stream; j.ev_begin = nullptr; j.ev_end = nullptr;
+  j.extra_bytes = 0;
+  Plan pl;
+  Partials part;
+  int rc = run_scan(j, &pl, &part, nullptr);
+  if (rc != LLC_OK) return rc;
+  FinalizeParams fp;
+  fp.B = a->B; fp.K = (int)a->L; fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
+  fp.log_kind = 1;
+  fp.in = part;
+  fp.X = a->X; fp.Y = a->Y; fp.match_k = nullptr; fp.accept = a->accept;
+  fp.keyX = nullptr; fp.keyY = a->keyY; fp.log_keyX = nullptr;
+  fp.y_given = 0; fp.bins = nullptr; fp.bins_stride_b = 0; fp.message = nullptr;
+  fp.stats = nullptr;  // pass 1's draft side is not part of the result: its reductions are not counted
+  if (launch_finalize(st, fp) != hipSuccess) return LLC_E_LAUNCH;
+
+  // pass 2, the decoders: X^(l) = argmin under lambda_p^(l) over the candidates of Y's bin
+  j.draft = a->logw_dec; j.target = a->logw_enc;
+  j.map = plain_rows(a->dec_stride_b, a->enc_stride_b);
+  j.draft_stride_k = a->dec_stride_l;
+  j.no_pool = true;
+  j.no_draft = false;
+  j.need_lse = a->keyX != nullptr;
+  j.bins = a->bins; j.bins_stride_b = a->bins_stride_b; j.bin_of = a->Y;
+  j.ev_begin = a->ev_scan_begin; j.ev_end = a->ev_scan_end;
+  rc = run_scan(j, &pl, &part, nullptr);
+  if (rc != LLC_OK) return rc;
+  fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
+  fp.in = part;
+  fp.X = a->X; fp.Y = a->Y; fp.match_k = a->match_l; fp.accept = a->accept;
+  fp.keyX = a->keyX; fp.keyY = nullptr;
+  fp.y_given = 1; fp.bins = a->bins; fp.bins_stride_b = a->bins_stride_b; fp.message = a->message;
+  fp.stats = a->stats;
+  if (launch_finalize(st, fp) != hipSuccess) return LLC_E_LAUNCH;
   return LLC_OK;
 }
 
@@ -387,6 +457,7 @@ int llc_verify(const llc_verify_args *a) {
   fp.in = part;
   fp.X = cand; fp.Y = nullptr; fp.match_k = nullptr; fp.accept = nullptr;
   fp.keyX = a->keyYk; fp.keyY = nullptr; fp.log_keyX = cand_key;
+  fp.y_given = 0; fp.bins = nullptr; fp.bins_stride_b = 0; fp.message = nullptr;
   fp.stats = a->stats;
   if (launch_finalize(st, fp) != hipSuccess) return LLC_E_LAUNCH;
 

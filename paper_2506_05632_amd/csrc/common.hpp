@@ -58,6 +58,10 @@ struct ScanParams {
   int vector_loads;         // rows are aligned for 4-element vector loads
   int force_exact;
   int no_pool;              // draft-side reductions only: the target is never read
+  int no_draft;             // pool only: the draft rows are never read, X comes out as -1
+  const uint8_t *bins;      // optional [B][V] bins of the candidates (bins_stride_b bytes per row):
+  long long bins_stride_b;  // on the draft side only candidates in the bin of index bin_of[b] count
+  const int32_t *bin_of;    // [B]
   int *shared_tau;          // [B][K+1] running bests shared by a row's workgroups, preset to
                             // the ordered image of +inf; nullptr when a row is one workgroup
   Partials out;
@@ -70,6 +74,10 @@ struct FinalizeParams {
   int log_kind;        // keys are in the log domain and need the normaliser
   Partials in;
   int32_t *X, *Y, *match_k;  // Y, accept may be null (draft side only)
+  int y_given;               // Y holds the pool's index already: only the accept test is taken
+  const uint8_t *bins;       // optional: message[b] = bin of candidate Y[b]
+  long long bins_stride_b;
+  int32_t *message;
   uint8_t *accept;
   float *keyX, *keyY;  // optional
   double *log_keyX;    // optional [B][K]: ln of the normalised winning key (log kinds)
@@ -104,6 +112,9 @@ struct LseParams {
   int per_k;      // every draft has its own row (else one row serves the K drafts)
   int with_target;  // also the target row's normaliser
   int vector_loads; // rows are aligned for 4-element vector loads
+  const uint8_t *bins;      // as in ScanParams: masks the draft rows
+  long long bins_stride_b;
+  const int32_t *bin_of;
   double *lse;    // [B][K+1]
 };
 

@@ -50,8 +50,15 @@ __global__ void __launch_bounds__(64) finalize_kernel(const FinalizeParams p) {
     if (p.stats != nullptr && degenerate) atomicAdd(&p.stats->degenerate, degenerate);
     return;
   }
-  // target side: the pool over draft groups and chunks
-  if (tid == 0) {
+  if (p.y_given) {
+    // the pool's index was settled by an earlier pass (binned selection): announce its bin
+    if (tid == 0) {
+      const int y = p.Y[b];
+      s_y = y;
+      if (p.message != nullptr) p.message[b] = (y >= 0 && p.bins != nullptr) ? (int)p.bins[b * p.bins_stride_b + y] : -1;
+    }
+  } else if (tid == 0) {
+    // target side: the pool over draft groups and chunks
     const long long o = b * p.n_kgroups * p.n_chunks;
     double bkey = __builtin_huge_val();
     int bidx = -1, bk = -1;
@@ -144,9 +151,22 @@ __global__ void __launch_bounds__(256) lse_kernel(const LseParams p) {
   float m = -inf;     // running maximum of the entries that carry mass
   double sum = 0.0;   // sum of exp((x - m)/T) over the entries seen
   const int G = (p.V + 3) >> 2;
+  // binned candidates: a draft row only lives on the announced bin (the target row is not masked)
+  const bool binned = p.bins != nullptr && which != kd;
+  const uint8_t *brow = binned ? p.bins + b * p.bins_stride_b : nullptr;
+  int announced = -1;
+  if (binned) {
+    const int y = p.bin_of[b];
+    if (y >= 0 && y < p.V) announced = (int)brow[y];
+  }
   for (int g = tid; g < G; g += 256) {
     float v[4];
     load_group<E>(row, g * 4, p.V, vec, v);
+    if (binned) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (g * 4 + j < p.V && (int)brow[g * 4 + j] != announced) v[j] = -inf;
+    }
     float gm = -inf;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {

@@ -220,6 +220,23 @@ __device__ __forceinline__ void unpack(const uint2 &r, float (&v)[4]) {
   v[3] = __uint_as_float(r.y & 0xFFFF0000u);
 }
 
+// Bins of four consecutive candidates (one byte each) and the mask they imply: a candidate whose
+// bin differs from the announced one carries no mass on the draft (decoder) side (paper Section
+// 5.1: the decoder's target distribution holds the indicator 1{l_i = l_j}).
+__device__ __forceinline__ uint32_t load_bins4(const uint8_t *row, int i0, int V, bool aligned) {
+  if (aligned && i0 + 3 < V) return *reinterpret_cast<const uint32_t *>(row + i0);
+  uint32_t w = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    if (i0 + j < V) w |= (uint32_t)row[i0 + j] << (8 * j);
+  return w;
+}
+__device__ __forceinline__ void mask_bins(uint32_t bins4, int announced, float fill, float (&v)[4]) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    if ((int)((bins4 >> (8 * j)) & 0xFFu) != announced) v[j] = fill;
+}
+
 template <typename T>
 __device__ __forceinline__ float load1(const typename T::elem *row, int i);
 template <>
@@ -378,7 +395,9 @@ __device__ __forceinline__ void offer_where(Lds &s, int slot, double key, int i,
 
 // One workgroup scans one (row, draft group, chunk).  KB = draft pairs per pass (KT = 2 KB
 // drafts): each pair of drafts shares its Philox blocks.
-template <typename T, int KB, bool SHARED, bool PROBS>
+// MASKED: the variant that knows binned candidates and the pool-only mode (built for fp32
+// log-weights only, which is what the compression scheme uses).
+template <typename T, int KB, bool SHARED, bool PROBS, bool MASKED>
 __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kernel(const ScanParams p) {
   using elem = typename T::elem;
   constexpr int KT = 2 * KB;
@@ -413,6 +432,21 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
 
   const elem *trow = reinterpret_cast<const elem *>(p.target) + p.map.target_off(b);
   const elem *drow0 = reinterpret_cast<const elem *>(p.draft) + p.map.draft_off(b);
+  // binned candidates: only those in the announced bin (the bin of the index in bin_of[b]) count
+  // on the draft side
+  const bool binned = MASKED && p.bins != nullptr;
+  const uint8_t *brow = binned ? p.bins + b * p.bins_stride_b : nullptr;
+  int announced = -1;
+  if (binned) {
+    const int y = p.bin_of[b];
+    if (y >= 0 && y < V) announced = (int)brow[y];
+  }
+  const bool bins_aligned = binned && (((uintptr_t)p.bins | (uintptr_t)p.bins_stride_b) & 3u) == 0;
+  // pool only (the encoder's pass of the binned selection): the draft rows are not read and no
+  // candidate counts on the draft side, as if every bin differed from the announced one
+  const bool no_draft = MASKED && p.no_draft != 0;
+  const bool draft_masked = binned || no_draft;
+  if (no_draft) announced = -2;
 
   // per-draft constants (wave-uniform)
   float cd23[KT];  // log2(e) / T_k scaled by 2^23 (an exact scaling: the plain factor is cd23 * 2^-23)
@@ -472,6 +506,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             const float ck = PROBS ? 1.0f : kLog2e / tk;
             float vd[4];
             load4<T>(drow0 + (SHARED ? 0 : (long long)k * p.draft_stride_k), g * 4, V, vec, fill, vd);
+            if (draft_masked) mask_bins(no_draft ? 0u : load_bins4(brow, g * 4, V, bins_aligned), announced, fill, vd);
             float a_k = __builtin_huge_valf();
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -539,20 +574,25 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
       // chains, thresholds and compares, so they have a whole tile of arithmetic to arrive.
       // Without a pool the target-side exponent is pinned at 0 (threshold 0: never a hit).
       using raw = typename T::raw;
-      auto load_tile = [&](const int g, const bool interior, raw &rq, raw (&rd)[KD]) {
+      auto load_tile = [&](const int g, const bool interior, raw &rq, raw (&rd)[KD], uint32_t &rb) {
+        if (binned && !no_draft) rb = load_bins4(brow, g * 4, V, bins_aligned);
         if (interior) {
           if (with_pool) rq = load_raw<T>(trow, g * 4);
+          if (!no_draft) {
 #pragma unroll
-          for (int kk = 0; kk < KD; ++kk) rd[kk] = load_raw<T>(drow[kk], g * 4);
+            for (int kk = 0; kk < KD; ++kk) rd[kk] = load_raw<T>(drow[kk], g * 4);
+          }
         } else {
           if (with_pool) rq = load_raw_checked<T>(trow, g * 4, V, vec, fill);
+          if (!no_draft) {
 #pragma unroll
-          for (int kk = 0; kk < KD; ++kk) rd[kk] = load_raw_checked<T>(drow[kk], g * 4, V, vec, fill);
+            for (int kk = 0; kk < KD; ++kk) rd[kk] = load_raw_checked<T>(drow[kk], g * 4, V, vec, fill);
+          }
         }
       };
       // The tile is kept in its raw form and widened where it is used, so that few registers
       // are live across the (rare) branch to the survivors' path, which widens it again.
-      auto process_tile = [&](const int g, const raw &rq, const raw (&rd)[KD]) {
+      auto process_tile = [&](const int g, const raw &rq, const raw (&rd)[KD], const uint32_t rb) {
         uint32_t up[KB][4];  // upper half-words: word j of block m = (index 4g+j, drafts 2m | 2m+1)
         philox_blocks<KB>((uint32_t)g, pair_base, row_lo, row_hi, p.seed_lo, p.seed_hi, up);
 
@@ -572,6 +612,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
           const float OX = load_offset(&s.O[0]);
           float vd[4];
           unpack(rd[0], vd);
+          if (draft_masked) mask_bins(rb, announced, fill, vd);
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             const float F = merged_exponent<PROBS>(vd[j], cd23[0], OX, FY[j]);
@@ -590,6 +631,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             float v0[4], v1[4];
             unpack(rd[SHARED ? 0 : 2 * m], v0);
             unpack(rd[SHARED ? 0 : 2 * m + 1], v1);
+            if (draft_masked) { mask_bins(rb, announced, fill, v0); mask_bins(rb, announced, fill, v1); }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
               const float F0 = merged_exponent<PROBS>(v0[j], cd23[2 * m], OX0, FY[j]);
@@ -611,6 +653,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             const float OX = load_offset(&s.O[0]);
             float vd[4];
             unpack(rd[0], vd);
+            if (draft_masked) mask_bins(rb, announced, fill, vd);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
               const uint32_t t = threshold_of(merged_exponent<PROBS>(vd[j], cd23[0], OX, FY[j]));
@@ -631,6 +674,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             float ve[4], vo[4];
             unpack(rd[SHARED ? 0 : ke], ve);
             unpack(rd[SHARED ? 0 : ko], vo);
+            if (draft_masked) { mask_bins(rb, announced, fill, ve); mask_bins(rb, announced, fill, vo); }
             unsigned hm = 0;  // bit 2j + h: element (index 4g + j, draft 2m + h) is a candidate
             if (SHARED && !hot &&
                 (pk_sub_sat_u16(up[m][0], cps[0]) | pk_sub_sat_u16(up[m][1], cps[1]) |
@@ -683,7 +727,8 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
       int it = 0;
       if (n_interior > 0) {
         raw rq = raw(), rd[KD];
-        load_tile(g_begin + tid, true, rq, rd);
+        uint32_t rb = 0;
+        load_tile(g_begin + tid, true, rq, rd, rb);
         // lanes 0..KT of the first wave follow the row's shared bounds: read every fourth
         // iteration, merged four iterations later (the load never has to be waited for)
         const bool follows = p.shared_tau != nullptr && tid <= KT &&
@@ -697,10 +742,12 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             seen = __hip_atomic_load(follow_slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           }
           raw nq = raw(), nd[KD];
+          uint32_t nb = 0;
           // the last interior tile prefetches itself again (in bounds, result unused)
-          load_tile(g_begin + min(it + 1, n_interior - 1) * kBlock + tid, true, nq, nd);
-          process_tile(g_begin + it * kBlock + tid, rq, rd);
+          load_tile(g_begin + min(it + 1, n_interior - 1) * kBlock + tid, true, nq, nd, nb);
+          process_tile(g_begin + it * kBlock + tid, rq, rd, rb);
           rq = nq;
+          rb = nb;
 #pragma unroll
           for (int kk = 0; kk < KD; ++kk) rd[kk] = nd[kk];
         }
@@ -709,8 +756,9 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         const int g = g_begin + it * kBlock + tid;
         if (g < g_end) {
           raw rq = raw(), rd[KD];
-          load_tile(g, false, rq, rd);
-          process_tile(g, rq, rd);
+          uint32_t rb = 0;
+          load_tile(g, false, rq, rd, rb);
+          process_tile(g, rq, rd, rb);
         }
       }
     }
@@ -786,6 +834,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         if (k >= p.K) break;
         float vd[4];
         load4<T>(drow0 + (SHARED ? 0 : (long long)k * p.draft_stride_k), g * 4, V, false, fill, vd);
+        if (draft_masked) mask_bins(no_draft ? 0u : load_bins4(brow, g * 4, V, bins_aligned), announced, fill, vd);
         uint32_t up[4], lo[4];
         philox_block((uint32_t)g, (uint32_t)(k >> 1), row_lo, row_hi, p.seed_lo, p.seed_hi, up);
         philox_block((uint32_t)g, (uint32_t)(k >> 1) | kLowBlock, row_lo, row_hi, p.seed_lo, p.seed_hi, lo);
@@ -857,20 +906,33 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
 // kt: drafts per workgroup pass (2, 4 or 8; 1 runs as 2: a draft pair shares its blocks).
 template <typename T, bool SHARED>
 hipError_t launch_scan(int kt, bool probs, unsigned grid, hipStream_t st, const ScanParams &p) {
-#define LLC_LAUNCH(KB_, PR_)                                                                \
-  hipLaunchKernelGGL((scan_kernel<T, KB_, SHARED, PR_>), dim3(grid), dim3(kBlock), 0, st, p); \
+#define LLC_LAUNCH(KB_, PR_, MK_)                                                                  \
+  hipLaunchKernelGGL((scan_kernel<T, KB_, SHARED, PR_, MK_>), dim3(grid), dim3(kBlock), 0, st, p); \
   return hipGetLastError();
+  const bool masked = p.bins != nullptr || p.no_draft != 0;
+  if (masked) {
+    // binned candidates / pool-only passes exist for fp32 log-weights
+    if constexpr (sizeof(typename T::elem) == 4) {
+      if (probs) return hipErrorInvalidValue;
+      switch (kt) {
+        case 2: LLC_LAUNCH(1, false, true)
+        case 4: LLC_LAUNCH(2, false, true)
+        case 8: LLC_LAUNCH(4, false, true)
+      }
+    }
+    return hipErrorInvalidValue;
+  }
   if (!probs) {
     switch (kt) {
-      case 2: LLC_LAUNCH(1, false)
-      case 4: LLC_LAUNCH(2, false)
-      case 8: LLC_LAUNCH(4, false)
+      case 2: LLC_LAUNCH(1, false, false)
+      case 4: LLC_LAUNCH(2, false, false)
+      case 8: LLC_LAUNCH(4, false, false)
     }
   } else {
     switch (kt) {
-      case 2: LLC_LAUNCH(1, true)
-      case 4: LLC_LAUNCH(2, true)
-      case 8: LLC_LAUNCH(4, true)
+      case 2: LLC_LAUNCH(1, true, false)
+      case 4: LLC_LAUNCH(2, true, false)
+      case 8: LLC_LAUNCH(4, true, false)
     }
   }
 #undef LLC_LAUNCH

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(binding.EXPORTS)
     for name in names:
         assert getattr(lib, name) is not None
-    assert llc.llc_version() == 102
+    assert llc.llc_version() == 103
     assert llc.llc_status_string(0) == "ok"
     assert "workspace" in llc.llc_status_string(-6)
 
@@ -41,7 +41,9 @@ def test_header_is_plain_c_and_matches_the_binding_layout(tmp_path):
         " offsetof(llc_couple_is_args, workspace), sizeof(llc_verify_args),"
         " offsetof(llc_verify_args, tokens), offsetof(llc_verify_args, workspace));"
         " printf(\"%zu %zu %zu\\n\", sizeof(llc_couple_topm_args), offsetof(llc_couple_topm_args, temp_draft),"
-        " offsetof(llc_couple_topm_args, stream)); return 0;}\n")
+        " offsetof(llc_couple_topm_args, stream));"
+        " printf(\"%zu %zu %zu\\n\", sizeof(llc_compress_select_args), offsetof(llc_compress_select_args, bins),"
+        " offsetof(llc_compress_select_args, workspace)); return 0;}\n")
     exe = tmp_path / "layout"
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
                     str(src), "-o", str(exe)], check=True)
@@ -51,7 +53,9 @@ def test_header_is_plain_c_and_matches_the_binding_layout(tmp_path):
             binding.CoupleArgs.workspace.offset, binding.CoupleArgs.ev_scan_begin.offset,
             binding.CoupleIsArgs.workspace.offset, ctypes.sizeof(binding.VerifyArgs),
             binding.VerifyArgs.tokens.offset, binding.VerifyArgs.workspace.offset,
-            ctypes.sizeof(binding.TopmArgs), binding.TopmArgs.temp_draft.offset, binding.TopmArgs.stream.offset]
+            ctypes.sizeof(binding.TopmArgs), binding.TopmArgs.temp_draft.offset, binding.TopmArgs.stream.offset,
+            ctypes.sizeof(binding.CompressSelectArgs), binding.CompressSelectArgs.bins.offset,
+            binding.CompressSelectArgs.workspace.offset]
     assert got == want
 
 
@@ -182,3 +186,30 @@ def test_topm_argument_errors_are_reported_before_any_launch(kw, code):
     assert lib.llc_couple_topm(ctypes.byref(_topm_args(**kw))) == code
     assert lib.llc_couple_topm(None) == -1
     assert lib.llc_couple_topm(ctypes.byref(_topm_args(B=0, draft_ids=None, X=None))) == 0
+
+
+def _select_args(**kw):
+    a = binding.CompressSelectArgs()
+    a.B, a.L, a.N = 4, 2, 64
+    a.logw_enc = a.logw_dec = 0x1000
+    a.enc_stride_b, a.dec_stride_b, a.dec_stride_l = 64, 128, 64
+    a.bins, a.bins_stride_b = 0x5000, 64
+    a.X = a.Y = a.accept = 0x2000
+    a.workspace, a.workspace_bytes = 0x4000, 1 << 30
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(bins=None), -1), (dict(logw_dec=None), -1), (dict(Y=None), -1),
+    (dict(L=0), -2), (dict(N=0), -2), (dict(bins_stride_b=-1), -2),
+    (dict(logw_enc=0x1002), -5),
+    (dict(workspace=None), -6), (dict(workspace_bytes=8), -6),
+    (dict(flags=2), -8), (dict(k_tile=7), -8),
+])
+def test_compress_select_argument_errors_are_reported_before_any_launch(kw, code):
+    lib = llc.load()
+    assert lib.llc_compress_select(ctypes.byref(_select_args(**kw))) == code
+    assert lib.llc_compress_select(None) == -1
+    assert lib.llc_compress_select(ctypes.byref(_select_args(B=0, bins=None, X=None))) == 0
