@@ -202,3 +202,25 @@ def test_verify_error_codes_on_device():
     assert e.value.code == -6
     out = llc.llc_verify(torch.empty(0, 3, 2, 64, device=DEV), torch.empty(0, 2, 2, dtype=torch.int32, device=DEV))
     assert out["Y"].shape == (0, 3)
+
+
+def test_per_draft_target_side_argmins_of_algorithm_1():
+    # llc_verify with L = 0 and one target row per sequence viewed K times (stride 0) returns, as
+    # Yk / keyYk, Algorithm 1's per-draft target-side argmins argmin_i S_i^(k) / q_i, whose
+    # minimum over k is Y: the quantities an active-set verifier keeps per draft
+    g = torch.Generator(device=DEV).manual_seed(23)
+    B, K, V = 33, 5, 7001
+    tq = 2 * torch.randn(B, V, generator=g, device=DEV)
+    view = tq[:, None, None, :].expand(B, 1, K, V)
+    gpu = llc.llc_verify(view, torch.empty(B, 0, K, dtype=torch.int32, device=DEV), temp_target=0.9,
+                         seed=14, row_offset=100, row_stride_s=1, want_keys=True, want_partials=True)
+    torch.cuda.synchronize()
+    t, dt = to_host(tq)
+    ref = oracle.couple(t, t, K, dtype=dt, temp_target=0.9, temp_draft_all=0.9, seed=14, row_offset=100,
+                        partials=True)
+    ok = ref["gapYk"] >= NEAR_TIE
+    assert np.array_equal(gpu["Yk"].cpu().numpy()[:, 0][ok], ref["Yk"][ok])
+    np.testing.assert_allclose(gpu["keyYk"].cpu().numpy()[:, 0][ok], ref["keyYk"][ok], rtol=KEY_RTOL)
+    clean = ref["gapY"] >= NEAR_TIE
+    assert np.array_equal(gpu["Y"].cpu().numpy()[:, 0][clean], ref["Y"][clean])
+    assert (gpu["n_out"] == 1).all()
