@@ -304,6 +304,13 @@ struct Lds {
   unsigned long long best[9];
   unsigned long long where[9];
   unsigned long long n_survivors, n_exact;
+  float cd23[8];         // per draft of this pass: log2(e) / T_k scaled by 2^23 ...
+  int kok[8];            // ... and whether its temperature is usable (for lanes that pick a draft at run time)
+  struct Stage {         // one lane's tile, laid out for the wave (survivors' path)
+    uint32_t up[16];
+    float vq[4];
+    float vd[32];
+  } stage[4];
   int *shared_tau;       // the row's running bests shared by all its workgroups (or null)
   int shared_base, shared_pool;  // where this workgroup's draft 0 and the pool sit in it
   float rec_a[kListCap];
@@ -472,6 +479,8 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
     s.where[tid] = ~0ull;
   }
   if (tid == 0) {
+#pragma unroll
+    for (int kk = 0; kk < KT; ++kk) { s.cd23[kk] = cd23[kk]; s.kok[kk] = kok[kk] ? 1 : 0; }
     s.count = 0; s.unsafe = p.force_exact ? 1 : 0; s.n_survivors = 0; s.n_exact = 0;
     s.shared_tau = p.shared_tau != nullptr ? p.shared_tau + b * (p.K + 1) : nullptr;
     s.shared_base = kbase;
@@ -641,82 +650,71 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             }
           }
         }
-        if (any || hot) {
-          // Rare: some half-word of this lane passed (or an element is hot).  Find the pairs
-          // concerned, draw their lower half-words, and run the full-word test.  Offsets are
-          // read again here: they only ever tighten, and a tighter threshold is still valid.
-          float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-          if (with_pool) unpack(rq, vq);
-          const float tau_y = unord32(__atomic_load_n(&s.tau[KT], __ATOMIC_RELAXED));
-          uint32_t cps[4] = {0u, 0u, 0u, 0u};  // shared layout: the main loop's test values again
-          if (SHARED) {
-            const float OX = load_offset(&s.O[0]);
-            float vd[4];
-            unpack(rd[0], vd);
-            if (draft_masked) mask_bins(rb, announced, fill, vd);
+        // Rare (about one wave and tile in ten): some lane has a half-word that passed, or a hot
+        // element.  The wave takes such lanes one at a time: the lane lays its tile out in LDS and
+        // the first 8 KB lanes each take one of its elements (index j of draft 2m + h), redo the
+        // test with that draft's own bound (the shared layout's main loop used the loosest one),
+        // draw the lower half-word where it still passes, and run the full-word test.  Bounds are
+        // read again here: they only ever tighten, and a tighter bound is still valid.
+        unsigned long long todo = __ballot(any || hot);
+        if (todo != 0ull) {
+          const int lane = tid & 63;
+          Lds::Stage &st = s.stage[tid >> 6];
+          while (todo != 0ull) {
+            const int src = __ffsll((long long)todo) - 1;
+            todo &= todo - 1ull;
+            if (lane == src) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const uint32_t t = threshold_of(merged_exponent<PROBS>(vd[j], cd23[0], OX, FY[j]));
-              cps[j] = coarse_pair(t, t);
+              for (int m = 0; m < KB; ++m)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) st.up[m * 4 + j] = up[m][j];
+              float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+              if (with_pool) unpack(rq, vq);
+#pragma unroll
+              for (int j = 0; j < 4; ++j) st.vq[j] = vq[j];
+#pragma unroll
+              for (int kk = 0; kk < KD; ++kk) {
+                float vd[4];
+                unpack(rd[kk], vd);
+                if (draft_masked) mask_bins(rb, announced, fill, vd);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) st.vd[kk * 4 + j] = vd[j];
+              }
             }
-          }
-#pragma unroll
-          for (int m = 0; m < KB; ++m) {
-            const int ke = 2 * m, ko = 2 * m + 1;        // slots of the pair's even and odd draft
-            // (the shared layout's main loop uses the loosest draft's offset; here each draft
-            // gets its own, so most of the other drafts' candidates end before the lower block)
-            const float tau_e = unord32(__atomic_load_n(&s.tau[ke], __ATOMIC_RELAXED));
-            const float tau_o = unord32(__atomic_load_n(&s.tau[ko], __ATOMIC_RELAXED));
-            const float OXe = SHARED ? make_offset<PROBS>(tau_e)
-                                     : (kok[ke] ? load_offset(&s.O[ke]) : -__builtin_huge_valf());
-            const float OXo = SHARED ? make_offset<PROBS>(tau_o)
-                                     : (kok[ko] ? load_offset(&s.O[ko]) : -__builtin_huge_valf());
-            float ve[4], vo[4];
-            unpack(rd[SHARED ? 0 : ke], ve);
-            unpack(rd[SHARED ? 0 : ko], vo);
-            if (draft_masked) { mask_bins(rb, announced, fill, ve); mask_bins(rb, announced, fill, vo); }
-            unsigned hm = 0;  // bit 2j + h: element (index 4g + j, draft 2m + h) is a candidate
-            if (SHARED && !hot &&
-                (pk_sub_sat_u16(up[m][0], cps[0]) | pk_sub_sat_u16(up[m][1], cps[1]) |
-                 pk_sub_sat_u16(up[m][2], cps[2]) | pk_sub_sat_u16(up[m][3], cps[3])) == 0u)
-              continue;  // this pair had no part in the hit
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const float Fe = merged_exponent<PROBS>(ve[j], cd23[ke], OXe, FY[j]);
-              const float Fo = merged_exponent<PROBS>(vo[j], cd23[ko], OXo, FY[j]);
-              const uint32_t dd = pk_sub_sat_u16(up[m][j], coarse_pair(threshold_of(Fe), threshold_of(Fo)));
-              if ((dd & 0xFFFFu) != 0u || Fe >= kCapHot) hm |= 1u << (2 * j);
-              if ((dd >> 16) != 0u || Fo >= kCapHot) hm |= 2u << (2 * j);
-            }
-            if (kbase + ko >= p.K) hm &= 0x55u;  // the odd draft of this pair is padding
-            if (kbase + ke >= p.K) hm = 0;
-            if (hm) {
-              uint32_t lo[4];
-              philox_block((uint32_t)g, (pair_base + m) | kLowBlock, row_lo, row_hi, p.seed_lo, p.seed_hi, lo);
-              while (hm) {
-                const int bit = __ffs(hm) - 1;
-                hm &= hm - 1;
-                const int j = bit >> 1, h = bit & 1;
-                const uint32_t uw = j == 0 ? up[m][0] : j == 1 ? up[m][1] : j == 2 ? up[m][2] : up[m][3];
-                const uint32_t lw = j == 0 ? lo[0] : j == 1 ? lo[1] : j == 2 ? lo[2] : lo[3];
-                const float dse = j == 0 ? ve[0] : j == 1 ? ve[1] : j == 2 ? ve[2] : ve[3];
-                const float dso = j == 0 ? vo[0] : j == 1 ? vo[1] : j == 2 ? vo[2] : vo[3];
-                const float ds = h ? dso : dse;
-                const float qs = j == 0 ? vq[0] : j == 1 ? vq[1] : j == 2 ? vq[2] : vq[3];
-                const float fy = j == 0 ? FY[0] : j == 1 ? FY[1] : j == 2 ? FY[2] : FY[3];
-                const int i = g * 4 + j;
-                if (i < V) {
-                  const float c23 = h ? cd23[ko] : cd23[ke];
-                  const float F = merged_exponent<PROBS>(ds, c23, h ? OXo : OXe, fy);
+            __builtin_amdgcn_wave_barrier();
+            const int gs = g - lane + src;  // the lanes of a wave hold consecutive groups
+            if (lane < 8 * KB) {
+              const int m = lane >> 3, j = (lane >> 1) & 3, h = lane & 1;
+              const int kk = 2 * m + h;
+              const int i = gs * 4 + j;
+              if (kbase + kk < p.K && i < V) {
+                const uint32_t uw = st.up[m * 4 + j];
+                const float ds = st.vd[(SHARED ? 0 : kk) * 4 + j], qs = st.vq[j];
+                const float c23 = s.cd23[kk];
+                const bool okk = s.kok[kk] != 0;
+                const float tau_d = unord32(__atomic_load_n(&s.tau[kk], __ATOMIC_RELAXED));
+                const float tau_y = unord32(__atomic_load_n(&s.tau[KT], __ATOMIC_RELAXED));
+                const float OYs = with_pool ? load_offset(&s.O[KT]) : -__builtin_huge_valf();
+                const float fy = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(qs), cq23, OYs), 0.0f, kCapHot);
+                const float OX = SHARED ? make_offset<PROBS>(tau_d)
+                                        : (okk ? load_offset(&s.O[kk]) : -__builtin_huge_valf());
+                const float F = merged_exponent<PROBS>(ds, c23, OX, fy);
+                const uint32_t t = threshold_of(F);
+                const uint32_t hw = h ? (uw >> 16) : (uw & 0xFFFFu);
+                if (F >= kCapHot || hw >= 0xFFFFu - (t >> 16)) {
+                  uint32_t lo[4];
+                  philox_block((uint32_t)gs, (pair_base + m) | kLowBlock, row_lo, row_hi, p.seed_lo, p.seed_hi, lo);
+                  const uint32_t lw = j == 0 ? lo[0] : j == 1 ? lo[1] : j == 2 ? lo[2] : lo[3];
                   const uint32_t x = element_word(uw, lw, h);
-                  if (F >= kCapHot || x >= ~threshold_of(F)) {
+                  if (F >= kCapHot || x >= ~t) {
                     ++my_survivors;
-                    level2<KT, SHARED, PROBS>(s, x, ds, qs, i, 2 * m + h, h ? kok[ko] : kok[ke], with_pool,
-                                              PROBS ? 1.0f : c23 * (1.0f / kTwo23), cq, h ? tau_o : tau_e, tau_y);
+                    level2<KT, SHARED, PROBS>(s, x, ds, qs, i, kk, okk, with_pool,
+                                              PROBS ? 1.0f : c23 * (1.0f / kTwo23), cq, tau_d, tau_y);
                   }
                 }
               }
             }
+            __builtin_amdgcn_wave_barrier();
           }
         }
       };
@@ -753,13 +751,13 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         }
       }
       for (; it < iters; ++it) {
+        // every lane takes part (the survivors' path works wave-wide); a group past the end of the
+        // row reads as entries without mass
         const int g = g_begin + it * kBlock + tid;
-        if (g < g_end) {
-          raw rq = raw(), rd[KD];
-          uint32_t rb = 0;
-          load_tile(g, false, rq, rd, rb);
-          process_tile(g, rq, rd, rb);
-        }
+        raw rq = raw(), rd[KD];
+        uint32_t rb = 0;
+        load_tile(g, false, rq, rd, rb);
+        process_tile(g, rq, rd, rb);
       }
     }
     __syncthreads();
