@@ -49,6 +49,8 @@ constexpr float kTwo23 = 8388608.0f;
 // that hi16(t) <= 0xFFFE.  An element whose exponent reaches the cap is "hot": it goes to
 // level 2 whatever its random word is.
 constexpr float kCapHot = 1333788288.0f;
+constexpr float kShift16 = 134217728.0f;                 // 16 * 2^23: lowers an exponent by 16
+constexpr float kCapHot16 = kCapHot - kShift16;          // the cap in the lowered domain (hi16 = 0xFFFE)
 constexpr uint32_t kLowBlock = 0x80000000u;  // bit 31 of counter word 1 marks the lower-half block
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLog2Ln2 = -0.5287663729448977f;  // log2(ln 2)
@@ -339,12 +341,6 @@ __device__ __forceinline__ float merged_exponent(float v, float c23, float O, fl
 __device__ __forceinline__ uint32_t threshold_of(float F) {
   return cvt_u32_saturating(__int_as_float((int)F));
 }
-// Half-word test value for a pair of thresholds (even draft in the lower half): the upper 16
-// bits h of a word can only pass x >= ~t if h >= 0xFFFF - hi16(t), i.e. if h > 0xFFFE - hi16(t).
-__device__ __forceinline__ uint32_t coarse_pair(uint32_t t_even, uint32_t t_odd) {
-  return 0xFFFEFFFEu - ((t_odd & 0xFFFF0000u) | (t_even >> 16));
-}
-
 // Lower tau[slot] to `a` and refresh the level-1 offset that depends on it.  When the row is
 // spread over several workgroups the new best is also posted to the row's shared array, from
 // which the others pick it up (a bound found in one chunk prunes all of them).
@@ -605,48 +601,52 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         uint32_t up[KB][4];  // upper half-words: word j of block m = (index 4g+j, drafts 2m | 2m+1)
         philox_blocks<KB>((uint32_t)g, pair_base, row_lo, row_hi, p.seed_lo, p.seed_hi, up);
 
-        const float OY = with_pool ? load_offset(&s.O[KT]) : -__builtin_huge_valf();
+        // The main loop works with exponents lowered by 16 (kShift16): the float such an exponent
+        // stands for is t / 2^16, so one conversion yields hi16(t) directly.
+        const float OY = (with_pool ? load_offset(&s.O[KT]) : -__builtin_huge_valf()) - kShift16;
         float FY[4];
         {
           float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
           if (with_pool) unpack(rq, vq);
 #pragma unroll
           for (int j = 0; j < 4; ++j)
-            FY[j] = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vq[j]), cq23, OY), 0.0f, kCapHot);
+            FY[j] = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vq[j]), cq23, OY), 0.0f, kCapHot16);
         }
 
         bool any = false, hot = false;
         if (SHARED) {
           // one threshold per index serves every draft: any_k (h_k > c) == (max_k h_k > c)
-          const float OX = load_offset(&s.O[0]);
+          const float OX = load_offset(&s.O[0]) - kShift16;
           float vd[4];
           unpack(rd[0], vd);
           if (draft_masked) mask_bins(rb, announced, fill, vd);
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const float F = merged_exponent<PROBS>(vd[j], cd23[0], OX, FY[j]);
-            hot |= F >= kCapHot;
-            const uint32_t t = threshold_of(F);
+            const float F = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vd[j]), cd23[0], OX), FY[j], kCapHot16);
+            hot |= F >= kCapHot16;
+            const uint32_t th = threshold_of(F);  // hi16(t) <= 0xFFFE
             uint32_t mx = up[0][j];
 #pragma unroll
             for (int m = 1; m < KB; ++m) mx = pk_max_u16(mx, up[m][j]);
-            any |= pk_sub_sat_u16(mx, coarse_pair(t, t)) != 0u;
+            // 0xFFFEFFFE - (th | th << 16) in one multiply-add
+            any |= pk_sub_sat_u16(mx, 0xFFFEFFFEu - th * 0x10001u) != 0u;
           }
         } else {
 #pragma unroll
           for (int m = 0; m < KB; ++m) {
-            const float OX0 = kok[2 * m] ? load_offset(&s.O[2 * m]) : -__builtin_huge_valf();
-            const float OX1 = kok[2 * m + 1] ? load_offset(&s.O[2 * m + 1]) : -__builtin_huge_valf();
+            const float OX0 = (kok[2 * m] ? load_offset(&s.O[2 * m]) : -__builtin_huge_valf()) - kShift16;
+            const float OX1 = (kok[2 * m + 1] ? load_offset(&s.O[2 * m + 1]) : -__builtin_huge_valf()) - kShift16;
             float v0[4], v1[4];
             unpack(rd[SHARED ? 0 : 2 * m], v0);
             unpack(rd[SHARED ? 0 : 2 * m + 1], v1);
             if (draft_masked) { mask_bins(rb, announced, fill, v0); mask_bins(rb, announced, fill, v1); }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-              const float F0 = merged_exponent<PROBS>(v0[j], cd23[2 * m], OX0, FY[j]);
-              const float F1 = merged_exponent<PROBS>(v1[j], cd23[2 * m + 1], OX1, FY[j]);
-              hot |= fmaxf(F0, F1) >= kCapHot;
-              any |= pk_sub_sat_u16(up[m][j], coarse_pair(threshold_of(F0), threshold_of(F1))) != 0u;
+              const float F0 = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(v0[j]), cd23[2 * m], OX0), FY[j], kCapHot16);
+              const float F1 = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(v1[j]), cd23[2 * m + 1], OX1), FY[j], kCapHot16);
+              hot |= fmaxf(F0, F1) >= kCapHot16;
+              const uint32_t pair = threshold_of(F0) | (threshold_of(F1) << 16);
+              any |= pk_sub_sat_u16(up[m][j], 0xFFFEFFFEu - pair) != 0u;
             }
           }
         }
@@ -724,9 +724,12 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
       const int n_interior = max(0, (interior_end - g_begin) / kBlock);
       int it = 0;
       if (n_interior > 0) {
-        raw rq = raw(), rd[KD];
-        uint32_t rb = 0;
-        load_tile(g_begin + tid, true, rq, rd, rb);
+        // the next tile's loads are issued one tile of arithmetic before they are used (a second
+        // register set consumed in turn instead of the copies below measured slower)
+        raw aq = raw(), ad[KD], bq = raw(), bd[KD];
+        uint32_t ab = 0, bb = 0;
+        const int g0 = g_begin + tid;
+        load_tile(g0, true, aq, ad, ab);
         // lanes 0..KT of the first wave follow the row's shared bounds: read every fourth
         // iteration, merged four iterations later (the load never has to be waited for)
         const bool follows = p.shared_tau != nullptr && tid <= KT &&
@@ -739,15 +742,11 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
               publish<KT, SHARED, PROBS>(s, tid, unord32(seen), false);
             seen = __hip_atomic_load(follow_slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           }
-          raw nq = raw(), nd[KD];
-          uint32_t nb = 0;
-          // the last interior tile prefetches itself again (in bounds, result unused)
-          load_tile(g_begin + min(it + 1, n_interior - 1) * kBlock + tid, true, nq, nd, nb);
-          process_tile(g_begin + it * kBlock + tid, rq, rd, rb);
-          rq = nq;
-          rb = nb;
+          load_tile(g0 + min(it + 1, n_interior - 1) * kBlock, true, bq, bd, bb);
+          process_tile(g0 + it * kBlock, aq, ad, ab);
+          aq = bq; ab = bb;
 #pragma unroll
-          for (int kk = 0; kk < KD; ++kk) rd[kk] = nd[kk];
+          for (int kk = 0; kk < KD; ++kk) ad[kk] = bd[kk];
         }
       }
       for (; it < iters; ++it) {
