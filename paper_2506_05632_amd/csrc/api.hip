@@ -49,7 +49,7 @@ int auto_chunks(long long B, long long n_kgroups, long long G) {
 }
 
 struct Layout {
-  size_t keyX, idxX, keyY, idxY, kY, lse, shared_tau, total;
+  size_t keyX, idxX, keyY, idxY, kY, lse, lse_part, shared_tau, total;
 };
 
 Layout layout_for(long long B, long long K, long long n_kgroups, long long n_chunks) {
@@ -61,6 +61,7 @@ Layout layout_for(long long B, long long K, long long n_kgroups, long long n_chu
   l.idxY = off; off += align256((size_t)(B * n_kgroups * n_chunks) * sizeof(int32_t));
   l.kY = off;   off += align256((size_t)(B * n_kgroups * n_chunks) * sizeof(int32_t));
   l.lse = off;  off += align256((size_t)(B * (K + 1)) * sizeof(double));
+  l.lse_part = off; off += align256((size_t)(B * (K + 1) * n_chunks) * sizeof(double));
   l.shared_tau = off; off += align256((size_t)(B * (K + 1)) * sizeof(int32_t));
   l.total = off;
   return l;
@@ -164,7 +165,14 @@ int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
   part.kY = (int32_t *)(ws + lay.kY);
   part.lse = (double *)(ws + lay.lse);
 
-  if (j.need_lse && j.kind != LLC_PROBS) {
+  // Row normalisers: with per-draft rows the scan forms them on its way (no second pass over the
+  // inputs); the shared layout and the binned passes use the normaliser kernel.
+  const bool masked = j.bins != nullptr || j.no_draft;
+  const bool fused_lse = j.need_lse && j.kind != LLC_PROBS && !shared && !masked;
+  part.lse_part = fused_lse ? (double *)(ws + lay.lse_part) : nullptr;
+  // (the target row's normaliser always comes from the normaliser kernel, so that keyY does not
+  // depend on how the drafts are laid out)
+  if (j.need_lse && j.kind != LLC_PROBS && (!fused_lse || !j.no_pool)) {
     LseParams lp;
     lp.draft = j.draft; lp.target = j.target;
     lp.map = j.map; lp.draft_stride_k = j.draft_stride_k;
@@ -175,6 +183,7 @@ int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
     lp.is_logits = logits ? 1 : 0;
     lp.per_k = shared ? 0 : 1;
     lp.with_target = j.no_pool ? 0 : 1;
+    lp.with_drafts = fused_lse ? 0 : 1;
     lp.vector_loads = vec ? 1 : 0;
     lp.bins = j.bins; lp.bins_stride_b = j.bins_stride_b; lp.bin_of = j.bin_of;
     lp.lse = part.lse;
@@ -190,6 +199,7 @@ int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
 
   ScanParams sp;
   sp.shared_tau = shared_tau;
+  sp.lse_part = part.lse_part;
   sp.bins = j.bins; sp.bins_stride_b = j.bins_stride_b; sp.bin_of = j.bin_of;
   sp.draft = j.draft; sp.target = j.target;
   sp.map = j.map; sp.draft_stride_k = j.draft_stride_k;

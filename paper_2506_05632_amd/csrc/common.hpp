@@ -21,6 +21,7 @@ struct Partials {
   int32_t *idxY;  // [B][n_kgroups][n_chunks]
   int32_t *kY;    // [B][n_kgroups][n_chunks]
   double *lse;    // [B][K+1]: ln sum exp(x/T) of draft k (k < K) and of the target (k == K)
+  double *lse_part;  // [B][K+1][n_chunks] per-chunk shares to merge into lse first, or nullptr
 };
 
 // Rows may be a two-level index b = outer * inner_count + inner (sequences x positions in
@@ -62,6 +63,8 @@ struct ScanParams {
   const uint8_t *bins;      // optional [B][V] bins of the candidates (bins_stride_b bytes per row):
   long long bins_stride_b;  // on the draft side only candidates in the bin of index bin_of[b] count
   const int32_t *bin_of;    // [B]
+  double *lse_part;         // [B][K+1][n_chunks] or nullptr: the scan also forms the rows' normalisers,
+                            // ln of every chunk's sum of exp(x/T) (merged by the finalize kernel)
   int *shared_tau;          // [B][K+1] running bests shared by a row's workgroups, preset to
                             // the ordered image of +inf; nullptr when a row is one workgroup
   Partials out;
@@ -111,6 +114,7 @@ struct LseParams {
   int is_logits;  // divide by the temperature
   int per_k;      // every draft has its own row (else one row serves the K drafts)
   int with_target;  // also the target row's normaliser
+  int with_drafts;  // the draft rows' normalisers (0: the scan kernel forms them itself)
   int vector_loads; // rows are aligned for 4-element vector loads
   const uint8_t *bins;      // as in ScanParams: masks the draft rows
   long long bins_stride_b;

@@ -24,6 +24,19 @@ __global__ void __launch_bounds__(64) finalize_kernel(const FinalizeParams p) {
   const long long b = blockIdx.x;
   const int tid = threadIdx.x;
   if (tid == 0) s_match = 0x7FFFFFFF;
+  if (p.in.lse_part != nullptr) {
+    // the scan left every chunk's share of the normalisers: ln sum_chunks exp(share)
+    for (int k = tid; k < p.K; k += 64) {  // (the target's normaliser is already in place)
+      const double *sh = p.in.lse_part + (b * (p.K + 1) + k) * p.n_chunks;
+      double m = -__builtin_huge_val();
+      for (int c = 0; c < p.n_chunks; ++c) m = fmax(m, sh[c]);
+      double sum = 0.0;
+      if (m > -__builtin_huge_val())
+        for (int c = 0; c < p.n_chunks; ++c) sum += exp(sh[c] - m);
+      p.in.lse[b * (p.K + 1) + k] = m > -__builtin_huge_val() ? m + log(sum) : -__builtin_huge_val();
+    }
+    __syncthreads();
+  }
 
   // draft side: one thread per k merges the chunks
   unsigned long long degenerate = 0;
@@ -127,9 +140,11 @@ __global__ void __launch_bounds__(256) lse_kernel(const LseParams p) {
   __shared__ float s_max[4];
   __shared__ double s_sum[4];
   const int kd = p.per_k ? p.K : 1;  // distinct draft rows
-  const int per_b = kd + (p.with_target ? 1 : 0);
+  const int nd = p.with_drafts ? kd : 0;
+  const int per_b = nd + (p.with_target ? 1 : 0);
   const long long b = blockIdx.x / (unsigned)per_b;
-  const int which = (int)(blockIdx.x % (unsigned)per_b);  // kd = the target row
+  int which = (int)(blockIdx.x % (unsigned)per_b);
+  if (which == nd) which = kd;  // kd = the target row
   const int tid = threadIdx.x;
   const E *row;
   float T;
@@ -306,7 +321,8 @@ hipError_t launch_finalize(hipStream_t s, const FinalizeParams &p) {
 hipError_t launch_lse(hipStream_t s, const LseParams &p) {
   if (p.B == 0) return hipSuccess;
   const int kd = p.per_k ? p.K : 1;
-  const unsigned grid = (unsigned)(p.B * (kd + (p.with_target ? 1 : 0)));
+  const unsigned grid = (unsigned)(p.B * ((p.with_drafts ? kd : 0) + (p.with_target ? 1 : 0)));
+  if (grid == 0) return hipSuccess;
   if (p.dtype == LLC_F32)
     hipLaunchKernelGGL(lse_kernel<float>, dim3(grid), dim3(256), 0, s, p);
   else

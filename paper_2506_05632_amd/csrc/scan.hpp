@@ -313,6 +313,9 @@ struct Lds {
     float vq[4];
     float vd[32];
   } stage[4];
+  int mref[9];           // LSE: ordered-int reference value of each slot's exponentials (a maximum seen in the warm-up)
+  int lse_redo;          // LSE: the running sums cannot be trusted (overflow, no reference, loop skipped)
+  double lse_wave[4][9]; // LSE: per-wave sums, added in a fixed order
   int *shared_tau;       // the row's running bests shared by all its workgroups (or null)
   int shared_base, shared_pool;  // where this workgroup's draft 0 and the pool sit in it
   float rec_a[kListCap];
@@ -396,11 +399,54 @@ __device__ __forceinline__ void offer_where(Lds &s, int slot, double key, int i,
     atomicMin(&s.where[slot], ((unsigned long long)(uint32_t)i << 32) | (uint32_t)k);
 }
 
+// ln sum exp(x/T) over one chunk of a row by the whole workgroup, exactly: maximum first, then
+// fp64 exponentials, sums added in a fixed order.  The cold companion of the running sums of the
+// LSE variant (used when those overflowed or were never formed).  Every thread gets the result.
+template <typename T>
+__device__ double chunk_lse_exact(const typename T::elem *row, int g_begin, int g_end, int V, double temp,
+                                  float *s_max, double *s_sum) {
+  const int tid = threadIdx.x;
+  const float inf = __builtin_huge_valf();
+  float m = -inf;
+  for (int g = g_begin + tid; g < g_end; g += kBlock) {
+    float v[4];
+    load4<T>(row, g * 4, V, false, -inf, v);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (v[j] < inf) m = fmaxf(m, v[j]);
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d));
+  __syncthreads();  // the scratch arrays may still be read from a previous call
+  if ((tid & 63) == 0) s_max[tid >> 6] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+  double sum = 0.0;
+  if (m > -inf) {
+    for (int g = g_begin + tid; g < g_end; g += kBlock) {
+      float v[4];
+      load4<T>(row, g * 4, V, false, -inf, v);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (v[j] < inf && v[j] > -inf) sum += exp(((double)v[j] - (double)m) / temp);
+    }
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d);
+  if ((tid & 63) == 0) s_sum[tid >> 6] = sum;
+  __syncthreads();
+  sum = (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]);
+  const bool ok = m > -inf && temp > 0.0 && temp < (double)inf;
+  return ok ? (double)m / temp + log(sum) : -__builtin_huge_val();
+}
+
 // One workgroup scans one (row, draft group, chunk).  KB = draft pairs per pass (KT = 2 KB
 // drafts): each pair of drafts shares its Philox blocks.
 // MASKED: the variant that knows binned candidates and the pool-only mode (built for fp32
 // log-weights only, which is what the compression scheme uses).
-template <typename T, int KB, bool SHARED, bool PROBS, bool MASKED>
+// LSE: the variant that also accumulates the rows' normalisers ln sum exp(x/T) while it scans
+// them (per-draft layouts of the logit kinds), so that no second pass over the inputs is needed.
+template <typename T, int KB, bool SHARED, bool PROBS, bool MASKED, bool LSE>
 __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kernel(const ScanParams p) {
   using elem = typename T::elem;
   constexpr int KT = 2 * KB;
@@ -465,6 +511,23 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
   const float Tq = p.temp_target;
   const float cq = PROBS ? 1.0f : kLog2e / Tq;
   const float cq23 = PROBS ? 1.0f : cq * kTwo23;
+  // LSE: log2(e)/T of every slot as a two-float sum (no systematic rounding of 1/T in the exponent)
+  float lse_hi[KT + 1], lse_lo[KT + 1];
+  const bool lse_target = false;  // the target row's normaliser is left to the normaliser kernel
+  if (LSE) {
+#pragma unroll
+    for (int kk = 0; kk <= KT; ++kk) {
+      float t = kk == KT ? Tq : p.temp_draft_all;
+      if (kk < KT && p.temp_draft != nullptr && kbase + kk < p.K) t = p.temp_draft[kbase + kk];
+      const double c64 = 1.4426950408889634 / (double)t;
+      lse_hi[kk] = (float)c64;
+      lse_lo[kk] = (float)(c64 - (double)lse_hi[kk]);
+    }
+  }
+  bool lse_ran = false;  // the main loop (which feeds the sums) was executed
+  double lse_acc[LSE ? KT + 1 : 1];
+#pragma unroll
+  for (int kk = 0; kk < (LSE ? KT + 1 : 1); ++kk) lse_acc[kk] = 0.0;
 
   if (tid < 9) {
     // unused draft slots sit at -inf so the shared layout's max over drafts ignores them
@@ -481,7 +544,9 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
     s.shared_tau = p.shared_tau != nullptr ? p.shared_tau + b * (p.K + 1) : nullptr;
     s.shared_base = kbase;
     s.shared_pool = p.K;
+    s.lse_redo = 0;
   }
+  if (LSE && tid < 9) s.mref[tid] = (int)0x80800000;  // ord32(-inf)
   __syncthreads();
 
   unsigned long long my_survivors = 0;
@@ -495,9 +560,16 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
       const int m = wv % KB;
       const int g = g_begin + (wv / KB) * 64 + (tid & 63);
       float a_even = __builtin_huge_valf(), a_odd = __builtin_huge_valf(), a_pool = __builtin_huge_valf();
+      // LSE: the largest values seen here become the reference of the running sums of exponentials
+      float r_even = -__builtin_huge_valf(), r_odd = -__builtin_huge_valf(), r_pool = -__builtin_huge_valf();
       if (g < g_end && kbase + 2 * m < p.K) {
         float vq[4] = {fill, fill, fill, fill};
         if (with_pool) load4<T>(trow, g * 4, V, vec, fill, vq);
+        if (LSE) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (vq[j] < __builtin_huge_valf()) r_pool = fmaxf(r_pool, vq[j]);
+        }
         uint32_t up[4], lo[4];
         philox_block((uint32_t)g, pair_base + m, row_lo, row_hi, p.seed_lo, p.seed_hi, up);
         philox_block((uint32_t)g, (pair_base + m) | kLowBlock, row_lo, row_hi, p.seed_lo, p.seed_hi, lo);
@@ -513,6 +585,11 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             load4<T>(drow0 + (SHARED ? 0 : (long long)k * p.draft_stride_k), g * 4, V, vec, fill, vd);
             if (draft_masked) mask_bins(no_draft ? 0u : load_bins4(brow, g * 4, V, bins_aligned), announced, fill, vd);
             float a_k = __builtin_huge_valf();
+            if (LSE) {
+#pragma unroll
+              for (int j = 0; j < 4; ++j)
+                if (vd[j] < __builtin_huge_valf()) (h == 0 ? r_even : r_odd) = fmaxf(h == 0 ? r_even : r_odd, vd[j]);
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
               const float l2S = approx_log2_race_time(element_word(up[j], lo[j], h));
@@ -535,6 +612,20 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         if (oe < 0x7F800000) atomicMin(&s.tau[2 * m], oe);
         if (oo < 0x7F800000) atomicMin(&s.tau[2 * m + 1], oo);
         if (op < 0x7F800000) atomicMin(&s.tau[KT], op);
+      }
+      if (LSE) {
+        int re = ord32(r_even), ro = ord32(r_odd), rp = ord32(r_pool);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+          re = max(re, __shfl_xor(re, d));
+          ro = max(ro, __shfl_xor(ro, d));
+          rp = max(rp, __shfl_xor(rp, d));
+        }
+        if ((tid & 63) == 0) {
+          atomicMax(&s.mref[2 * m], re);
+          atomicMax(&s.mref[2 * m + 1], ro);
+          atomicMax(&s.mref[KT], rp);
+        }
       }
       __syncthreads();
       if (tid <= KT) {
@@ -570,6 +661,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
     // No branch depends on the draft index: a padded draft (kbase + kk >= K) reads the last
     // real row and its half-words are tested like the others; only its hits are masked off.
     if (!s.unsafe) {
+      lse_ran = true;
       constexpr int KD = SHARED ? 1 : KT;
       const elem *drow[KD];
 #pragma unroll
@@ -597,6 +689,23 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
       };
       // The tile is kept in its raw form and widened where it is used, so that few registers
       // are live across the (rare) branch to the survivors' path, which widens it again.
+      float lse_ref[LSE ? KT + 1 : 1];
+      if (LSE) {
+#pragma unroll
+        for (int kk = 0; kk <= KT; ++kk) lse_ref[LSE ? kk : 0] = unord32(s.mref[kk]);
+      }
+      // LSE: four terms exp((x - ref)/T) of one slot, summed in fp32 and added to its fp64 sum.
+      // Entries without mass give 0 (-inf and NaN are clamped to a finite distance); +inf, a value
+      // far above the reference, or no reference at all give inf or NaN, which is noticed at the end.
+      auto lse_add = [&](const int slot, const float (&v)[4]) {
+        float part = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float d = fmaxf(v[j] - lse_ref[LSE ? slot : 0], -65536.0f);
+          part += exp2f(fmaf(d, lse_hi[slot], d * lse_lo[slot]));
+        }
+        lse_acc[LSE ? slot : 0] += (double)part;
+      };
       auto process_tile = [&](const int g, const raw &rq, const raw (&rd)[KD], const uint32_t rb) {
         uint32_t up[KB][4];  // upper half-words: word j of block m = (index 4g+j, drafts 2m | 2m+1)
         philox_blocks<KB>((uint32_t)g, pair_base, row_lo, row_hi, p.seed_lo, p.seed_hi, up);
@@ -611,6 +720,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
 #pragma unroll
           for (int j = 0; j < 4; ++j)
             FY[j] = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vq[j]), cq23, OY), 0.0f, kCapHot16);
+          if (LSE && lse_target) lse_add(KT, vq);
         }
 
         bool any = false, hot = false;
@@ -640,6 +750,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             unpack(rd[SHARED ? 0 : 2 * m], v0);
             unpack(rd[SHARED ? 0 : 2 * m + 1], v1);
             if (draft_masked) { mask_bins(rb, announced, fill, v0); mask_bins(rb, announced, fill, v1); }
+            if (LSE) { lse_add(2 * m, v0); lse_add(2 * m + 1, v1); }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
               const float F0 = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(v0[j]), cd23[2 * m], OX0), FY[j], kCapHot16);
@@ -869,6 +980,58 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
   }
   __syncthreads();
 
+  // ---- LSE: this chunk's share of every slot's normaliser, ln of (sum of exp(x/T) over the chunk)
+  if (LSE) {
+    const int wv = tid >> 6;
+#pragma unroll
+    for (int kk = 0; kk <= KT; ++kk) {
+      double v = lse_acc[LSE ? kk : 0];
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+      if ((tid & 63) == 0) s.lse_wave[wv][kk] = v;
+    }
+    __syncthreads();
+    const bool slot_used = tid < KT ? (kbase + tid < p.K) : (tid == KT && lse_target);
+    double share = -__builtin_huge_val();
+    if (tid <= KT && slot_used) {
+      const double tot = (s.lse_wave[0][tid] + s.lse_wave[1][tid]) + (s.lse_wave[2][tid] + s.lse_wave[3][tid]);
+      const float ref = unord32(s.mref[tid]);
+      float tk = tid == KT ? Tq : p.temp_draft_all;
+      if (tid < KT && p.temp_draft != nullptr) tk = p.temp_draft[kbase + tid];
+      const bool t_ok = tk > 0.0f && tk < __builtin_huge_valf();
+      if (!t_ok) {
+        share = -__builtin_huge_val();
+      } else if (!lse_ran) {
+        s.lse_redo = 1;
+      } else if (!(ref > -__builtin_huge_valf())) {
+        if (tot != 0.0) s.lse_redo = 1;  // mass appeared although the warm-up saw none
+      } else if (!(tot >= 1.0 && tot < __builtin_huge_val())) {
+        s.lse_redo = 1;                  // overflow, NaN, or the reference's own term is missing
+      } else {
+        share = (double)ref / (double)tk + log(tot);
+      }
+    }
+    __syncthreads();
+    if (s.lse_redo) {  // uniform
+      float *s_max = reinterpret_cast<float *>(&s.lse_wave[0][0]);
+      double *s_sum = &s.lse_wave[1][0];
+#pragma unroll 1
+      for (int kk = 0; kk <= KT; ++kk) {
+        const bool used = kk < KT ? (kbase + kk < p.K) : lse_target;
+        if (!used) continue;  // uniform
+        float tk = kk == KT ? Tq : p.temp_draft_all;
+        if (kk < KT && p.temp_draft != nullptr) tk = p.temp_draft[kbase + kk];
+        const elem *rowp = kk == KT ? trow : drow0 + (long long)(kbase + kk) * p.draft_stride_k;
+        const double v = chunk_lse_exact<T>(rowp, g_begin, g_end, V, (double)tk, s_max, s_sum);
+        if (tid == kk) share = v;
+      }
+    }
+    if (tid <= KT && slot_used) {
+      const long long slot = tid < KT ? kbase + tid : p.K;
+      p.lse_part[(b * (p.K + 1) + slot) * p.n_chunks + chunk] = share;
+    }
+  }
+
   // ---- partial results of this (row, draft group, chunk)
   if (tid <= KT) {
     const bool has = s.where[tid] != ~0ull;
@@ -903,33 +1066,45 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
 // kt: drafts per workgroup pass (2, 4 or 8; 1 runs as 2: a draft pair shares its blocks).
 template <typename T, bool SHARED>
 hipError_t launch_scan(int kt, bool probs, unsigned grid, hipStream_t st, const ScanParams &p) {
-#define LLC_LAUNCH(KB_, PR_, MK_)                                                                  \
-  hipLaunchKernelGGL((scan_kernel<T, KB_, SHARED, PR_, MK_>), dim3(grid), dim3(kBlock), 0, st, p); \
+#define LLC_LAUNCH(KB_, PR_, MK_, LS_)                                                                  \
+  hipLaunchKernelGGL((scan_kernel<T, KB_, SHARED, PR_, MK_, LS_>), dim3(grid), dim3(kBlock), 0, st, p); \
   return hipGetLastError();
   const bool masked = p.bins != nullptr || p.no_draft != 0;
+  if (p.lse_part != nullptr) {
+    // fused normalisers: per-draft layout, logit kinds, no bins
+    if constexpr (!SHARED) {
+      if (probs || masked) return hipErrorInvalidValue;
+      switch (kt) {
+        case 2: LLC_LAUNCH(1, false, false, true)
+        case 4: LLC_LAUNCH(2, false, false, true)
+        case 8: LLC_LAUNCH(4, false, false, true)
+      }
+    }
+    return hipErrorInvalidValue;
+  }
   if (masked) {
     // binned candidates / pool-only passes exist for fp32 log-weights
     if constexpr (sizeof(typename T::elem) == 4) {
       if (probs) return hipErrorInvalidValue;
       switch (kt) {
-        case 2: LLC_LAUNCH(1, false, true)
-        case 4: LLC_LAUNCH(2, false, true)
-        case 8: LLC_LAUNCH(4, false, true)
+        case 2: LLC_LAUNCH(1, false, true, false)
+        case 4: LLC_LAUNCH(2, false, true, false)
+        case 8: LLC_LAUNCH(4, false, true, false)
       }
     }
     return hipErrorInvalidValue;
   }
   if (!probs) {
     switch (kt) {
-      case 2: LLC_LAUNCH(1, false, false)
-      case 4: LLC_LAUNCH(2, false, false)
-      case 8: LLC_LAUNCH(4, false, false)
+      case 2: LLC_LAUNCH(1, false, false, false)
+      case 4: LLC_LAUNCH(2, false, false, false)
+      case 8: LLC_LAUNCH(4, false, false, false)
     }
   } else {
     switch (kt) {
-      case 2: LLC_LAUNCH(1, true, false)
-      case 4: LLC_LAUNCH(2, true, false)
-      case 8: LLC_LAUNCH(4, true, false)
+      case 2: LLC_LAUNCH(1, true, false, false)
+      case 4: LLC_LAUNCH(2, true, false, false)
+      case 8: LLC_LAUNCH(4, true, false, false)
     }
   }
 #undef LLC_LAUNCH

@@ -73,8 +73,10 @@ def test_compress_select_single_bin_is_llc_couple_is_and_launch_shapes_do_not_ma
     enc, dec, bins = _case(12, 4, 9000, 16, seed=7)
     one = llc.llc_compress_select(enc, dec, torch.zeros_like(bins), seed=5, want_keys=True)
     plain = llc.llc_couple_is(enc, dec, seed=5, want_keys=True)
-    for name in ("X", "Y", "accept", "match_k", "keyX", "keyY"):
+    for name in ("X", "Y", "accept", "match_k"):
         assert torch.equal(one[name], plain[name]), name
+    for name in ("keyX", "keyY"):   # normalisers summed in another order: equal up to the last bits
+        torch.testing.assert_close(one[name], plain[name], rtol=1e-6, atol=0)
     base = llc.llc_compress_select(enc, dec, bins, seed=5, want_keys=True)
     for vc, kt in ((1, 2), (3, 4), (7, 8)):
         other = llc.llc_compress_select(enc, dec, bins, seed=5, want_keys=True, v_chunks=vc, k_tile=kt)

@@ -150,7 +150,11 @@ def test_verify_results_do_not_depend_on_launch_shape():
         other = run_verify(w, want_keys=True, want_partials=True, v_chunks=vc, k_tile=kt)
         torch.cuda.synchronize()
         for name in base:
-            assert torch.equal(base[name], other[name]), name
+            if name.startswith("key"):
+                # the normalisers are summed chunk by chunk: the last bits may depend on the split
+                torch.testing.assert_close(base[name], other[name], rtol=1e-6, atol=0)
+            else:
+                assert torch.equal(base[name], other[name]), name
     exact = run_verify(w, want_keys=True, want_partials=True, flags=llc.FLAG_EXACT_SCAN)
     torch.cuda.synchronize()
     for name in ("Y", "n_out", "active", "Yk"):
