@@ -71,3 +71,57 @@ def conditional_bound(lam_q_at_y, lam_p_at_y):
     with np.errstate(divide="ignore"):
         ratio = lam_q_at_y[:, None] / lam_p_at_y
     return np.sum(1.0 / (K + ratio), axis=1)
+
+
+def lml_bound_support(p, q, K):
+    """Theorem 1, eq. (1), for distributions that may have entries without mass.
+
+    The limits of the formula: an index j with p_j = 0 or q_j = 0 adds no term (its inner sum
+    is infinite, or its numerator side vanishes), while as a summand i such an index still
+    contributes the mass it has on the other side: q_i/q_j if p_i = 0 (its ratio q/p is
+    infinite), p_i/p_j if q_i = 0 (ratio 0).  With strictly positive inputs this is lml_bound.
+    """
+    p = np.asarray(p, np.float64)
+    q = np.asarray(q, np.float64)
+    keep = (p > 0) | (q > 0)
+    p, q = p[keep], q[keep]
+    with np.errstate(divide="ignore"):
+        r = np.where(p > 0, q / np.where(p > 0, p, 1.0), np.inf)
+    order = np.argsort(r, kind="stable")
+    ps, qs = p[order], q[order]
+    q_suffix = np.cumsum(qs[::-1])[::-1]
+    p_prefix = np.cumsum(ps) - ps
+    both = (ps > 0) & (qs > 0)
+    denom = q_suffix[both] / qs[both] + p_prefix[both] / ps[both] + (K - 1) * qs.sum() / qs[both]
+    return float(np.sum(K / denom))
+
+
+def distributions(values, kind, temp=1.0):
+    """Rows of fp64 probabilities from rows of logits (softmax of x / T, T read as the float32
+    the sampler takes), log-weights (normalised exp) or probabilities (divided by their sum)."""
+    x = np.asarray(values, np.float64)
+    if kind == "probs":
+        w = np.where(np.isfinite(x) & (x > 0), x, 0.0)
+    else:
+        t = float(np.float32(temp)) if kind == "logits" else 1.0
+        ok = np.isfinite(x)
+        m = np.max(np.where(ok, x, -np.inf), axis=-1, keepdims=True)
+        with np.errstate(invalid="ignore"):
+            w = np.where(ok, np.exp((np.where(ok, x, 0.0) - m) / t), 0.0)
+    return w / w.sum(axis=-1, keepdims=True)
+
+
+def lml_rows(draft, target, ks, kind="logits", temp_draft=1.0, temp_target=1.0):
+    """Per row and per list size: Theorem 1's bound, its relaxed form, and the TV distance."""
+    p = distributions(draft, kind, temp_draft)
+    q = distributions(target, kind, temp_target)
+    B = p.shape[0]
+    bound = np.empty((B, len(ks)))
+    relaxed = np.empty((B, len(ks)))
+    for b in range(B):
+        both = (p[b] > 0) & (q[b] > 0)
+        for n, K in enumerate(ks):
+            bound[b, n] = lml_bound_support(p[b], q[b], K)
+            relaxed[b, n] = lml_relaxed(p[b][both], q[b][both], K)
+    tv = 0.5 * np.abs(p - q).sum(axis=1)
+    return {"bound": bound, "relaxed": relaxed, "tv": tv}
