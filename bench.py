@@ -48,6 +48,7 @@ MEASURED_TRAFFIC_BYTES = {
     "is_n65536_l4_f32": 5397.2e6 + 0.4e6,
     "specdec_v32000_k4_bf16": 33.3e6 + 0.4e6,
     "verify_largevocab_s128_l7_k8_v128256": 4271.4e6 + 20.4e6,
+    "lml_largevocab_v128256_k8_f32": 77219.9e6 + 13717.9e6,
 }
 
 
@@ -263,6 +264,79 @@ def bench_topm(args):
     print(json.dumps(result))
 
 
+def bench_lml(args):
+    """Theorem 1's bound for K = 1, 2, 4, 8 on config 3's rows (a diagnostic, not the hot path)."""
+    import numpy as np
+    import torch
+    import paper_2506_05632_amd as llc
+    from oracle import lml
+    from paper_2506_05632_amd import workloads
+
+    dev = "cuda:0"
+    w = workloads.make(3, dev, rows=args.rows or None)
+    draft = w.draft if w.draft.dim() == 2 else w.draft[:, 0]
+    ks = [1, 2, 4, 8]
+    ws = torch.empty(llc.llc_lml_workspace_size(w.B, w.V), dtype=torch.uint8, device=dev)
+    out = {"bound": torch.empty(w.B, len(ks), dtype=torch.float64, device=dev),
+           "relaxed": torch.empty(w.B, len(ks), dtype=torch.float64, device=dev),
+           "tv": torch.empty(w.B, dtype=torch.float64, device=dev)}
+    ev = HipEvents(args.steps)
+
+    def step(i=None):
+        llc.llc_lml_bound(draft, w.target, ks, temp_draft=w.temp_draft, temp_target=w.temp_target,
+                          workspace=ws, out=out, events=None if i is None else ev.pairs[i])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = [ev.elapsed_ms(i) for i in range(args.steps)]
+    ev.close()
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+    kern_s = sum(kern_ms) / len(kern_ms) / 1e3
+    elems = w.B * w.V
+    # what the kernel's own design moves per element: both inputs five times (normalisers twice,
+    # keys, two gathers by sorted index) and four sort passes that read and write a key and an index
+    esize = draft.element_size()
+    alg_bytes = elems * (2 * esize + 8)          # inputs once, the sorted order written once
+    design_bytes = elems * (10 * esize + 8 + 4 * 16)
+    hbm = alg_bytes / kern_s / 1e9
+    roofline = {"bound": "hbm", "achieved": hbm, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm / HBM_PEAK_GBS,
+                "kernel": "lml_kernel", "traffic": MEASURED_TRAFFIC_BYTES.get("lml_" + w.name), "kernel_ms": kern_s * 1e3, "kernel_ms_min": min(kern_ms),
+                "algorithmic_bytes": alg_bytes, "design_bytes": design_bytes,
+                "note": "one workgroup sorts one row through memory (four radix passes with scattered 8-byte "
+                        "stores, then gathers by sorted index): a diagnostic, bound by the traffic of its own "
+                        "design (about 40x the algorithmic bytes), not by the streaming roofline"}
+    result = {
+        "metric": "Melem/s (B*V) of Theorem 1's bound for four list sizes", "value": elems / (wall / args.steps) / 1e6,
+        "unit": "Melem/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 sort keys + f64 sums", "data": "synthetic",
+        "config": {"workload": "lml_" + w.name, "B": w.B, "V": w.V, "list_sizes": ks, "input_dtype": str(draft.dtype),
+                   "mean_bound": [float(v) for v in out["bound"].mean(0)], "mean_tv": float(out["tv"].mean())},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        n = min(w.B, 64)
+        d = draft[:n].float().cpu().numpy()
+        t = w.target[:n].float().cpu().numpy()
+        t0 = time.perf_counter()
+        lml.lml_rows(d, t, ks, temp_draft=w.temp_draft, temp_target=w.temp_target)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": n * w.V / dt / 1e6, "unit": "Melem/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"the first {n} rows, {dt:.2f} s wall, numpy on one thread"}
+    print(json.dumps(result))
+
+
 def run_cpu_baseline(w, budget_s=12.0, bins=None):
     import oracle
     kinds = {"logits": oracle.LOGITS, "probs": oracle.PROBS, "logw": oracle.LOGW}
@@ -300,7 +374,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=3)
-    ap.add_argument("--workload", choices=["couple", "verify", "topm"], default="couple")
+    ap.add_argument("--workload", choices=["couple", "verify", "topm", "lml"], default="couple")
     ap.add_argument("--bins", type=int, default=0,
                     help="with --config 5: give every candidate one of BINS bins and run the compression "
                          "scheme's binned selection (llc_compress_select) instead of llc_couple_is")
@@ -323,6 +397,8 @@ def main():
     if args.workload == "verify":
         bench_verify(args)
         return
+    if args.workload == "lml":
+        return bench_lml(args)
     if args.workload == "topm":
         bench_topm(args)
         return

@@ -28,7 +28,7 @@
 extern "C" {
 #endif
 
-#define LLC_VERSION 103
+#define LLC_VERSION 104
 
 enum {
   LLC_OK = 0,
@@ -263,6 +263,45 @@ typedef struct llc_couple_topm_args {
   void *ev_begin, *ev_end;  /* optional hipEvent_t pair recorded around the kernel        */
 } llc_couple_topm_args;
 
+/* Arguments of llc_lml_bound: the list matching lemma's lower bound on the probability that the
+ * target's sample is in the list (Theorem 1, eq. (1)), per row and for several list sizes K at
+ * once, for K drafts drawn i.i.d. from the row's proposal p against the row's target q:
+ *   bound[b,n] = sum_j K_n / sum_i ( max{q_i/q_j, p_i/p_j} + (K_n - 1) q_i/q_j ).
+ * Also, on request, the relaxed form stated after the theorem,
+ *   relaxed[b,n] = sum_j q_j / (1 + q_j / (K_n p_j)),
+ * and the total variation distance tv[b] = (1/2) sum_j |p_j - q_j| (the introduction's two-party
+ * bound is (1 - tv)/(1 + tv)).  A diagnostic: it draws no randomness.
+ *
+ * Inputs as in llc_couple with one proposal row per batch row (draft is [B,V]); p and q are the
+ * softmax of logits / temperature, the normalised exp of log-weights, or the given probabilities
+ * divided by their sum.  An entry without mass on one side (logit -inf, probability 0) adds no
+ * term j but still counts as a summand i with the mass it has on the other side (the limit of the
+ * formula); NaN and +inf entries carry no mass.  Results are fp64; indices whose q/p agree to fp32
+ * precision are ordered arbitrarily, which moves a result by a relative 2^-23 at most.
+ * The workspace (llc_lml_workspace_size bytes, 256-byte aligned, device) belongs to the call
+ * until it has finished. */
+#define LLC_LML_MAX_K 8
+typedef struct llc_lml_args {
+  int64_t B, V;             /* B >= 0, 1 <= V < 2^31 - 4                                  */
+  int32_t dtype;            /* LLC_F32 | LLC_BF16 (both inputs)                           */
+  int32_t kind;             /* LLC_LOGITS | LLC_PROBS | LLC_LOGW                          */
+  const void *draft;        /* device, [B,V]                                              */
+  int64_t draft_stride_b;   /* elements                                                   */
+  const void *target;       /* device, [B,V]                                              */
+  int64_t target_stride_b;
+  float temp_target;        /* > 0; LLC_LOGITS only                                       */
+  float temp_draft;         /* > 0; LLC_LOGITS only                                       */
+  int32_t n_k;              /* 1..LLC_LML_MAX_K list sizes                                */
+  int32_t k[LLC_LML_MAX_K]; /* each >= 1                                                  */
+  double *bound;            /* device [B,n_k] required */
+  double *relaxed;          /* device [B,n_k] optional */
+  double *tv;               /* device [B]     optional */
+  void *workspace;
+  size_t workspace_bytes;
+  void *stream;
+  void *ev_begin, *ev_end;  /* optional hipEvent_t pair recorded around the kernel        */
+} llc_lml_args;
+
 /* Algorithm 1 on a batch (Section 3).  Asynchronous on a->stream. */
 int llc_couple(const llc_couple_args *a);
 
@@ -277,6 +316,12 @@ int llc_couple_topm(const llc_couple_topm_args *a);
 
 /* Algorithm 2's verification loop (Section 4.2) on S sequences.  Asynchronous. */
 int llc_verify(const llc_verify_args *a);
+
+/* Theorem 1's lower bound on the matching probability, per row (Section 3).  Asynchronous. */
+int llc_lml_bound(const llc_lml_args *a);
+
+/* Bytes of device scratch llc_lml_bound needs; 0 on bad shapes. */
+size_t llc_lml_workspace_size(int64_t B, int64_t V);
 
 /* Bytes of device scratch either call needs for this shape (any options); 0 on bad shapes. */
 size_t llc_couple_workspace_size(int64_t B, int64_t K, int64_t V);

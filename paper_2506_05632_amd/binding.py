@@ -18,8 +18,9 @@ LOGITS, PROBS, LOGW = 0, 1, 2
 FLAG_EXACT_SCAN = 1
 
 _KINDS = {"logits": LOGITS, "probs": PROBS, "logw": LOGW}
-EXPORTS = ["llc_couple", "llc_couple_is", "llc_couple_topm", "llc_compress_select", "llc_verify", "llc_couple_workspace_size",
-           "llc_verify_workspace_size", "llc_status_string", "llc_version"]
+EXPORTS = ["llc_couple", "llc_couple_is", "llc_couple_topm", "llc_compress_select", "llc_verify", "llc_lml_bound",
+           "llc_couple_workspace_size", "llc_verify_workspace_size", "llc_lml_workspace_size", "llc_status_string",
+           "llc_version"]
 
 
 class LlcStats(ctypes.Structure):
@@ -122,6 +123,24 @@ class VerifyArgs(ctypes.Structure):
     ]
 
 
+LML_MAX_K = 8
+
+
+class LmlArgs(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int64), ("V", ctypes.c_int64),
+        ("dtype", ctypes.c_int32), ("kind", ctypes.c_int32),
+        ("draft", ctypes.c_void_p), ("draft_stride_b", ctypes.c_int64),
+        ("target", ctypes.c_void_p), ("target_stride_b", ctypes.c_int64),
+        ("temp_target", ctypes.c_float), ("temp_draft", ctypes.c_float),
+        ("n_k", ctypes.c_int32), ("k", ctypes.c_int32 * LML_MAX_K),
+        ("bound", ctypes.c_void_p), ("relaxed", ctypes.c_void_p), ("tv", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("stream", ctypes.c_void_p),
+        ("ev_begin", ctypes.c_void_p), ("ev_end", ctypes.c_void_p),
+    ]
+
+
 _lib = None
 
 
@@ -144,6 +163,10 @@ def load():
         lib.llc_couple_topm.restype = ctypes.c_int
         lib.llc_verify.argtypes = [ctypes.POINTER(VerifyArgs)]
         lib.llc_verify.restype = ctypes.c_int
+        lib.llc_lml_bound.argtypes = [ctypes.POINTER(LmlArgs)]
+        lib.llc_lml_bound.restype = ctypes.c_int
+        lib.llc_lml_workspace_size.argtypes = [ctypes.c_int64] * 2
+        lib.llc_lml_workspace_size.restype = ctypes.c_size_t
         lib.llc_couple_workspace_size.argtypes = [ctypes.c_int64] * 3
         lib.llc_couple_workspace_size.restype = ctypes.c_size_t
         lib.llc_verify_workspace_size.argtypes = [ctypes.c_int64] * 4
@@ -175,6 +198,10 @@ def llc_couple_workspace_size(B: int, K: int, V: int) -> int:
 
 def llc_verify_workspace_size(S: int, L: int, K: int, V: int) -> int:
     return load().llc_verify_workspace_size(S, L, K, V)
+
+
+def llc_lml_workspace_size(B: int, V: int) -> int:
+    return load().llc_lml_workspace_size(B, V)
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -488,6 +515,58 @@ def llc_verify(target: torch.Tensor, tokens: torch.Tensor, *, kind="logits", tem
     rc = lib.llc_verify(ctypes.byref(a))
     if rc != 0:
         raise LlcError(rc)
+    return out
+
+
+def llc_lml_bound(draft: torch.Tensor, target: torch.Tensor, ks, *, kind="logits", temp_target: float = 1.0,
+                  temp_draft: float = 1.0, want_relaxed: bool = True, want_tv: bool = True,
+                  workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None, events=None) -> dict:
+    """Theorem 1's lower bound on the matching probability for the list sizes `ks`, per row.
+
+    draft, target: [B,V] device tensors (float32 or bfloat16, last dimension contiguous).
+    Returns float64 tensors bound [B,len(ks)] and, if asked, relaxed [B,len(ks)] and tv [B].
+    Asynchronous on the current stream; the workspace belongs to the call until it has finished.
+    """
+    lib = load()
+    if not (draft.is_cuda and target.is_cuda):
+        raise ValueError("llc_lml_bound needs device tensors (there is no CPU path)")
+    if draft.dtype != target.dtype or draft.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("draft and target must both be float32 or both bfloat16")
+    if draft.dim() != 2 or draft.shape != target.shape or draft.stride(1) != 1 or target.stride(1) != 1:
+        raise ValueError("draft and target must be [B,V] with a contiguous last dimension")
+    ks = [int(k) for k in ks]
+    if not 1 <= len(ks) <= LML_MAX_K:
+        raise ValueError(f"between 1 and {LML_MAX_K} list sizes")
+    B, V = target.shape
+    dev = target.device
+    if out is None:
+        out = {"bound": torch.empty(B, len(ks), dtype=torch.float64, device=dev)}
+        if want_relaxed:
+            out["relaxed"] = torch.empty(B, len(ks), dtype=torch.float64, device=dev)
+        if want_tv:
+            out["tv"] = torch.empty(B, dtype=torch.float64, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(llc_lml_workspace_size(B, V), 256), dtype=torch.uint8, device=dev)
+    a = LmlArgs()
+    a.B, a.V = B, V
+    a.dtype = F32 if draft.dtype == torch.float32 else BF16
+    a.kind = _KINDS[kind]
+    a.draft, a.draft_stride_b = draft.data_ptr(), draft.stride(0)
+    a.target, a.target_stride_b = target.data_ptr(), target.stride(0)
+    a.temp_target, a.temp_draft = temp_target, temp_draft
+    a.n_k = len(ks)
+    for n, k in enumerate(ks):
+        a.k[n] = k
+    a.bound = out["bound"].data_ptr()
+    a.relaxed, a.tv = _ptr(out.get("relaxed")), _ptr(out.get("tv"))
+    a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
+    a.stream = _stream_handle(dev)
+    if events is not None:
+        a.ev_begin, a.ev_end = events
+    rc = lib.llc_lml_bound(ctypes.byref(a))
+    if rc != 0:
+        raise LlcError(rc)
+    out["_workspace"] = workspace  # keeps the scratch alive until the caller drops the result
     return out
 
 

@@ -254,7 +254,7 @@ const char *llc_status_string(int code) {
     case LLC_E_ALIGN: return "input pointer not aligned to its element size";
     case LLC_E_WORKSPACE: return "workspace missing, misaligned or too small";
     case LLC_E_LAUNCH: return "kernel launch failed";
-    case LLC_E_OPTION: return "v_chunks, k_tile or flags out of range";
+    case LLC_E_OPTION: return "v_chunks, k_tile, flags or list sizes out of range";
     default: return "unknown status";
   }
 }
@@ -407,6 +407,47 @@ int llc_couple_topm(const llc_couple_topm_args *a) {
   hipStream_t st = (hipStream_t)a->stream;
   if (a->ev_begin != nullptr && hipEventRecord((hipEvent_t)a->ev_begin, st) != hipSuccess) return LLC_E_LAUNCH;
   if (launch_topm(st, p) != hipSuccess) return LLC_E_LAUNCH;
+  if (a->ev_end != nullptr && hipEventRecord((hipEvent_t)a->ev_end, st) != hipSuccess) return LLC_E_LAUNCH;
+  return LLC_OK;
+}
+
+size_t llc_lml_workspace_size(int64_t B, int64_t V) {
+  if (!shape_ok(B, 1, V)) return 0;
+  // two buffers of (key, index) pairs per row
+  return align256((size_t)B * 2 * (size_t)V * 8) + 256;
+}
+
+int llc_lml_bound(const llc_lml_args *a) {
+  if (a == nullptr) return LLC_E_NULL;
+  if (!shape_ok(a->B, 1, a->V) || a->B > 0x7FFFFFFFLL) return LLC_E_SHAPE;
+  if (a->n_k < 1 || a->n_k > LLC_LML_MAX_K) return LLC_E_OPTION;
+  for (int n = 0; n < a->n_k; ++n)
+    if (a->k[n] < 1) return LLC_E_OPTION;
+  if (a->B == 0) return LLC_OK;
+  if (a->draft == nullptr || a->target == nullptr || a->bound == nullptr) return LLC_E_NULL;
+  if (a->draft_stride_b < 0 || a->target_stride_b < 0) return LLC_E_SHAPE;
+  if (a->dtype != LLC_F32 && a->dtype != LLC_BF16) return LLC_E_DTYPE;
+  if (a->kind != LLC_LOGITS && a->kind != LLC_PROBS && a->kind != LLC_LOGW) return LLC_E_DTYPE;
+  const bool logits = a->kind == LLC_LOGITS;
+  if (logits && (!good_temp(a->temp_target) || !good_temp(a->temp_draft))) return LLC_E_TEMP;
+  const size_t esize = a->dtype == LLC_F32 ? 4 : 2;
+  if (((uintptr_t)a->draft % esize) != 0 || ((uintptr_t)a->target % esize) != 0) return LLC_E_ALIGN;
+  if (a->workspace == nullptr || ((uintptr_t)a->workspace & 255) != 0 ||
+      a->workspace_bytes < llc_lml_workspace_size(a->B, a->V))
+    return LLC_E_WORKSPACE;
+  LmlParams p;
+  p.B = a->B; p.V = (int)a->V; p.dtype = a->dtype; p.probs = a->kind == LLC_PROBS ? 1 : 0;
+  p.draft = a->draft; p.target = a->target;
+  p.draft_stride_b = a->draft_stride_b; p.target_stride_b = a->target_stride_b;
+  p.temp_draft = logits ? a->temp_draft : 1.0f;
+  p.temp_target = logits ? a->temp_target : 1.0f;
+  p.n_k = a->n_k;
+  for (int n = 0; n < LLC_LML_MAX_K; ++n) p.k[n] = n < a->n_k ? a->k[n] : 1;
+  p.bound = a->bound; p.relaxed = a->relaxed; p.tv = a->tv;
+  p.pairs = (uint2 *)a->workspace;
+  hipStream_t st = (hipStream_t)a->stream;
+  if (a->ev_begin != nullptr && hipEventRecord((hipEvent_t)a->ev_begin, st) != hipSuccess) return LLC_E_LAUNCH;
+  if (launch_lml(st, p) != hipSuccess) return LLC_E_LAUNCH;
   if (a->ev_end != nullptr && hipEventRecord((hipEvent_t)a->ev_end, st) != hipSuccess) return LLC_E_LAUNCH;
   return LLC_OK;
 }

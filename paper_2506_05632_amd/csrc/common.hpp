@@ -143,6 +143,25 @@ struct TopmParams {
   llc_stats *stats;
 };
 
+// Theorem 1's bound per row (diagnostics): one workgroup sorts a row by q/p and sums.
+constexpr int kLmlMaxK = LLC_LML_MAX_K;
+struct LmlParams {
+  long long B;
+  int V;
+  int dtype;
+  int probs;        // inputs are probabilities (else logits / log-weights)
+  const void *draft;
+  const void *target;
+  long long draft_stride_b, target_stride_b;
+  float temp_draft, temp_target;  // 1 for log-weights and probabilities
+  int n_k;
+  int k[kLmlMaxK];  // list sizes
+  double *bound;    // [B][n_k]
+  double *relaxed;  // [B][n_k] or nullptr
+  double *tv;       // [B] or nullptr
+  uint2 *pairs;     // workspace [B][2][V] (sort key, index)
+};
+
 // One launcher per (element type, draft layout); defined in scan_*.hip.
 // kt: drafts per workgroup pass (1, 2, 4, 8); probs: inputs are probabilities.
 hipError_t launch_scan_f32_shared(int kt, bool probs, unsigned grid, hipStream_t s, const ScanParams &p);
@@ -155,5 +174,6 @@ hipError_t launch_lse(hipStream_t s, const LseParams &p);
 hipError_t launch_verify(hipStream_t s, const VerifyParams &p);
 hipError_t launch_fill(hipStream_t s, int32_t *dst, long long n, int32_t value);
 hipError_t launch_topm(hipStream_t s, const TopmParams &p);
+hipError_t launch_lml(hipStream_t s, const LmlParams &p);
 
 }  // namespace llc

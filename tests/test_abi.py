@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(binding.EXPORTS)
     for name in names:
         assert getattr(lib, name) is not None
-    assert llc.llc_version() == 103
+    assert llc.llc_version() == 104
     assert llc.llc_status_string(0) == "ok"
     assert "workspace" in llc.llc_status_string(-6)
 
@@ -43,7 +43,9 @@ def test_header_is_plain_c_and_matches_the_binding_layout(tmp_path):
         " printf(\"%zu %zu %zu\\n\", sizeof(llc_couple_topm_args), offsetof(llc_couple_topm_args, temp_draft),"
         " offsetof(llc_couple_topm_args, stream));"
         " printf(\"%zu %zu %zu\\n\", sizeof(llc_compress_select_args), offsetof(llc_compress_select_args, bins),"
-        " offsetof(llc_compress_select_args, workspace)); return 0;}\n")
+        " offsetof(llc_compress_select_args, workspace));"
+        " printf(\"%zu %zu %zu %zu\\n\", sizeof(llc_lml_args), offsetof(llc_lml_args, k),"
+        " offsetof(llc_lml_args, bound), offsetof(llc_lml_args, ev_begin)); return 0;}\n")
     exe = tmp_path / "layout"
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
                     str(src), "-o", str(exe)], check=True)
@@ -55,7 +57,9 @@ def test_header_is_plain_c_and_matches_the_binding_layout(tmp_path):
             binding.VerifyArgs.tokens.offset, binding.VerifyArgs.workspace.offset,
             ctypes.sizeof(binding.TopmArgs), binding.TopmArgs.temp_draft.offset, binding.TopmArgs.stream.offset,
             ctypes.sizeof(binding.CompressSelectArgs), binding.CompressSelectArgs.bins.offset,
-            binding.CompressSelectArgs.workspace.offset]
+            binding.CompressSelectArgs.workspace.offset,
+            ctypes.sizeof(binding.LmlArgs), binding.LmlArgs.k.offset, binding.LmlArgs.bound.offset,
+            binding.LmlArgs.ev_begin.offset]
     assert got == want
 
 
@@ -213,3 +217,40 @@ def test_compress_select_argument_errors_are_reported_before_any_launch(kw, code
     assert lib.llc_compress_select(ctypes.byref(_select_args(**kw))) == code
     assert lib.llc_compress_select(None) == -1
     assert lib.llc_compress_select(ctypes.byref(_select_args(B=0, bins=None, X=None))) == 0
+
+
+def _lml_args(**kw):
+    a = binding.LmlArgs()
+    a.B, a.V = 4, 64
+    a.dtype, a.kind = binding.F32, binding.LOGITS
+    a.draft = a.target = 0x1000
+    a.draft_stride_b = a.target_stride_b = 64
+    a.temp_target = a.temp_draft = 1.0
+    a.n_k = 2
+    a.k[0], a.k[1] = 1, 8
+    a.bound = 0x2000
+    a.workspace, a.workspace_bytes = 0x4000, 1 << 30
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(draft=None), -1), (dict(bound=None), -1),
+    (dict(V=0), -2), (dict(B=-1), -2), (dict(target_stride_b=-1), -2),
+    (dict(temp_draft=0.0), -3), (dict(temp_target=float("nan")), -3),
+    (dict(dtype=2), -4), (dict(kind=9), -4),
+    (dict(target=0x1001), -5),
+    (dict(workspace=None), -6), (dict(workspace=0x4008), -6), (dict(workspace_bytes=1000), -6),
+    (dict(n_k=0), -8), (dict(n_k=9), -8),
+])
+def test_lml_argument_errors_are_reported_before_any_launch(kw, code):
+    lib = llc.load()
+    assert lib.llc_lml_bound(ctypes.byref(_lml_args(**kw))) == code
+    assert lib.llc_lml_bound(None) == -1
+    bad_k = _lml_args()
+    bad_k.k[1] = 0
+    assert lib.llc_lml_bound(ctypes.byref(bad_k)) == -8
+    assert lib.llc_lml_bound(ctypes.byref(_lml_args(B=0, draft=None, bound=None))) == 0
+    assert llc.llc_lml_workspace_size(4, 64) >= 4 * 64 * 16
+    assert llc.llc_lml_workspace_size(4, 0) == 0
