@@ -49,8 +49,12 @@ constexpr float kTwo23 = 8388608.0f;
 // that hi16(t) <= 0xFFFE.  An element whose exponent reaches the cap is "hot": it goes to
 // level 2 whatever its random word is.
 constexpr float kCapHot = 1333788288.0f;
-constexpr float kShift16 = 134217728.0f;                 // 16 * 2^23: lowers an exponent by 16
-constexpr float kCapHot16 = kCapHot - kShift16;          // the cap in the lowered domain (hi16 = 0xFFFE)
+// The main loop lowers its exponents by 32, so that the float an exponent stands for is t / 2^32
+// in [0, 1) and one conversion to a normalised 16-bit integer (round(f * 65535), measured: to
+// nearest) yields hi16(t) for two thresholds at once.  The conversion must not come out below
+// floor(f * 65536): 1024 units of the scaled exponent raise f by a factor >= 1 + 2^-14 > 65536/65535.
+constexpr float kShift32 = 268435456.0f - 1024.0f;       // 32 * 2^23, less the raise
+constexpr float kCapHot32 = kCapHot - 268435456.0f;      // the cap in the lowered domain (hi16 <= 0xFFFE)
 constexpr uint32_t kLowBlock = 0x80000000u;  // bit 31 of counter word 1 marks the lower-half block
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLog2Ln2 = -0.5287663729448977f;  // log2(ln 2)
@@ -343,6 +347,11 @@ __device__ __forceinline__ float merged_exponent(float v, float c23, float O, fl
 // The threshold t on ~x that a scaled exponent stands for (t <= 0xFFFE8000).
 __device__ __forceinline__ uint32_t threshold_of(float F) {
   return cvt_u32_saturating(__int_as_float((int)F));
+}
+// hi16 of the thresholds that two scaled exponents lowered by 32 stand for (never below the true
+// value, at most 0xFFFE), packed: the first in the lower half.
+__device__ __forceinline__ uint32_t packed_hi16(float F0, float F1) {
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pknorm_u16(__int_as_float((int)F0), __int_as_float((int)F1)));
 }
 // Lower tau[slot] to `a` and refresh the level-1 offset that depends on it.  When the row is
 // spread over several workgroups the new best is also posted to the row's shared array, from
@@ -710,42 +719,39 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         uint32_t up[KB][4];  // upper half-words: word j of block m = (index 4g+j, drafts 2m | 2m+1)
         philox_blocks<KB>((uint32_t)g, pair_base, row_lo, row_hi, p.seed_lo, p.seed_hi, up);
 
-        // The main loop works with exponents lowered by 16 (kShift16): the float such an exponent
-        // stands for is t / 2^16, so one conversion yields hi16(t) directly.
-        const float OY = (with_pool ? load_offset(&s.O[KT]) : -__builtin_huge_valf()) - kShift16;
+        // The main loop works with exponents lowered by 32 (kShift32): see packed_hi16.
+        const float OY = (with_pool ? load_offset(&s.O[KT]) : -__builtin_huge_valf()) - kShift32;
         float FY[4];
         {
           float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
           if (with_pool) unpack(rq, vq);
 #pragma unroll
           for (int j = 0; j < 4; ++j)
-            FY[j] = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vq[j]), cq23, OY), 0.0f, kCapHot16);
+            FY[j] = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vq[j]), cq23, OY), 0.0f, kCapHot32);
           if (LSE && lse_target) lse_add(KT, vq);
         }
 
         bool any = false, hot = false;
         if (SHARED) {
           // one threshold per index serves every draft: any_k (h_k > c) == (max_k h_k > c)
-          const float OX = load_offset(&s.O[0]) - kShift16;
+          const float OX = load_offset(&s.O[0]) - kShift32;
           float vd[4];
           unpack(rd[0], vd);
           if (draft_masked) mask_bins(rb, announced, fill, vd);
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const float F = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vd[j]), cd23[0], OX), FY[j], kCapHot16);
-            hot |= F >= kCapHot16;
-            const uint32_t th = threshold_of(F);  // hi16(t) <= 0xFFFE
+            const float F = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vd[j]), cd23[0], OX), FY[j], kCapHot32);
+            hot |= F >= kCapHot32;
             uint32_t mx = up[0][j];
 #pragma unroll
             for (int m = 1; m < KB; ++m) mx = pk_max_u16(mx, up[m][j]);
-            // 0xFFFEFFFE - (th | th << 16) in one multiply-add
-            any |= pk_sub_sat_u16(mx, 0xFFFEFFFEu - th * 0x10001u) != 0u;
+            any |= pk_sub_sat_u16(mx, 0xFFFEFFFEu - packed_hi16(F, F)) != 0u;
           }
         } else {
 #pragma unroll
           for (int m = 0; m < KB; ++m) {
-            const float OX0 = (kok[2 * m] ? load_offset(&s.O[2 * m]) : -__builtin_huge_valf()) - kShift16;
-            const float OX1 = (kok[2 * m + 1] ? load_offset(&s.O[2 * m + 1]) : -__builtin_huge_valf()) - kShift16;
+            const float OX0 = (kok[2 * m] ? load_offset(&s.O[2 * m]) : -__builtin_huge_valf()) - kShift32;
+            const float OX1 = (kok[2 * m + 1] ? load_offset(&s.O[2 * m + 1]) : -__builtin_huge_valf()) - kShift32;
             float v0[4], v1[4];
             unpack(rd[SHARED ? 0 : 2 * m], v0);
             unpack(rd[SHARED ? 0 : 2 * m + 1], v1);
@@ -753,11 +759,10 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             if (LSE) { lse_add(2 * m, v0); lse_add(2 * m + 1, v1); }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-              const float F0 = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(v0[j]), cd23[2 * m], OX0), FY[j], kCapHot16);
-              const float F1 = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(v1[j]), cd23[2 * m + 1], OX1), FY[j], kCapHot16);
-              hot |= fmaxf(F0, F1) >= kCapHot16;
-              const uint32_t pair = threshold_of(F0) | (threshold_of(F1) << 16);
-              any |= pk_sub_sat_u16(up[m][j], 0xFFFEFFFEu - pair) != 0u;
+              const float F0 = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(v0[j]), cd23[2 * m], OX0), FY[j], kCapHot32);
+              const float F1 = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(v1[j]), cd23[2 * m + 1], OX1), FY[j], kCapHot32);
+              hot |= fmaxf(F0, F1) >= kCapHot32;
+              any |= pk_sub_sat_u16(up[m][j], 0xFFFEFFFEu - packed_hi16(F0, F1)) != 0u;
             }
           }
         }
