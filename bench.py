@@ -142,7 +142,7 @@ def bench_verify(args):
     def step(i=None):
         llc.llc_verify(w.target, w.tokens, temp_target=w.temp_target, seed=w.seed + (0 if i is None else i),
                        workspace=ws, out=out, v_chunks=args.v_chunks, k_tile=args.k_tile,
-                       scan_events=None if i is None else ev.pairs[i])
+                       scan_events=None if i is None else ev.pairs[i], strong=args.strong)
 
     for _ in range(args.warmup):
         step()
@@ -180,7 +180,7 @@ def bench_verify(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32/u16+f32 (Philox words, packed 16-bit compares, fp32 thresholds, fp64 tie resolution and normalisers)",
         "data": "synthetic",
-        "config": {"workload": w.name, "S": w.S, "L": w.L, "K": w.K, "V": w.V,
+        "config": {"workload": w.name + ("_strong" if args.strong else ""), "S": w.S, "L": w.L, "K": w.K, "V": w.V,
                    "input_dtype": str(w.dtype), "temperature": w.temp_target,
                    "outputs": "Y,n_out,active",
                    "mean_tokens_per_block": float(out["n_out"].float().mean())},
@@ -374,6 +374,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--strong", action="store_true",
+                    help="--workload verify: the strongly drafter-invariant loop (Appendix B)")
     ap.add_argument("--workload", choices=["couple", "verify", "topm", "lml"], default="couple")
     ap.add_argument("--bins", type=int, default=0,
                     help="with --config 5: give every candidate one of BINS bins and run the compression "

@@ -28,7 +28,7 @@
 extern "C" {
 #endif
 
-#define LLC_VERSION 104
+#define LLC_VERSION 105
 
 enum {
   LLC_OK = 0,
@@ -52,7 +52,8 @@ enum {
 };
 
 enum {
-  LLC_FLAG_EXACT_SCAN = 1 /* debugging: evaluate every key in fp64, no prefilter     */
+  LLC_FLAG_EXACT_SCAN = 1, /* debugging: evaluate every key in fp64, no prefilter     */
+  LLC_FLAG_STRONG = 2      /* llc_verify only: the strongly drafter-invariant loop    */
 };
 
 /* Optional device counters, accumulated with atomics (zero them yourself). */
@@ -194,6 +195,13 @@ typedef struct llc_compress_select_args {
  * j >= n_out[s].  active[s,k] = 1 iff draft k is still viable at the end (all L tokens
  * accepted).  keyY[s,j] = the winning S/q.  Yk / keyYk[s,j,k] = draft k's own
  * argmin_i S_i^(j,k)/q_i^(j,k) and its key, whether or not k was viable.
+ *
+ * flags & LLC_FLAG_STRONG: the strongly drafter-invariant form (Appendix B).  The minimum of a
+ * position runs over all K drafts' race times: a viable draft is priced with its own row as
+ * above, a draft that has been dropped with the row of the first draft that is still viable
+ * (whose prefix is the output so far).  The viability rule and every output are as above.  The
+ * positions are then processed one after the other (L extra, small, passes over one row per
+ * sequence).
  */
 typedef struct llc_verify_args {
   int64_t S, L, K, V;       /* S >= 0, L >= 0, K in 1..64, V >= 1                       */

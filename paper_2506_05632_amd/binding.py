@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(HERE, "libllc_hip.so")
 F32, BF16 = 0, 1
 LOGITS, PROBS, LOGW = 0, 1, 2
 FLAG_EXACT_SCAN = 1
+FLAG_STRONG = 2
 
 _KINDS = {"logits": LOGITS, "probs": PROBS, "logw": LOGW}
 EXPORTS = ["llc_couple", "llc_couple_is", "llc_couple_topm", "llc_compress_select", "llc_verify", "llc_lml_bound",
@@ -458,7 +459,7 @@ def llc_verify(target: torch.Tensor, tokens: torch.Tensor, *, kind="logits", tem
                row_stride_j: int = 1, want_keys: bool = False, want_partials: bool = False,
                stats: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
                out: Optional[dict] = None, flags: int = 0, v_chunks: int = 0, k_tile: int = 0,
-               scan_events=None) -> dict:
+               scan_events=None, strong: bool = False) -> dict:
     """Algorithm 2's verification loop on device tensors.
 
     target: [S, L+1, K, V] float32 or bfloat16 (q^(j,k); position L is the bonus position),
@@ -509,6 +510,8 @@ def llc_verify(target: torch.Tensor, tokens: torch.Tensor, *, kind="logits", tem
     a.stats = _ptr(stats)
     a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
     a.stream = _stream_handle(dev)
+    if strong:
+        flags |= FLAG_STRONG  # Appendix B: the pool runs over all K drafts' race times
     a.flags, a.v_chunks, a.k_tile = flags, v_chunks, k_tile
     if scan_events is not None:
         a.ev_scan_begin, a.ev_scan_end = scan_events

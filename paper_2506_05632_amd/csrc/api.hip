@@ -83,9 +83,24 @@ RowMap plain_rows(long long draft_stride_b, long long target_stride_b) {
   return m;
 }
 
-// llc_verify keeps, beyond the scan's partials, ln(key) [B][K] fp64 and the index [B][K].
-size_t verify_extra_bytes(long long B, long long K) {
-  return align256((size_t)(B * K) * sizeof(double)) + align256((size_t)(B * K) * sizeof(int32_t));
+// llc_verify keeps, beyond the scan's partials, ln(key) [B][K] fp64 and the index [B][K], and for
+// the strong form the loop's state: per sequence K viability bytes, K second candidates (key and
+// index), a running flag and the next position's row offset.
+struct VerifyExtra {
+  size_t cand_key, cand, viable, running, next_off, cand2_key, cand2, total;
+};
+VerifyExtra verify_extra(long long S, long long B, long long K) {
+  VerifyExtra e;
+  size_t off = 0;
+  e.cand_key = off; off += align256((size_t)(B * K) * sizeof(double));
+  e.cand = off; off += align256((size_t)(B * K) * sizeof(int32_t));
+  e.viable = off; off += align256((size_t)(S * K));
+  e.running = off; off += align256((size_t)S * sizeof(int32_t));
+  e.next_off = off; off += align256((size_t)S * sizeof(long long));
+  e.cand2_key = off; off += align256((size_t)(S * K) * sizeof(double));
+  e.cand2 = off; off += align256((size_t)(S * K) * sizeof(int32_t));
+  e.total = off;
+  return e;
 }
 
 // One scan over B rows: what llc_couple and llc_verify have in common.
@@ -105,6 +120,7 @@ struct ScanJob {
   const uint8_t *bins = nullptr;  // binned candidates: mask of the draft rows (see ScanParams)
   long long bins_stride_b = 0;
   const int32_t *bin_of = nullptr;
+  const long long *draft_row_off = nullptr;  // per-row extra offset of the draft row (see ScanParams)
   int flags, v_chunks, k_tile;
   llc_stats *stats;
   void *workspace;
@@ -186,6 +202,7 @@ int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
     lp.with_drafts = fused_lse ? 0 : 1;
     lp.vector_loads = vec ? 1 : 0;
     lp.bins = j.bins; lp.bins_stride_b = j.bins_stride_b; lp.bin_of = j.bin_of;
+    lp.draft_row_off = j.draft_row_off;
     lp.lse = part.lse;
     if (launch_lse(st, lp) != hipSuccess) return LLC_E_LAUNCH;
   }
@@ -201,6 +218,7 @@ int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
   sp.shared_tau = shared_tau;
   sp.lse_part = part.lse_part;
   sp.bins = j.bins; sp.bins_stride_b = j.bins_stride_b; sp.bin_of = j.bin_of;
+  sp.draft_row_off = j.draft_row_off;
   sp.draft = j.draft; sp.target = j.target;
   sp.map = j.map; sp.draft_stride_k = j.draft_stride_k;
   sp.B = j.B; sp.K = (int)j.K; sp.V = (int)j.V;
@@ -457,7 +475,7 @@ size_t llc_verify_workspace_size(int64_t S, int64_t L, int64_t K, int64_t V) {
   const long long B = S * (L + 1);
   const size_t base = llc_couple_workspace_size(B, K, V);
   if (base == 0) return 0;
-  return base + verify_extra_bytes(B, K);
+  return base + verify_extra(S, B, K).total;
 }
 
 int llc_verify(const llc_verify_args *a) {
@@ -488,18 +506,21 @@ int llc_verify(const llc_verify_args *a) {
   j.no_pool = true;
   j.need_lse = true;  // keys of different rows are compared: they must be normalised
   j.force_perk = true;
-  j.flags = a->flags; j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;
+  if (a->flags & ~(LLC_FLAG_EXACT_SCAN | LLC_FLAG_STRONG)) return LLC_E_OPTION;
+  const bool strong = (a->flags & LLC_FLAG_STRONG) != 0;
+  j.flags = a->flags & LLC_FLAG_EXACT_SCAN; j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;
   j.stats = a->stats; j.workspace = a->workspace; j.workspace_bytes = a->workspace_bytes;
   j.stream = a->stream; j.ev_begin = a->ev_scan_begin; j.ev_end = a->ev_scan_end;
-  j.extra_bytes = verify_extra_bytes(B, a->K);
+  const VerifyExtra ex = verify_extra(a->S, B, a->K);
+  j.extra_bytes = ex.total;
 
   Plan pl;
   Partials part;
   char *extra = nullptr;
   const int rc = run_scan(j, &pl, &part, &extra);
   if (rc != LLC_OK) return rc;
-  double *cand_key = (double *)extra;
-  int32_t *cand = a->Yk != nullptr ? a->Yk : (int32_t *)(extra + align256((size_t)(B * a->K) * sizeof(double)));
+  double *cand_key = (double *)(extra + ex.cand_key);
+  int32_t *cand = a->Yk != nullptr ? a->Yk : (int32_t *)(extra + ex.cand);
 
   hipStream_t st = (hipStream_t)a->stream;
   FinalizeParams fp;
@@ -511,6 +532,53 @@ int llc_verify(const llc_verify_args *a) {
   fp.y_given = 0; fp.bins = nullptr; fp.bins_stride_b = 0; fp.message = nullptr;
   fp.stats = a->stats;
   if (launch_finalize(st, fp) != hipSuccess) return LLC_E_LAUNCH;
+
+  if (strong) {
+    // Appendix B: position by position, because which drafts are dropped (and whose row prices
+    // them) is only known once the position before is settled.  The dropped drafts of a position
+    // all take the first viable draft's row: one scan in the shared-proposal layout per position
+    // over the S sequences, skipped by the kernels for sequences that have nothing to price.
+    StrongStepParams ss;
+    ss.S = a->S; ss.L = (int)a->L; ss.K = (int)a->K;
+    ss.cand = cand; ss.cand_key = cand_key;
+    ss.cand2 = (int32_t *)(extra + ex.cand2); ss.cand2_key = (double *)(extra + ex.cand2_key);
+    ss.tokens = a->tokens; ss.tok_stride_s = a->tok_stride_s; ss.tok_stride_j = a->tok_stride_j;
+    ss.stride_k = a->stride_k;
+    ss.viable = (uint8_t *)(extra + ex.viable); ss.running = (int32_t *)(extra + ex.running);
+    ss.next_off = (long long *)(extra + ex.next_off);
+    ss.Y = a->Y; ss.n_out = a->n_out; ss.active = a->active; ss.keyY = a->keyY;
+    const size_t esize = a->dtype == LLC_F32 ? 4 : 2;
+    for (long long pos = 0; pos <= a->L; ++pos) {
+      if (pos > 0) {
+        ScanJob q = j;
+        q.B = a->S;
+        q.draft = (const char *)a->target + (size_t)(pos * a->stride_j) * esize;
+        q.target = q.draft;
+        q.map = plain_rows(a->stride_s, a->stride_s);
+        q.map.row_outer = a->row_stride_s;
+        q.row_offset = a->row_offset + (uint64_t)(pos * a->row_stride_j);
+        q.draft_stride_k = 0;       // one row prices all K drafts' race times
+        q.force_perk = false;
+        q.draft_row_off = ss.next_off;
+        q.stats = nullptr; q.ev_begin = nullptr; q.ev_end = nullptr;
+        q.workspace_bytes = (size_t)(extra - (char *)a->workspace);  // the first scan's partials are spent
+        q.extra_bytes = 0;
+        Plan pl2;
+        Partials part2;
+        const int rc2 = run_scan(q, &pl2, &part2, nullptr);
+        if (rc2 != LLC_OK) return rc2;
+        FinalizeParams f2 = fp;
+        f2.B = a->S; f2.n_chunks = pl2.n_chunks; f2.n_kgroups = pl2.n_kgroups;
+        f2.in = part2;
+        f2.X = (int32_t *)(extra + ex.cand2); f2.keyX = nullptr;
+        f2.log_keyX = (double *)(extra + ex.cand2_key); f2.stats = nullptr;
+        if (launch_finalize(st, f2) != hipSuccess) return LLC_E_LAUNCH;
+      }
+      ss.j = (int)pos;
+      if (launch_strong_step(st, ss) != hipSuccess) return LLC_E_LAUNCH;
+    }
+    return LLC_OK;
+  }
 
   VerifyParams vp;
   vp.S = a->S; vp.L = (int)a->L; vp.K = (int)a->K;

@@ -65,6 +65,8 @@ struct ScanParams {
   const int32_t *bin_of;    // [B]
   double *lse_part;         // [B][K+1][n_chunks] or nullptr: the scan also forms the rows' normalisers,
                             // ln of every chunk's sum of exp(x/T) (merged by the finalize kernel)
+  const long long *draft_row_off;  // optional [B]: elements added to row b's draft offset; a negative
+                            // entry means the row is not wanted (its partial results come out empty)
   int *shared_tau;          // [B][K+1] running bests shared by a row's workgroups, preset to
                             // the ordered image of +inf; nullptr when a row is one workgroup
   Partials out;
@@ -119,7 +121,31 @@ struct LseParams {
   const uint8_t *bins;      // as in ScanParams: masks the draft rows
   long long bins_stride_b;
   const int32_t *bin_of;
+  const long long *draft_row_off;  // as in ScanParams (rows that are not wanted are skipped)
   double *lse;    // [B][K+1]
+};
+
+// One position of Algorithm 2's loop in its strongly drafter-invariant form (Appendix B): the pool
+// runs over all K drafts' race times; a viable draft is priced with its own target row, a dropped
+// one with the row of the first viable draft.
+struct StrongStepParams {
+  long long S;
+  int L, K, j;               // position j of 0..L
+  const int32_t *cand;       // [S][L+1][K] own-row argmins (viable drafts)
+  const double *cand_key;    // [S][L+1][K] ln of their normalised keys
+  const int32_t *cand2;      // [S][K] argmins of this position priced with the first viable draft's row
+  const double *cand2_key;   // [S][K]  (only read for dropped drafts; unused at j == 0)
+  const int32_t *tokens;
+  long long tok_stride_s, tok_stride_j;
+  long long stride_k;        // of the target tensor, for the next position's row offsets
+  uint8_t *viable;           // [S][K] state, set up at j == 0
+  int32_t *running;          // [S] state
+  long long *next_off;       // [S] out: stride_k * (first viable draft) if the next position needs
+                             // dropped drafts priced, else -1
+  int32_t *Y;                // [S][L+1]
+  int32_t *n_out;            // [S]
+  uint8_t *active;           // [S][K] optional
+  float *keyY;               // [S][L+1] optional
 };
 
 // Algorithm 1 on candidate lists: one workgroup per row, every key exact.
@@ -172,6 +198,7 @@ hipError_t launch_scan_bf16_perk(int kt, bool probs, unsigned grid, hipStream_t 
 hipError_t launch_finalize(hipStream_t s, const FinalizeParams &p);
 hipError_t launch_lse(hipStream_t s, const LseParams &p);
 hipError_t launch_verify(hipStream_t s, const VerifyParams &p);
+hipError_t launch_strong_step(hipStream_t s, const StrongStepParams &p);
 hipError_t launch_fill(hipStream_t s, int32_t *dst, long long n, int32_t value);
 hipError_t launch_topm(hipStream_t s, const TopmParams &p);
 hipError_t launch_lml(hipStream_t s, const LmlParams &p);

@@ -148,11 +148,16 @@ __global__ void __launch_bounds__(256) lse_kernel(const LseParams p) {
   const int tid = threadIdx.x;
   const E *row;
   float T;
+  long long extra = 0;
+  if (p.draft_row_off != nullptr) {
+    extra = p.draft_row_off[b];
+    if (extra < 0) return;  // the row is not wanted
+  }
   if (which == kd) {
     row = reinterpret_cast<const E *>(p.target) + p.map.target_off(b);
     T = p.temp_target;
   } else {
-    row = reinterpret_cast<const E *>(p.draft) + p.map.draft_off(b) + (long long)which * p.draft_stride_k;
+    row = reinterpret_cast<const E *>(p.draft) + p.map.draft_off(b) + extra + (long long)which * p.draft_stride_k;
     T = p.temp_draft != nullptr ? p.temp_draft[which] : p.temp_draft_all;
   }
   if (!p.is_logits) T = 1.0f;
@@ -293,6 +298,70 @@ __global__ void __launch_bounds__(64) verify_kernel(const VerifyParams p) {
   if (p.active != nullptr && lane < K) p.active[s * K + lane] = viable ? 1 : 0;
 }
 
+// One position of the loop in its strong form (Appendix B).  One wavefront per sequence, lane k
+// holds draft k.  At j == 0 the state is set up (every draft viable).
+__global__ void __launch_bounds__(64) strong_step_kernel(const StrongStepParams p) {
+  const long long s = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int L = p.L, K = p.K, j = p.j;
+  int32_t *Y = p.Y + s * (L + 1);
+  float *keyY = p.keyY != nullptr ? p.keyY + s * (L + 1) : nullptr;
+  bool viable = lane < K;
+  bool running = true;
+  if (j > 0) {
+    viable = lane < K && p.viable[s * K + lane] != 0;
+    running = p.running[s] != 0;
+  }
+  if (!running) {  // uniform: the loop ended at an earlier position
+    if (lane == 0) {
+      Y[j] = -1;
+      if (keyY != nullptr) keyY[j] = __builtin_huge_valf();
+      p.next_off[s] = -1;
+    }
+    return;
+  }
+  double key = __builtin_huge_val();
+  int idx = -1;
+  if (lane < K) {
+    if (viable) {
+      key = p.cand_key[(s * (L + 1) + j) * K + lane];
+      idx = p.cand[(s * (L + 1) + j) * K + lane];
+    } else {
+      key = p.cand2_key[s * K + lane];
+      idx = p.cand2[s * K + lane];
+    }
+  }
+  double bkey = idx >= 0 ? key : __builtin_huge_val();
+  int bidx = idx, bk = lane;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    const double okey = __shfl_xor(bkey, d);
+    const int oidx = __shfl_xor(bidx, d);
+    const int ok = __shfl_xor(bk, d);
+    if (beats(okey, oidx, ok, bkey, bidx, bk)) { bkey = okey; bidx = oidx; bk = ok; }
+  }
+  if (lane == 0) {
+    Y[j] = bidx;
+    if (keyY != nullptr) keyY[j] = bidx >= 0 ? (float)exp(bkey) : __builtin_huge_valf();
+  }
+  bool more = j < L;
+  if (more) {
+    const int tok = lane < K ? p.tokens[s * p.tok_stride_s + (long long)j * p.tok_stride_j + lane] : -2;
+    viable = viable && tok == bidx;
+    more = __ballot(viable) != 0ull;
+  }
+  const unsigned long long mask = __ballot(viable);
+  if (lane < K) p.viable[s * K + lane] = viable ? 1 : 0;
+  if (lane == 0) {
+    p.running[s] = more ? 1 : 0;
+    if (!more) p.n_out[s] = j + 1;
+    // the next position prices the dropped drafts with the first viable draft's row, if there are any
+    const bool some_dropped = __popcll(mask) < K;
+    p.next_off[s] = (more && some_dropped) ? (long long)(__ffsll((long long)mask) - 1) * p.stride_k : -1;
+  }
+  if (!more && p.active != nullptr && lane < K) p.active[s * K + lane] = viable ? 1 : 0;
+}
+
 __global__ void __launch_bounds__(256) fill_kernel(int32_t *dst, long long n, int32_t value) {
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   if (i < n) dst[i] = value;
@@ -309,6 +378,12 @@ hipError_t launch_fill(hipStream_t s, int32_t *dst, long long n, int32_t value) 
 hipError_t launch_verify(hipStream_t s, const VerifyParams &p) {
   if (p.S == 0) return hipSuccess;
   hipLaunchKernelGGL(verify_kernel, dim3((unsigned)p.S), dim3(64), 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_strong_step(hipStream_t s, const StrongStepParams &p) {
+  if (p.S == 0) return hipSuccess;
+  hipLaunchKernelGGL(strong_step_kernel, dim3((unsigned)p.S), dim3(64), 0, s, p);
   return hipGetLastError();
 }
 

@@ -490,6 +490,27 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
 
   const elem *trow = reinterpret_cast<const elem *>(p.target) + p.map.target_off(b);
   const elem *drow0 = reinterpret_cast<const elem *>(p.draft) + p.map.draft_off(b);
+  if (p.draft_row_off != nullptr) {
+    const long long off = p.draft_row_off[b];
+    if (off < 0) {
+      // the row is not wanted: empty partial results (uniform over the workgroup, before any barrier)
+      if (tid < KT) {
+        if (kbase + tid < p.K) {
+          const long long o = (b * p.K + kbase + tid) * p.n_chunks + chunk;
+          p.out.keyX[o] = __builtin_huge_val();
+          p.out.idxX[o] = -1;
+          if (LSE) p.lse_part[(b * (p.K + 1) + kbase + tid) * p.n_chunks + chunk] = -__builtin_huge_val();
+        }
+      } else if (tid == KT) {
+        const long long o = (b * p.n_kgroups + kg) * p.n_chunks + chunk;
+        p.out.keyY[o] = __builtin_huge_val();
+        p.out.idxY[o] = -1;
+        p.out.kY[o] = -1;
+      }
+      return;
+    }
+    drow0 += off;
+  }
   // binned candidates: only those in the announced bin (the bin of the index in bin_of[b]) count
   // on the draft side
   const bool binned = MASKED && p.bins != nullptr;

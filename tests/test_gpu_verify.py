@@ -19,7 +19,7 @@ _KIND = {"logits": oracle.LOGITS, "logw": oracle.LOGW}
 
 
 def oracle_verify(target, tokens, seqs, *, kind="logits", temp_target=1.0, seed=0, row_offset=0,
-                  row_stride_s=None, row_stride_j=1):
+                  row_stride_s=None, row_stride_j=1, strong=False):
     """Oracle on sequences [s0, s1), keyed as the same global rows."""
     s0, s1 = seqs
     t, dt = to_host(target[s0:s1])
@@ -27,7 +27,7 @@ def oracle_verify(target, tokens, seqs, *, kind="logits", temp_target=1.0, seed=
     rs = L1 if row_stride_s is None else row_stride_s
     tok = tokens[s0:s1].detach().cpu().numpy() if L1 > 1 else np.zeros((s1 - s0, 0, target.shape[2]), np.int32)
     return oracle.verify(t, tok, dtype=dt, kind=_KIND[kind], temp_target=temp_target, seed=seed,
-                         row_offset=row_offset + s0 * rs, row_stride_s=rs, row_stride_j=row_stride_j)
+                         row_offset=row_offset + s0 * rs, row_stride_s=rs, row_stride_j=row_stride_j, strong=strong)
 
 
 def compare_verify(gpu, ref, seqs=None):
@@ -118,14 +118,15 @@ def test_verify_bf16_full():
     assert s[2] == 0
 
 
-def test_verify_large_vocab_sampled_sequences():
+@pytest.mark.parametrize("strong", [False, True])
+def test_verify_large_vocab_sampled_sequences(strong):
     w = workloads.make_verify("largevocab", DEV)          # the shape bench.py --workload verify times
     stats = llc.new_stats(DEV)
-    gpu = run_verify(w, want_keys=True, stats=stats)
+    gpu = run_verify(w, want_keys=True, stats=stats, strong=strong)
     torch.cuda.synchronize()
     near = 0
     for seqs in [(0, 2), (63, 65), (126, 128)]:
-        ref = oracle_verify(w.target, w.tokens, seqs, temp_target=w.temp_target, seed=w.seed)
+        ref = oracle_verify(w.target, w.tokens, seqs, temp_target=w.temp_target, seed=w.seed, strong=strong)
         near += compare_verify(gpu, ref, seqs)
     s = stats.cpu().numpy()
     print(f"verify large: near-ties {near}, survivors {s[0]} of {w.elems}, exact {s[1]}, slow blocks {s[2]}")
@@ -228,3 +229,50 @@ def test_per_draft_target_side_argmins_of_algorithm_1():
     clean = ref["gapY"] >= NEAR_TIE
     assert np.array_equal(gpu["Y"].cpu().numpy()[:, 0][clean], ref["Y"][clean])
     assert (gpu["n_out"] == 1).all()
+
+
+@pytest.mark.parametrize("name", ["tiny", "small_bf16"])
+def test_strong_variant_matches_the_oracle(name):
+    # Appendix B: dropped drafts stay in the pool, priced with the first viable draft's row
+    w = workloads.make_verify(name, DEV)
+    gpu = run_verify(w, want_keys=True, strong=True)
+    torch.cuda.synchronize()
+    ref = oracle_verify(w.target, w.tokens, (0, w.S), temp_target=w.temp_target, seed=w.seed, strong=True)
+    near = compare_verify({k: gpu[k] for k in ("Y", "n_out", "active", "keyY")}, ref)
+    plain = oracle_verify(w.target, w.tokens, (0, w.S), temp_target=w.temp_target, seed=w.seed)
+    assert near <= 1
+    # the two variants differ somewhere (else this test shows nothing) and agree on the first token
+    assert not np.array_equal(ref["Y"], plain["Y"])
+    assert np.array_equal(ref["Y"][:, 0], plain["Y"][:, 0])
+
+
+def test_strong_variant_with_coupled_drafts_row_strides_and_launch_shapes():
+    g = torch.Generator(device="cpu").manual_seed(37)
+    S, L, K, V = 30, 4, 5, 5000
+    target = (1.5 * torch.randn(S, L + 1, K, V, generator=g)).to(DEV)
+    # draft tokens that often agree with the target's sample: where `keep` is set a draft copies the
+    # oracle's output of that position (found position by position), elsewhere it stays random
+    tok = torch.randint(0, V, (S, L, K), generator=g, dtype=torch.int32)
+    keep = torch.rand(S, L, K, generator=g) < 0.6
+    kw = dict(seed=5, row_stride_s=64, row_stride_j=3, row_offset=1 << 33, strong=True)
+    for _ in range(L):
+        y = torch.from_numpy(oracle_verify(target, tok, (0, S), **kw)["Y"][:, :L].copy()).to(torch.int32)
+        tok = torch.where(keep & (y[:, :, None] >= 0), y[:, :, None].expand(S, L, K), tok)
+    tok = tok.to(DEV)
+    ref = oracle_verify(target, tok, (0, S), **kw)
+    assert ref["n_out"].max() > 2
+    for vc, kt in ((0, 0), (3, 2), (1, 8)):
+        gpu = llc.llc_verify(target, tok, seed=5, row_stride_s=64, row_stride_j=3, row_offset=1 << 33,
+                             want_keys=True, strong=True, v_chunks=vc, k_tile=kt)
+        torch.cuda.synchronize()
+        compare_verify({k: gpu[k] for k in ("Y", "n_out", "active", "keyY")}, ref)
+
+
+def test_strong_variant_ignores_the_draft_tokens_in_distribution_of_the_first_miss():
+    # with no draft ever matching, the loop stops after the first token in both variants
+    w = workloads.make_verify("tiny", DEV)
+    tok = torch.full_like(w.tokens, -5)
+    a = llc.llc_verify(w.target, tok, temp_target=w.temp_target, seed=w.seed, strong=True)
+    b = llc.llc_verify(w.target, tok, temp_target=w.temp_target, seed=w.seed)
+    torch.cuda.synchronize()
+    assert torch.equal(a["Y"], b["Y"]) and (a["n_out"] == 1).all() and (a["active"] == 0).all()
