@@ -45,16 +45,18 @@ constexpr float kEps1 = 0x1p-7f;       // slack of the integer prefilter
 constexpr float kPseudoLog = 0.0861f;  // max of log2(1+f) - f: slack when log2 p is read off the bits
 constexpr float kTauLimit = 1024.0f;
 constexpr float kTwo23 = 8388608.0f;
-// Cap of the scaled exponent in the main loop: the bit pattern of the float 0xFFFE8000, so
-// that hi16(t) <= 0xFFFE.  An element whose exponent reaches the cap is "hot": it goes to
-// level 2 whatever its random word is.
+// Cap of the scaled exponent where thresholds are formed in full (the candidates' path): the
+// bit pattern of the float 0xFFFE8000.  An element whose exponent reaches the cap is "hot": it
+// goes to level 2 whatever its random word is.
 constexpr float kCapHot = 1333788288.0f;
 // The main loop lowers its exponents by 32, so that the float an exponent stands for is t / 2^32
-// in [0, 1) and one conversion to a normalised 16-bit integer (round(f * 65535), measured: to
+// in [0, 1] and one conversion to a normalised 16-bit integer (round(f * 65535), measured: to
 // nearest) yields hi16(t) for two thresholds at once.  The conversion must not come out below
 // floor(f * 65536): 1024 units of the scaled exponent raise f by a factor >= 1 + 2^-14 > 65536/65535.
+// The lowered exponent is capped at the bit pattern of 1.0f: a hot element (and a few just below)
+// gets the half-word threshold 0xFFFF, which every half-word passes.
 constexpr float kShift32 = 268435456.0f - 1024.0f;       // 32 * 2^23, less the raise
-constexpr float kCapHot32 = kCapHot - 268435456.0f;      // the cap in the lowered domain (hi16 <= 0xFFFE)
+constexpr float kCapOne32 = 1065353216.0f;               // 0x3F800000 read as an integer
 constexpr uint32_t kLowBlock = 0x80000000u;  // bit 31 of counter word 1 marks the lower-half block
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLog2Ln2 = -0.5287663729448977f;  // log2(ln 2)
@@ -128,8 +130,8 @@ __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
   return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2v, a),
                                                                 __builtin_bit_cast(ushort2v, b)));
 }
-__device__ __forceinline__ uint32_t pk_sub_sat_u16(uint32_t a, uint32_t b) {
-  return __builtin_bit_cast(uint32_t, __builtin_elementwise_sub_sat(__builtin_bit_cast(ushort2v, a),
+__device__ __forceinline__ uint32_t pk_add_sat_u16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_add_sat(__builtin_bit_cast(ushort2v, a),
                                                                     __builtin_bit_cast(ushort2v, b)));
 }
 
@@ -349,7 +351,7 @@ __device__ __forceinline__ uint32_t threshold_of(float F) {
   return cvt_u32_saturating(__int_as_float((int)F));
 }
 // hi16 of the thresholds that two scaled exponents lowered by 32 stand for (never below the true
-// value, at most 0xFFFE), packed: the first in the lower half.
+// value; 0xFFFF at the cap), packed: the first in the lower half.
 __device__ __forceinline__ uint32_t packed_hi16(float F0, float F1) {
   return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pknorm_u16(__int_as_float((int)F0), __int_as_float((int)F1)));
 }
@@ -748,11 +750,13 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
           if (with_pool) unpack(rq, vq);
 #pragma unroll
           for (int j = 0; j < 4; ++j)
-            FY[j] = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vq[j]), cq23, OY), 0.0f, kCapHot32);
+            FY[j] = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vq[j]), cq23, OY), 0.0f, kCapOne32);
           if (LSE && lse_target) lse_add(KT, vq);
         }
 
-        bool any = false, hot = false;
+        // A half-word h passes its threshold th iff h + th >= 0xFFFF, i.e. iff the saturating sum
+        // is 0xFFFF; the largest sum of the tile is kept and looked at once.
+        uint32_t most = 0u;
         if (SHARED) {
           // one threshold per index serves every draft: any_k (h_k > c) == (max_k h_k > c)
           const float OX = load_offset(&s.O[0]) - kShift32;
@@ -761,12 +765,11 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
           if (draft_masked) mask_bins(rb, announced, fill, vd);
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const float F = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vd[j]), cd23[0], OX), FY[j], kCapHot32);
-            hot |= F >= kCapHot32;
+            const float F = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vd[j]), cd23[0], OX), FY[j], kCapOne32);
             uint32_t mx = up[0][j];
 #pragma unroll
             for (int m = 1; m < KB; ++m) mx = pk_max_u16(mx, up[m][j]);
-            any |= pk_sub_sat_u16(mx, 0xFFFEFFFEu - packed_hi16(F, F)) != 0u;
+            most = pk_max_u16(most, pk_add_sat_u16(mx, packed_hi16(F, F)));
           }
         } else {
 #pragma unroll
@@ -780,10 +783,9 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             if (LSE) { lse_add(2 * m, v0); lse_add(2 * m + 1, v1); }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-              const float F0 = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(v0[j]), cd23[2 * m], OX0), FY[j], kCapHot32);
-              const float F1 = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(v1[j]), cd23[2 * m + 1], OX1), FY[j], kCapHot32);
-              hot |= fmaxf(F0, F1) >= kCapHot32;
-              any |= pk_sub_sat_u16(up[m][j], 0xFFFEFFFEu - packed_hi16(F0, F1)) != 0u;
+              const float F0 = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(v0[j]), cd23[2 * m], OX0), FY[j], kCapOne32);
+              const float F1 = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(v1[j]), cd23[2 * m + 1], OX1), FY[j], kCapOne32);
+              most = pk_max_u16(most, pk_add_sat_u16(up[m][j], packed_hi16(F0, F1)));
             }
           }
         }
@@ -793,7 +795,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         // test with that draft's own bound (the shared layout's main loop used the loosest one),
         // draw the lower half-word where it still passes, and run the full-word test.  Bounds are
         // read again here: they only ever tighten, and a tighter bound is still valid.
-        unsigned long long todo = __ballot(any || hot);
+        unsigned long long todo = __ballot((most & 0xFFFFu) == 0xFFFFu || (most >> 16) == 0xFFFFu);
         if (todo != 0ull) {
           const int lane = tid & 63;
           Lds::Stage &st = s.stage[tid >> 6];
