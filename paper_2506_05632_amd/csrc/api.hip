@@ -87,7 +87,7 @@ RowMap plain_rows(long long draft_stride_b, long long target_stride_b) {
 // the strong form the loop's state: per sequence K viability bytes, K second candidates (key and
 // index), a running flag and the next position's row offset.
 struct VerifyExtra {
-  size_t cand_key, cand, viable, running, next_off, cand2_key, cand2, total;
+  size_t cand_key, cand, viable, running, next_off, cand2_key, cand2, lse, lse_sel, total;
 };
 VerifyExtra verify_extra(long long S, long long B, long long K) {
   VerifyExtra e;
@@ -99,6 +99,8 @@ VerifyExtra verify_extra(long long S, long long B, long long K) {
   e.next_off = off; off += align256((size_t)S * sizeof(long long));
   e.cand2_key = off; off += align256((size_t)(S * K) * sizeof(double));
   e.cand2 = off; off += align256((size_t)(S * K) * sizeof(int32_t));
+  e.lse = off; off += align256((size_t)(B * (K + 1)) * sizeof(double));      // the one-shot scan's normalisers
+  e.lse_sel = off; off += align256((size_t)(S * (K + 1)) * sizeof(double));  // those of the rows that price a position
   e.total = off;
   return e;
 }
@@ -121,6 +123,7 @@ struct ScanJob {
   long long bins_stride_b = 0;
   const int32_t *bin_of = nullptr;
   const long long *draft_row_off = nullptr;  // per-row extra offset of the draft row (see ScanParams)
+  size_t lse_in_extra = (size_t)-1;  // keep the normalisers at this offset of the caller's region
   int flags, v_chunks, k_tile;
   llc_stats *stats;
   void *workspace;
@@ -179,7 +182,7 @@ int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
   part.keyY = (double *)(ws + lay.keyY);
   part.idxY = (int32_t *)(ws + lay.idxY);
   part.kY = (int32_t *)(ws + lay.kY);
-  part.lse = (double *)(ws + lay.lse);
+  part.lse = (double *)(ws + (j.lse_in_extra == (size_t)-1 ? lay.lse : lay.total + j.lse_in_extra));
 
   // Row normalisers: with per-draft rows the scan forms them on its way (no second pass over the
   // inputs); the shared layout and the binned passes use the normaliser kernel.
@@ -513,6 +516,7 @@ int llc_verify(const llc_verify_args *a) {
   j.stream = a->stream; j.ev_begin = a->ev_scan_begin; j.ev_end = a->ev_scan_end;
   const VerifyExtra ex = verify_extra(a->S, B, a->K);
   j.extra_bytes = ex.total;
+  if (strong) j.lse_in_extra = ex.lse;  // the loop over positions reuses the workspace in front of it
 
   Plan pl;
   Partials part;
@@ -546,6 +550,7 @@ int llc_verify(const llc_verify_args *a) {
     ss.stride_k = a->stride_k;
     ss.viable = (uint8_t *)(extra + ex.viable); ss.running = (int32_t *)(extra + ex.running);
     ss.next_off = (long long *)(extra + ex.next_off);
+    ss.lse = (const double *)(extra + ex.lse); ss.lse_sel = (double *)(extra + ex.lse_sel);
     ss.Y = a->Y; ss.n_out = a->n_out; ss.active = a->active; ss.keyY = a->keyY;
     const size_t esize = a->dtype == LLC_F32 ? 4 : 2;
     for (long long pos = 0; pos <= a->L; ++pos) {
@@ -560,6 +565,8 @@ int llc_verify(const llc_verify_args *a) {
         q.draft_stride_k = 0;       // one row prices all K drafts' race times
         q.force_perk = false;
         q.draft_row_off = ss.next_off;
+        q.need_lse = false;         // the rows' normalisers are known from the one-shot scan
+        q.lse_in_extra = (size_t)-1;
         q.stats = nullptr; q.ev_begin = nullptr; q.ev_end = nullptr;
         q.workspace_bytes = (size_t)(extra - (char *)a->workspace);  // the first scan's partials are spent
         q.extra_bytes = 0;
@@ -570,6 +577,7 @@ int llc_verify(const llc_verify_args *a) {
         FinalizeParams f2 = fp;
         f2.B = a->S; f2.n_chunks = pl2.n_chunks; f2.n_kgroups = pl2.n_kgroups;
         f2.in = part2;
+        f2.in.lse = ss.lse_sel;
         f2.X = (int32_t *)(extra + ex.cand2); f2.keyX = nullptr;
         f2.log_keyX = (double *)(extra + ex.cand2_key); f2.stats = nullptr;
         if (launch_finalize(st, f2) != hipSuccess) return LLC_E_LAUNCH;

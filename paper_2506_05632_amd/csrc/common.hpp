@@ -142,6 +142,8 @@ struct StrongStepParams {
   int32_t *running;          // [S] state
   long long *next_off;       // [S] out: stride_k * (first viable draft) if the next position needs
                              // dropped drafts priced, else -1
+  const double *lse;         // [S][L+1][K+1] normalisers of every (position, draft) row
+  double *lse_sel;           // [S][K+1] out: the normaliser of the row that prices the next position
   int32_t *Y;                // [S][L+1]
   int32_t *n_out;            // [S]
   uint8_t *active;           // [S][K] optional

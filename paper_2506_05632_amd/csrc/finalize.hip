@@ -359,6 +359,10 @@ __global__ void __launch_bounds__(64) strong_step_kernel(const StrongStepParams 
     const bool some_dropped = __popcll(mask) < K;
     p.next_off[s] = (more && some_dropped) ? (long long)(__ffsll((long long)mask) - 1) * p.stride_k : -1;
   }
+  if (more && lane < K) {
+    const int kref = __ffsll((long long)mask) - 1;
+    p.lse_sel[s * (K + 1) + lane] = p.lse[(s * (L + 1) + j + 1) * (K + 1) + kref];
+  }
   if (!more && p.active != nullptr && lane < K) p.active[s * K + lane] = viable ? 1 : 0;
 }
 

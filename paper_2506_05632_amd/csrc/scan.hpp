@@ -873,13 +873,15 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         // iteration, merged four iterations later (the load never has to be waited for)
         const bool follows = p.shared_tau != nullptr && tid <= KT &&
                              (tid == KT ? with_pool : (kbase + tid < p.K));
-        const int *follow_slot = follows ? p.shared_tau + b * (p.K + 1) + (tid < KT ? kbase + tid : p.K) : nullptr;
+        // (the slot is kept as an index: the row's base is wave-uniform)
+        const int *row_tau = p.shared_tau != nullptr ? p.shared_tau + b * (p.K + 1) : nullptr;
+        const int follow_idx = tid < KT ? kbase + tid : p.K;
         int seen = 0x7F800000;
         for (; it < n_interior; ++it) {
           if (follows && (it & 3) == 0) {
             if (seen < __atomic_load_n(&s.tau[tid], __ATOMIC_RELAXED))
               publish<KT, SHARED, PROBS>(s, tid, unord32(seen), false);
-            seen = __hip_atomic_load(follow_slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            seen = __hip_atomic_load(row_tau + follow_idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           }
           load_tile(g0 + min(it + 1, n_interior - 1) * kBlock, true, bq, bd, bb);
           process_tile(g0 + it * kBlock, aq, ad, ab);
