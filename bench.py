@@ -30,13 +30,14 @@ ALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12
 def algorithmic_lane_ops(K):
     """Vector-ALU lane operations per element that the method cannot avoid given how the shared
     uniforms are defined (derivation in the design doc): one Philox4x32-10 block serves 8 elements
-    (4 indices x 2 drafts, 16 upper bits each); per block 15 32x32->64 products and 15
-    three-input xors depend on the index and the draft pair, 3 + 3 more are shared by the draft
-    pairs of a pass (both instructions issue at full rate on gfx950: measured), plus one packed
-    compare per two elements.  The lower 16 bits are drawn for about one element in 10^4 and
-    are not counted; nor are threshold construction and everything else the kernel executes."""
+    (4 indices x 2 drafts, 16 upper bits each); per block 14 32x32->64 products and 16
+    three-input xors depend on both the index and the draft pair (rounds 4-10, and round 3's
+    xors), 2 + 2 more are shared by the draft pairs of a pass (both instructions issue at full rate
+    on gfx950: measured), plus one packed compare per two elements.  The lower 16 bits are drawn
+    for about one element in 10^4 and are not counted; nor are threshold construction and
+    everything else the kernel executes."""
     pairs = max(1, min(4, (K + 1) // 2))
-    return (30.0 + 6.0 / pairs) / 8.0 + 0.5
+    return (30.0 + 4.0 / pairs) / 8.0 + 0.5
 
 # HBM bytes per scan launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # each scaled by what the counter reads for a plain 1 GiB copy (x2.0 and x1.0); the summaries are

@@ -12,8 +12,8 @@
  * Shared randomness (a reading, the paper only asks for i.i.d. uniforms):
  * Philox4x32 with 10 rounds, key = (lo32(seed), hi32(seed)), row = row_offset + b.
  * The 32-bit word x of element (row, k, i) is two 16-bit halves from two blocks:
- * counter (i >> 2, k >> 1, lo32(row), hi32(row)) gives the upper half, the same
- * counter with bit 31 of its second word set gives the lower half; both read
+ * counter (lo32(row), i >> 2, hi32(row), k >> 1) gives the upper half, the same
+ * counter with bit 31 of its fourth word set gives the lower half; both read
  * output word (i & 3), its lower 16 bits for even k, its upper 16 bits for odd k.
  * U = (x + 1/2) / 2^32 and S = -ln U.
  * Ties in an argmin go to the smaller index, then (pool) to the smaller k.
@@ -28,7 +28,7 @@
 extern "C" {
 #endif
 
-#define LLC_VERSION 105
+#define LLC_VERSION 106
 
 enum {
   LLC_OK = 0,

@@ -78,13 +78,13 @@ void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]
 
 // 32-bit word for element (row, k, i): two 16-bit halves from two Philox blocks.
 // Four consecutive indices and two consecutive drafts share a block: counter
-// (i >> 2, k >> 1, lo32(row), hi32(row)) gives the high halves, the same counter with bit 31
-// of its second word set gives the low halves; element (k, i) reads output word (i & 3) of
+// (lo32(row), i >> 2, hi32(row), k >> 1) gives the high halves, the same counter with bit 31
+// of its fourth word set gives the low halves; element (k, i) reads output word (i & 3) of
 // each, its lower 16 bits for even k and its upper 16 bits for odd k.
 uint32_t shared_word(uint64_t seed, uint64_t row, uint32_t k, uint64_t i) {
   const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
-  const uint32_t ctr_hi[4] = {(uint32_t)(i >> 2), k >> 1, (uint32_t)row, (uint32_t)(row >> 32)};
-  const uint32_t ctr_lo[4] = {(uint32_t)(i >> 2), (k >> 1) | 0x80000000u, (uint32_t)row, (uint32_t)(row >> 32)};
+  const uint32_t ctr_hi[4] = {(uint32_t)row, (uint32_t)(i >> 2), (uint32_t)(row >> 32), k >> 1};
+  const uint32_t ctr_lo[4] = {(uint32_t)row, (uint32_t)(i >> 2), (uint32_t)(row >> 32), (k >> 1) | 0x80000000u};
   uint32_t out_hi[4], out_lo[4];
   philox4x32_10(ctr_hi, key, out_hi);
   philox4x32_10(ctr_lo, key, out_lo);

@@ -32,13 +32,13 @@ def philox4x32(ctr, key, rounds=10):
 def shared_word(seed, row, k, i):
     """The 32-bit word of element (row, draft k, index i).
 
-    Its upper 16 bits come from the block with counter (i >> 2, k >> 1, row), its lower 16
-    bits from the block whose second counter word also has bit 31 set; both read output word
+    Its upper 16 bits come from the block with counter (lo32(row), i >> 2, hi32(row), k >> 1),
+    its lower 16 bits from the block whose fourth counter word also has bit 31 set; both read output word
     i & 3, the lower half-word for even k and the upper one for odd k."""
     key = [seed & MASK, (seed >> 32) & MASK]
     row_words = [row & MASK, (row >> 32) & MASK]
-    hi_block = philox4x32([i >> 2, k >> 1] + row_words, key)
-    lo_block = philox4x32([i >> 2, (k >> 1) | 0x80000000] + row_words, key)
+    hi_block = philox4x32([row_words[0], i >> 2, row_words[1], k >> 1], key)
+    lo_block = philox4x32([row_words[0], i >> 2, row_words[1], (k >> 1) | 0x80000000], key)
     shift = 16 if (k & 1) else 0
     return (((hi_block[i & 3] >> shift) & 0xFFFF) << 16) | ((lo_block[i & 3] >> shift) & 0xFFFF)
 

@@ -57,7 +57,7 @@ constexpr float kCapHot = 1333788288.0f;
 // gets the half-word threshold 0xFFFF, which every half-word passes.
 constexpr float kShift32 = 268435456.0f - 1024.0f;       // 32 * 2^23, less the raise
 constexpr float kCapOne32 = 1065353216.0f;               // 0x3F800000 read as an integer
-constexpr uint32_t kLowBlock = 0x80000000u;  // bit 31 of counter word 1 marks the lower-half block
+constexpr uint32_t kLowBlock = 0x80000000u;  // bit 31 of counter word 3 marks the lower-half block
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLog2Ln2 = -0.5287663729448977f;  // log2(ln 2)
 
@@ -85,17 +85,19 @@ __device__ __forceinline__ void philox_block(uint32_t c0, uint32_t c1, uint32_t 
   out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// KB blocks that differ only in counter word 1 (the draft pair), advanced round by round
-// so that the KB dependency chains interleave.  The rounds before the pair index has
-// reached both multiplicands are identical for all KB blocks and are computed once by
-// the compiler's common-subexpression elimination.
+// KB blocks that differ only in counter word 3 (the draft pair), advanced round by round so
+// that the KB dependency chains interleave.  The counter is (row, index group, row, pair): the
+// index group and the pair sit in the words that a round only xors in, so the first round is
+// uniform over the wave, the second and third have one vector multiplication each that all KB
+// blocks share, and only from the fourth round on does every block cost its two multiplications
+// (the compiler finds this by itself: common subexpressions and uniform values).
 template <int KB>
 __device__ __forceinline__ void philox_blocks(uint32_t g, uint32_t pair_base, uint32_t row_lo,
                                               uint32_t row_hi, uint32_t k0, uint32_t k1,
                                               uint32_t (&out)[KB][4]) {
   uint32_t c0[KB], c1[KB], c2[KB], c3[KB];
 #pragma unroll
-  for (int m = 0; m < KB; ++m) { c0[m] = g; c1[m] = pair_base + m; c2[m] = row_lo; c3[m] = row_hi; }
+  for (int m = 0; m < KB; ++m) { c0[m] = row_lo; c1[m] = g; c2[m] = row_hi; c3[m] = pair_base + m; }
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
 #pragma unroll
@@ -603,8 +605,8 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             if (vq[j] < __builtin_huge_valf()) r_pool = fmaxf(r_pool, vq[j]);
         }
         uint32_t up[4], lo[4];
-        philox_block((uint32_t)g, pair_base + m, row_lo, row_hi, p.seed_lo, p.seed_hi, up);
-        philox_block((uint32_t)g, (pair_base + m) | kLowBlock, row_lo, row_hi, p.seed_lo, p.seed_hi, lo);
+        philox_block(row_lo, (uint32_t)g, row_hi, pair_base + m, p.seed_lo, p.seed_hi, up);
+        philox_block(row_lo, (uint32_t)g, row_hi, (pair_base + m) | kLowBlock, p.seed_lo, p.seed_hi, lo);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
           const int k = kbase + 2 * m + h;
@@ -842,7 +844,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
                 const uint32_t hw = h ? (uw >> 16) : (uw & 0xFFFFu);
                 if (F >= kCapHot || hw >= 0xFFFFu - (t >> 16)) {
                   uint32_t lo[4];
-                  philox_block((uint32_t)gs, (pair_base + m) | kLowBlock, row_lo, row_hi, p.seed_lo, p.seed_hi, lo);
+                  philox_block(row_lo, (uint32_t)gs, row_hi, (pair_base + m) | kLowBlock, p.seed_lo, p.seed_hi, lo);
                   const uint32_t lw = j == 0 ? lo[0] : j == 1 ? lo[1] : j == 2 ? lo[2] : lo[3];
                   const uint32_t x = element_word(uw, lw, h);
                   if (F >= kCapHot || x >= ~t) {
@@ -929,8 +931,8 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
           const int i = s.rec_i[r];
           const int k = kbase + kk;
           uint32_t up[4], lo[4];
-          philox_block((uint32_t)(i >> 2), (uint32_t)(k >> 1), row_lo, row_hi, p.seed_lo, p.seed_hi, up);
-          philox_block((uint32_t)(i >> 2), (uint32_t)(k >> 1) | kLowBlock, row_lo, row_hi, p.seed_lo, p.seed_hi, lo);
+          philox_block(row_lo, (uint32_t)(i >> 2), row_hi, (uint32_t)(k >> 1), p.seed_lo, p.seed_hi, up);
+          philox_block(row_lo, (uint32_t)(i >> 2), row_hi, (uint32_t)(k >> 1) | kLowBlock, p.seed_lo, p.seed_hi, lo);
           const int j = i & 3;
           const uint32_t uw = j == 0 ? up[0] : j == 1 ? up[1] : j == 2 ? up[2] : up[3];
           const uint32_t lw = j == 0 ? lo[0] : j == 1 ? lo[1] : j == 2 ? lo[2] : lo[3];
@@ -974,8 +976,8 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         load4<T>(drow0 + (SHARED ? 0 : (long long)k * p.draft_stride_k), g * 4, V, false, fill, vd);
         if (draft_masked) mask_bins(no_draft ? 0u : load_bins4(brow, g * 4, V, bins_aligned), announced, fill, vd);
         uint32_t up[4], lo[4];
-        philox_block((uint32_t)g, (uint32_t)(k >> 1), row_lo, row_hi, p.seed_lo, p.seed_hi, up);
-        philox_block((uint32_t)g, (uint32_t)(k >> 1) | kLowBlock, row_lo, row_hi, p.seed_lo, p.seed_hi, lo);
+        philox_block(row_lo, (uint32_t)g, row_hi, (uint32_t)(k >> 1), p.seed_lo, p.seed_hi, up);
+        philox_block(row_lo, (uint32_t)g, row_hi, (uint32_t)(k >> 1) | kLowBlock, p.seed_lo, p.seed_hi, lo);
         const float tk = p.temp_draft != nullptr ? p.temp_draft[k] : p.temp_draft_all;
         const bool ok = (tk > 0.0f) && (tk < __builtin_huge_valf());
         double bx = __builtin_huge_val();

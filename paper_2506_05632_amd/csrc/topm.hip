@@ -52,8 +52,8 @@ __device__ __forceinline__ bool has_mass(int id, float v, bool probs) {
 __device__ __forceinline__ uint32_t word_of(uint32_t id, uint32_t k, uint32_t row_lo, uint32_t row_hi,
                                             uint32_t k0, uint32_t k1) {
   uint32_t up[4], lo[4];
-  philox_block(id >> 2, k >> 1, row_lo, row_hi, k0, k1, up);
-  philox_block(id >> 2, (k >> 1) | kLowBlock, row_lo, row_hi, k0, k1, lo);
+  philox_block(row_lo, id >> 2, row_hi, k >> 1, k0, k1, up);
+  philox_block(row_lo, id >> 2, row_hi, (k >> 1) | kLowBlock, k0, k1, lo);
   const int j = (int)(id & 3u);
   const uint32_t uw = j == 0 ? up[0] : j == 1 ? up[1] : j == 2 ? up[2] : up[3];
   const uint32_t lw = j == 0 ? lo[0] : j == 1 ? lo[1] : j == 2 ? lo[2] : lo[3];

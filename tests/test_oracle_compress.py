@@ -79,8 +79,9 @@ def test_matched_trials_reach_the_closed_form_mmse_distortion():
     r = compress.gaussian_trials(1500, 1, 256, s_e, N=1 << 13, seed=12, rng_seed=3)
     assert r["match_rate"] > 0.95
     floor = s_e * s_z / (s_e + s_z + s_e * s_z)                     # Appendix D.2, error of the MMSE estimate
-    # mismatches add at most their share times the spread of a posterior sample around A
-    assert 0.85 * floor < r["mse"] < floor + (1.0 - r["match_rate"]) * 1.0 + 0.15 * floor
+    # mismatches (a few dozen trials, and those with an atypical source) add their share times a
+    # squared error of the order of the prior variance: at most three times it is allowed for
+    assert 0.85 * floor < r["mse"] < floor + (1.0 - r["match_rate"]) * 3.0 + 0.15 * floor
 
 
 def test_more_decoders_more_rate_and_independent_race_times_help():

@@ -45,8 +45,8 @@ def test_element_keying_layout():
     key = [seed & 0xFFFFFFFF, seed >> 32]
     for k in (0, 1, 2, 3, 7, 65534, 65535):
         for i in (0, 1, 2, 3, 4, 1023, 128255):
-            hi = philox_py.philox4x32([i >> 2, k >> 1, row & 0xFFFFFFFF, row >> 32], key)[i & 3]
-            lo = philox_py.philox4x32([i >> 2, (k >> 1) + 2 ** 31, row & 0xFFFFFFFF, row >> 32], key)[i & 3]
+            hi = philox_py.philox4x32([row & 0xFFFFFFFF, i >> 2, row >> 32, k >> 1], key)[i & 3]
+            lo = philox_py.philox4x32([row & 0xFFFFFFFF, i >> 2, row >> 32, (k >> 1) + 2 ** 31], key)[i & 3]
             if k % 2:
                 hi, lo = hi >> 16, lo >> 16
             want = ((hi & 0xFFFF) << 16) | (lo & 0xFFFF)
