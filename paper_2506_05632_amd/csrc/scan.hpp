@@ -880,6 +880,17 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         const int follow_idx = tid < KT ? kbase + tid : p.K;
         int seen = 0x7F800000;
         for (; it < n_interior; ++it) {
+          // A SIMD serves its wavefronts oldest first, so the workgroups of a CU drift apart and the
+          // last one finishes on a nearly empty machine.  The wave's own priority therefore falls as
+          // it advances (3, 2, 1, 0 by quarters of its tiles): whoever is behind is served first.
+          if ((it & 7) == 0) {
+            switch (min(3, (4 * it) / n_interior)) {
+              case 0: __builtin_amdgcn_s_setprio(3); break;
+              case 1: __builtin_amdgcn_s_setprio(2); break;
+              case 2: __builtin_amdgcn_s_setprio(1); break;
+              default: __builtin_amdgcn_s_setprio(0); break;
+            }
+          }
           if (follows && (it & 3) == 0) {
             if (seen < __atomic_load_n(&s.tau[tid], __ATOMIC_RELAXED))
               publish<KT, SHARED, PROBS>(s, tid, unord32(seen), false);
