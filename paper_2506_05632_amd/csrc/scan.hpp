@@ -882,9 +882,11 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         for (; it < n_interior; ++it) {
           // A SIMD serves its wavefronts oldest first, so the workgroups of a CU drift apart and the
           // last one finishes on a nearly empty machine.  The wave's own priority therefore falls as
-          // it advances (3, 2, 1, 0 by quarters of its tiles): whoever is behind is served first.
+          // it advances, in steps at 1/2, 3/4 and 7/8 of its tiles: whoever is behind a step is
+          // served first and the waves meet again at every step, the last time close to the end.
           if ((it & 7) == 0) {
-            switch (min(3, (4 * it) / n_interior)) {
+            const int left = n_interior - it;
+            switch (left * 2 > n_interior ? 0 : left * 4 > n_interior ? 1 : left * 8 > n_interior ? 2 : 3) {
               case 0: __builtin_amdgcn_s_setprio(3); break;
               case 1: __builtin_amdgcn_s_setprio(2); break;
               case 2: __builtin_amdgcn_s_setprio(1); break;
