@@ -879,18 +879,23 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         const int *row_tau = p.shared_tau != nullptr ? p.shared_tau + b * (p.K + 1) : nullptr;
         const int follow_idx = tid < KT ? kbase + tid : p.K;
         int seen = 0x7F800000;
+        int prio_step = -1;
         for (; it < n_interior; ++it) {
           // A SIMD serves its wavefronts oldest first, so the workgroups of a CU drift apart and the
           // last one finishes on a nearly empty machine.  The wave's own priority therefore falls as
           // it advances, in steps at 1/2, 3/4 and 7/8 of its tiles: whoever is behind a step is
           // served first and the waves meet again at every step, the last time close to the end.
-          if ((it & 7) == 0) {
+          {
             const int left = n_interior - it;
-            switch (left * 2 > n_interior ? 0 : left * 4 > n_interior ? 1 : left * 8 > n_interior ? 2 : 3) {
-              case 0: __builtin_amdgcn_s_setprio(3); break;
-              case 1: __builtin_amdgcn_s_setprio(2); break;
-              case 2: __builtin_amdgcn_s_setprio(1); break;
-              default: __builtin_amdgcn_s_setprio(0); break;
+            const int step = left * 2 > n_interior ? 0 : left * 4 > n_interior ? 1 : left * 8 > n_interior ? 2 : 3;
+            if (step != prio_step) {  // uniform
+              prio_step = step;
+              switch (step) {
+                case 0: __builtin_amdgcn_s_setprio(3); break;
+                case 1: __builtin_amdgcn_s_setprio(2); break;
+                case 2: __builtin_amdgcn_s_setprio(1); break;
+                default: __builtin_amdgcn_s_setprio(0); break;
+              }
             }
           }
           if (follows && (it & 3) == 0) {
