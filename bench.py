@@ -29,7 +29,7 @@ ALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12
 
 def algorithmic_lane_ops(K):
     """Vector-ALU lane operations per element that the method cannot avoid given how the shared
-    uniforms are defined (derivation in the design doc): one Philox4x32-10 block serves 8 elements
+    uniforms are defined: one Philox4x32-10 block serves 8 elements
     (4 indices x 2 drafts, 16 upper bits each); per block 14 32x32->64 products and 16
     three-input xors depend on both the index and the draft pair (rounds 4-10, and round 3's
     xors), 2 + 2 more are shared by the draft pairs of a pass (both instructions issue at full rate
@@ -88,7 +88,7 @@ class HipEvents:
 
 
 def algorithmic_bytes(w, materialised):
-    """Input bytes one call must read (outputs are negligible): the design doc, 'algorithmic bytes'."""
+    """Input bytes one call must read, every input row once (outputs are negligible)."""
     es = 4 if str(w.dtype).endswith("float32") else 2
     draft_rows = w.B * (w.K if (materialised or not w.shared_draft) else 1)
     return (draft_rows + w.B) * w.V * es
@@ -394,7 +394,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (rows shard across GPUs with no "
-              "communication; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "communication, through row_offset); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     if args.workload == "verify":
