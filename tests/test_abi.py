@@ -85,7 +85,7 @@ def _args(**kw):
     (dict(dtype=7), -4), (dict(kind=5), -4),
     (dict(draft=0x1002), -5),
     (dict(workspace=None), -6), (dict(workspace=0x4010), -6), (dict(workspace_bytes=16), -6),
-    (dict(flags=64), -8), (dict(v_chunks=5000), -8), (dict(k_tile=3), -8),
+    (dict(flags=64), -8), (dict(flags=2), -8), (dict(v_chunks=5000), -8), (dict(k_tile=3), -8),
 ])
 def test_argument_errors_are_reported_before_any_launch(kw, code):
     # every one of these returns on the host: no kernel runs, no GPU is needed
@@ -148,7 +148,7 @@ def _verify_args(**kw):
     (dict(kind=binding.PROBS), -4), (dict(dtype=9), -4),
     (dict(target=0x1002), -5),
     (dict(workspace=None), -6), (dict(workspace_bytes=1024), -6),
-    (dict(k_tile=5), -8),
+    (dict(k_tile=5), -8), (dict(flags=4), -8),
 ])
 def test_verify_argument_errors_are_reported_before_any_launch(kw, code):
     lib = llc.load()

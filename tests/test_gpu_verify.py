@@ -276,3 +276,13 @@ def test_strong_variant_ignores_the_draft_tokens_in_distribution_of_the_first_mi
     b = llc.llc_verify(w.target, tok, temp_target=w.temp_target, seed=w.seed)
     torch.cuda.synchronize()
     assert torch.equal(a["Y"], b["Y"]) and (a["n_out"] == 1).all() and (a["active"] == 0).all()
+
+
+def test_strong_variant_through_the_all_fp64_scan():
+    # the debugging flag and the strong flag combine: same tokens from the scan without a prefilter
+    w = workloads.make_verify("tiny", DEV)
+    a = run_verify(w, strong=True)
+    b = run_verify(w, strong=True, flags=llc.FLAG_EXACT_SCAN)
+    torch.cuda.synchronize()
+    for name in ("Y", "n_out", "active"):
+        assert torch.equal(a[name], b[name]), name
