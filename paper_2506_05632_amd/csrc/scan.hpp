@@ -309,6 +309,7 @@ __device__ __forceinline__ double exact_key(double S, float v, double T) {
 struct Lds {
   int tau[9];            // ordered-int log2 keys: drafts 0..KT-1, pool at [KT]
   int O[9];              // bits of the level-1 offsets (tau + slack + bias) 2^23; shared layout: [0] = max over drafts
+  int OL[9];             // the same lowered for the main loop (see kShift32); -inf for a reduction that is not taken
   int count;             // records appended (may exceed kListCap)
   int unsafe;            // chunk must be redone in fp64
   unsigned long long best[9];
@@ -343,6 +344,11 @@ __device__ __forceinline__ void store_offset(int *slot, float O) {
 __device__ __forceinline__ float load_offset(const int *slot) {
   return __int_as_float(__atomic_load_n(slot, __ATOMIC_RELAXED));
 }
+// An offset is kept in both forms: as it is (candidates' path) and lowered for the main loop.
+__device__ __forceinline__ void store_offsets(Lds &s, int slot, float O) {
+  store_offset(&s.O[slot], O);
+  store_offset(&s.OL[slot], O - kShift32);
+}
 // Scaled exponent of one element's threshold, merged with the target side's (FY) and capped.
 template <bool PROBS>
 __device__ __forceinline__ float merged_exponent(float v, float c23, float O, float FY) {
@@ -370,9 +376,9 @@ __device__ __forceinline__ void publish(Lds &s, int slot, float a, bool post = t
     int m = s.tau[0];
 #pragma unroll
     for (int kk = 1; kk < KT; ++kk) m = max(m, __atomic_load_n(&s.tau[kk], __ATOMIC_RELAXED));
-    store_offset(&s.O[0], make_offset<PROBS>(unord32(m)));
+    store_offsets(s, 0, make_offset<PROBS>(unord32(m)));
   } else {
-    store_offset(&s.O[slot], make_offset<PROBS>(unord32(__atomic_load_n(&s.tau[slot], __ATOMIC_RELAXED))));
+    store_offsets(s, slot, make_offset<PROBS>(unord32(__atomic_load_n(&s.tau[slot], __ATOMIC_RELAXED))));
   }
 }
 
@@ -568,6 +574,13 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
     const bool used = (tid == KT) || (tid < KT && kbase + tid < p.K);
     s.tau[tid] = used ? 0x7F800000 : (int)0x80800000;  // ord32(+inf) : ord32(-inf)
     s.O[tid] = 0x7F800000;
+    bool live = tid == KT && with_pool;
+    if (tid < KT && kbase + tid < p.K) {
+      float t = p.temp_draft_all;
+      if (p.temp_draft != nullptr) t = p.temp_draft[kbase + tid];
+      live = (t > 0.0f) && (t < __builtin_huge_valf());
+    }
+    s.OL[tid] = live ? 0x7F800000 : (int)0xFF800000;  // +inf until the warm-up has a bound : -inf
     s.best[tid] = kOrdInf64;
     s.where[tid] = ~0ull;
   }
@@ -681,12 +694,13 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
           int m = s.tau[0];
 #pragma unroll
           for (int kk = 1; kk < KT; ++kk) m = max(m, s.tau[kk]);
-          store_offset(&s.O[0], make_offset<PROBS>(unord32(m)));
+          if (kok[0]) store_offsets(s, 0, make_offset<PROBS>(unord32(m)));
         } else {
 #pragma unroll
-          for (int kk = 0; kk < KT; ++kk) store_offset(&s.O[kk], make_offset<PROBS>(unord32(s.tau[kk])));
+          for (int kk = 0; kk < KT; ++kk)
+            if (kok[kk]) store_offsets(s, kk, make_offset<PROBS>(unord32(s.tau[kk])));
         }
-        store_offset(&s.O[KT], make_offset<PROBS>(unord32(s.tau[KT])));
+        if (with_pool) store_offsets(s, KT, make_offset<PROBS>(unord32(s.tau[KT])));
       }
       __syncthreads();
     }
@@ -745,7 +759,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         philox_blocks<KB>((uint32_t)g, pair_base, row_lo, row_hi, p.seed_lo, p.seed_hi, up);
 
         // The main loop works with exponents lowered by 32 (kShift32): see packed_hi16.
-        const float OY = (with_pool ? load_offset(&s.O[KT]) : -__builtin_huge_valf()) - kShift32;
+        const float OY = load_offset(&s.OL[KT]);  // (-inf without a pool)
         float FY[4];
         {
           float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -761,7 +775,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         uint32_t most = 0u;
         if (SHARED) {
           // one threshold per index serves every draft: any_k (h_k > c) == (max_k h_k > c)
-          const float OX = load_offset(&s.O[0]) - kShift32;
+          const float OX = load_offset(&s.OL[0]);
           float vd[4];
           unpack(rd[0], vd);
           if (draft_masked) mask_bins(rb, announced, fill, vd);
@@ -776,8 +790,8 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         } else {
 #pragma unroll
           for (int m = 0; m < KB; ++m) {
-            const float OX0 = (kok[2 * m] ? load_offset(&s.O[2 * m]) : -__builtin_huge_valf()) - kShift32;
-            const float OX1 = (kok[2 * m + 1] ? load_offset(&s.O[2 * m + 1]) : -__builtin_huge_valf()) - kShift32;
+            const float OX0 = load_offset(&s.OL[2 * m]);  // (-inf for a draft that is not taken)
+            const float OX1 = load_offset(&s.OL[2 * m + 1]);
             float v0[4], v1[4];
             unpack(rd[SHARED ? 0 : 2 * m], v0);
             unpack(rd[SHARED ? 0 : 2 * m + 1], v1);
