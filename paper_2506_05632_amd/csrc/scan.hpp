@@ -762,8 +762,8 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         const float OY = load_offset(&s.OL[KT]);  // (-inf without a pool)
         float FY[4];
         {
-          float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-          if (with_pool) unpack(rq, vq);
+          float vq[4];
+          unpack(rq, vq);  // (without a pool the tile's target part keeps its initial zeros, and OY is -inf)
 #pragma unroll
           for (int j = 0; j < 4; ++j)
             FY[j] = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vq[j]), cq23, OY), 0.0f, kCapOne32);
