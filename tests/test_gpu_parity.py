@@ -235,6 +235,20 @@ def test_masked_degenerate_and_one_hot_rows():
     assert stats.cpu().numpy()[3] == 1 + K
 
 
+@pytest.mark.parametrize("K,shared", [(300, True), (70, False), (1000, True)])
+def test_many_drafts(K, shared):
+    # many draft groups per row: the pool's bound and argmin are merged over all of them
+    g = torch.Generator(device=DEV).manual_seed(K)
+    B, V = 3, 700
+    tq = 2 * torch.randn(B, V, generator=g, device=DEV)
+    td = tq + torch.randn(B, V, generator=g, device=DEV) if shared else \
+        tq[:, None, :] + torch.randn(B, K, V, generator=g, device=DEV)
+    gpu = llc.llc_couple(td, tq, K, seed=19, want_keys=True)
+    torch.cuda.synchronize()
+    ref = oracle_rows(td, tq, K, (0, B), kind="logits", temp_target=1.0, temp_draft=1.0, seed=19)
+    compare(gpu, ref)
+
+
 def test_identical_distributions_always_accept():
     g = torch.Generator(device=DEV).manual_seed(10)
     z = 3 * torch.randn(300, 7001, generator=g, device=DEV)
