@@ -10,7 +10,7 @@
 //    word x and xt = ~x, 1 - U = (xt + 1/2) 2^-32, so the test is xt <= t with an
 //    integer threshold t >= 2^(32 + tau) p.  t is built from the raw input by one
 //    fused multiply-add into the exponent/mantissa field of a float (a
-//    piecewise-linear 2^y that never under-estimates) and one conversion.
+//    piecewise-linear 2^y that never under-estimates) and two conversions.
 //    The draft-side and target-side thresholds are merged by a median-of-three.
 //    The word's upper and lower 16 bits come from two different Philox blocks, and
 //    the upper half alone decides almost every element (x >= ~t needs

@@ -249,6 +249,20 @@ def test_many_drafts(K, shared):
     compare(gpu, ref)
 
 
+def test_one_very_long_row_is_spread_over_a_thousand_workgroups():
+    # a single row of five million entries: the planner cuts it into the most chunks it allows
+    g = torch.Generator(device=DEV).manual_seed(55)
+    V, K = 5_000_011, 3
+    tq = 2 * torch.randn(1, V, generator=g, device=DEV)
+    td = tq + torch.randn(1, V, generator=g, device=DEV)
+    stats = llc.new_stats(DEV)
+    gpu = llc.llc_couple(td, tq, K, seed=2, want_keys=True, stats=stats)
+    torch.cuda.synchronize()
+    ref = oracle_rows(td, tq, K, (0, 1), kind="logits", temp_target=1.0, temp_draft=1.0, seed=2)
+    compare(gpu, ref)
+    assert stats.cpu().numpy()[2] == 0  # no workgroup fell back to the all-fp64 scan
+
+
 def test_identical_distributions_always_accept():
     g = torch.Generator(device=DEV).manual_seed(10)
     z = 3 * torch.randn(300, 7001, generator=g, device=DEV)
