@@ -285,7 +285,8 @@ typedef struct llc_couple_topm_args {
  * divided by their sum.  An entry without mass on one side (logit -inf, probability 0) adds no
  * term j but still counts as a summand i with the mass it has on the other side (the limit of the
  * formula); NaN and +inf entries carry no mass.  Results are fp64; indices whose q/p agree to fp32
- * precision are ordered arbitrarily, which moves a result by a relative 2^-23 at most.
+ * precision are ordered arbitrarily and the masses enter the running sums rounded to fp32, which
+ * together move a result by a relative 2^-22 at most.
  * The workspace (llc_lml_workspace_size bytes, 256-byte aligned, device) belongs to the call
  * until it has finished. */
 #define LLC_LML_MAX_K 8

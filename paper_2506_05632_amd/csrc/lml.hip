@@ -217,14 +217,20 @@ __global__ void __launch_bounds__(kThreads) lml_kernel(const LmlParams p) {
   __syncthreads();
   // after four passes the sorted order is back in the first buffer (in == buf_a)
 
-  // ---- running sums over the sorted order.  Each part's masses first, then every wavefront
-  // walks its part with the masses of the parts before it as the carry.
+  // ---- running sums over the sorted order.  One pass gathers the masses by sorted index, leaves
+  // them in sorted order in the spare buffer (as fp32: a relative 2^-24 per mass) and adds up each
+  // part's masses; then every wavefront walks its part, reading the masses back in order, with
+  // the masses of the parts before it as the carry.
+  float2 *mass = reinterpret_cast<float2 *>(out);
   double seg_p = 0.0, seg_q = 0.0;
   for (int j = seg_begin + lane; j < seg_end; j += 64) {
     const int i = (int)in[j].y;
     const double lp = sp.log_mass(elem<E>(prow, i)), lq = sq.log_mass(elem<E>(qrow, i));
-    seg_p += lp > -__builtin_huge_val() ? exp(lp) : 0.0;
-    seg_q += lq > -__builtin_huge_val() ? exp(lq) : 0.0;
+    const float pf = lp > -__builtin_huge_val() ? (float)exp(lp) : 0.0f;
+    const float qf = lq > -__builtin_huge_val() ? (float)exp(lq) : 0.0f;
+    mass[j] = make_float2(pf, qf);
+    seg_p += (double)pf;
+    seg_q += (double)qf;
   }
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) { seg_p += __shfl_xor(seg_p, d); seg_q += __shfl_xor(seg_q, d); }
@@ -242,10 +248,9 @@ __global__ void __launch_bounds__(kThreads) lml_kernel(const LmlParams p) {
     const int j = j0 + lane;
     double pm = 0.0, qm = 0.0;
     if (j < seg_end) {
-      const int i = (int)in[j].y;
-      const double lp = sp.log_mass(elem<E>(prow, i)), lq = sq.log_mass(elem<E>(qrow, i));
-      pm = lp > -__builtin_huge_val() ? exp(lp) : 0.0;
-      qm = lq > -__builtin_huge_val() ? exp(lq) : 0.0;
+      const float2 m = mass[j];  // written by this lane in the pass above
+      pm = (double)m.x;
+      qm = (double)m.y;
     }
     double pin = pm, qin = qm;  // inclusive sums over the lanes of this tile
 #pragma unroll
