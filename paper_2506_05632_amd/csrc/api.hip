@@ -87,9 +87,9 @@ RowMap plain_rows(long long draft_stride_b, long long target_stride_b) {
 // the strong form the loop's state: per sequence K viability bytes, K second candidates (key and
 // index), a running flag and the next position's row offset.
 struct VerifyExtra {
-  size_t cand_key, cand, viable, running, next_off, cand2_key, cand2, lse, lse_sel, total;
+  size_t cand_key, cand, viable, running, next_off, tau_all, lse, lse_sel, total;
 };
-VerifyExtra verify_extra(long long S, long long B, long long K) {
+VerifyExtra verify_extra(long long S, long long B, long long K) {  // B = S (L + 1)
   VerifyExtra e;
   size_t off = 0;
   e.cand_key = off; off += align256((size_t)(B * K) * sizeof(double));
@@ -97,8 +97,7 @@ VerifyExtra verify_extra(long long S, long long B, long long K) {
   e.viable = off; off += align256((size_t)(S * K));
   e.running = off; off += align256((size_t)S * sizeof(int32_t));
   e.next_off = off; off += align256((size_t)S * sizeof(long long));
-  e.cand2_key = off; off += align256((size_t)(S * K) * sizeof(double));
-  e.cand2 = off; off += align256((size_t)(S * K) * sizeof(int32_t));
+  e.tau_all = off; off += align256((size_t)((B - S) * (K + 1)) * sizeof(int32_t));  // running bests of positions 1..L
   e.lse = off; off += align256((size_t)(B * (K + 1)) * sizeof(double));      // the one-shot scan's normalisers
   e.lse_sel = off; off += align256((size_t)(S * (K + 1)) * sizeof(double));  // those of the rows that price a position
   e.total = off;
@@ -124,6 +123,7 @@ struct ScanJob {
   const int32_t *bin_of = nullptr;
   const long long *draft_row_off = nullptr;  // per-row extra offset of the draft row (see ScanParams)
   size_t lse_in_extra = (size_t)-1;  // keep the normalisers at this offset of the caller's region
+  int32_t *tau_ready = nullptr;      // the rows' shared running bests, already reset, if not in the workspace
   int flags, v_chunks, k_tile;
   llc_stats *stats;
   void *workspace;
@@ -213,8 +213,12 @@ int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
   // a row spread over several workgroups shares its running bests through the workspace
   int32_t *shared_tau = nullptr;
   if (pl.n_chunks * pl.n_kgroups > 1) {
-    shared_tau = (int32_t *)(ws + lay.shared_tau);
-    if (launch_fill(st, shared_tau, j.B * (j.K + 1), 0x7F800000) != hipSuccess) return LLC_E_LAUNCH;
+    if (j.tau_ready != nullptr) {
+      shared_tau = j.tau_ready;
+    } else {
+      shared_tau = (int32_t *)(ws + lay.shared_tau);
+      if (launch_fill(st, shared_tau, j.B * (j.K + 1), 0x7F800000) != hipSuccess) return LLC_E_LAUNCH;
+    }
   }
 
   ScanParams sp;
@@ -541,11 +545,13 @@ int llc_verify(const llc_verify_args *a) {
     // Appendix B: position by position, because which drafts are dropped (and whose row prices
     // them) is only known once the position before is settled.  The dropped drafts of a position
     // all take the first viable draft's row: one scan in the shared-proposal layout per position
-    // over the S sequences, skipped by the kernels for sequences that have nothing to price.
+    // over the S sequences, skipped by the kernels for sequences that have nothing to price, and
+    // one step kernel, which also merges that scan's chunks: two launches per position.
     StrongStepParams ss;
     ss.S = a->S; ss.L = (int)a->L; ss.K = (int)a->K;
     ss.cand = cand; ss.cand_key = cand_key;
-    ss.cand2 = (int32_t *)(extra + ex.cand2); ss.cand2_key = (double *)(extra + ex.cand2_key);
+    ss.part_key = nullptr; ss.part_idx = nullptr; ss.n_chunks = 0;
+    ss.tau_all = (int32_t *)(extra + ex.tau_all);
     ss.tokens = a->tokens; ss.tok_stride_s = a->tok_stride_s; ss.tok_stride_j = a->tok_stride_j;
     ss.stride_k = a->stride_k;
     ss.viable = (uint8_t *)(extra + ex.viable); ss.running = (int32_t *)(extra + ex.running);
@@ -567,6 +573,7 @@ int llc_verify(const llc_verify_args *a) {
         q.draft_row_off = ss.next_off;
         q.need_lse = false;         // the rows' normalisers are known from the one-shot scan
         q.lse_in_extra = (size_t)-1;
+        q.tau_ready = ss.tau_all + (pos - 1) * a->S * (a->K + 1);
         q.stats = nullptr; q.ev_begin = nullptr; q.ev_end = nullptr;
         q.workspace_bytes = (size_t)(extra - (char *)a->workspace);  // the first scan's partials are spent
         q.extra_bytes = 0;
@@ -574,13 +581,7 @@ int llc_verify(const llc_verify_args *a) {
         Partials part2;
         const int rc2 = run_scan(q, &pl2, &part2, nullptr);
         if (rc2 != LLC_OK) return rc2;
-        FinalizeParams f2 = fp;
-        f2.B = a->S; f2.n_chunks = pl2.n_chunks; f2.n_kgroups = pl2.n_kgroups;
-        f2.in = part2;
-        f2.in.lse = ss.lse_sel;
-        f2.X = (int32_t *)(extra + ex.cand2); f2.keyX = nullptr;
-        f2.log_keyX = (double *)(extra + ex.cand2_key); f2.stats = nullptr;
-        if (launch_finalize(st, f2) != hipSuccess) return LLC_E_LAUNCH;
+        ss.part_key = part2.keyX; ss.part_idx = part2.idxX; ss.n_chunks = pl2.n_chunks;
       }
       ss.j = (int)pos;
       if (launch_strong_step(st, ss) != hipSuccess) return LLC_E_LAUNCH;

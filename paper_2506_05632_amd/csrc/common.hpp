@@ -133,8 +133,12 @@ struct StrongStepParams {
   int L, K, j;               // position j of 0..L
   const int32_t *cand;       // [S][L+1][K] own-row argmins (viable drafts)
   const double *cand_key;    // [S][L+1][K] ln of their normalised keys
-  const int32_t *cand2;      // [S][K] argmins of this position priced with the first viable draft's row
-  const double *cand2_key;   // [S][K]  (only read for dropped drafts; unused at j == 0)
+  // this position priced with the first viable draft's row, as the scan left it: per-chunk
+  // partial argmins (only read for dropped drafts; unused at j == 0)
+  const double *part_key;    // [S][K][n_chunks] ln-domain keys before the normaliser is added
+  const int32_t *part_idx;   // [S][K][n_chunks]
+  int n_chunks;
+  int32_t *tau_all;          // [L][S][K+1] the later positions' shared running bests: reset at j == 0
   const int32_t *tokens;
   long long tok_stride_s, tok_stride_j;
   long long stride_k;        // of the target tensor, for the next position's row offsets

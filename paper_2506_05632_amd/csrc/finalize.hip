@@ -196,7 +196,7 @@ __global__ void __launch_bounds__(256) lse_kernel(const LseParams p) {
     if (gm > m) {
       if (m > -inf) {
         const float d = m - gm;
-        sum *= (double)exp2f(fmaf(d, c_hi, d * c_lo));
+        sum *= (double)__builtin_amdgcn_exp2f(fmaf(d, c_hi, d * c_lo));
       }
       m = gm;
     }
@@ -207,7 +207,7 @@ __global__ void __launch_bounds__(256) lse_kernel(const LseParams p) {
         // <= 0; entries without mass are clamped to a finite distance whose term is exactly 0
         // (an infinite one would meet c_lo's sign in the two-float product)
         const float d = fmaxf(v[j] - m, -65536.0f);
-        part += exp2f(fmaf(d, c_hi, d * c_lo));
+        part += __builtin_amdgcn_exp2f(fmaf(d, c_hi, d * c_lo));
       }
       sum += (double)part;
     }
@@ -308,6 +308,11 @@ __global__ void __launch_bounds__(64) strong_step_kernel(const StrongStepParams 
   float *keyY = p.keyY != nullptr ? p.keyY + s * (L + 1) : nullptr;
   bool viable = lane < K;
   bool running = true;
+  if (j == 0 && p.tau_all != nullptr) {
+    // the scans of the later positions find their rows' running bests reset
+    for (int t = lane; t < L * (K + 1); t += 64)
+      p.tau_all[((long long)(t / (K + 1)) * p.S + s) * (K + 1) + t % (K + 1)] = 0x7F800000;
+  }
   if (j > 0) {
     viable = lane < K && p.viable[s * K + lane] != 0;
     running = p.running[s] != 0;
@@ -327,8 +332,14 @@ __global__ void __launch_bounds__(64) strong_step_kernel(const StrongStepParams 
       key = p.cand_key[(s * (L + 1) + j) * K + lane];
       idx = p.cand[(s * (L + 1) + j) * K + lane];
     } else {
-      key = p.cand2_key[s * K + lane];
-      idx = p.cand2[s * K + lane];
+      // merge the chunks of this draft's scan (as the finalize kernel does) and normalise
+      const long long o = (s * K + lane) * p.n_chunks;
+      for (int c = 0; c < p.n_chunks; ++c) {
+        const double ckey = p.part_key[o + c];
+        const int cidx = p.part_idx[o + c];
+        if (beats(ckey, cidx, 0, key, idx, 0)) { key = ckey; idx = cidx; }
+      }
+      key = idx >= 0 ? key + p.lse_sel[s * (K + 1) + lane] : __builtin_huge_val();
     }
   }
   double bkey = idx >= 0 ? key : __builtin_huge_val();

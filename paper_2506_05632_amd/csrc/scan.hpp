@@ -750,7 +750,8 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const float d = fmaxf(v[j] - lse_ref[LSE ? slot : 0], -65536.0f);
-          part += exp2f(fmaf(d, lse_hi[slot], d * lse_lo[slot]));
+          // (the bare hardware exp2: a term below 2^-126 of the largest one may flush to 0)
+          part += __builtin_amdgcn_exp2f(fmaf(d, lse_hi[slot], d * lse_lo[slot]));
         }
         lse_acc[LSE ? slot : 0] += (double)part;
       };
@@ -879,8 +880,9 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
       const int n_interior = max(0, (interior_end - g_begin) / kBlock);
       int it = 0;
       if (n_interior > 0) {
-        // the next tile's loads are issued one tile of arithmetic before they are used (a second
-        // register set consumed in turn instead of the copies below measured slower)
+        // the next tile's loads are issued one tile of arithmetic before they are used (two
+        // register sets that swap roles in a loop unrolled twice, instead of the copies below,
+        // measured slower in both layouts)
         raw aq = raw(), ad[KD], bq = raw(), bd[KD];
         uint32_t ab = 0, bb = 0;
         const int g0 = g_begin + tid;
