@@ -84,8 +84,9 @@ RowMap plain_rows(long long draft_stride_b, long long target_stride_b) {
 }
 
 // llc_verify keeps, beyond the scan's partials, ln(key) [B][K] fp64 and the index [B][K], and for
-// the strong form the loop's state: per sequence K viability bytes, K second candidates (key and
-// index), a running flag and the next position's row offset.
+// the strong form the loop's state: per sequence K viability bytes, a running flag and the next
+// position's row offset; the running bests that the scans of positions 1..L share; the
+// normalisers of every row and of the rows that price the position at hand.
 struct VerifyExtra {
   size_t cand_key, cand, viable, running, next_off, tau_all, lse, lse_sel, total;
 };
