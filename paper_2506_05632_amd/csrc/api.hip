@@ -439,8 +439,8 @@ int llc_couple_topm(const llc_couple_topm_args *a) {
 
 size_t llc_lml_workspace_size(int64_t B, int64_t V) {
   if (!shape_ok(B, 1, V)) return 0;
-  // two buffers of (key, index) pairs per row
-  return align256((size_t)B * 2 * (size_t)V * 8) + 256;
+  // per row two buffers of sort keys (4 bytes) and two of mass pairs (8 bytes)
+  return align256((size_t)B * 24 * (size_t)V) + 256;
 }
 
 int llc_lml_bound(const llc_lml_args *a) {
@@ -470,7 +470,7 @@ int llc_lml_bound(const llc_lml_args *a) {
   p.n_k = a->n_k;
   for (int n = 0; n < LLC_LML_MAX_K; ++n) p.k[n] = n < a->n_k ? a->k[n] : 1;
   p.bound = a->bound; p.relaxed = a->relaxed; p.tv = a->tv;
-  p.pairs = (uint2 *)a->workspace;
+  p.work = (char *)a->workspace;
   hipStream_t st = (hipStream_t)a->stream;
   if (a->ev_begin != nullptr && hipEventRecord((hipEvent_t)a->ev_begin, st) != hipSuccess) return LLC_E_LAUNCH;
   if (launch_lml(st, p) != hipSuccess) return LLC_E_LAUNCH;

@@ -191,7 +191,7 @@ struct LmlParams {
   double *bound;    // [B][n_k]
   double *relaxed;  // [B][n_k] or nullptr
   double *tv;       // [B] or nullptr
-  uint2 *pairs;     // workspace [B][2][V] (sort key, index)
+  char *work;       // workspace: per row two buffers of V sort keys, then two of V (p-mass, q-mass) pairs
 };
 
 // One launcher per (element type, draft layout); defined in scan_*.hip.

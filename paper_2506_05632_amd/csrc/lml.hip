@@ -8,9 +8,10 @@
 // max{q_i/q_j, p_i/p_j} is q_i/q_j exactly when q_i/p_i >= q_j/p_j, so with the indices sorted by
 // r = q/p the inner sum is (the q-mass from j on)/q_j + (the p-mass before j)/p_j + (K-1) Q/q_j:
 // one sort and one running sum per row.  One workgroup does a whole row: normalisers, sort keys,
-// four passes of a stable 8-bit radix sort on the fp32 image of ln r through two buffers in the
-// workspace, and the running sums in fp64.  Indices whose r agree to fp32 precision may come out
-// in either order, which moves their contribution by a relative 2^-23 at most.
+// four passes of a stable 8-bit radix sort on the fp32 image of ln r, in which the two masses of
+// an entry (rounded to fp32) travel with its key through two buffers in the workspace, and the
+// running sums in fp64.  Indices whose r agree to fp32 precision may come out in either order,
+// which together with the rounding of the masses moves a result by a relative 2^-22 at most.
 // Entries without mass on one side follow the limits: p_j = 0 or q_j = 0 gives term j = 0; as a
 // summand i such an entry still counts with the mass it has on the other side.
 #include "common.hpp"
@@ -18,8 +19,10 @@
 namespace llc {
 namespace {
 
-constexpr int kThreads = 1024;        // sixteen wavefronts share a row: each owns a sixteenth of it
+constexpr int kThreads = 512;         // eight wavefronts share a row
 constexpr int kWaves = kThreads / 64;
+constexpr int kRounds = 8;            // elements a thread holds per tile of the sort
+constexpr int kTile = kThreads * kRounds;
 
 template <typename E>
 __device__ __forceinline__ float elem(const E *row, int i);
@@ -104,22 +107,35 @@ __device__ __forceinline__ uint32_t sort_key(float f) {
 template <typename E>
 __global__ void __launch_bounds__(kThreads) lml_kernel(const LmlParams p) {
   __shared__ double s_red[kWaves];
-  __shared__ int s_bins[kWaves][256];
-  __shared__ int s_wave_total[4];
+  __shared__ unsigned short s_cnt[kWaves][256];  // per wavefront and digit of a tile: counts, then starts
+  __shared__ int s_goff[256];          // where a digit's run continues in the output
+  __shared__ int s_tstart[256];        // where a digit's run starts inside the tile
+  __shared__ int s_gbase[256];         // s_goff - s_tstart of the tile at hand
+  __shared__ uint32_t st_key[kTile];   // the tile in digit order, on its way out
+  __shared__ float2 st_mass[kTile];
   __shared__ double s_seg[kWaves][2];
+  __shared__ int s_total[4][256];      // how often every digit of every pass occurs in the row
+  // while the keys are made the staging area holds the counters: per pass, wavefront and digit
+  static_assert(sizeof(st_mass) >= 4 * kWaves * 256 * sizeof(int), "the counters do not fit");
+  int (*hist)[kWaves][256] = reinterpret_cast<int (*)[kWaves][256]>(st_mass);
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const long long b = blockIdx.x;
   const int V = p.V;
   const E *prow = reinterpret_cast<const E *>(p.draft) + b * p.draft_stride_b;
   const E *qrow = reinterpret_cast<const E *>(p.target) + b * p.target_stride_b;
-  // (key, index) pairs travel together: one 8-byte store per element and pass
-  uint2 *buf_a = p.pairs + (size_t)b * 2 * V, *buf_b = buf_a + V;
+  // per row: two key buffers, then two buffers of (p-mass, q-mass)
+  char *work = p.work + (size_t)b * 24u * (size_t)V;
+  uint32_t *key_a = reinterpret_cast<uint32_t *>(work), *key_b = key_a + V;
+  float2 *mass_a = reinterpret_cast<float2 *>(work + 8u * (size_t)V), *mass_b = mass_a + V;
 
   const Side sp = normalise<E>(prow, V, p.probs, p.temp_draft, s_red);
   const Side sq = normalise<E>(qrow, V, p.probs, p.temp_target, s_red);
 
-  // ---- sort keys, and the sums that need no order
+  // ---- sort keys with the masses that travel with them, how often every digit occurs (the
+  // arithmetic around them hides the counters' collisions), and the sums that need no order
+  for (int j = tid; j < 4 * kWaves * 256; j += kThreads) (&hist[0][0][0])[j] = 0;
+  __syncthreads();
   double tv = 0.0, relaxed[kLmlMaxK];
 #pragma unroll
   for (int kk = 0; kk < kLmlMaxK; ++kk) relaxed[kk] = 0.0;
@@ -128,8 +144,12 @@ __global__ void __launch_bounds__(kThreads) lml_kernel(const LmlParams p) {
     const bool hp = lp > -__builtin_huge_val(), hq = lq > -__builtin_huge_val();
     float lr = -__builtin_huge_valf();           // no target mass (or none at all): sorts first
     if (hq) lr = hp ? (float)(lq - lp) : __builtin_huge_valf();
-    buf_a[i] = make_uint2(sort_key(lr), (uint32_t)i);
     const double pm = hp ? exp(lp) : 0.0, qm = hq ? exp(lq) : 0.0;
+    const uint32_t key = sort_key(lr);
+    key_a[i] = key;
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) atomicAdd(&hist[pass][wv][(key >> (8 * pass)) & 255u], 1);
+    mass_a[i] = make_float2((float)pm, (float)qm);
     tv += fabs(pm - qm);
     if (hp && hq) {
 #pragma unroll
@@ -145,92 +165,148 @@ __global__ void __launch_bounds__(kThreads) lml_kernel(const LmlParams p) {
       if (tid == 0 && p.relaxed != nullptr) p.relaxed[b * p.n_k + kk] = r;
     }
   if (tid == 0 && p.tv != nullptr) p.tv[b] = 0.5 * tv;
+  // (block_sum has synchronised since the last counter was bumped)
+  for (int j = tid; j < 4 * 256; j += kThreads) {
+    int total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) total += hist[j >> 8][w][j & 255];
+    s_total[j >> 8][j & 255] = total;
+  }
 
-  // ---- stable radix sort, 8 bits a pass.  Wavefront w owns the w-th part of the row: it counts
-  // its digits, gets its own start inside every digit's range (after the parts before it), and
-  // then moves its part tile by tile in order, so equal digits keep their order.
-  const int seg = (V + kWaves - 1) / kWaves;
-  const int seg_begin = min(wv * seg, V), seg_end = min(seg_begin + seg, V);
-  uint2 *in = buf_a, *out = buf_b;
+  // ---- stable radix sort, 8 bits a pass.  A pass takes the row a tile of kTile entries at a
+  // time: wavefront w holds the w-th part of the tile,
+  // ranks them among the tile's entries of the same digit (within the wavefront by ballots, in
+  // order; across wavefronts by a prefix over their counts), the tile is laid out in digit order
+  // in LDS, and is written from there so that neighbouring threads write neighbouring addresses
+  // (a digit's entries of one tile are contiguous in the output).
+  uint32_t *kin = key_a, *kout = key_b;
+  float2 *min_ = mass_a, *mout = mass_b;
 #pragma unroll 1
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 8 * pass;
     __syncthreads();  // the previous pass's (or the key loop's) stores are done and visible
-    for (int j = tid; j < kWaves * 256; j += kThreads) (&s_bins[0][0])[j] = 0;
-    __syncthreads();
-    for (int i = seg_begin + lane; i < seg_end; i += 64) atomicAdd(&s_bins[wv][(in[i].x >> shift) & 255u], 1);
-    __syncthreads();
-    {
-      // thread t < 256 = digit t: where the digit's range starts, then every part's start inside it
-      int total = 0;
-      if (tid < 256) {
+    if (wv == 0) {
+      // lane l takes digits l, 64 + l, 128 + l, 192 + l: the start of every digit's run
+      int carry = 0;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) total += s_bins[w][tid];
-      }
-      int incl = total;
+      for (int q = 0; q < 4; ++q) {
+        const int d = q * 64 + lane;
+        const int total = s_total[pass][d];
+        int incl = total;
 #pragma unroll
-      for (int d = 1; d < 64; d <<= 1) {
-        const int up = __shfl_up(incl, d);
-        if (lane >= d) incl += up;
+        for (int dd = 1; dd < 64; dd <<= 1) {
+          const int up = __shfl_up(incl, dd);
+          if (lane >= dd) incl += up;
+        }
+        s_goff[d] = carry + incl - total;
+        carry += __shfl(incl, 63);
       }
-      if (tid < 256 && lane == 63) s_wave_total[wv] = incl;
+    }
+#pragma unroll 1
+    for (int t0 = 0; t0 < V; t0 += kTile) {
+      __syncthreads();  // the tile before is on its way out of LDS; s_goff is in place
+      for (int j = tid; j < kWaves * 256; j += kThreads) (&s_cnt[0][0])[j] = 0;
       __syncthreads();
-      if (tid < 256) {
-        int start = incl - total;
-        for (int w = 0; w < wv; ++w) start += s_wave_total[w];
+      uint32_t key[kRounds];
+      float2 mass[kRounds];
+      int where[kRounds];  // rank among the wavefront's entries of the same digit
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-          const int c = s_bins[w][tid];
-          s_bins[w][tid] = start;
-          start += c;
+      for (int e = 0; e < kRounds; ++e) {
+        const int i = t0 + wv * (64 * kRounds) + e * 64 + lane;
+        const bool valid = i < V;
+        key[e] = valid ? kin[i] : 0u;
+        mass[e] = valid ? min_[i] : make_float2(0.0f, 0.0f);
+      }
+#pragma unroll
+      for (int e = 0; e < kRounds; ++e) {
+        const bool valid = t0 + wv * (64 * kRounds) + e * 64 + lane < V;
+        const uint32_t d = (key[e] >> shift) & 255u;
+        // lanes of this round with the same digit
+        unsigned long long peers = __ballot(valid);
+#pragma unroll
+        for (int bit = 0; bit < 8; ++bit) {
+          const bool set = (d >> bit) & 1u;
+          const unsigned long long have = __ballot(set);
+          peers &= set ? have : ~have;
+        }
+        where[e] = 0;
+        if (valid) {
+          const int rank = __popcll(peers & ((1ull << lane) - 1ull));
+          const int seen = s_cnt[wv][d];
+          if (rank == 0) s_cnt[wv][d] = (unsigned short)(seen + __popcll(peers));
+          where[e] = seen + rank;
+        }
+        __builtin_amdgcn_wave_barrier();
+      }
+      __syncthreads();
+      if (wv == 0) {
+        // per digit: every wavefront's start inside the digit's part of the tile, the part's start
+        // inside the tile, and where the part goes in the output
+        int carry = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int d = q * 64 + lane;
+          int total = 0;
+#pragma unroll
+          for (int w = 0; w < kWaves; ++w) {
+            const int c = s_cnt[w][d];
+            s_cnt[w][d] = (unsigned short)total;
+            total += c;
+          }
+          int incl = total;
+#pragma unroll
+          for (int dd = 1; dd < 64; dd <<= 1) {
+            const int up = __shfl_up(incl, dd);
+            if (lane >= dd) incl += up;
+          }
+          const int start = carry + incl - total;
+          carry += __shfl(incl, 63);
+          const int g = s_goff[d];
+          s_tstart[d] = start;
+          s_gbase[d] = g - start;
+          s_goff[d] = g + total;
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < kRounds; ++e) {
+        if (t0 + wv * (64 * kRounds) + e * 64 + lane < V) {
+          const uint32_t d = (key[e] >> shift) & 255u;
+          const int pos = s_tstart[d] + s_cnt[wv][d] + where[e];
+          st_key[pos] = key[e];
+          st_mass[pos] = mass[e];
+        }
+      }
+      __syncthreads();
+      const int n_tile = min(kTile, V - t0);
+#pragma unroll
+      for (int e = 0; e < kRounds; ++e) {
+        const int pos = e * kThreads + tid;
+        if (pos < n_tile) {
+          const uint32_t k = st_key[pos];
+          const int g = s_gbase[(k >> shift) & 255u] + pos;
+          kout[g] = k;
+          mout[g] = st_mass[pos];
         }
       }
     }
-    __syncthreads();
-    // (the next tile is fetched before this one is placed)
-    uint2 next = make_uint2(0u, 0u);
-    if (seg_begin + lane < seg_end) next = in[seg_begin + lane];
-    for (int i0 = seg_begin; i0 < seg_end; i0 += 64) {
-      const int i = i0 + lane;
-      const bool valid = i < seg_end;
-      const uint2 cur = next;
-      if (i + 64 < seg_end) next = in[i + 64];
-      const uint32_t d = (cur.x >> shift) & 255u;
-      // lanes of this tile with the same digit
-      unsigned long long peers = __ballot(valid);
-#pragma unroll
-      for (int bit = 0; bit < 8; ++bit) {
-        const bool set = (d >> bit) & 1u;
-        const unsigned long long have = __ballot(set);
-        peers &= set ? have : ~have;
-      }
-      if (valid) {
-        const int rank = __popcll(peers & ((1ull << lane) - 1ull));
-        const int start = s_bins[wv][d];
-        if (rank == 0) s_bins[wv][d] = start + __popcll(peers);
-        out[start + rank] = cur;
-      }
-      __builtin_amdgcn_wave_barrier();
-    }
-    uint2 *t = in; in = out; out = t;
+    { uint32_t *t = kin; kin = kout; kout = t; }
+    { float2 *t = min_; min_ = mout; mout = t; }
   }
   __syncthreads();
-  // after four passes the sorted order is back in the first buffer (in == buf_a)
+  // after four passes the sorted order is back in the first buffers (min_ == mass_a)
 
-  // ---- running sums over the sorted order.  One pass gathers the masses by sorted index, leaves
-  // them in sorted order in the spare buffer (as fp32: a relative 2^-24 per mass) and adds up each
-  // part's masses; then every wavefront walks its part, reading the masses back in order, with
-  // the masses of the parts before it as the carry.
-  float2 *mass = reinterpret_cast<float2 *>(out);
+  // ---- running sums over the sorted order.  Wavefront w takes the w-th part of the row: first
+  // every part's masses are added up, then every wavefront walks its part with the masses of the
+  // parts before it as the carry.
+  const int seg = (V + kWaves - 1) / kWaves;
+  const int seg_begin = min(wv * seg, V), seg_end = min(seg_begin + seg, V);
+  const float2 *mass = min_;
   double seg_p = 0.0, seg_q = 0.0;
   for (int j = seg_begin + lane; j < seg_end; j += 64) {
-    const int i = (int)in[j].y;
-    const double lp = sp.log_mass(elem<E>(prow, i)), lq = sq.log_mass(elem<E>(qrow, i));
-    const float pf = lp > -__builtin_huge_val() ? (float)exp(lp) : 0.0f;
-    const float qf = lq > -__builtin_huge_val() ? (float)exp(lq) : 0.0f;
-    mass[j] = make_float2(pf, qf);
-    seg_p += (double)pf;
-    seg_q += (double)qf;
+    const float2 m = mass[j];
+    seg_p += (double)m.x;
+    seg_q += (double)m.y;
   }
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) { seg_p += __shfl_xor(seg_p, d); seg_q += __shfl_xor(seg_q, d); }
@@ -248,7 +324,7 @@ __global__ void __launch_bounds__(kThreads) lml_kernel(const LmlParams p) {
     const int j = j0 + lane;
     double pm = 0.0, qm = 0.0;
     if (j < seg_end) {
-      const float2 m = mass[j];  // written by this lane in the pass above
+      const float2 m = mass[j];
       pm = (double)m.x;
       qm = (double)m.y;
     }
