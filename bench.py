@@ -49,7 +49,7 @@ MEASURED_TRAFFIC_BYTES = {
     "is_n65536_l4_f32": 5381.6e6 + 0.3e6,
     "specdec_v32000_k4_bf16": 33.3e6 + 0.5e6,
     "verify_largevocab_s128_l7_k8_v128256": 4214.8e6 + 1.5e6,
-    "lml_largevocab_v128256_k8_f32": 43188.7e6 + 14733.0e6,
+    "lml_largevocab_v128256_k8_f32": 11557.8e6 + 9424.1e6,
 }
 
 

@@ -16,6 +16,8 @@
 // summand i such an entry still counts with the mass it has on the other side.
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace llc {
 namespace {
 
@@ -202,8 +204,9 @@ __global__ void __launch_bounds__(kThreads) lml_kernel(const LmlParams p) {
         carry += __shfl(incl, 63);
       }
     }
-#pragma unroll 1
-    for (int t0 = 0; t0 < V; t0 += kTile) {
+    // (FULL: every entry of the tile exists, nothing is checked)
+    auto sort_tile = [&](auto full_tag, const int t0) {
+      constexpr bool FULL = decltype(full_tag)::value;
       __syncthreads();  // the tile before is on its way out of LDS; s_goff is in place
       for (int j = tid; j < kWaves * 256; j += kThreads) (&s_cnt[0][0])[j] = 0;
       __syncthreads();
@@ -213,27 +216,29 @@ __global__ void __launch_bounds__(kThreads) lml_kernel(const LmlParams p) {
 #pragma unroll
       for (int e = 0; e < kRounds; ++e) {
         const int i = t0 + wv * (64 * kRounds) + e * 64 + lane;
-        const bool valid = i < V;
+        const bool valid = FULL || i < V;
         key[e] = valid ? kin[i] : 0u;
         mass[e] = valid ? min_[i] : make_float2(0.0f, 0.0f);
       }
 #pragma unroll
       for (int e = 0; e < kRounds; ++e) {
-        const bool valid = t0 + wv * (64 * kRounds) + e * 64 + lane < V;
+        const bool valid = FULL || t0 + wv * (64 * kRounds) + e * 64 + lane < V;
         const uint32_t d = (key[e] >> shift) & 255u;
-        // lanes of this round with the same digit
-        unsigned long long peers = __ballot(valid);
+        // lanes of this round with the same digit: bit by bit, keep those whose bit is like mine
+        const unsigned long long live = __ballot(valid);
+        uint32_t peers_lo = (uint32_t)live, peers_hi = (uint32_t)(live >> 32);
 #pragma unroll
         for (int bit = 0; bit < 8; ++bit) {
-          const bool set = (d >> bit) & 1u;
-          const unsigned long long have = __ballot(set);
-          peers &= set ? have : ~have;
+          const uint32_t mine = (uint32_t)__builtin_amdgcn_sbfe((int)d, bit, 1);  // all ones if the bit is set
+          const unsigned long long have = __ballot(mine != 0u);
+          peers_lo &= ~((uint32_t)have ^ mine);
+          peers_hi &= ~((uint32_t)(have >> 32) ^ mine);
         }
         where[e] = 0;
         if (valid) {
-          const int rank = __popcll(peers & ((1ull << lane) - 1ull));
+          const int rank = (int)__builtin_amdgcn_mbcnt_hi(peers_hi, __builtin_amdgcn_mbcnt_lo(peers_lo, 0u));
           const int seen = s_cnt[wv][d];
-          if (rank == 0) s_cnt[wv][d] = (unsigned short)(seen + __popcll(peers));
+          if (rank == 0) s_cnt[wv][d] = (unsigned short)(seen + __popc(peers_lo) + __popc(peers_hi));
           where[e] = seen + rank;
         }
         __builtin_amdgcn_wave_barrier();
@@ -270,7 +275,7 @@ __global__ void __launch_bounds__(kThreads) lml_kernel(const LmlParams p) {
       __syncthreads();
 #pragma unroll
       for (int e = 0; e < kRounds; ++e) {
-        if (t0 + wv * (64 * kRounds) + e * 64 + lane < V) {
+        if (FULL || t0 + wv * (64 * kRounds) + e * 64 + lane < V) {
           const uint32_t d = (key[e] >> shift) & 255u;
           const int pos = s_tstart[d] + s_cnt[wv][d] + where[e];
           st_key[pos] = key[e];
@@ -278,18 +283,22 @@ __global__ void __launch_bounds__(kThreads) lml_kernel(const LmlParams p) {
         }
       }
       __syncthreads();
-      const int n_tile = min(kTile, V - t0);
+      const int n_tile = FULL ? kTile : min(kTile, V - t0);
 #pragma unroll
       for (int e = 0; e < kRounds; ++e) {
         const int pos = e * kThreads + tid;
-        if (pos < n_tile) {
+        if (FULL || pos < n_tile) {
           const uint32_t k = st_key[pos];
           const int g = s_gbase[(k >> shift) & 255u] + pos;
           kout[g] = k;
           mout[g] = st_mass[pos];
         }
       }
-    }
+    };
+    int t0 = 0;
+#pragma unroll 1
+    for (; t0 + kTile <= V; t0 += kTile) sort_tile(std::true_type(), t0);
+    if (t0 < V) sort_tile(std::false_type(), t0);
     { uint32_t *t = kin; kin = kout; kout = t; }
     { float2 *t = min_; min_ = mout; mout = t; }
   }
