@@ -32,7 +32,8 @@ def check(draft, target, ks, rows=None, **kw):
     return gpu, ref
 
 
-@pytest.mark.parametrize("V", [1, 2, 63, 64, 65, 255, 256, 257, 1000, 4099])
+# (the sort takes a row 4096 entries at a time: one tile exactly, one entry more, several tiles)
+@pytest.mark.parametrize("V", [1, 2, 63, 64, 65, 255, 256, 257, 1000, 4095, 4096, 4097, 8192, 12289])
 @pytest.mark.parametrize("kind", ["logits", "logw", "probs"])
 def test_small_rows_all_kinds_and_ragged_lengths(V, kind):
     g = torch.Generator(device=DEV).manual_seed(100 + V)
@@ -109,3 +110,18 @@ def test_large_vocabulary_workload_sampled_rows():
     print(f"config 3: mean bound for K=1,2,4,8: {b.mean(0)}; mean tv {gpu['tv'].mean().item():.3f}")
     assert (b >= 0).all() and (b <= 1 + 1e-9).all() and (np.diff(b, axis=1) >= -1e-9).all()
     assert (gpu["relaxed"].cpu().numpy() <= b + 1e-9).all()
+
+
+def test_rows_of_many_equal_ratios_and_of_few_distinct_ones():
+    """The sort's digits at their most lopsided: every entry with the same ratio q/p (all keys
+    equal), two values only, and ratios that differ in the last bits of the key only."""
+    g = torch.Generator(device=DEV).manual_seed(77)
+    V = 9000
+    tq = torch.randn(4, V, generator=g, device=DEV)
+    td = tq.clone()
+    td[1] = tq[1] + 0.5                                  # softmax undoes the shift: p = q up to the sum's rounding
+    td[2, ::2] += 1.0                                    # two ratios
+    td[3] = tq[3] + 1e-6 * torch.randn(V, generator=g, device=DEV)  # ratios within a few ulps of 1
+    gpu, ref = check(td, tq, KS)
+    got = gpu["bound"].cpu().numpy()
+    assert np.allclose(got[0], 1.0, rtol=1e-12) and np.allclose(got[1], 1.0, rtol=1e-6)
