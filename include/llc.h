@@ -291,7 +291,7 @@ typedef struct llc_couple_topm_args {
  * until it has finished. */
 #define LLC_LML_MAX_K 8
 typedef struct llc_lml_args {
-  int64_t B, V;             /* B >= 0, 1 <= V < 2^31 - 4                                  */
+  int64_t B, V;             /* 0 <= B < 2^31, 1 <= V <= 2^28                              */
   int32_t dtype;            /* LLC_F32 | LLC_BF16 (both inputs)                           */
   int32_t kind;             /* LLC_LOGITS | LLC_PROBS | LLC_LOGW                          */
   const void *draft;        /* device, [B,V]                                              */

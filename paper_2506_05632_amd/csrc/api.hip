@@ -437,15 +437,18 @@ int llc_couple_topm(const llc_couple_topm_args *a) {
   return LLC_OK;
 }
 
+// (one workgroup sorts a whole row, and its loops count entries in 32 bits with room to spare)
+constexpr long long kLmlMaxV = 1LL << 28;
+
 size_t llc_lml_workspace_size(int64_t B, int64_t V) {
-  if (!shape_ok(B, 1, V)) return 0;
+  if (!shape_ok(B, 1, V) || V > kLmlMaxV) return 0;
   // per row two buffers of sort keys (4 bytes) and two of mass pairs (8 bytes)
   return align256((size_t)B * 24 * (size_t)V) + 256;
 }
 
 int llc_lml_bound(const llc_lml_args *a) {
   if (a == nullptr) return LLC_E_NULL;
-  if (!shape_ok(a->B, 1, a->V) || a->B > 0x7FFFFFFFLL) return LLC_E_SHAPE;
+  if (!shape_ok(a->B, 1, a->V) || a->B > 0x7FFFFFFFLL || a->V > kLmlMaxV) return LLC_E_SHAPE;
   if (a->n_k < 1 || a->n_k > LLC_LML_MAX_K) return LLC_E_OPTION;
   for (int n = 0; n < a->n_k; ++n)
     if (a->k[n] < 1) return LLC_E_OPTION;

@@ -237,7 +237,7 @@ def _lml_args(**kw):
 
 @pytest.mark.parametrize("kw,code", [
     (dict(draft=None), -1), (dict(bound=None), -1),
-    (dict(V=0), -2), (dict(B=-1), -2), (dict(target_stride_b=-1), -2),
+    (dict(V=0), -2), (dict(B=-1), -2), (dict(target_stride_b=-1), -2), (dict(V=(1 << 28) + 1), -2),
     (dict(temp_draft=0.0), -3), (dict(temp_target=float("nan")), -3),
     (dict(dtype=2), -4), (dict(kind=9), -4),
     (dict(target=0x1001), -5),
@@ -252,5 +252,6 @@ def test_lml_argument_errors_are_reported_before_any_launch(kw, code):
     bad_k.k[1] = 0
     assert lib.llc_lml_bound(ctypes.byref(bad_k)) == -8
     assert lib.llc_lml_bound(ctypes.byref(_lml_args(B=0, draft=None, bound=None))) == 0
-    assert llc.llc_lml_workspace_size(4, 64) >= 4 * 64 * 16
+    assert llc.llc_lml_workspace_size(4, 64) >= 4 * 64 * 24
     assert llc.llc_lml_workspace_size(4, 0) == 0
+    assert llc.llc_lml_workspace_size(1, 1 << 28) >= 24 << 28 and llc.llc_lml_workspace_size(1, (1 << 28) + 1) == 0

@@ -125,3 +125,27 @@ def test_rows_of_many_equal_ratios_and_of_few_distinct_ones():
     gpu, ref = check(td, tq, KS)
     got = gpu["bound"].cpu().numpy()
     assert np.allclose(got[0], 1.0, rtol=1e-12) and np.allclose(got[1], 1.0, rtol=1e-6)
+
+
+def test_the_longest_row_the_interface_accepts():
+    """V = 2^28, the most llc_lml_bound takes.  The mass sits on some thousand entries (the first and
+    the last ones among them); entries without mass on either side add nothing to any sum, so the
+    oracle is given the entries with mass alone."""
+    V, M = 1 << 28, 20000
+    g = torch.Generator(device=DEV).manual_seed(5)
+    ids = torch.randint(0, V, (M,), generator=g, device=DEV, dtype=torch.int64)
+    ids = torch.cat([ids, torch.arange(0, 5, device=DEV), torch.arange(V - 5, V, device=DEV)]).unique()
+    vq = 2 * torch.randn(ids.numel(), generator=g, device=DEV)
+    vd = vq + torch.randn(ids.numel(), generator=g, device=DEV)
+    vd[::7] = -float("inf")  # some entries with target mass only
+    tq = torch.full((1, V), -float("inf"), device=DEV)
+    td = torch.full((1, V), -float("inf"), device=DEV)
+    tq[0, ids] = vq
+    td[0, ids] = vd
+    gpu = llc.llc_lml_bound(td, tq, KS, temp_draft=1.2, temp_target=0.8)
+    torch.cuda.synchronize()
+    ref = lml.lml_rows(vd.cpu().numpy()[None], vq.cpu().numpy()[None], KS, temp_draft=1.2, temp_target=0.8)
+    for name in ("bound", "relaxed", "tv"):
+        np.testing.assert_allclose(gpu[name].cpu().numpy(), ref[name], rtol=RTOL, atol=1e-12, err_msg=name)
+    del tq, td, gpu
+    torch.cuda.empty_cache()

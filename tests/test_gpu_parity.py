@@ -263,6 +263,33 @@ def test_one_very_long_row_is_spread_over_a_thousand_workgroups():
     assert stats.cpu().numpy()[2] == 0  # no workgroup fell back to the all-fp64 scan
 
 
+def test_the_longest_row_the_interface_accepts():
+    """V = 2^31 - 5, the largest the ABI takes: 32-bit index arithmetic at its limit.  The mass sits
+    on a few thousand entries (the first and the last ones among them), so the oracle's candidate-
+    list form, whose uniforms are keyed by the same indices, gives the expected result."""
+    import oracle
+    V, K, M = 2**31 - 5, 3, 4000
+    g = torch.Generator(device=DEV).manual_seed(91)
+    ids = torch.randint(0, V, (M,), generator=g, device=DEV, dtype=torch.int64)
+    ids = torch.cat([ids, torch.arange(0, 6, device=DEV), torch.arange(V - 6, V, device=DEV)]).unique()
+    vq = 2 * torch.randn(ids.numel(), generator=g, device=DEV)
+    vd = vq + torch.randn(ids.numel(), generator=g, device=DEV)
+    tq = torch.full((1, V), -float("inf"), device=DEV)
+    td = torch.full((1, V), -float("inf"), device=DEV)
+    tq[0, ids] = vq
+    td[0, ids] = vd
+    ids32 = ids.to(torch.int32).cpu().numpy().reshape(1, -1)
+    ref = oracle.couple_topm(ids32, vd.cpu().numpy().reshape(1, -1), ids32, vq.cpu().numpy().reshape(1, -1), K,
+                             kind=oracle.LOGITS, temp_target=0.9, temp_draft_all=1.1, seed=17)
+    for kw in (dict(), dict(flags=llc.FLAG_EXACT_SCAN)):
+        stats = llc.new_stats(DEV)
+        gpu = llc.llc_couple(td, tq, K, seed=17, temp_target=0.9, temp_draft=1.1, want_keys=True, stats=stats, **kw)
+        torch.cuda.synchronize()
+        compare(gpu, ref)
+    del tq, td
+    torch.cuda.empty_cache()
+
+
 def test_identical_distributions_always_accept():
     g = torch.Generator(device=DEV).manual_seed(10)
     z = 3 * torch.randn(300, 7001, generator=g, device=DEV)
