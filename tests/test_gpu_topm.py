@@ -71,6 +71,21 @@ def test_topm_shapes_kinds_and_temperatures(kind, K, Md, Mt):
     compare(gpu, ref)
 
 
+def test_topm_longest_lists_and_largest_token_ids():
+    """65536 candidates a list (the most the interface takes), token ids up to 2^31 - 1."""
+    g = torch.Generator(device=DEV).manual_seed(8)
+    B, K, M = 2, 3, 65536
+    t_ids = torch.randint(0, 2**31 - 1, (B, M), generator=g, device=DEV, dtype=torch.int64).to(torch.int32)
+    t_ids[:, -1] = 2**31 - 1
+    d_ids = t_ids.flip(1).contiguous()                   # the same tokens in another order
+    t_val = 2 * torch.randn(B, M, generator=g, device=DEV)
+    d_val = 2 * torch.randn(B, M, generator=g, device=DEV)
+    gpu = llc.llc_couple_topm(d_ids, d_val, t_ids, t_val, K, seed=3, want_keys=True)
+    torch.cuda.synchronize()
+    ref = oracle_topm(d_ids, d_val, t_ids, t_val, K, seed=3)
+    compare(gpu, ref)
+
+
 def test_topm_empty_slots_duplicates_strided_views_and_lists_without_mass():
     g = torch.Generator(device=DEV).manual_seed(5)
     B, K, Md, Mt, V = 12, 3, 33, 40, 900

@@ -162,16 +162,17 @@ def test_verify_results_do_not_depend_on_launch_shape():
         assert torch.equal(base[name], exact[name]), name
 
 
-@pytest.mark.parametrize("L,K,V", [(0, 1, 777), (0, 5, 1025), (1, 1, 4099), (5, 2, 333), (2, 64, 517)])
-def test_verify_edge_shapes(L, K, V):
+@pytest.mark.parametrize("strong", [False, True])
+@pytest.mark.parametrize("L,K,V", [(0, 1, 777), (0, 5, 1025), (1, 1, 4099), (5, 2, 333), (2, 64, 517), (4, 64, 130)])
+def test_verify_edge_shapes(L, K, V, strong):
     g = torch.Generator(device=DEV).manual_seed(L * 1000 + K * 10 + V)
     S = 7
     target = 3 * torch.randn(S, L + 1, K, V, generator=g, device=DEV)
     target[:, 0, 1:] = target[:, 0, :1]
     tokens = target[:, :L].argmax(dim=3).to(torch.int32)
-    gpu = llc.llc_verify(target, tokens, temp_target=0.6, seed=17, row_offset=5, want_keys=True)
+    gpu = llc.llc_verify(target, tokens, temp_target=0.6, seed=17, row_offset=5, want_keys=True, strong=strong)
     torch.cuda.synchronize()
-    ref = oracle_verify(target, tokens, (0, S), temp_target=0.6, seed=17, row_offset=5)
+    ref = oracle_verify(target, tokens, (0, S), temp_target=0.6, seed=17, row_offset=5, strong=strong)
     compare_verify(gpu, ref)
 
 
