@@ -156,7 +156,10 @@ __global__ void __launch_bounds__(kThreads) lml_kernel(const LmlParams p) {
     if (hp && hq) {
 #pragma unroll
       for (int kk = 0; kk < kLmlMaxK; ++kk)
-        if (kk < p.n_k) relaxed[kk] += qm / (1.0 + qm / ((double)p.k[kk] * pm));
+        if (kk < p.n_k) {  // q / (1 + q / (K p)) with one division
+          const double kp = (double)p.k[kk] * pm;
+          relaxed[kk] += kp * qm / (kp + qm);
+        }
     }
   }
   tv = block_sum(tv, s_red);
@@ -346,12 +349,13 @@ __global__ void __launch_bounds__(kThreads) lml_kernel(const LmlParams p) {
     if (pm > 0.0 && qm > 0.0) {
       const double p_pre = p_before + (pin - pm);             // mass of p strictly before j
       const double q_suf = q_total - (q_before + (qin - qm));  // mass of q from j on
-      const double common = q_suf / qm + p_pre / pm;
+      // K / (q_suf/q_j + p_pre/p_j + (K - 1) Q/q_j), numerator and denominator times q_j
+      const double common = q_suf + p_pre * (qm / pm);
 #pragma unroll
       for (int kk = 0; kk < kLmlMaxK; ++kk)
         if (kk < p.n_k) {
           const double K = (double)p.k[kk];
-          acc[kk] += K / (common + (K - 1.0) * q_total / qm);
+          acc[kk] += K * qm / (common + (K - 1.0) * q_total);
         }
     }
     p_before += __shfl(pin, 63);
