@@ -28,12 +28,14 @@
 extern "C" {
 #endif
 
-#define LLC_VERSION 106
+#define LLC_VERSION 107
 
 enum {
   LLC_OK = 0,
   LLC_E_NULL = -1,      /* a required pointer is NULL                                   */
-  LLC_E_SHAPE = -2,     /* B < 0, K < 1, V < 1, V >= 2^31 - 4, K > 65535, bad strides   */
+  LLC_E_SHAPE = -2,     /* B < 0, K < 1, V < 1, V >= 2^31 - 4, K > 65535, bad strides, or
+                           more than 2^24 - 1 workgroups in one launch (B * ceil(K / k_tile)
+                           * v_chunks: split such a batch over several calls)            */
   LLC_E_TEMP = -3,      /* a host-visible temperature is not finite and > 0             */
   LLC_E_DTYPE = -4,     /* unknown dtype / kind, or a combination that is not built     */
   LLC_E_ALIGN = -5,     /* an input base pointer is not aligned to its element size     */
@@ -53,7 +55,11 @@ enum {
 
 enum {
   LLC_FLAG_EXACT_SCAN = 1, /* debugging: evaluate every key in fp64, no prefilter     */
-  LLC_FLAG_STRONG = 2      /* llc_verify only: the strongly drafter-invariant loop    */
+  LLC_FLAG_STRONG = 2,     /* llc_verify only: the strongly drafter-invariant loop    */
+  LLC_FLAG_DRY_RUN = 4     /* llc_couple, llc_couple_is, llc_compress_select, llc_verify: check
+                              the arguments, plan every launch of the call and check the
+                              workspace against the plan, then return without launching
+                              anything (no pointer is dereferenced)                    */
 };
 
 /* Optional device counters, accumulated with atomics (zero them yourself). */
@@ -62,6 +68,13 @@ typedef struct llc_stats {
   unsigned long long exact_evals; /* keys evaluated in fp64                                  */
   unsigned long long slow_blocks; /* workgroups that fell back to the all-fp64 scan          */
   unsigned long long degenerate;  /* reductions that found no entry with positive probability */
+  unsigned long long near_ties;   /* reductions whose winner is within 1e-6 (relative, in S/p) of
+                                     the best key at another index: there the exact fp64 argmin
+                                     returned here and an argmin taken in other arithmetic may
+                                     differ (the paper's own caveat on floating-point determinism,
+                                     Section 5.3).  llc_couple, llc_couple_is, llc_compress_select:
+                                     every draft's reduction and the pool's; llc_verify: the pool
+                                     of every emitted position; llc_couple_topm: both sides        */
 } llc_stats;
 
 /* Arguments of llc_couple: one call runs Algorithm 1 of the paper on B rows.
@@ -332,10 +345,13 @@ int llc_lml_bound(const llc_lml_args *a);
 /* Bytes of device scratch llc_lml_bound needs; 0 on bad shapes. */
 size_t llc_lml_workspace_size(int64_t B, int64_t V);
 
-/* Bytes of device scratch either call needs for this shape (any options); 0 on bad shapes. */
+/* Bytes of device scratch llc_couple, llc_couple_is and llc_compress_select need for this shape:
+ * enough for any k_tile and for v_chunks = 0 (the library's choice) or up to 16; an explicit
+ * v_chunks = c above 16 needs ceil(c / 16) times as much.  0 on bad shapes. */
 size_t llc_couple_workspace_size(int64_t B, int64_t K, int64_t V);
 
-/* Bytes of device scratch llc_verify needs for this shape (any options); 0 on bad shapes. */
+/* Bytes of device scratch llc_verify needs for this shape, either form of the loop (same rule
+ * for v_chunks and k_tile); 0 on bad shapes. */
 size_t llc_verify_workspace_size(int64_t S, int64_t L, int64_t K, int64_t V);
 
 /* Text for a return code (static storage). */

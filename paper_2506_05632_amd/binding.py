@@ -17,6 +17,7 @@ F32, BF16 = 0, 1
 LOGITS, PROBS, LOGW = 0, 1, 2
 FLAG_EXACT_SCAN = 1
 FLAG_STRONG = 2
+FLAG_DRY_RUN = 4
 
 _KINDS = {"logits": LOGITS, "probs": PROBS, "logw": LOGW}
 EXPORTS = ["llc_couple", "llc_couple_is", "llc_couple_topm", "llc_compress_select", "llc_verify", "llc_lml_bound",
@@ -26,7 +27,11 @@ EXPORTS = ["llc_couple", "llc_couple_is", "llc_couple_topm", "llc_compress_selec
 
 class LlcStats(ctypes.Structure):
     _fields_ = [("survivors", ctypes.c_ulonglong), ("exact_evals", ctypes.c_ulonglong),
-                ("slow_blocks", ctypes.c_ulonglong), ("degenerate", ctypes.c_ulonglong)]
+                ("slow_blocks", ctypes.c_ulonglong), ("degenerate", ctypes.c_ulonglong),
+                ("near_ties", ctypes.c_ulonglong)]
+
+
+STATS_FIELDS = ("survivors", "exact_evals", "slow_blocks", "degenerate", "near_ties")
 
 
 class CoupleArgs(ctypes.Structure):
@@ -149,7 +154,7 @@ def load():
     """Load the HIP library (built by paper_2506_05632_amd/build.py); raise if it is not there."""
     global _lib
     if _lib is None:
-        path = os.environ.get("LLC_HIP_LIB", LIB_PATH)  # override: try another build of the library
+        path = LIB_PATH
         if not os.path.exists(path):
             raise RuntimeError(f"{path} is missing: run `python -m paper_2506_05632_amd.build` "
                                "(there is no CPU fallback)")
@@ -214,8 +219,9 @@ def _stream_handle(device):
 
 
 def new_stats(device) -> torch.Tensor:
-    """Four zeroed 64-bit device counters laid out as llc_stats."""
-    return torch.zeros(4, dtype=torch.int64, device=device)
+    """Zeroed 64-bit device counters laid out as llc_stats (survivors, exact_evals, slow_blocks,
+    degenerate, near_ties)."""
+    return torch.zeros(len(STATS_FIELDS), dtype=torch.int64, device=device)
 
 
 def llc_couple(draft: torch.Tensor, target: torch.Tensor, K: int, *, kind="logits",

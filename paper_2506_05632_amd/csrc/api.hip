@@ -8,6 +8,7 @@ namespace llc {
 namespace {
 
 constexpr int kMaxChunks = 4096;
+constexpr long long kMaxBlocks = 0xFFFFFFFFLL / kBlock;  // workgroups of one launch
 constexpr int kPlannedChunkFloor = 16;  // the workspace always covers this many chunks
 constexpr long long kTargetBlocks = 1024;  // four resident workgroups on each of 256 CUs
 constexpr long long kMinTilesPerChunk = 8; // a chunk pays its own warm-up: keep it worth it
@@ -49,7 +50,7 @@ int auto_chunks(long long B, long long n_kgroups, long long G) {
 }
 
 struct Layout {
-  size_t keyX, idxX, keyY, idxY, kY, lse, lse_part, shared_tau, total;
+  size_t keyX, idxX, keyY, idxY, kY, secX, secY, lse, lse_part, shared_tau, total;
 };
 
 Layout layout_for(long long B, long long K, long long n_kgroups, long long n_chunks) {
@@ -60,6 +61,8 @@ Layout layout_for(long long B, long long K, long long n_kgroups, long long n_chu
   l.keyY = off; off += align256((size_t)(B * n_kgroups * n_chunks) * sizeof(double));
   l.idxY = off; off += align256((size_t)(B * n_kgroups * n_chunks) * sizeof(int32_t));
   l.kY = off;   off += align256((size_t)(B * n_kgroups * n_chunks) * sizeof(int32_t));
+  l.secX = off; off += align256((size_t)(B * K * n_chunks) * sizeof(double));
+  l.secY = off; off += align256((size_t)(B * n_kgroups * n_chunks) * sizeof(double));
   l.lse = off;  off += align256((size_t)(B * (K + 1)) * sizeof(double));
   l.lse_part = off; off += align256((size_t)(B * (K + 1) * n_chunks) * sizeof(double));
   l.shared_tau = off; off += align256((size_t)(B * (K + 1)) * sizeof(int32_t));
@@ -88,12 +91,13 @@ RowMap plain_rows(long long draft_stride_b, long long target_stride_b) {
 // position's row offset; the running bests that the scans of positions 1..L share; the
 // normalisers of every row and of the rows that price the position at hand.
 struct VerifyExtra {
-  size_t cand_key, cand, viable, running, next_off, tau_all, lse, lse_sel, total;
+  size_t cand_key, cand_sec, cand, viable, running, next_off, tau_all, lse, lse_sel, total;
 };
 VerifyExtra verify_extra(long long S, long long B, long long K) {  // B = S (L + 1)
   VerifyExtra e;
   size_t off = 0;
   e.cand_key = off; off += align256((size_t)(B * K) * sizeof(double));
+  e.cand_sec = off; off += align256((size_t)(B * K) * sizeof(double));
   e.cand = off; off += align256((size_t)(B * K) * sizeof(int32_t));
   e.viable = off; off += align256((size_t)(S * K));
   e.running = off; off += align256((size_t)S * sizeof(int32_t));
@@ -123,7 +127,9 @@ struct ScanJob {
   long long bins_stride_b = 0;
   const int32_t *bin_of = nullptr;
   const long long *draft_row_off = nullptr;  // per-row extra offset of the draft row (see ScanParams)
+  long long draft_row_off_unit = 0;  // every entry of draft_row_off is a multiple of this many elements
   size_t lse_in_extra = (size_t)-1;  // keep the normalisers at this offset of the caller's region
+  size_t extra_at = (size_t)-1;      // where the caller's region starts (default: right behind the partials)
   int32_t *tau_ready = nullptr;      // the rows' shared running bests, already reset, if not in the workspace
   int flags, v_chunks, k_tile;
   llc_stats *stats;
@@ -132,12 +138,19 @@ struct ScanJob {
   void *stream, *ev_begin, *ev_end;
 };
 
-// Checks the options, plans the launch, carves the workspace and enqueues the normaliser pass
-// (if asked) and the scan kernel.  *extra (if given) receives the caller's region.
-int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
+// What the host decides about one scan before anything is launched.
+struct ScanPlan {
+  Plan pl;
+  Layout lay;
+  bool shared, vec;
+  long long blocks;
+};
+
+// Checks the options and plans the launch; touches neither the workspace nor the device.
+int plan_scan(const ScanJob &j, ScanPlan *out) {
   if (j.dtype != LLC_F32 && j.dtype != LLC_BF16) return LLC_E_DTYPE;
   if (j.kind != LLC_LOGITS && j.kind != LLC_PROBS && j.kind != LLC_LOGW) return LLC_E_DTYPE;
-  if (j.flags & ~LLC_FLAG_EXACT_SCAN) return LLC_E_OPTION;
+  if (j.flags & ~LLC_FLAG_EXACT_SCAN) return LLC_E_OPTION;  // (the entry points strip their own flags)
   if (j.v_chunks < 0 || j.v_chunks > kMaxChunks) return LLC_E_OPTION;
   if (j.k_tile != 0 && j.k_tile != 1 && j.k_tile != 2 && j.k_tile != 4 && j.k_tile != 8)
     return LLC_E_OPTION;
@@ -152,29 +165,51 @@ int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
   const float *temp_draft = logits ? j.temp_draft : nullptr;
   const bool shared = j.draft_stride_k == 0 && temp_draft == nullptr && !j.force_perk;
 
-  Plan pl;
+  Plan &pl = out->pl;
   pl.kt = j.k_tile != 0 ? (j.k_tile == 1 ? 2 : j.k_tile) : auto_ktile(j.K, shared);
   pl.n_kgroups = (int)((j.K + pl.kt - 1) / pl.kt);
   const long long G = (j.V + 3) / 4;
   plan_chunks(G, j.v_chunks != 0 ? j.v_chunks : auto_chunks(j.B, pl.n_kgroups, G), &pl.n_chunks,
               &pl.groups_per_chunk);
-  const long long blocks = j.B * pl.n_kgroups * pl.n_chunks;
-  if (blocks > 0x7FFFFFFFLL) return LLC_E_SHAPE;
-
-  const Layout lay = layout_for(j.B, j.K, pl.n_kgroups, pl.n_chunks);
-  if (j.workspace == nullptr || ((uintptr_t)j.workspace & 255) != 0 ||
-      j.workspace_bytes < lay.total + j.extra_bytes)
-    return LLC_E_WORKSPACE;
-  char *ws = (char *)j.workspace;
-  if (extra != nullptr) *extra = ws + lay.total;
+  out->blocks = j.B * pl.n_kgroups * pl.n_chunks;
+  // (a launch takes fewer than 2^32 threads in all)
+  if (out->blocks > kMaxBlocks) return LLC_E_SHAPE;
+  out->lay = layout_for(j.B, j.K, pl.n_kgroups, pl.n_chunks);
+  out->shared = shared;
 
   // vector loads need every row to start on a 4-element boundary of a 16-byte (fp32) or
-  // 8-byte (bf16) aligned base
+  // 8-byte (bf16) aligned base (per-row offsets of the draft rows included)
   const size_t vbytes = 4 * esize;
   const RowMap &m = j.map;
-  const bool vec = ((uintptr_t)j.draft % vbytes) == 0 && ((uintptr_t)j.target % vbytes) == 0 &&
-                   (m.draft_outer % 4) == 0 && (m.draft_inner % 4) == 0 && (j.draft_stride_k % 4) == 0 &&
-                   (m.target_outer % 4) == 0 && (m.target_inner % 4) == 0;
+  out->vec = ((uintptr_t)j.draft % vbytes) == 0 && ((uintptr_t)j.target % vbytes) == 0 &&
+             (m.draft_outer % 4) == 0 && (m.draft_inner % 4) == 0 && (j.draft_stride_k % 4) == 0 &&
+             (m.target_outer % 4) == 0 && (m.target_inner % 4) == 0 &&
+             (j.draft_row_off == nullptr || (j.draft_row_off_unit % 4) == 0);
+  return LLC_OK;
+}
+
+// Where the caller's own region starts, and what the whole call needs.
+size_t extra_offset(const ScanJob &j, const ScanPlan &sp) {
+  return j.extra_at == (size_t)-1 ? sp.lay.total : j.extra_at;
+}
+bool workspace_ok(const ScanJob &j, const ScanPlan &sp) {
+  const size_t at = extra_offset(j, sp);
+  return j.workspace != nullptr && ((uintptr_t)j.workspace & 255) == 0 && at >= sp.lay.total &&
+         j.workspace_bytes >= at + j.extra_bytes;
+}
+
+// Carves the workspace and enqueues the normaliser pass (if asked) and the scan kernel of a
+// planned job whose workspace has been checked.  *extra (if given) receives the caller's region.
+int launch_scan_job(const ScanJob &j, const ScanPlan &plan, Partials *partials, char **extra) {
+  const Plan &pl = plan.pl;
+  const Layout &lay = plan.lay;
+  const bool shared = plan.shared, vec = plan.vec;
+  const long long blocks = plan.blocks;
+  const bool logits = j.kind == LLC_LOGITS;
+  const float *temp_draft = logits ? j.temp_draft : nullptr;
+  char *ws = (char *)j.workspace;
+  const size_t extra_off = extra_offset(j, plan);
+  if (extra != nullptr) *extra = ws + extra_off;
 
   hipStream_t st = (hipStream_t)j.stream;
   Partials part;
@@ -183,7 +218,9 @@ int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
   part.keyY = (double *)(ws + lay.keyY);
   part.idxY = (int32_t *)(ws + lay.idxY);
   part.kY = (int32_t *)(ws + lay.kY);
-  part.lse = (double *)(ws + (j.lse_in_extra == (size_t)-1 ? lay.lse : lay.total + j.lse_in_extra));
+  part.secX = (double *)(ws + lay.secX);
+  part.secY = (double *)(ws + lay.secY);
+  part.lse = (double *)(ws + (j.lse_in_extra == (size_t)-1 ? lay.lse : extra_off + j.lse_in_extra));
 
   // Row normalisers: with per-draft rows the scan forms them on its way (no second pass over the
   // inputs); the shared layout and the binned passes use the normaliser kernel.
@@ -256,12 +293,66 @@ int run_scan(const ScanJob &j, Plan *plan, Partials *partials, char **extra) {
   if (e != hipSuccess) return LLC_E_LAUNCH;
   if (j.ev_end != nullptr && hipEventRecord((hipEvent_t)j.ev_end, st) != hipSuccess)
     return LLC_E_LAUNCH;
-  *plan = pl;
   *partials = part;
   return LLC_OK;
 }
 
+// Plan, check the workspace, launch.  With the dry-run flag nothing is launched (*dry is set).
+int run_scan(const ScanJob &j, bool dry_run, Plan *plan, Partials *partials, char **extra) {
+  ScanPlan sp;
+  const int rc = plan_scan(j, &sp);
+  if (rc != LLC_OK) return rc;
+  if (!workspace_ok(j, sp)) return LLC_E_WORKSPACE;
+  *plan = sp.pl;
+  if (dry_run) return LLC_OK;
+  return launch_scan_job(j, sp, partials, extra);
+}
+
 }  // namespace
+
+// llc_couple on a given workspace (the caller's, or the library's own static one).
+int couple_on(const llc_couple_args *a, void *workspace, size_t workspace_bytes) {
+  if (a == nullptr) return LLC_E_NULL;
+  if (!shape_ok(a->B, a->K, a->V)) return LLC_E_SHAPE;
+  if (a->B == 0) return LLC_OK;  // nothing to read or write: pointers may be NULL
+  if (a->draft == nullptr || a->target == nullptr || a->X == nullptr || a->Y == nullptr ||
+      a->accept == nullptr)
+    return LLC_E_NULL;
+  if (a->draft_stride_b < 0 || a->draft_stride_k < 0 || a->target_stride_b < 0) return LLC_E_SHAPE;
+  const bool dry = (a->flags & LLC_FLAG_DRY_RUN) != 0;
+
+  ScanJob j;
+  j.B = a->B; j.K = a->K; j.V = a->V; j.dtype = a->dtype; j.kind = a->kind;
+  j.draft = a->draft; j.target = a->target;
+  j.map = plain_rows(a->draft_stride_b, a->target_stride_b);
+  j.draft_stride_k = a->draft_stride_k;
+  j.temp_target = a->temp_target; j.temp_draft_all = a->temp_draft_all; j.temp_draft = a->temp_draft;
+  j.seed = a->seed; j.row_offset = a->row_offset;
+  j.no_pool = false;
+  j.need_lse = a->keyX != nullptr || a->keyY != nullptr;
+  j.flags = a->flags & ~LLC_FLAG_DRY_RUN; j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;
+  j.stats = a->stats; j.workspace = workspace; j.workspace_bytes = workspace_bytes;
+  j.stream = a->stream; j.ev_begin = a->ev_scan_begin; j.ev_end = a->ev_scan_end;
+  j.extra_bytes = 0;
+
+  Plan pl;
+  Partials part;
+  const int rc = run_scan(j, dry, &pl, &part, nullptr);
+  if (rc != LLC_OK || dry) return rc;
+
+  FinalizeParams fp;
+  fp.B = a->B; fp.K = (int)a->K; fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
+  fp.log_kind = a->kind != LLC_PROBS ? 1 : 0;
+  fp.in = part;
+  fp.X = a->X; fp.Y = a->Y; fp.match_k = a->match_k; fp.accept = a->accept;
+  fp.keyX = a->keyX; fp.keyY = a->keyY; fp.log_keyX = nullptr; fp.log_secX = nullptr;
+  fp.y_given = 0; fp.bins = nullptr; fp.bins_stride_b = 0; fp.message = nullptr;
+  fp.count_draft = 1; fp.count_pool = 1; fp.count_near = 1;
+  fp.stats = a->stats;
+  if (launch_finalize((hipStream_t)a->stream, fp) != hipSuccess) return LLC_E_LAUNCH;
+  return LLC_OK;
+}
+
 }  // namespace llc
 
 using namespace llc;
@@ -298,42 +389,7 @@ size_t llc_couple_workspace_size(int64_t B, int64_t K, int64_t V) {
 
 int llc_couple(const llc_couple_args *a) {
   if (a == nullptr) return LLC_E_NULL;
-  if (!shape_ok(a->B, a->K, a->V)) return LLC_E_SHAPE;
-  if (a->B == 0) return LLC_OK;  // nothing to read or write: pointers may be NULL
-  if (a->draft == nullptr || a->target == nullptr || a->X == nullptr || a->Y == nullptr ||
-      a->accept == nullptr)
-    return LLC_E_NULL;
-  if (a->draft_stride_b < 0 || a->draft_stride_k < 0 || a->target_stride_b < 0) return LLC_E_SHAPE;
-
-  ScanJob j;
-  j.B = a->B; j.K = a->K; j.V = a->V; j.dtype = a->dtype; j.kind = a->kind;
-  j.draft = a->draft; j.target = a->target;
-  j.map = plain_rows(a->draft_stride_b, a->target_stride_b);
-  j.draft_stride_k = a->draft_stride_k;
-  j.temp_target = a->temp_target; j.temp_draft_all = a->temp_draft_all; j.temp_draft = a->temp_draft;
-  j.seed = a->seed; j.row_offset = a->row_offset;
-  j.no_pool = false;
-  j.need_lse = a->keyX != nullptr || a->keyY != nullptr;
-  j.flags = a->flags; j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;
-  j.stats = a->stats; j.workspace = a->workspace; j.workspace_bytes = a->workspace_bytes;
-  j.stream = a->stream; j.ev_begin = a->ev_scan_begin; j.ev_end = a->ev_scan_end;
-  j.extra_bytes = 0;
-
-  Plan pl;
-  Partials part;
-  const int rc = run_scan(j, &pl, &part, nullptr);
-  if (rc != LLC_OK) return rc;
-
-  FinalizeParams fp;
-  fp.B = a->B; fp.K = (int)a->K; fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
-  fp.log_kind = a->kind != LLC_PROBS ? 1 : 0;
-  fp.in = part;
-  fp.X = a->X; fp.Y = a->Y; fp.match_k = a->match_k; fp.accept = a->accept;
-  fp.keyX = a->keyX; fp.keyY = a->keyY; fp.log_keyX = nullptr;
-  fp.y_given = 0; fp.bins = nullptr; fp.bins_stride_b = 0; fp.message = nullptr;
-  fp.stats = a->stats;
-  if (launch_finalize((hipStream_t)a->stream, fp) != hipSuccess) return LLC_E_LAUNCH;
-  return LLC_OK;
+  return couple_on(a, a->workspace, a->workspace_bytes);
 }
 
 int llc_compress_select(const llc_compress_select_args *a) {
@@ -346,6 +402,7 @@ int llc_compress_select(const llc_compress_select_args *a) {
   if (a->enc_stride_b < 0 || a->dec_stride_b < 0 || a->dec_stride_l < 0 || a->bins_stride_b < 0)
     return LLC_E_SHAPE;
   hipStream_t st = (hipStream_t)a->stream;
+  const bool dry = (a->flags & LLC_FLAG_DRY_RUN) != 0;
 
   // pass 1, the encoder: Y = the pool argmin under lambda_q over the L sets of race times (the
   // shared-proposal scan without a draft side; its X comes out as -1 and pass 2 overwrites it)
@@ -359,22 +416,29 @@ int llc_compress_select(const llc_compress_select_args *a) {
   j.no_pool = false;
   j.no_draft = true;
   j.need_lse = a->keyY != nullptr;
-  j.flags = a->flags; j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;
+  j.flags = a->flags & ~LLC_FLAG_DRY_RUN; j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;
   j.stats = a->stats; j.workspace = a->workspace; j.workspace_bytes = a->workspace_bytes;
   j.stream = a->stream; j.ev_begin = nullptr; j.ev_end = nullptr;
   j.extra_bytes = 0;
   Plan pl;
   Partials part;
-  int rc = run_scan(j, &pl, &part, nullptr);
+  int rc = run_scan(j, dry, &pl, &part, nullptr);
   if (rc != LLC_OK) return rc;
+  if (dry) {  // the decoders' pass is planned as well, nothing is launched
+    j.draft = a->logw_dec; j.map = plain_rows(a->dec_stride_b, a->enc_stride_b);
+    j.draft_stride_k = a->dec_stride_l; j.no_pool = true; j.no_draft = false;
+    j.bins = a->bins; j.bins_stride_b = a->bins_stride_b; j.bin_of = a->Y;
+    return run_scan(j, true, &pl, &part, nullptr);
+  }
   FinalizeParams fp;
   fp.B = a->B; fp.K = (int)a->L; fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
   fp.log_kind = 1;
   fp.in = part;
   fp.X = a->X; fp.Y = a->Y; fp.match_k = nullptr; fp.accept = a->accept;
-  fp.keyX = nullptr; fp.keyY = a->keyY; fp.log_keyX = nullptr;
+  fp.keyX = nullptr; fp.keyY = a->keyY; fp.log_keyX = nullptr; fp.log_secX = nullptr;
   fp.y_given = 0; fp.bins = nullptr; fp.bins_stride_b = 0; fp.message = nullptr;
-  fp.stats = nullptr;  // pass 1's draft side is not part of the result: its reductions are not counted
+  fp.count_draft = 0; fp.count_pool = 1; fp.count_near = 1;  // pass 1's draft side is not part of the result
+  fp.stats = a->stats;
   if (launch_finalize(st, fp) != hipSuccess) return LLC_E_LAUNCH;
 
   // pass 2, the decoders: X^(l) = argmin under lambda_p^(l) over the candidates of Y's bin
@@ -386,13 +450,14 @@ int llc_compress_select(const llc_compress_select_args *a) {
   j.need_lse = a->keyX != nullptr;
   j.bins = a->bins; j.bins_stride_b = a->bins_stride_b; j.bin_of = a->Y;
   j.ev_begin = a->ev_scan_begin; j.ev_end = a->ev_scan_end;
-  rc = run_scan(j, &pl, &part, nullptr);
+  rc = run_scan(j, false, &pl, &part, nullptr);
   if (rc != LLC_OK) return rc;
   fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
   fp.in = part;
   fp.X = a->X; fp.Y = a->Y; fp.match_k = a->match_l; fp.accept = a->accept;
   fp.keyX = a->keyX; fp.keyY = nullptr;
   fp.y_given = 1; fp.bins = a->bins; fp.bins_stride_b = a->bins_stride_b; fp.message = a->message;
+  fp.count_draft = 1; fp.count_pool = 0; fp.count_near = 1;
   fp.stats = a->stats;
   if (launch_finalize(st, fp) != hipSuccess) return LLC_E_LAUNCH;
   return LLC_OK;
@@ -484,9 +549,12 @@ int llc_lml_bound(const llc_lml_args *a) {
 size_t llc_verify_workspace_size(int64_t S, int64_t L, int64_t K, int64_t V) {
   if (S < 0 || L < 0 || L > (1 << 20) || K > 64) return 0;
   const long long B = S * (L + 1);
-  const size_t base = llc_couple_workspace_size(B, K, V);
-  if (base == 0) return 0;
-  return base + verify_extra(S, B, K).total;
+  // the one-shot scan over all S(L+1) rows, or (strong form) a later position's scan over S rows,
+  // whichever needs more room in front of the verifier's own region
+  const size_t all = llc_couple_workspace_size(B, K, V);
+  const size_t one = llc_couple_workspace_size(S, K, V);
+  if (all == 0 || one == 0) return 0;
+  return (all > one ? all : one) + verify_extra(S, B, K).total;
 }
 
 int llc_verify(const llc_verify_args *a) {
@@ -517,8 +585,9 @@ int llc_verify(const llc_verify_args *a) {
   j.no_pool = true;
   j.need_lse = true;  // keys of different rows are compared: they must be normalised
   j.force_perk = true;
-  if (a->flags & ~(LLC_FLAG_EXACT_SCAN | LLC_FLAG_STRONG)) return LLC_E_OPTION;
+  if (a->flags & ~(LLC_FLAG_EXACT_SCAN | LLC_FLAG_STRONG | LLC_FLAG_DRY_RUN)) return LLC_E_OPTION;
   const bool strong = (a->flags & LLC_FLAG_STRONG) != 0;
+  const bool dry = (a->flags & LLC_FLAG_DRY_RUN) != 0;
   j.flags = a->flags & LLC_FLAG_EXACT_SCAN; j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;
   j.stats = a->stats; j.workspace = a->workspace; j.workspace_bytes = a->workspace_bytes;
   j.stream = a->stream; j.ev_begin = a->ev_scan_begin; j.ev_end = a->ev_scan_end;
@@ -526,12 +595,46 @@ int llc_verify(const llc_verify_args *a) {
   j.extra_bytes = ex.total;
   if (strong) j.lse_in_extra = ex.lse;  // the loop over positions reuses the workspace in front of it
 
-  Plan pl;
+  // Everything is planned before anything is launched, so that a refusal comes up front.  The
+  // strong form's later positions are scans over the S sequences in the shared-proposal layout
+  // (one row prices all K drafts' race times); they reuse the room in front of the verifier's own
+  // region, which therefore starts behind the larger of the two layouts.
+  ScanPlan plan_all;
+  int rc = plan_scan(j, &plan_all);
+  if (rc != LLC_OK) return rc;
+  ScanJob q = j;  // one later position (the fields that differ between positions are set in the loop)
+  ScanPlan plan_one;
+  const size_t esize = a->dtype == LLC_F32 ? 4 : 2;
+  if (strong && a->L > 0) {
+    q.B = a->S;
+    q.map = plain_rows(a->stride_s, a->stride_s);
+    q.map.row_outer = a->row_stride_s;
+    q.draft_stride_k = 0;
+    q.force_perk = false;
+    q.draft_row_off_unit = a->stride_k;   // the offsets are (first viable draft) * stride_k
+    q.need_lse = false;                   // the rows' normalisers are known from the one-shot scan
+    q.lse_in_extra = (size_t)-1;
+    q.stats = nullptr; q.ev_begin = nullptr; q.ev_end = nullptr;
+    q.extra_bytes = 0;
+    q.draft = (const char *)a->target + (size_t)a->stride_j * esize;  // position 1 stands for all
+    q.target = q.draft;
+    // (positions differ by a multiple of stride_j: the alignment that position 1 shows must hold
+    // for all of them, so the vector path also needs stride_j to be a multiple of 4)
+    rc = plan_scan(q, &plan_one);
+    if (rc != LLC_OK) return rc;
+    if ((a->stride_j % 4) != 0) plan_one.vec = false;
+    if (plan_one.lay.total > plan_all.lay.total) j.extra_at = plan_one.lay.total;
+  }
+  if (!workspace_ok(j, plan_all)) return LLC_E_WORKSPACE;
+  if (dry) return LLC_OK;
+
+  Plan pl = plan_all.pl;
   Partials part;
   char *extra = nullptr;
-  const int rc = run_scan(j, &pl, &part, &extra);
+  rc = launch_scan_job(j, plan_all, &part, &extra);
   if (rc != LLC_OK) return rc;
   double *cand_key = (double *)(extra + ex.cand_key);
+  double *cand_sec = (double *)(extra + ex.cand_sec);
   int32_t *cand = a->Yk != nullptr ? a->Yk : (int32_t *)(extra + ex.cand);
 
   hipStream_t st = (hipStream_t)a->stream;
@@ -540,8 +643,9 @@ int llc_verify(const llc_verify_args *a) {
   fp.log_kind = 1;
   fp.in = part;
   fp.X = cand; fp.Y = nullptr; fp.match_k = nullptr; fp.accept = nullptr;
-  fp.keyX = a->keyYk; fp.keyY = nullptr; fp.log_keyX = cand_key;
+  fp.keyX = a->keyYk; fp.keyY = nullptr; fp.log_keyX = cand_key; fp.log_secX = cand_sec;
   fp.y_given = 0; fp.bins = nullptr; fp.bins_stride_b = 0; fp.message = nullptr;
+  fp.count_draft = 1; fp.count_pool = 0; fp.count_near = 0;  // (near-ties: those of the loop's pools, counted there)
   fp.stats = a->stats;
   if (launch_finalize(st, fp) != hipSuccess) return LLC_E_LAUNCH;
 
@@ -553,8 +657,9 @@ int llc_verify(const llc_verify_args *a) {
     // one step kernel, which also merges that scan's chunks: two launches per position.
     StrongStepParams ss;
     ss.S = a->S; ss.L = (int)a->L; ss.K = (int)a->K;
-    ss.cand = cand; ss.cand_key = cand_key;
-    ss.part_key = nullptr; ss.part_idx = nullptr; ss.n_chunks = 0;
+    ss.cand = cand; ss.cand_key = cand_key; ss.cand_sec = cand_sec;
+    ss.part_key = nullptr; ss.part_idx = nullptr; ss.part_sec = nullptr; ss.n_chunks = 0;
+    ss.stats = a->stats;
     ss.tau_all = (int32_t *)(extra + ex.tau_all);
     ss.tokens = a->tokens; ss.tok_stride_s = a->tok_stride_s; ss.tok_stride_j = a->tok_stride_j;
     ss.stride_k = a->stride_k;
@@ -562,30 +667,21 @@ int llc_verify(const llc_verify_args *a) {
     ss.next_off = (long long *)(extra + ex.next_off);
     ss.lse = (const double *)(extra + ex.lse); ss.lse_sel = (double *)(extra + ex.lse_sel);
     ss.Y = a->Y; ss.n_out = a->n_out; ss.active = a->active; ss.keyY = a->keyY;
-    const size_t esize = a->dtype == LLC_F32 ? 4 : 2;
+    // the first scan's partials are spent: the later positions' scans take the room in front of
+    // the verifier's region (checked above to hold either layout)
+    q.workspace_bytes = (size_t)(extra - (char *)a->workspace);
+    q.draft_row_off = ss.next_off;
     for (long long pos = 0; pos <= a->L; ++pos) {
       if (pos > 0) {
-        ScanJob q = j;
-        q.B = a->S;
         q.draft = (const char *)a->target + (size_t)(pos * a->stride_j) * esize;
         q.target = q.draft;
-        q.map = plain_rows(a->stride_s, a->stride_s);
-        q.map.row_outer = a->row_stride_s;
         q.row_offset = a->row_offset + (uint64_t)(pos * a->row_stride_j);
-        q.draft_stride_k = 0;       // one row prices all K drafts' race times
-        q.force_perk = false;
-        q.draft_row_off = ss.next_off;
-        q.need_lse = false;         // the rows' normalisers are known from the one-shot scan
-        q.lse_in_extra = (size_t)-1;
         q.tau_ready = ss.tau_all + (pos - 1) * a->S * (a->K + 1);
-        q.stats = nullptr; q.ev_begin = nullptr; q.ev_end = nullptr;
-        q.workspace_bytes = (size_t)(extra - (char *)a->workspace);  // the first scan's partials are spent
-        q.extra_bytes = 0;
-        Plan pl2;
         Partials part2;
-        const int rc2 = run_scan(q, &pl2, &part2, nullptr);
+        const int rc2 = launch_scan_job(q, plan_one, &part2, nullptr);
         if (rc2 != LLC_OK) return rc2;
-        ss.part_key = part2.keyX; ss.part_idx = part2.idxX; ss.n_chunks = pl2.n_chunks;
+        ss.part_key = part2.keyX; ss.part_idx = part2.idxX; ss.part_sec = part2.secX;
+        ss.n_chunks = plan_one.pl.n_chunks;
       }
       ss.j = (int)pos;
       if (launch_strong_step(st, ss) != hipSuccess) return LLC_E_LAUNCH;
@@ -595,7 +691,8 @@ int llc_verify(const llc_verify_args *a) {
 
   VerifyParams vp;
   vp.S = a->S; vp.L = (int)a->L; vp.K = (int)a->K;
-  vp.cand = cand; vp.cand_key = cand_key;
+  vp.cand = cand; vp.cand_key = cand_key; vp.cand_sec = cand_sec;
+  vp.stats = a->stats;
   vp.tokens = a->tokens; vp.tok_stride_s = a->tok_stride_s; vp.tok_stride_j = a->tok_stride_j;
   vp.Y = a->Y; vp.n_out = a->n_out; vp.active = a->active; vp.keyY = a->keyY;
   if (launch_verify(st, vp) != hipSuccess) return LLC_E_LAUNCH;

@@ -20,6 +20,8 @@ struct Partials {
   double *keyY;   // [B][n_kgroups][n_chunks]
   int32_t *idxY;  // [B][n_kgroups][n_chunks]
   int32_t *kY;    // [B][n_kgroups][n_chunks]
+  double *secX;   // [B][K][n_chunks] runner-up keys: the smallest key at an index other than the
+  double *secY;   // [B][n_kgroups][n_chunks] winner's (+inf if none was seen within the band)
   double *lse;    // [B][K+1]: ln sum exp(x/T) of draft k (k < K) and of the target (k == K)
   double *lse_part;  // [B][K+1][n_chunks] per-chunk shares to merge into lse first, or nullptr
 };
@@ -86,6 +88,10 @@ struct FinalizeParams {
   uint8_t *accept;
   float *keyX, *keyY;  // optional
   double *log_keyX;    // optional [B][K]: ln of the normalised winning key (log kinds)
+  double *log_secX;    // optional [B][K]: the same for the runner-up (another index) of that reduction
+  int count_draft;     // count the draft side's reductions in stats->degenerate
+  int count_pool;      // count the pool's
+  int count_near;      // also count the near-ties of the sides that are counted
   llc_stats *stats;
 };
 
@@ -95,12 +101,14 @@ struct VerifyParams {
   int L, K;
   const int32_t *cand;       // [S][L+1][K] argmin_i S_i^(j,k) / q_i^(j,k)
   const double *cand_key;    // [S][L+1][K] ln of its normalised key
+  const double *cand_sec;    // [S][L+1][K] ln of the normalised runner-up key of the same reduction
   const int32_t *tokens;     // draft tokens
   long long tok_stride_s, tok_stride_j;
   int32_t *Y;                // [S][L+1]
   int32_t *n_out;            // [S]
   uint8_t *active;           // [S][K] optional
   float *keyY;               // [S][L+1] optional
+  llc_stats *stats;          // optional: near_ties of the emitted positions
 };
 
 struct LseParams {
@@ -133,10 +141,12 @@ struct StrongStepParams {
   int L, K, j;               // position j of 0..L
   const int32_t *cand;       // [S][L+1][K] own-row argmins (viable drafts)
   const double *cand_key;    // [S][L+1][K] ln of their normalised keys
+  const double *cand_sec;    // [S][L+1][K] ln of the normalised runner-up keys
   // this position priced with the first viable draft's row, as the scan left it: per-chunk
   // partial argmins (only read for dropped drafts; unused at j == 0)
   const double *part_key;    // [S][K][n_chunks] ln-domain keys before the normaliser is added
   const int32_t *part_idx;   // [S][K][n_chunks]
+  const double *part_sec;    // [S][K][n_chunks] runner-up keys of the same partial reductions
   int n_chunks;
   int32_t *tau_all;          // [L][S][K+1] the later positions' shared running bests: reset at j == 0
   const int32_t *tokens;
@@ -152,6 +162,7 @@ struct StrongStepParams {
   int32_t *n_out;            // [S]
   uint8_t *active;           // [S][K] optional
   float *keyY;               // [S][L+1] optional
+  llc_stats *stats;          // optional: near_ties of the emitted positions
 };
 
 // Algorithm 1 on candidate lists: one workgroup per row, every key exact.
@@ -200,6 +211,9 @@ hipError_t launch_scan_f32_shared(int kt, bool probs, unsigned grid, hipStream_t
 hipError_t launch_scan_f32_perk(int kt, bool probs, unsigned grid, hipStream_t s, const ScanParams &p);
 hipError_t launch_scan_bf16_shared(int kt, bool probs, unsigned grid, hipStream_t s, const ScanParams &p);
 hipError_t launch_scan_bf16_perk(int kt, bool probs, unsigned grid, hipStream_t s, const ScanParams &p);
+
+// llc_couple on a given workspace (api.hip).
+int couple_on(const llc_couple_args *a, void *workspace, size_t workspace_bytes);
 
 hipError_t launch_finalize(hipStream_t s, const FinalizeParams &p);
 hipError_t launch_lse(hipStream_t s, const LseParams &p);

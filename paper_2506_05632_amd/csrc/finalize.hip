@@ -18,6 +18,17 @@ __device__ __forceinline__ bool beats(double key, int idx, int k, double bkey, i
   return k < bk;
 }
 
+// A winner within this relative distance (in S/p) of the best key at another index is a near-tie.
+constexpr double kNearTie = 1e-6;
+
+// Whether the runner-up key is that close.  Log-domain keys are ln(S/p) up to a constant that both
+// share, so the relative distance is expm1 of their difference.
+__device__ __forceinline__ bool near_tie(double best, double second, int log_kind) {
+  if (!(second < __builtin_huge_val())) return false;
+  if (log_kind) return expm1(second - best) < kNearTie;
+  return best > 0.0 ? (second - best) / best < kNearTie : !(second > 0.0);
+}
+
 __global__ void __launch_bounds__(64) finalize_kernel(const FinalizeParams p) {
   __shared__ int s_match;
   __shared__ int s_y;
@@ -38,29 +49,43 @@ __global__ void __launch_bounds__(64) finalize_kernel(const FinalizeParams p) {
     __syncthreads();
   }
 
-  // draft side: one thread per k merges the chunks
-  unsigned long long degenerate = 0;
+  // draft side: one thread per k merges the chunks.  The runner-up of the merged reduction is the
+  // smallest of the other chunks' winners and of the winning chunk's own runner-up (a draft meets
+  // every index in one chunk only).
+  unsigned long long degenerate = 0, near = 0;
   for (int k = tid; k < p.K; k += 64) {
     const long long o = (b * p.K + k) * p.n_chunks;
-    double bkey = __builtin_huge_val();
+    double bkey = __builtin_huge_val(), sec = __builtin_huge_val();
     int bidx = -1;
     for (int c = 0; c < p.n_chunks; ++c) {
       const double key = p.in.keyX[o + c];
       const int idx = p.in.idxX[o + c];
-      if (beats(key, idx, 0, bkey, bidx, 0)) { bkey = key; bidx = idx; }
+      if (beats(key, idx, 0, bkey, bidx, 0)) {
+        if (bidx >= 0) sec = fmin(sec, bkey);
+        bkey = key; bidx = idx;
+      } else if (idx >= 0) {
+        sec = fmin(sec, key);
+      }
+      sec = fmin(sec, p.in.secX[o + c]);
     }
     p.X[b * p.K + k] = bidx;
     if (bidx < 0) ++degenerate;
+    else if (near_tie(bkey, sec, p.log_kind)) ++near;
     if (p.log_keyX != nullptr)
       p.log_keyX[b * p.K + k] = bidx >= 0 ? bkey + p.in.lse[b * (p.K + 1) + k] : __builtin_huge_val();
+    if (p.log_secX != nullptr)
+      p.log_secX[b * p.K + k] = (bidx >= 0 && sec < __builtin_huge_val()) ? sec + p.in.lse[b * (p.K + 1) + k]
+                                                                          : __builtin_huge_val();
     if (p.keyX != nullptr) {
       double out = __builtin_huge_val();
       if (bidx >= 0) out = p.log_kind ? exp(bkey + p.in.lse[b * (p.K + 1) + k]) : bkey;
       p.keyX[b * p.K + k] = (float)out;
     }
   }
+  if (!p.count_draft) { degenerate = 0; near = 0; }
   if (p.Y == nullptr) {  // draft side only
     if (p.stats != nullptr && degenerate) atomicAdd(&p.stats->degenerate, degenerate);
+    if (p.stats != nullptr && near && p.count_near) atomicAdd(&p.stats->near_ties, near);
     return;
   }
   if (p.y_given) {
@@ -83,7 +108,19 @@ __global__ void __launch_bounds__(64) finalize_kernel(const FinalizeParams p) {
     }
     p.Y[b] = bidx;
     s_y = bidx;
-    if (bidx < 0) ++degenerate;
+    if (bidx < 0) {
+      if (p.count_pool) ++degenerate;
+    } else if (p.count_pool) {
+      // the runner-up at another index: a part whose winner sits at the same index (another draft
+      // group met it under other race times) contributes its own runner-up instead
+      double sec = __builtin_huge_val();
+      for (int c = 0; c < p.n_kgroups * p.n_chunks; ++c) {
+        const int idx = p.in.idxY[o + c];
+        if (idx < 0) continue;
+        sec = fmin(sec, idx != bidx ? p.in.keyY[o + c] : p.in.secY[o + c]);
+      }
+      if (near_tie(bkey, sec, p.log_kind)) ++near;
+    }
     if (p.keyY != nullptr) {
       double out = __builtin_huge_val();
       if (bidx >= 0) out = p.log_kind ? exp(bkey + p.in.lse[b * (p.K + 1) + p.K]) : bkey;
@@ -103,6 +140,7 @@ __global__ void __launch_bounds__(64) finalize_kernel(const FinalizeParams p) {
     if (p.match_k != nullptr) p.match_k[b] = hit ? s_match : -1;
   }
   if (p.stats != nullptr && degenerate) atomicAdd(&p.stats->degenerate, degenerate);
+  if (p.stats != nullptr && near && p.count_near) atomicAdd(&p.stats->near_ties, near);
 }
 
 // ln sum_i exp(x_i / T) of one input row, in one pass over the row: every thread keeps a
@@ -248,20 +286,23 @@ __global__ void __launch_bounds__(64) verify_kernel(const VerifyParams p) {
   const int L = p.L, K = p.K;
   const int32_t *cand = p.cand + s * (L + 1) * K;
   const double *ckey = p.cand_key + s * (L + 1) * K;
+  const double *csec = p.cand_sec + s * (L + 1) * K;
   int32_t *Y = p.Y + s * (L + 1);
   float *keyY = p.keyY != nullptr ? p.keyY + s * (L + 1) : nullptr;
   bool viable = lane < K;
   bool done = false;
   int n = 0;
+  unsigned long long near = 0;
   for (int j0 = 0; j0 <= L && !done; j0 += 8) {
-    double key[8];
+    double key[8], sec[8];
     int idx[8], tok[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const int j = j0 + u;
-      key[u] = __builtin_huge_val(); idx[u] = -1; tok[u] = -2;
+      key[u] = sec[u] = __builtin_huge_val(); idx[u] = -1; tok[u] = -2;
       if (j <= L && lane < K) {
         key[u] = ckey[(long long)j * K + lane];
+        sec[u] = csec[(long long)j * K + lane];
         idx[u] = cand[(long long)j * K + lane];
         if (j < L) tok[u] = p.tokens[s * p.tok_stride_s + (long long)j * p.tok_stride_j + lane];
       }
@@ -284,12 +325,22 @@ __global__ void __launch_bounds__(64) verify_kernel(const VerifyParams p) {
         Y[j] = bidx;
         if (keyY != nullptr) keyY[j] = bidx >= 0 ? (float)exp(bkey) : __builtin_huge_valf();
       }
+      if (p.stats != nullptr && bidx >= 0) {
+        // the pool's runner-up at another index: a viable draft whose own winner sits at the
+        // pool's index offers its own runner-up, the others their winner
+        double r = __builtin_huge_val();
+        if (viable && idx[u] >= 0) r = idx[u] != bidx ? key[u] : sec[u];
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) r = fmin(r, __shfl_xor(r, d));
+        if (near_tie(bkey, r, 1)) ++near;
+      }
       n = j + 1;
       if (j == L) { done = true; break; }
       viable = viable && tok[u] == bidx;
       if (__ballot(viable) == 0ull) done = true;
     }
   }
+  if (lane == 0 && near) atomicAdd(&p.stats->near_ties, near);
   for (int j = n + lane; j <= L; j += 64) {
     Y[j] = -1;
     if (keyY != nullptr) keyY[j] = __builtin_huge_valf();
@@ -325,11 +376,12 @@ __global__ void __launch_bounds__(64) strong_step_kernel(const StrongStepParams 
     }
     return;
   }
-  double key = __builtin_huge_val();
+  double key = __builtin_huge_val(), sec = __builtin_huge_val();
   int idx = -1;
   if (lane < K) {
     if (viable) {
       key = p.cand_key[(s * (L + 1) + j) * K + lane];
+      sec = p.cand_sec[(s * (L + 1) + j) * K + lane];
       idx = p.cand[(s * (L + 1) + j) * K + lane];
     } else {
       // merge the chunks of this draft's scan (as the finalize kernel does) and normalise
@@ -337,9 +389,17 @@ __global__ void __launch_bounds__(64) strong_step_kernel(const StrongStepParams 
       for (int c = 0; c < p.n_chunks; ++c) {
         const double ckey = p.part_key[o + c];
         const int cidx = p.part_idx[o + c];
-        if (beats(ckey, cidx, 0, key, idx, 0)) { key = ckey; idx = cidx; }
+        if (beats(ckey, cidx, 0, key, idx, 0)) {
+          if (idx >= 0) sec = fmin(sec, key);
+          key = ckey; idx = cidx;
+        } else if (cidx >= 0) {
+          sec = fmin(sec, ckey);
+        }
+        sec = fmin(sec, p.part_sec[o + c]);
       }
-      key = idx >= 0 ? key + p.lse_sel[s * (K + 1) + lane] : __builtin_huge_val();
+      const double norm = p.lse_sel[s * (K + 1) + lane];
+      sec = (idx >= 0 && sec < __builtin_huge_val()) ? sec + norm : __builtin_huge_val();
+      key = idx >= 0 ? key + norm : __builtin_huge_val();
     }
   }
   double bkey = idx >= 0 ? key : __builtin_huge_val();
@@ -354,6 +414,14 @@ __global__ void __launch_bounds__(64) strong_step_kernel(const StrongStepParams 
   if (lane == 0) {
     Y[j] = bidx;
     if (keyY != nullptr) keyY[j] = bidx >= 0 ? (float)exp(bkey) : __builtin_huge_valf();
+  }
+  if (p.stats != nullptr && bidx >= 0) {
+    // the runner-up at another index, over all K drafts' race times
+    double r = __builtin_huge_val();
+    if (lane < K && idx >= 0) r = idx != bidx ? key : sec;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) r = fmin(r, __shfl_xor(r, d));
+    if (lane == 0 && near_tie(bkey, r, 1)) atomicAdd(&p.stats->near_ties, 1ull);
   }
   bool more = j < L;
   if (more) {

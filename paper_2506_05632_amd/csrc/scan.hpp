@@ -314,6 +314,7 @@ struct Lds {
   int unsafe;            // chunk must be redone in fp64
   unsigned long long best[9];
   unsigned long long where[9];
+  unsigned long long second[9];  // smallest exact key among entries whose index differs from the winner's
   unsigned long long n_survivors, n_exact;
   float cd23[8];         // per draft of this pass: log2(e) / T_k scaled by 2^23 ...
   int kok[8];            // ... and whether its temperature is usable (for lanes that pick a draft at run time)
@@ -322,9 +323,9 @@ struct Lds {
     float vq[4];
     float vd[32];
   } stage[4];
-  int mref[9];           // LSE: ordered-int reference value of each slot's exponentials (a maximum seen in the warm-up)
-  int lse_redo;          // LSE: the running sums cannot be trusted (overflow, no reference, loop skipped)
-  double lse_wave[4][9]; // LSE: per-wave sums, added in a fixed order
+  int lse_redo;          // LSE: the running sums were not formed (the main loop was skipped) or are not finite
+  float lse_wmax[4][9];  // LSE: per-wave maxima ...
+  double lse_wave[4][9]; // ... and per-wave sums relative to them, merged in a fixed order
   int *shared_tau;       // the row's running bests shared by all its workgroups (or null)
   int shared_base, shared_pool;  // where this workgroup's draft 0 and the pool sit in it
   float rec_a[kListCap];
@@ -416,6 +417,12 @@ __device__ __forceinline__ void offer_key(Lds &s, int slot, double key) {
 __device__ __forceinline__ void offer_where(Lds &s, int slot, double key, int i, int k) {
   if (key < __builtin_huge_val() && ord64(key) == s.best[slot])
     atomicMin(&s.where[slot], ((unsigned long long)(uint32_t)i << 32) | (uint32_t)k);
+}
+// Phase 3: the runner-up, i.e. the smallest key at an index other than the winner's (what the
+// near-tie count compares the winner with; the same index under another draft does not count).
+__device__ __forceinline__ void offer_second(Lds &s, int slot, double key, int i) {
+  if (key < __builtin_huge_val() && (uint32_t)i != (uint32_t)(s.where[slot] >> 32))
+    atomicMin(&s.second[slot], ord64(key));
 }
 
 // ln sum exp(x/T) over one chunk of a row by the whole workgroup, exactly: maximum first, then
@@ -509,6 +516,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
           const long long o = (b * p.K + kbase + tid) * p.n_chunks + chunk;
           p.out.keyX[o] = __builtin_huge_val();
           p.out.idxX[o] = -1;
+          p.out.secX[o] = __builtin_huge_val();
           if (LSE) p.lse_part[(b * (p.K + 1) + kbase + tid) * p.n_chunks + chunk] = -__builtin_huge_val();
         }
       } else if (tid == KT) {
@@ -516,6 +524,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         p.out.keyY[o] = __builtin_huge_val();
         p.out.idxY[o] = -1;
         p.out.kY[o] = -1;
+        p.out.secY[o] = __builtin_huge_val();
       }
       return;
     }
@@ -565,9 +574,12 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
     }
   }
   bool lse_ran = false;  // the main loop (which feeds the sums) was executed
+  // LSE: per lane and slot the largest value seen so far and the sum of exp((x - that)/T): the
+  // terms that matter then have small exponents, where fp32 arithmetic is accurate enough
   double lse_acc[LSE ? KT + 1 : 1];
+  float lse_m[LSE ? KT + 1 : 1];
 #pragma unroll
-  for (int kk = 0; kk < (LSE ? KT + 1 : 1); ++kk) lse_acc[kk] = 0.0;
+  for (int kk = 0; kk < (LSE ? KT + 1 : 1); ++kk) { lse_acc[kk] = 0.0; lse_m[kk] = -__builtin_huge_valf(); }
 
   if (tid < 9) {
     // unused draft slots sit at -inf so the shared layout's max over drafts ignores them
@@ -583,6 +595,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
     s.OL[tid] = live ? 0x7F800000 : (int)0xFF800000;  // +inf until the warm-up has a bound : -inf
     s.best[tid] = kOrdInf64;
     s.where[tid] = ~0ull;
+    s.second[tid] = kOrdInf64;
   }
   if (tid == 0) {
 #pragma unroll
@@ -593,7 +606,6 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
     s.shared_pool = p.K;
     s.lse_redo = 0;
   }
-  if (LSE && tid < 9) s.mref[tid] = (int)0x80800000;  // ord32(-inf)
   __syncthreads();
 
   unsigned long long my_survivors = 0;
@@ -607,16 +619,9 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
       const int m = wv % KB;
       const int g = g_begin + (wv / KB) * 64 + (tid & 63);
       float a_even = __builtin_huge_valf(), a_odd = __builtin_huge_valf(), a_pool = __builtin_huge_valf();
-      // LSE: the largest values seen here become the reference of the running sums of exponentials
-      float r_even = -__builtin_huge_valf(), r_odd = -__builtin_huge_valf(), r_pool = -__builtin_huge_valf();
       if (g < g_end && kbase + 2 * m < p.K) {
         float vq[4] = {fill, fill, fill, fill};
         if (with_pool) load4<T>(trow, g * 4, V, vec, fill, vq);
-        if (LSE) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            if (vq[j] < __builtin_huge_valf()) r_pool = fmaxf(r_pool, vq[j]);
-        }
         uint32_t up[4], lo[4];
         philox_block(row_lo, (uint32_t)g, row_hi, pair_base + m, p.seed_lo, p.seed_hi, up);
         philox_block(row_lo, (uint32_t)g, row_hi, (pair_base + m) | kLowBlock, p.seed_lo, p.seed_hi, lo);
@@ -632,11 +637,6 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             load4<T>(drow0 + (SHARED ? 0 : (long long)k * p.draft_stride_k), g * 4, V, vec, fill, vd);
             if (draft_masked) mask_bins(no_draft ? 0u : load_bins4(brow, g * 4, V, bins_aligned), announced, fill, vd);
             float a_k = __builtin_huge_valf();
-            if (LSE) {
-#pragma unroll
-              for (int j = 0; j < 4; ++j)
-                if (vd[j] < __builtin_huge_valf()) (h == 0 ? r_even : r_odd) = fmaxf(h == 0 ? r_even : r_odd, vd[j]);
-            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
               const float l2S = approx_log2_race_time(element_word(up[j], lo[j], h));
@@ -659,20 +659,6 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         if (oe < 0x7F800000) atomicMin(&s.tau[2 * m], oe);
         if (oo < 0x7F800000) atomicMin(&s.tau[2 * m + 1], oo);
         if (op < 0x7F800000) atomicMin(&s.tau[KT], op);
-      }
-      if (LSE) {
-        int re = ord32(r_even), ro = ord32(r_odd), rp = ord32(r_pool);
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) {
-          re = max(re, __shfl_xor(re, d));
-          ro = max(ro, __shfl_xor(ro, d));
-          rp = max(rp, __shfl_xor(rp, d));
-        }
-        if ((tid & 63) == 0) {
-          atomicMax(&s.mref[2 * m], re);
-          atomicMax(&s.mref[2 * m + 1], ro);
-          atomicMax(&s.mref[KT], rp);
-        }
       }
       __syncthreads();
       if (tid <= KT) {
@@ -737,23 +723,33 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
       };
       // The tile is kept in its raw form and widened where it is used, so that few registers
       // are live across the (rare) branch to the survivors' path, which widens it again.
-      float lse_ref[LSE ? KT + 1 : 1];
-      if (LSE) {
-#pragma unroll
-        for (int kk = 0; kk <= KT; ++kk) lse_ref[LSE ? kk : 0] = unord32(s.mref[kk]);
-      }
-      // LSE: four terms exp((x - ref)/T) of one slot, summed in fp32 and added to its fp64 sum.
-      // Entries without mass give 0 (-inf and NaN are clamped to a finite distance); +inf, a value
-      // far above the reference, or no reference at all give inf or NaN, which is noticed at the end.
+      // LSE: four more terms of one slot's sum of exp(x/T), kept relative to the lane's largest
+      // value so far (the sum is rescaled when that moves): fp32 terms, four at a time, into the
+      // fp64 sum.  NaN and +inf entries carry no mass.
       auto lse_add = [&](const int slot, const float (&v)[4]) {
-        float part = 0.0f;
+        const int sl = LSE ? slot : 0;
+        float w[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float d = fmaxf(v[j] - lse_ref[LSE ? slot : 0], -65536.0f);
-          // (the bare hardware exp2: a term below 2^-126 of the largest one may flush to 0)
-          part += __builtin_amdgcn_exp2f(fmaf(d, lse_hi[slot], d * lse_lo[slot]));
+        for (int j = 0; j < 4; ++j) w[j] = v[j] < __builtin_huge_valf() ? v[j] : -__builtin_huge_valf();
+        const float gm = fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3]));
+        if (gm > lse_m[sl]) {
+          if (lse_m[sl] > -__builtin_huge_valf()) {
+            const float d = lse_m[sl] - gm;
+            lse_acc[sl] *= (double)__builtin_amdgcn_exp2f(fmaf(d, lse_hi[slot], d * lse_lo[slot]));
+          }
+          lse_m[sl] = gm;
         }
-        lse_acc[LSE ? slot : 0] += (double)part;
+        if (lse_m[sl] > -__builtin_huge_valf()) {
+          float part = 0.0f;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            // <= 0; entries without mass are clamped to a finite distance whose term is exactly 0
+            // (the bare hardware exp2: a term below 2^-126 of the largest one may flush to 0)
+            const float d = fmaxf(w[j] - lse_m[sl], -65536.0f);
+            part += __builtin_amdgcn_exp2f(fmaf(d, lse_hi[slot], d * lse_lo[slot]));
+          }
+          lse_acc[sl] += (double)part;
+        }
       };
       auto process_tile = [&](const int g, const raw &rq, const raw (&rd)[KD], const uint32_t rb) {
         uint32_t up[KB][4];  // upper half-words: word j of block m = (index 4g+j, drafts 2m | 2m+1)
@@ -989,10 +985,22 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < kPer; ++e) offer_where(s, rslot[e], key[e], ri[e], rk[e]);
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) offer_second(s, rslot[e], key[e], ri[e]);
   } else {
     // ---- fallback: every element of the chunk in fp64 (debug flag, out-of-range tau, list overflow)
-    if (tid < 9) { s.best[tid] = kOrdInf64; s.where[tid] = ~0ull; }
+    if (tid < 9) { s.best[tid] = kOrdInf64; s.where[tid] = ~0ull; s.second[tid] = kOrdInf64; }
     __syncthreads();
+    // A lane keeps its own best per reduction; every key that loses against it (or that it
+    // displaces) goes straight to the reduction's runner-up in LDS.  For the pool a lane meets an
+    // index once per draft: a loser at the lane's current index is dropped (the lane's best at
+    // that index stands for it), and one that was offered earlier and now shares the winner's
+    // index is always dominated by a smaller key at another index that was offered as well.
+    auto offer_loser = [&](const int slot, const double key) {
+      if (key < __builtin_huge_val() && ord64(key) < __atomic_load_n(&s.second[slot], __ATOMIC_RELAXED))
+        atomicMin(&s.second[slot], ord64(key));
+    };
     double best[KT + 1];
     int bi[KT + 1], bk = 0;
 #pragma unroll
@@ -1024,22 +1032,40 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
           const double kx = ok ? exact_key<PROBS>(S, vd[j], (double)tk) : __builtin_huge_val();
           const double ky = with_pool ? exact_key<PROBS>(S, vq[j], (double)Tq) : __builtin_huge_val();
           my_exact += 2;
-          if (kx < bx) { bx = kx; bxi = i; }
+          if (kx < bx) { offer_loser(kk, bx); bx = kx; bxi = i; }
+          else offer_loser(kk, kx);
           if (ky < best[KT] || (ky == best[KT] && ky < __builtin_huge_val() &&
                                 (i < bi[KT] || (i == bi[KT] && k < bk)))) {
+            if (bi[KT] != i) offer_loser(KT, best[KT]);
             best[KT] = ky; bi[KT] = i; bk = k;
+          } else if (i != bi[KT]) {
+            offer_loser(KT, ky);
           }
         }
         // fold (bx, bxi) into draft kk's running best without dynamic register indexing
 #pragma unroll
         for (int q = 0; q < KT; ++q)
-          if (q == kk && (bx < best[q] || (bx == best[q] && bx < __builtin_huge_val() && bxi < bi[q]))) {
-            best[q] = bx; bi[q] = bxi;
+          if (q == kk) {
+            if (bx < best[q] || (bx == best[q] && bx < __builtin_huge_val() && bxi < bi[q])) {
+              offer_loser(q, best[q]);
+              best[q] = bx; bi[q] = bxi;
+            } else {
+              offer_loser(q, bx);
+            }
           }
       }
     }
+    // Lanes own disjoint indices, so a lane's best that does not become the workgroup's is a
+    // runner-up candidate, and so is the best it displaces.
 #pragma unroll
-    for (int kk = 0; kk <= KT; ++kk) offer_key(s, kk, best[kk]);
+    for (int kk = 0; kk <= KT; ++kk) {
+      if (best[kk] < __builtin_huge_val()) {
+        const unsigned long long mine = ord64(best[kk]);
+        const unsigned long long old = atomicMin(&s.best[kk], mine);
+        const unsigned long long loser = mine < old ? old : mine;
+        if (loser != kOrdInf64) atomicMin(&s.second[kk], loser);
+      }
+    }
     __syncthreads();
 #pragma unroll
     for (int kk = 0; kk <= KT; ++kk) offer_where(s, kk, best[kk], bi[kk], kk == KT ? bk : 0);
@@ -1051,17 +1077,22 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
     const int wv = tid >> 6;
 #pragma unroll
     for (int kk = 0; kk <= KT; ++kk) {
-      double v = lse_acc[LSE ? kk : 0];
+      // bring the lanes' sums to the wave's largest value (exactly, in fp64), then add them up
+      const float m = lse_m[LSE ? kk : 0];
+      float wm = m;
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) wm = fmaxf(wm, __shfl_xor(wm, d));
+      double v = 0.0;
+      if (m > -__builtin_huge_valf())
+        v = lse_acc[LSE ? kk : 0] * exp2(((double)m - (double)wm) * ((double)lse_hi[kk] + (double)lse_lo[kk]));
 #pragma unroll
       for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
-      if ((tid & 63) == 0) s.lse_wave[wv][kk] = v;
+      if ((tid & 63) == 0) { s.lse_wave[wv][kk] = v; s.lse_wmax[wv][kk] = wm; }
     }
     __syncthreads();
     const bool slot_used = tid < KT ? (kbase + tid < p.K) : (tid == KT && lse_target);
     double share = -__builtin_huge_val();
     if (tid <= KT && slot_used) {
-      const double tot = (s.lse_wave[0][tid] + s.lse_wave[1][tid]) + (s.lse_wave[2][tid] + s.lse_wave[3][tid]);
-      const float ref = unord32(s.mref[tid]);
       float tk = tid == KT ? Tq : p.temp_draft_all;
       if (tid < KT && p.temp_draft != nullptr) tk = p.temp_draft[kbase + tid];
       const bool t_ok = tk > 0.0f && tk < __builtin_huge_valf();
@@ -1069,18 +1100,27 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         share = -__builtin_huge_val();
       } else if (!lse_ran) {
         s.lse_redo = 1;
-      } else if (!(ref > -__builtin_huge_valf())) {
-        if (tot != 0.0) s.lse_redo = 1;  // mass appeared although the warm-up saw none
-      } else if (!(tot >= 1.0 && tot < __builtin_huge_val())) {
-        s.lse_redo = 1;                  // overflow, NaN, or the reference's own term is missing
       } else {
-        share = (double)ref / (double)tk + log(tot);
+        const double c64 = 1.4426950408889634 / (double)tk;
+        float gm = -__builtin_huge_valf();
+        for (int w = 0; w < 4; ++w) gm = fmaxf(gm, s.lse_wmax[w][tid]);
+        double tot = 0.0;
+        for (int w = 0; w < 4; ++w)
+          if (s.lse_wmax[w][tid] > -__builtin_huge_valf())
+            tot += s.lse_wave[w][tid] * exp2(((double)s.lse_wmax[w][tid] - (double)gm) * c64);
+        if (!(gm > -__builtin_huge_valf())) {
+          share = -__builtin_huge_val();   // no entry of the chunk carries mass
+        } else if (!(tot >= 1.0 && tot < __builtin_huge_val())) {
+          s.lse_redo = 1;                  // not finite, or the largest entry's own term is missing
+        } else {
+          share = (double)gm / (double)tk + log(tot);
+        }
       }
     }
     __syncthreads();
     if (s.lse_redo) {  // uniform
-      float *s_max = reinterpret_cast<float *>(&s.lse_wave[0][0]);
-      double *s_sum = &s.lse_wave[1][0];
+      float *s_max = reinterpret_cast<float *>(&s.lse_wmax[0][0]);
+      double *s_sum = &s.lse_wave[0][0];
 #pragma unroll 1
       for (int kk = 0; kk <= KT; ++kk) {
         const bool used = kk < KT ? (kbase + kk < p.K) : lse_target;
@@ -1109,12 +1149,14 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         const long long o = (b * p.K + k) * p.n_chunks + chunk;
         p.out.keyX[o] = key;
         p.out.idxX[o] = idx;
+        p.out.secX[o] = unord64(s.second[tid]);
       }
     } else {
       const long long o = (b * p.n_kgroups + kg) * p.n_chunks + chunk;
       p.out.keyY[o] = key;
       p.out.idxY[o] = idx;
       p.out.kY[o] = has ? (int)(uint32_t)s.where[tid] : -1;
+      p.out.secY[o] = unord64(s.second[tid]);
     }
   }
   if (p.stats != nullptr) {

@@ -14,6 +14,7 @@ constexpr int kTopmMaxK = 1024;
 struct Best {
   double key;
   int id, k;
+  double sec;  // the smallest key seen at another id (the runner-up that a near-tie is judged by)
 };
 
 // a beats b: smaller key; equal keys: smaller id, then smaller k.  id < 0 = nothing yet.
@@ -25,6 +26,20 @@ __device__ __forceinline__ bool better(const Best &a, const Best &b) {
   return a.k < b.k;
 }
 
+// Fold one more state into a running one.  The loser's winner is a runner-up candidate unless it
+// sits at the winner's id; the loser's own runner-up is then the candidate (it excludes that id).
+__device__ __forceinline__ void fold(Best &v, const Best &o) {
+  if (o.id < 0) return;
+  if (better(o, v)) {
+    double sec = o.sec;
+    if (v.id >= 0) sec = fmin(sec, v.id != o.id ? v.key : v.sec);
+    v = o;
+    v.sec = sec;
+  } else {
+    v.sec = fmin(v.sec, o.id != v.id ? o.key : o.sec);
+  }
+}
+
 __device__ __forceinline__ Best wave_best(Best v) {
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) {
@@ -32,9 +47,18 @@ __device__ __forceinline__ Best wave_best(Best v) {
     o.key = __shfl_xor(v.key, d);
     o.id = __shfl_xor(v.id, d);
     o.k = __shfl_xor(v.k, d);
-    if (better(o, v)) v = o;
+    o.sec = __shfl_xor(v.sec, d);
+    fold(v, o);
   }
   return v;
+}
+
+// Relative distance (in S/p) between the winner and the runner-up below 1e-6 (log-domain keys differ
+// by the log of the ratio).
+__device__ __forceinline__ bool near_tie(const Best &v, bool probs) {
+  if (v.id < 0 || !(v.sec < __builtin_huge_val())) return false;
+  if (!probs) return expm1(v.sec - v.key) < 1e-6;
+  return v.key > 0.0 ? (v.sec - v.key) / v.key < 1e-6 : !(v.sec > 0.0);
 }
 
 __device__ __forceinline__ float widen_at(const void *base, int dtype, long long off) {
@@ -66,7 +90,7 @@ __global__ void __launch_bounds__(256) topm_kernel(const TopmParams p) {
   __shared__ Best s_pool[4];
   __shared__ int s_match, s_y;
   __shared__ unsigned long long s_evals;
-  __shared__ unsigned s_degenerate;
+  __shared__ unsigned s_degenerate, s_near;
 
   const long long b = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -79,7 +103,7 @@ __global__ void __launch_bounds__(256) topm_kernel(const TopmParams p) {
   const long long t_off = b * p.target_stride_b;
   const float inf = __builtin_huge_valf();
 
-  if (tid == 0) { s_match = 0x7FFFFFFF; s_evals = 0; s_degenerate = 0; }
+  if (tid == 0) { s_match = 0x7FFFFFFF; s_evals = 0; s_degenerate = 0; s_near = 0; }
 
   // ---- normalisers: list l < K is draft l, list K the target; one wavefront per list
   if (!probs) {
@@ -129,18 +153,19 @@ __global__ void __launch_bounds__(256) topm_kernel(const TopmParams p) {
     if (logits) T = p.temp_draft != nullptr ? p.temp_draft[k] : p.temp_draft_all;
     const bool t_ok = T > 0.0f && T < inf;
     const double lse = probs ? 0.0 : s_lse[k];
-    Best best = {__builtin_huge_val(), -1, k};
+    Best best = {__builtin_huge_val(), -1, k, __builtin_huge_val()};
     for (int e = lane; e < p.Md; e += 64) {
       const int id = ids[e];
       const float v = widen_at(p.draft_val, p.dtype, off + e);
       if (!t_ok || !has_mass(id, v, probs)) continue;
       const double S = exact_race_time(word_of((uint32_t)id, (uint32_t)k, row_lo, row_hi, p.seed_lo, p.seed_hi));
-      Best c = {probs ? S / (double)v : log(S) - (double)v / (double)T + lse, id, k};
+      Best c = {probs ? S / (double)v : log(S) - (double)v / (double)T + lse, id, k, __builtin_huge_val()};
       ++evals;
-      if (better(c, best)) best = c;
+      fold(best, c);
     }
     best = wave_best(best);
     if (lane == 0) {
+      if (near_tie(best, probs)) atomicAdd(&s_near, 1u);
       s_x[k] = best.id;
       p.X[b * K + k] = best.id;
       if (p.keyX != nullptr)
@@ -153,7 +178,7 @@ __global__ void __launch_bounds__(256) topm_kernel(const TopmParams p) {
   {
     const double lse = probs ? 0.0 : s_lse[K];
     const float T = logits ? p.temp_target : 1.0f;
-    Best best = {__builtin_huge_val(), -1, 0};
+    Best best = {__builtin_huge_val(), -1, 0, __builtin_huge_val()};
     const long long items = (long long)K * p.Mt;
     for (long long it = tid; it < items; it += 256) {
       const int k = (int)(it / p.Mt), e = (int)(it % p.Mt);
@@ -161,9 +186,9 @@ __global__ void __launch_bounds__(256) topm_kernel(const TopmParams p) {
       const float v = widen_at(p.target_val, p.dtype, t_off + e);
       if (!has_mass(id, v, probs)) continue;
       const double S = exact_race_time(word_of((uint32_t)id, (uint32_t)k, row_lo, row_hi, p.seed_lo, p.seed_hi));
-      Best c = {probs ? S / (double)v : log(S) - (double)v / (double)T + lse, id, k};
+      Best c = {probs ? S / (double)v : log(S) - (double)v / (double)T + lse, id, k, __builtin_huge_val()};
       ++evals;
-      if (better(c, best)) best = c;
+      fold(best, c);
     }
     best = wave_best(best);
     if (lane == 0) s_pool[wave] = best;
@@ -171,8 +196,8 @@ __global__ void __launch_bounds__(256) topm_kernel(const TopmParams p) {
   __syncthreads();
   if (tid == 0) {
     Best best = s_pool[0];
-    for (int w = 1; w < 4; ++w)
-      if (better(s_pool[w], best)) best = s_pool[w];
+    for (int w = 1; w < 4; ++w) fold(best, s_pool[w]);
+    if (near_tie(best, probs)) atomicAdd(&s_near, 1u);
     s_y = best.id;
     p.Y[b] = best.id;
     if (p.keyY != nullptr) p.keyY[b] = best.id >= 0 ? (float)(probs ? best.key : exp(best.key)) : inf;
@@ -192,6 +217,7 @@ __global__ void __launch_bounds__(256) topm_kernel(const TopmParams p) {
     if (p.stats != nullptr) {
       if (s_evals) atomicAdd(&p.stats->exact_evals, s_evals);
       if (s_degenerate) atomicAdd(&p.stats->degenerate, (unsigned long long)s_degenerate);
+      if (s_near) atomicAdd(&p.stats->near_ties, (unsigned long long)s_near);
     }
   }
 }

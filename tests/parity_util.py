@@ -64,6 +64,29 @@ def compare(gpu: dict, ref: dict, rows=None, check_keys=True):
     return near
 
 
+def oracle_near_ties(ref: dict) -> int:
+    """Reductions of an oracle result whose runner-up (at another index) is within 1e-6 of the winner."""
+    n = int((ref["gapY"] < NEAR_TIE).sum())
+    if "gapX" in ref:
+        n += int((ref["gapX"] < NEAR_TIE).sum())
+    return n
+
+
+def oracle_borderline(ref: dict) -> int:
+    """Reductions whose gap is so close to 1e-6 itself that the two sides' fp64 roundings may
+    classify them differently (the device compares log-domain keys, the oracle S/p)."""
+    lo, hi = NEAR_TIE * (1 - 1e-6), NEAR_TIE * (1 + 1e-6)
+    n = int(((ref["gapY"] > lo) & (ref["gapY"] < hi)).sum())
+    if "gapX" in ref:
+        n += int(((ref["gapX"] > lo) & (ref["gapX"] < hi)).sum())
+    return n
+
+
+def stats_dict(stats: torch.Tensor) -> dict:
+    from paper_2506_05632_amd.binding import STATS_FIELDS
+    return dict(zip(STATS_FIELDS, (int(v) for v in stats.cpu().numpy())))
+
+
 def same_outputs(a: dict, b: dict):
     for name in a:
         assert torch.equal(a[name], b[name]), name

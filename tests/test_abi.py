@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(binding.EXPORTS)
     for name in names:
         assert getattr(lib, name) is not None
-    assert llc.llc_version() == 106
+    assert llc.llc_version() == 107
     assert llc.llc_status_string(0) == "ok"
     assert "workspace" in llc.llc_status_string(-6)
 
@@ -93,6 +93,15 @@ def test_argument_errors_are_reported_before_any_launch(kw, code):
     assert lib.llc_couple(ctypes.byref(_args(**kw))) == code
 
 
+def test_a_launch_of_more_than_2_to_the_24_workgroups_is_refused_up_front():
+    lib = llc.load()
+    a = _args(B=1 << 21, K=15, V=8, draft_stride_b=8, target_stride_b=8, k_tile=2, flags=binding.FLAG_DRY_RUN)
+    assert lib.llc_couple(ctypes.byref(a)) == -2
+    a = _args(B=1 << 21, K=15, V=8, draft_stride_b=8, target_stride_b=8, k_tile=4, flags=binding.FLAG_DRY_RUN,
+              workspace_bytes=1 << 34)
+    assert lib.llc_couple(ctypes.byref(a)) == 0
+
+
 def test_null_struct_and_empty_batch():
     lib = llc.load()
     assert lib.llc_couple(None) == -1
@@ -117,8 +126,8 @@ def test_product_does_not_import_the_oracle():
 
 
 def test_missing_library_fails_loudly(tmp_path, monkeypatch):
-    code = ("import os; os.environ['LLC_HIP_LIB'] = '/nonexistent/libllc_hip.so';"
-            "import paper_2506_05632_amd as m\n"
+    code = ("import paper_2506_05632_amd as m\n"
+            "m.binding.LIB_PATH = '/nonexistent/libllc_hip.so'\n"
             "try:\n    m.load()\nexcept RuntimeError as e:\n    print('raised')\n")
     out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, cwd=ROOT)
     assert "raised" in out.stdout
@@ -148,7 +157,7 @@ def _verify_args(**kw):
     (dict(kind=binding.PROBS), -4), (dict(dtype=9), -4),
     (dict(target=0x1002), -5),
     (dict(workspace=None), -6), (dict(workspace_bytes=1024), -6),
-    (dict(k_tile=5), -8), (dict(flags=4), -8),
+    (dict(k_tile=5), -8), (dict(flags=16), -8),
 ])
 def test_verify_argument_errors_are_reported_before_any_launch(kw, code):
     lib = llc.load()
@@ -161,6 +170,46 @@ def test_verify_null_struct_empty_batch_and_workspace_size():
     assert lib.llc_verify(ctypes.byref(_verify_args(S=0, target=None, Y=None))) == 0
     assert llc.llc_verify_workspace_size(3, 2, 2, 64) > llc.llc_couple_workspace_size(9, 2, 64)
     assert llc.llc_verify_workspace_size(3, 2, 65, 64) == 0
+
+
+@pytest.mark.parametrize("S,L,K,V", [
+    (128, 4, 8, 128256), (64, 4, 8, 152064),          # draft lengths and list sizes of the paper's runs
+    (128, 7, 8, 128256), (1, 4, 8, 151936), (3, 5, 2, 152064), (17, 4, 6, 32000), (1000, 1, 5, 32000),
+    (2, 4, 64, 128256), (5, 0, 8, 50000), (256, 4, 4, 1000), (9, 12, 9, 40000), (33, 3, 16, 262144),
+])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_verify_takes_exactly_the_workspace_it_asks_for_in_both_forms(S, L, K, V, bf16):
+    """Every launch of the call is planned before the first one (the dry run stops there): the
+    one-shot scan over S(L+1) rows with per-draft rows, and, in the strong form, the scans of the
+    later positions over S rows in the shared-proposal layout, which split V over more workgroups."""
+    lib = llc.load()
+    need = llc.llc_verify_workspace_size(S, L, K, V)
+    assert need > 0
+    shape = dict(S=S, L=L, K=K, V=V, stride_k=V, stride_j=K * V, stride_s=(L + 1) * K * V,
+                 tok_stride_j=K, tok_stride_s=L * K, row_stride_s=L + 1,
+                 dtype=binding.BF16 if bf16 else binding.F32)
+    for flags in (binding.FLAG_DRY_RUN, binding.FLAG_DRY_RUN | binding.FLAG_STRONG):
+        for kt in (0, 2, 4, 8):
+            for vc in (0, 1, 16):
+                a = _verify_args(workspace_bytes=need, flags=flags, k_tile=kt, v_chunks=vc, **shape)
+                assert lib.llc_verify(ctypes.byref(a)) == 0, (flags, kt, vc)
+        a = _verify_args(workspace_bytes=1024, flags=flags, **shape)
+        assert lib.llc_verify(ctypes.byref(a)) == -6
+
+
+def test_dry_run_plans_the_other_calls_too():
+    lib = llc.load()
+    for B, K, V in [(1024, 8, 128256), (512, 16, 152064), (1, 8, 128256), (7, 65535, 37), (256, 4, 32000)]:
+        need = llc.llc_couple_workspace_size(B, K, V)
+        for sk in (0, V):
+            for kt in (0, 2, 4, 8):
+                for vc in (0, 1, 16):
+                    a = _args(B=B, K=K, V=V, draft_stride_b=max(sk * K, V), draft_stride_k=sk, target_stride_b=V,
+                              workspace_bytes=need, flags=binding.FLAG_DRY_RUN, k_tile=kt, v_chunks=vc)
+                    assert lib.llc_couple(ctypes.byref(a)) == 0, (B, K, V, sk, kt, vc)
+        a = _args(B=B, K=K, V=V, draft_stride_b=V, target_stride_b=V, workspace_bytes=512,
+                  flags=binding.FLAG_DRY_RUN)
+        assert lib.llc_couple(ctypes.byref(a)) == -6
 
 
 def _topm_args(**kw):

@@ -7,7 +7,7 @@ import torch
 import oracle
 import paper_2506_05632_amd as llc
 from paper_2506_05632_amd import workloads
-from parity_util import KEY_RTOL, NEAR_TIE
+from parity_util import KEY_RTOL, NEAR_TIE, oracle_borderline, oracle_near_ties, stats_dict
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -62,7 +62,7 @@ def test_compress_select_shapes(B, L, N, l_max):
     ref = oracle.compress_select(enc.cpu().numpy(), dec.cpu().numpy(), bins.cpu().numpy(), seed=3,
                                  row_offset=(1 << 36) + 1)
     compare_select(gpu, ref)
-    assert stats.cpu().numpy()[2] == 0
+    assert stats_dict(stats)["slow_blocks"] == 0
     # every decoder answers inside the announced bin
     X, msg = gpu["X"].long(), gpu["message"]
     ok = X >= 0
@@ -109,19 +109,24 @@ def test_compress_select_shared_decoder_weights_strided_views_and_empty_bins():
     assert (gpu["X"][2] == -1).all() and gpu["accept"][2].item() == 0
 
 
-def test_compress_select_config5_with_bins_sampled_rows():
+def test_compress_select_config5_with_bins_full():
     w = workloads.make(5, DEV)                       # the importance-form workload, now with 16 bins
     g = torch.Generator(device=DEV).manual_seed(77)
     bins = torch.randint(0, 16, (w.B, w.V), generator=g, device=DEV, dtype=torch.uint8)
     stats = llc.new_stats(DEV)
     gpu = llc.llc_compress_select(w.target, w.draft, bins, seed=w.seed, want_keys=True, stats=stats)
     torch.cuda.synchronize()
-    near = 0
-    for rows in [(0, 16), (2040, 2056), (4080, 4096)]:
+    excused, near_oracle, borderline = 0, 0, 0
+    for r0 in range(0, w.B, 512):                    # every row, 512 at a time (host memory)
+        rows = (r0, min(w.B, r0 + 512))
         ref = oracle.compress_select(w.target[rows[0]:rows[1]].cpu().numpy(), w.draft[rows[0]:rows[1]].cpu().numpy(),
                                      bins[rows[0]:rows[1]].cpu().numpy(), seed=w.seed, row_offset=rows[0])
-        near += compare_select(gpu, ref, rows)
-    s = stats.cpu().numpy()
-    print(f"config5 + 16 bins: near-ties {near}, survivors {s[0]}, exact {s[1]}, slow blocks {s[2]}, "
+        excused += compare_select(gpu, ref, rows)
+        near_oracle += oracle_near_ties(ref)
+        borderline += oracle_borderline(ref)
+    s = stats_dict(stats)
+    print(f"config5 + 16 bins: {w.B} rows compared, excused mismatches {excused}, near-ties oracle {near_oracle} / "
+          f"device {s['near_ties']}, survivors {s['survivors']}, exact {s['exact_evals']}, slow blocks {s['slow_blocks']}, "
           f"match rate {gpu['accept'].float().mean().item():.3f}")
-    assert s[2] == 0
+    assert s["slow_blocks"] == 0
+    assert abs(s["near_ties"] - near_oracle) <= borderline and near_oracle <= 2 and excused <= near_oracle

@@ -6,7 +6,7 @@ import torch
 import oracle
 import paper_2506_05632_amd as llc
 from paper_2506_05632_amd import workloads
-from parity_util import compare, to_host
+from parity_util import compare, oracle_borderline, oracle_near_ties, stats_dict, to_host
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -32,9 +32,12 @@ def test_topm_workloads_full(name):
     torch.cuda.synchronize()
     ref = oracle_topm(w.draft_ids, w.draft_val, w.target_ids, w.target_val, w.K, seed=w.seed)
     near = compare(gpu, ref)
-    s = stats.cpu().numpy()
-    print(f"{w.name}: near-ties {near}, exact evaluations {s[1]}, accept rate {ref['accept'].mean():.3f}")
-    assert s[1] == 2 * w.elems and s[3] == 0
+    s = stats_dict(stats)
+    want = oracle_near_ties(ref)
+    print(f"{w.name}: excused mismatches {near}, near-ties oracle {want} / device {s['near_ties']}, "
+          f"exact evaluations {s['exact_evals']}, accept rate {ref['accept'].mean():.3f}")
+    assert s["exact_evals"] == 2 * w.elems and s["degenerate"] == 0
+    assert abs(s["near_ties"] - want) <= oracle_borderline(ref)
     assert ref["accept"].mean() > 0.5
     # the same answer as the dense sampler on rows that carry no mass off the lists (first rows)
     n = min(w.B, 6)
@@ -105,7 +108,7 @@ def test_topm_empty_slots_duplicates_strided_views_and_lists_without_mass():
     ref = oracle_topm(d_ids, d_val, t_ids, t_val, K, seed=8)
     compare(gpu, ref)
     assert gpu["Y"][0].item() == -1 and gpu["accept"][0].item() == 0 and gpu["X"][1, 1].item() == -1
-    assert stats.cpu().numpy()[3] == 2
+    assert stats_dict(stats)["degenerate"] == 2
     # bf16 values, one list per row shared by the K drafts
     ids0 = d_ids[:, 0].contiguous()
     val0 = d_val[:, 0].contiguous().to(torch.bfloat16)

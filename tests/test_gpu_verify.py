@@ -11,7 +11,7 @@ import torch
 import oracle
 import paper_2506_05632_amd as llc
 from paper_2506_05632_amd import workloads
-from parity_util import KEY_RTOL, NEAR_TIE, to_host
+from parity_util import KEY_RTOL, NEAR_TIE, stats_dict, to_host
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -53,6 +53,11 @@ def compare_verify(gpu, ref, seqs=None):
             assert g["n_out"][s] == ref["n_out"][s]
             assert np.array_equal(g["active"][s], ref["active"][s])
     return near
+
+
+def oracle_verify_near_ties(ref):
+    """Emitted positions whose pool ended within 1e-6 of its runner-up (what the device counts)."""
+    return int(((ref["Y"] >= 0) & (ref["gap"] < NEAR_TIE)).sum())
 
 
 def run_verify(w, **kw):
@@ -113,28 +118,32 @@ def test_verify_bf16_full():
     torch.cuda.synchronize()
     ref = oracle_verify(w.target, w.tokens, (0, w.S), temp_target=w.temp_target, seed=w.seed)
     near = compare_verify(gpu, ref)
-    s = stats.cpu().numpy()
-    print(f"verify bf16: near-ties {near}, survivors {s[0]} of {w.elems}, exact {s[1]}, slow blocks {s[2]}")
-    assert s[2] == 0
+    s = stats_dict(stats)
+    print(f"verify bf16: excused {near}, near-ties oracle {oracle_verify_near_ties(ref)} / device {s['near_ties']}, "
+          f"survivors {s['survivors']} of {w.elems}, exact {s['exact_evals']}, slow blocks {s['slow_blocks']}")
+    assert s["slow_blocks"] == 0 and s["near_ties"] == oracle_verify_near_ties(ref)
 
 
 @pytest.mark.parametrize("strong", [False, True])
-def test_verify_large_vocab_sampled_sequences(strong):
+def test_verify_large_vocab_full(strong):
     w = workloads.make_verify("largevocab", DEV)          # the shape bench.py --workload verify times
     stats = llc.new_stats(DEV)
     gpu = run_verify(w, want_keys=True, stats=stats, strong=strong)
     torch.cuda.synchronize()
-    near = 0
-    for seqs in [(0, 2), (63, 65), (126, 128)]:
+    excused, near_oracle = 0, 0
+    for s0 in range(0, w.S, 32):                          # every sequence, 32 at a time (host memory)
+        seqs = (s0, min(w.S, s0 + 32))
         ref = oracle_verify(w.target, w.tokens, seqs, temp_target=w.temp_target, seed=w.seed, strong=strong)
-        near += compare_verify(gpu, ref, seqs)
-    s = stats.cpu().numpy()
-    print(f"verify large: near-ties {near}, survivors {s[0]} of {w.elems}, exact {s[1]}, slow blocks {s[2]}")
-    assert s[2] == 0
+        excused += compare_verify(gpu, ref, seqs)
+        near_oracle += oracle_verify_near_ties(ref)
+    s = stats_dict(stats)
+    print(f"verify large (strong={strong}): {w.S} sequences compared, excused {excused}, near-ties oracle "
+          f"{near_oracle} / device {s['near_ties']}, survivors {s['survivors']} of {w.elems}, exact "
+          f"{s['exact_evals']}, slow blocks {s['slow_blocks']}")
+    assert s["slow_blocks"] == 0
+    assert s["near_ties"] == near_oracle and near_oracle <= 2 and excused <= near_oracle
     Y, n = gpu["Y"].cpu().numpy(), gpu["n_out"].cpu().numpy()
     assert n.min() >= 1 and n.max() <= w.L + 1
-    for srow in range(w.S):
-        assert (Y[srow, :n[srow]] >= 0).all() and (Y[srow, :n[srow]] < w.V).all() and (Y[srow, n[srow]:] == -1).all()
     # the first token is position 0's pool argmin, where all K rows coincide: Algorithm 1's Y on that row
     # (rows of llc_couple are consecutive; position 0 of sequence s is row s*(L+1))
     for srow in range(0, w.S, 17):
@@ -142,6 +151,58 @@ def test_verify_large_vocab_sampled_sequences(strong):
                              temp_target=w.temp_target, temp_draft=w.temp_target, seed=w.seed,
                              row_offset=srow * (w.L + 1))
         assert one["Y"].item() == Y[srow, 0]
+
+
+def test_strong_form_at_the_paper_s_draft_length_and_list_size_with_the_largest_vocabulary():
+    """S=64, L=4, K=8, V=152064 with the library's own launch plan: the later positions' scans split
+    V over more workgroups than the one-shot scan does and need more room for their partial
+    results than it; the workspace of llc_verify_workspace_size must hold both."""
+    S, L, K, V = 64, 4, 8, 152064
+    g = torch.Generator(device=DEV).manual_seed(640)
+    target = torch.empty(S, L + 1, K, V, device=DEV)
+    for j in range(L + 1):
+        target[:, j] = 2.5 * torch.randn(S, K, V, generator=g, device=DEV)
+    target[:, 0, 1:] = target[:, 0, :1]
+    tokens = target[:, :L].argmax(dim=3).to(torch.int32)
+    flip = torch.rand(S, L, K, generator=g, device=DEV) < 0.5
+    tokens = torch.where(flip, torch.randint(0, V, (S, L, K), generator=g, device=DEV, dtype=torch.int32), tokens)
+    kw = dict(temp_target=0.5, seed=99, row_offset=7)
+    ref = oracle_verify(target, tokens, (0, S), strong=True, **kw)
+    for _ in range(L):      # let some drafts follow the output, so that later positions are reached
+        y = torch.from_numpy(ref["Y"][:, :L].copy()).to(DEV)
+        follow = (torch.rand(S, L, K, generator=g, device=DEV) < 0.5) & (y[:, :, None] >= 0)
+        tokens = torch.where(follow, y[:, :, None].expand(S, L, K).to(torch.int32), tokens)
+        ref = oracle_verify(target, tokens, (0, S), strong=True, **kw)
+    assert ref["n_out"].max() >= 3
+    ws = torch.empty(llc.llc_verify_workspace_size(S, L, K, V), dtype=torch.uint8, device=DEV)
+    gpu = llc.llc_verify(target, tokens, want_keys=True, strong=True, workspace=ws, **kw)
+    torch.cuda.synchronize()
+    compare_verify({k: gpu[k] for k in ("Y", "n_out", "active", "keyY")}, ref)
+
+
+def test_strong_form_prices_dropped_drafts_with_rows_that_are_not_vector_aligned():
+    """Contiguous [S, L+1, K, V] with odd V and K = 4: the rows of drafts 1..3 start off a
+    four-element boundary.  Draft 0 is dropped at position 0, so the later positions are priced
+    with another draft's (unaligned) row."""
+    S, L, K, V = 9, 3, 4, 2051
+    g = torch.Generator(device=DEV).manual_seed(2051)
+    target = 2 * torch.randn(S, L + 1, K, V, generator=g, device=DEV)
+    target[:, 0, 1:] = target[:, 0, :1]
+    kw = dict(temp_target=0.8, seed=12, row_offset=3)
+    tokens = torch.randint(0, V, (S, L, K), generator=g, device=DEV, dtype=torch.int32)
+    for _ in range(L + 1):   # drafts 1..3 follow the output, draft 0 never does
+        ref = oracle_verify(target, tokens, (0, S), strong=True, **kw)
+        y = torch.from_numpy(ref["Y"][:, :L].copy()).to(DEV).to(torch.int32)
+        tokens[:, :, 1:] = torch.where(y[:, :, None] >= 0, y[:, :, None].expand(S, L, K - 1), tokens[:, :, 1:])
+        tokens[:, :, 0] = torch.where(tokens[:, :, 0] == y, (y + 1) % V, tokens[:, :, 0])
+    ref = oracle_verify(target, tokens, (0, S), strong=True, **kw)
+    assert (ref["n_out"] == L + 1).all() and (ref["active"][:, 0] == 0).all()
+    for dt in (torch.float32, torch.bfloat16):
+        t = target.to(dt)
+        r = oracle_verify(t, tokens, (0, S), strong=True, **kw)
+        gpu = llc.llc_verify(t, tokens, want_keys=True, strong=True, **kw)
+        torch.cuda.synchronize()
+        compare_verify({k: gpu[k] for k in ("Y", "n_out", "active", "keyY")}, r)
 
 
 def test_verify_results_do_not_depend_on_launch_shape():
