@@ -41,7 +41,8 @@ enum {
   LLC_E_ALIGN = -5,     /* an input base pointer is not aligned to its element size     */
   LLC_E_WORKSPACE = -6, /* workspace missing, misaligned (256 B) or too small           */
   LLC_E_LAUNCH = -7,    /* the HIP runtime refused a launch (hipGetLastError)           */
-  LLC_E_OPTION = -8     /* v_chunks / k_tile / flags out of range                       */
+  LLC_E_OPTION = -8,    /* v_chunks / k_tile / flags out of range                       */
+  LLC_E_SCRATCH = -9    /* llc_couple_static: the call needs more than LLC_STATIC_SCRATCH_BYTES */
 };
 
 enum { LLC_F32 = 0, LLC_BF16 = 1 };
@@ -326,6 +327,19 @@ typedef struct llc_lml_args {
 
 /* Algorithm 1 on a batch (Section 3).  Asynchronous on a->stream. */
 int llc_couple(const llc_couple_args *a);
+
+/* llc_couple for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels and same results as llc_couple, but a->workspace and a->workspace_bytes are
+ * ignored: the partial results live in an array of LLC_STATIC_SCRATCH_BYTES that is part of
+ * the library's device code (each GPU the library runs on holds its copy until the process
+ * ends).  The call allocates and frees nothing.  The device that a->stream belongs to must be
+ * the current device.  A shape whose partial results do not fit (roughly B * K * chunks above
+ * 2^19) returns LLC_E_SCRATCH before anything is launched.  All calls on one GPU share the
+ * array: calls that may overlap in time (different streams, different threads) race; order
+ * them on one stream.  Nothing is carried over between calls. */
+#define LLC_STATIC_SCRATCH_BYTES (16u << 20)
+int llc_couple_static(const llc_couple_args *a);
 
 /* Appendix C's index selection at the encoder and the L decoders.  Asynchronous. */
 int llc_couple_is(const llc_couple_is_args *a);

@@ -20,7 +20,7 @@ FLAG_STRONG = 2
 FLAG_DRY_RUN = 4
 
 _KINDS = {"logits": LOGITS, "probs": PROBS, "logw": LOGW}
-EXPORTS = ["llc_couple", "llc_couple_is", "llc_couple_topm", "llc_compress_select", "llc_verify", "llc_lml_bound",
+EXPORTS = ["llc_couple", "llc_couple_static", "llc_couple_is", "llc_couple_topm", "llc_compress_select", "llc_verify", "llc_lml_bound",
            "llc_couple_workspace_size", "llc_verify_workspace_size", "llc_lml_workspace_size", "llc_status_string",
            "llc_version"]
 
@@ -161,6 +161,8 @@ def load():
         lib = ctypes.CDLL(path)
         lib.llc_couple.argtypes = [ctypes.POINTER(CoupleArgs)]
         lib.llc_couple.restype = ctypes.c_int
+        lib.llc_couple_static.argtypes = [ctypes.POINTER(CoupleArgs)]
+        lib.llc_couple_static.restype = ctypes.c_int
         lib.llc_couple_is.argtypes = [ctypes.POINTER(CoupleIsArgs)]
         lib.llc_couple_is.restype = ctypes.c_int
         lib.llc_compress_select.argtypes = [ctypes.POINTER(CompressSelectArgs)]
@@ -229,7 +231,8 @@ def llc_couple(draft: torch.Tensor, target: torch.Tensor, K: int, *, kind="logit
                temp_draft_per_k: Optional[torch.Tensor] = None, seed: int = 0, row_offset: int = 0,
                want_keys: bool = False, want_match: bool = True, stats: Optional[torch.Tensor] = None,
                workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None,
-               flags: int = 0, v_chunks: int = 0, k_tile: int = 0, scan_events=None) -> dict:
+               flags: int = 0, v_chunks: int = 0, k_tile: int = 0, scan_events=None,
+               _static: bool = False) -> dict:
     """Algorithm 1 on device tensors.
 
     draft: [B,V] (the K drafts of a row share it) or [B,K,V]; target: [B,V]; both
@@ -263,7 +266,7 @@ def llc_couple(draft: torch.Tensor, target: torch.Tensor, K: int, *, kind="logit
         if want_keys:
             out["keyX"] = torch.empty(B, K, dtype=torch.float32, device=dev)
             out["keyY"] = torch.empty(B, dtype=torch.float32, device=dev)
-    if workspace is None:
+    if workspace is None and not _static:
         workspace = new_workspace(B, K, V, dev)
     a = CoupleArgs()
     a.B, a.K, a.V = B, K, V
@@ -281,15 +284,28 @@ def llc_couple(draft: torch.Tensor, target: torch.Tensor, K: int, *, kind="logit
     a.match_k = _ptr(out.get("match_k"))
     a.keyX, a.keyY = _ptr(out.get("keyX")), _ptr(out.get("keyY"))
     a.stats = _ptr(stats)
-    a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
+    if not _static:
+        a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
     a.stream = _stream_handle(dev)
     a.flags, a.v_chunks, a.k_tile = flags, v_chunks, k_tile
     if scan_events is not None:
         a.ev_scan_begin, a.ev_scan_end = scan_events
-    rc = lib.llc_couple(ctypes.byref(a))
+    rc = lib.llc_couple_static(ctypes.byref(a)) if _static else lib.llc_couple(ctypes.byref(a))
     if rc != 0:
         raise LlcError(rc)
     return out
+
+
+def llc_couple_static(draft: torch.Tensor, target: torch.Tensor, K: int, *, out: dict, **kw) -> dict:
+    """llc_couple without a workspace and without any allocation: the partial results live in the
+    library's own static device array (LLC_STATIC_SCRATCH_BYTES).  The caller passes the output
+    tensors (`out` with X, Y, accept and optionally match_k, keyX, keyY), so that this wrapper
+    allocates nothing either; the tensors' device must be the current device.  Calls on one GPU
+    that may overlap in time race on the array."""
+    if kw.get("workspace") is not None:
+        raise ValueError("llc_couple_static takes no workspace")
+    with torch.cuda.device(target.device):
+        return llc_couple(draft, target, K, out=out, _static=True, **kw)
 
 
 def llc_couple_is(logw_enc: torch.Tensor, logw_dec: torch.Tensor, *, seed: int = 0,

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libllc_hip.so")
-SOURCES = ["api.hip", "finalize.hip", "topm.hip", "lml.hip", "scan_f32_shared.hip", "scan_f32_perk.hip",
+SOURCES = ["api.hip", "static_scratch.hip", "finalize.hip", "topm.hip", "lml.hip", "scan_f32_shared.hip", "scan_f32_perk.hip",
            "scan_bf16_shared.hip", "scan_bf16_perk.hip"]
 HEADERS = ["common.hpp", "scan.hpp", os.path.join("..", "..", "include", "llc.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

@@ -372,6 +372,7 @@ const char *llc_status_string(int code) {
     case LLC_E_WORKSPACE: return "workspace missing, misaligned or too small";
     case LLC_E_LAUNCH: return "kernel launch failed";
     case LLC_E_OPTION: return "v_chunks, k_tile, flags or list sizes out of range";
+    case LLC_E_SCRATCH: return "the call needs more than the library's static scratch (LLC_STATIC_SCRATCH_BYTES)";
     default: return "unknown status";
   }
 }
