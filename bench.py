@@ -14,6 +14,7 @@ the headline metric is quoted on.  Prints ONE JSON line.
 import argparse
 import ctypes
 import json
+import math
 import os
 import sys
 import time
@@ -127,34 +128,40 @@ def run_cpu_baseline_verify(w, budget_s=12.0):
                       f"first rejection, the GPU path evaluates every position)"}
 
 
-def bench_verify(args):
+def measure_verify(args, *, strong=False, steps=None, warmup=None, want_workload=False):
     import torch
     import paper_2506_05632_amd as llc
     from paper_2506_05632_amd import workloads
 
+    steps = steps or args.steps
+    warmup = args.warmup if warmup is None else warmup
     dev = "cuda:0"
     w = workloads.make_verify("largevocab", dev)
     ws = torch.empty(llc.llc_verify_workspace_size(w.S, w.L, w.K, w.V), dtype=torch.uint8, device=dev)
     out = {"Y": torch.empty(w.S, w.L + 1, dtype=torch.int32, device=dev),
            "n_out": torch.empty(w.S, dtype=torch.int32, device=dev),
            "active": torch.empty(w.S, w.K, dtype=torch.uint8, device=dev)}
-    ev = HipEvents(args.steps)
+    ev = HipEvents(steps)
 
-    def step(i=None):
+    def step(i=None, stats=None):
         llc.llc_verify(w.target, w.tokens, temp_target=w.temp_target, seed=w.seed + (0 if i is None else i),
                        workspace=ws, out=out, v_chunks=args.v_chunks, k_tile=args.k_tile,
-                       scan_events=None if i is None else ev.pairs[i], strong=args.strong)
+                       scan_events=None if i is None else ev.pairs[i], strong=strong, stats=stats)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    scan_ms = [ev.elapsed_ms(i) for i in range(args.steps)]
+    scan_ms = [ev.elapsed_ms(i) for i in range(steps)]
     ev.close()
+    stats = llc.new_stats(dev)
+    step(None, stats)
+    torch.cuda.synchronize()
+    counters = dict(zip(llc.binding.STATS_FIELDS, (int(v) for v in stats.cpu().numpy())))
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -171,21 +178,36 @@ def bench_verify(args):
     hbm_frac, alu_frac = hbm_achieved / HBM_PEAK_GBS, alu_achieved / ALU_PEAK_TLANEOPS
     roofline = {"bound": "hbm", "achieved": hbm_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": hbm_frac, "kernel": "scan_kernel", "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+                "traffic_source": "recorded from profiles/ (rocprofv3 --pmc of this command, scaled by a plain "
+                                  "copy); not measured in this run",
                 "kernel_ms": scan_avg_s * 1e3, "kernel_ms_min": min(scan_ms),
                 "algorithmic_bytes": alg_bytes, "algorithmic_lane_ops_per_elem": alg_ops,
-                "hbm_frac": hbm_frac, "alu_frac": alu_frac}
+                "hbm_frac": hbm_frac, "alu_frac": alu_frac,
+                "step_hbm_frac": alg_bytes / (wall / steps) / 1e9 / HBM_PEAK_GBS}
+    res = {"value": elems / (wall / steps) / 1e9, "ms_per_step": wall / steps * 1e3, "steps": steps, "warmup": warmup,
+           "config": {"workload": w.name + ("_strong" if strong else ""), "S": w.S, "L": w.L, "K": w.K, "V": w.V,
+                      "input_dtype": str(w.dtype), "temperature": w.temp_target,
+                      "outputs": "Y,n_out,active",
+                      "mean_tokens_per_block": float(out["n_out"].float().mean()),
+                      "near_ties": counters["near_ties"], "slow_blocks": counters["slow_blocks"]},
+           "roofline": roofline}
+    if want_workload:
+        res["_workload"] = w
+    return res
+
+
+def bench_verify(args):
+    r = measure_verify(args, strong=args.strong, want_workload=True)
+    w = r.pop("_workload")
     result = {
         "metric": "Gelem/s (S*(L+1)*K*V) of Algorithm 2's verification loop",
-        "value": elems / (wall / args.steps) / 1e9, "unit": "Gelem/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3,
+        "value": r["value"], "unit": "Gelem/s", "n_gpus": 1,
+        "steps": r["steps"], "warmup": r["warmup"], "ms_per_step": r["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32/u16+f32 (Philox words, packed 16-bit compares, fp32 thresholds, fp64 tie resolution and normalisers)",
         "data": "synthetic",
-        "config": {"workload": w.name + ("_strong" if args.strong else ""), "S": w.S, "L": w.L, "K": w.K, "V": w.V,
-                   "input_dtype": str(w.dtype), "temperature": w.temp_target,
-                   "outputs": "Y,n_out,active",
-                   "mean_tokens_per_block": float(out["n_out"].float().mean())},
-        "roofline": roofline,
+        "config": r["config"],
+        "roofline": r["roofline"],
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = run_cpu_baseline_verify(w)
@@ -369,6 +391,155 @@ def run_cpu_baseline(w, budget_s=12.0, bins=None):
                       f"{dt:.2f} s wall, OpenMP over rows"}
 
 
+def measure_couple(args, config, *, materialised=False, keys=False, bins=0, rows=0, steps=None, warmup=None,
+                   want_workload=False):
+    """Time llc_couple (or, with bins, llc_compress_select) on one configuration; returns the
+    fields of a bench line (without cpu_baseline)."""
+    import torch
+    import paper_2506_05632_amd as llc
+    from paper_2506_05632_amd import workloads
+
+    steps = steps or args.steps
+    warmup = args.warmup if warmup is None else warmup
+    dev = "cuda:0"
+    w = workloads.make(config, dev, rows=rows or None)
+    draft = w.draft
+    if materialised and w.shared_draft:
+        draft = w.draft[:, None, :].expand(w.B, w.K, w.V).contiguous()
+    ws = llc.new_workspace(w.B, w.K, w.V, dev, v_chunks=args.v_chunks)
+    out = {"X": torch.empty(w.B, w.K, dtype=torch.int32, device=dev),
+           "Y": torch.empty(w.B, dtype=torch.int32, device=dev),
+           "accept": torch.empty(w.B, dtype=torch.uint8, device=dev),
+           "match_k": torch.empty(w.B, dtype=torch.int32, device=dev)}
+    if keys:
+        out["keyX"] = torch.empty(w.B, w.K, dtype=torch.float32, device=dev)
+        out["keyY"] = torch.empty(w.B, dtype=torch.float32, device=dev)
+    ev = HipEvents(steps)
+
+    bin_t, decode = None, {}
+    if bins:
+        assert config == 5 and 1 <= bins <= 256, "--bins goes with --config 5"
+        gb = torch.Generator(device=dev)
+        gb.manual_seed(4242)
+        bin_t = torch.randint(0, bins, (w.B, w.V), generator=gb, device=dev, dtype=torch.uint8)
+        out["message"] = torch.empty(w.B, dtype=torch.int32, device=dev)
+        # the decoders' outputs and the trial's distortion (Appendix C, Appendix D.2): candidates in
+        # the paper's parametrisation W = A + eta, i.e. the standardised candidates divided by rho
+        out["W"] = torch.empty(w.B, w.K, dtype=torch.float32, device=dev)
+        out["A_hat"] = torch.empty(w.B, w.K, dtype=torch.float32, device=dev)
+        out["sq_err"] = torch.empty(w.B, dtype=torch.float32, device=dev)
+        decode = dict(cand=(w.extra["u"] / w.extra["rho"]).contiguous(), side=w.extra["y"], source=w.extra["x"],
+                      var_w_given_a=w.extra["var_w_given_a"], var_t_given_a=w.extra["var_t_given_a"])
+
+    def step(i=None, stats=None):
+        if bin_t is not None:
+            llc.llc_compress_select(w.target, w.draft, bin_t, seed=w.seed + (0 if i is None else i),
+                                    row_offset=w.row_offset, workspace=ws, out=out, v_chunks=args.v_chunks,
+                                    k_tile=args.k_tile, scan_events=None if i is None else ev.pairs[i],
+                                    stats=stats, **decode)
+            return
+        llc.llc_couple(draft, w.target, w.K, kind=w.kind, temp_target=w.temp_target,
+                       temp_draft=w.temp_draft, seed=w.seed + (0 if i is None else i),
+                       row_offset=w.row_offset, workspace=ws, out=out,
+                       v_chunks=args.v_chunks, k_tile=args.k_tile,
+                       scan_events=None if i is None else ev.pairs[i], stats=stats)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    scan_ms = [ev.elapsed_ms(i) for i in range(steps)]
+    ev.close()
+    # outside the timed region: one more call that counts near-ties and prefilter survivors
+    stats = llc.new_stats(dev)
+    step(None, stats)
+    torch.cuda.synchronize()
+    counters = dict(zip(llc.binding.STATS_FIELDS, (int(v) for v in stats.cpu().numpy())))
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+    scan_avg_s = sum(scan_ms) / len(scan_ms) / 1e3
+    ms_per_step = wall / steps * 1e3
+    elems = w.elems
+    value = elems / (wall / steps) / 1e9
+    alg_bytes = algorithmic_bytes(w, materialised)
+    alg_ops = algorithmic_lane_ops(w.K)
+    alu_achieved = alg_ops * elems / scan_avg_s / 1e12
+    name = w.name + ("_materialised" if materialised and w.shared_draft else "")
+    if bin_t is not None:
+        name += f"_bins{bins}"
+        # the timed kernel is the decoders' scan: their rows and one byte per candidate (the
+        # encoder's pass before it reads its row once more and is part of the step, not of this figure)
+        alg_bytes = w.B * w.K * w.V * 4 + w.B * w.V
+    if rows:
+        name += f"_rows{w.B}"
+    hbm_achieved = alg_bytes / scan_avg_s / 1e9
+    alu_frac, hbm_frac = alu_achieved / ALU_PEAK_TLANEOPS, hbm_achieved / HBM_PEAK_GBS
+    # The figure of merit is the fraction of the HBM roofline on the algorithmic bytes; the
+    # instruction-issue fraction is reported beside it (its per-element count describes this
+    # kernel's design, it is not an independent floor).
+    roofline = {"bound": "hbm", "achieved": hbm_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_frac,
+                "kernel": "scan_kernel", "traffic": MEASURED_TRAFFIC_BYTES.get(name),
+                "traffic_source": "recorded from profiles/ (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this "
+                                  "command, scaled by a plain copy); not measured in this run",
+                "kernel_ms": scan_avg_s * 1e3, "kernel_ms_min": min(scan_ms),
+                "algorithmic_bytes": alg_bytes, "algorithmic_lane_ops_per_elem": alg_ops,
+                "hbm_frac": hbm_frac, "alu_frac": alu_frac,
+                "step_hbm_frac": alg_bytes / (wall / steps) / 1e9 / HBM_PEAK_GBS}
+    config_d = {"workload": name, "B": w.B, "K": w.K, "V": w.V, "input_dtype": str(w.dtype),
+                "temperature": w.temp_target,
+                "draft_layout": "[B,K,V]" if (materialised or not w.shared_draft) else "[B,V] shared by the K drafts",
+                "outputs": "X,Y,accept,match_k" + (",keyX,keyY" if keys else ""),
+                "accept_rate": float(out["accept"].float().mean()),
+                "near_ties": counters["near_ties"], "prefilter_survivors": counters["survivors"],
+                "exact_evaluations": counters["exact_evals"], "slow_blocks": counters["slow_blocks"]}
+    if bin_t is not None:
+        db = 10.0 * torch.log10(out["sq_err"].double())
+        config_d.update({"outputs": config_d["outputs"] + ",message,W,A_hat,sq_err",
+                         "match_rate": config_d.pop("accept_rate"),
+                         "distortion_db_mean_over_trials": float(db.mean()),
+                         "distortion_db_of_mean": float(10.0 * torch.log10(out["sq_err"].double().mean())),
+                         "rate_bits": math.log2(bins)})
+    res = {"value": value, "ms_per_step": ms_per_step, "steps": steps, "warmup": warmup,
+           "config": config_d, "roofline": roofline}
+    if want_workload:
+        res["_workload"], res["_bins"] = w, bin_t
+    return res
+
+
+def secondary_lines(args):
+    """The other large workloads under the same clock, fewer steps each: kernel time, achieved
+    fraction of the HBM roofline on the algorithmic bytes, whole-call throughput."""
+    import gc
+    import torch
+    out = []
+    todo = [("couple", dict(config=3, materialised=True)), ("couple", dict(config=3, keys=True)),
+            ("couple", dict(config=4)), ("couple", dict(config=5)), ("couple", dict(config=5, bins=16)),
+            ("couple", dict(config=2)), ("verify", dict(strong=False)), ("verify", dict(strong=True))]
+    for kind, kw in todo:
+        if kind == "couple":
+            r = measure_couple(args, steps=30, warmup=10, **kw)
+        else:
+            r = measure_verify(args, steps=30, warmup=10, **kw)
+        rl = r["roofline"]
+        out.append({"workload": r["config"]["workload"] + ("_keys" if kw.get("keys") else ""),
+                    "value": r["value"], "unit": "Gelem/s", "ms_per_step": r["ms_per_step"], "steps": r["steps"],
+                    "kernel_ms": rl["kernel_ms"], "frac": rl["frac"], "bound": rl["bound"],
+                    "algorithmic_bytes": rl["algorithmic_bytes"], "traffic": rl["traffic"],
+                    "near_ties": r["config"].get("near_ties")})
+        gc.collect()
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -386,6 +557,8 @@ def main():
                     help="give the K i.i.d. drafts as a [B,K,V] tensor instead of one shared [B,V] row")
     ap.add_argument("--keys", action="store_true", help="also produce the winning keys (adds the normaliser pass)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="only the headline line: skip the other workloads that the default run also times")
     ap.add_argument("--v-chunks", type=int, default=0)
     ap.add_argument("--k-tile", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -406,107 +579,29 @@ def main():
         bench_topm(args)
         return
 
-    import torch
-    import paper_2506_05632_amd as llc
-    from paper_2506_05632_amd import workloads
-
-    dev = "cuda:0"
-    w = workloads.make(args.config, dev, rows=args.rows or None)
-    draft = w.draft
-    if args.materialised and w.shared_draft:
-        draft = w.draft[:, None, :].expand(w.B, w.K, w.V).contiguous()
-    ws = llc.new_workspace(w.B, w.K, w.V, dev, v_chunks=args.v_chunks)
-    out = {"X": torch.empty(w.B, w.K, dtype=torch.int32, device=dev),
-           "Y": torch.empty(w.B, dtype=torch.int32, device=dev),
-           "accept": torch.empty(w.B, dtype=torch.uint8, device=dev),
-           "match_k": torch.empty(w.B, dtype=torch.int32, device=dev)}
-    if args.keys:
-        out["keyX"] = torch.empty(w.B, w.K, dtype=torch.float32, device=dev)
-        out["keyY"] = torch.empty(w.B, dtype=torch.float32, device=dev)
-    ev = HipEvents(args.steps)
-
-    bins = None
-    if args.bins:
-        assert args.config == 5 and 1 <= args.bins <= 256, "--bins goes with --config 5"
-        gb = torch.Generator(device=dev)
-        gb.manual_seed(4242)
-        bins = torch.randint(0, args.bins, (w.B, w.V), generator=gb, device=dev, dtype=torch.uint8)
-        out["message"] = torch.empty(w.B, dtype=torch.int32, device=dev)
-
-    def step(i=None):
-        if bins is not None:
-            llc.llc_compress_select(w.target, w.draft, bins, seed=w.seed + (0 if i is None else i),
-                                    row_offset=w.row_offset, workspace=ws, out=out, v_chunks=args.v_chunks,
-                                    k_tile=args.k_tile, scan_events=None if i is None else ev.pairs[i])
-            return
-        llc.llc_couple(draft, w.target, w.K, kind=w.kind, temp_target=w.temp_target,
-                       temp_draft=w.temp_draft, seed=w.seed + (0 if i is None else i),
-                       row_offset=w.row_offset, workspace=ws, out=out,
-                       v_chunks=args.v_chunks, k_tile=args.k_tile,
-                       scan_events=None if i is None else ev.pairs[i])
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-
-    scan_ms = [ev.elapsed_ms(i) for i in range(args.steps)]
-    ev.close()
-    if args.calibrate_copy:
-        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-    scan_avg_s = sum(scan_ms) / len(scan_ms) / 1e3
-    ms_per_step = wall / args.steps * 1e3
-    elems = w.elems
-    value = elems / (wall / args.steps) / 1e9
-    alg_bytes = algorithmic_bytes(w, args.materialised)
-    alg_ops = algorithmic_lane_ops(w.K)
-    alu_achieved = alg_ops * elems / scan_avg_s / 1e12
-    name = w.name + ("_materialised" if args.materialised and w.shared_draft else "")
-    if bins is not None:
-        name += f"_bins{args.bins}"
-        # the timed kernel is the decoders' scan: their rows and one byte per candidate (the
-        # encoder's pass before it reads its row once more and is part of the step, not of this figure)
-        alg_bytes = w.B * w.K * w.V * 4 + w.B * w.V
-    if args.rows:
-        name += f"_rows{w.B}"
-    hbm_achieved = alg_bytes / scan_avg_s / 1e9
-    alu_frac, hbm_frac = alu_achieved / ALU_PEAK_TLANEOPS, hbm_achieved / HBM_PEAK_GBS
-    # the ceiling that binds this workload is the one it sits closer to
-    if hbm_frac >= alu_frac:
-        roofline = {"bound": "hbm", "achieved": hbm_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": hbm_frac}
-    else:
-        roofline = {"bound": "alu", "achieved": alu_achieved, "peak": ALU_PEAK_TLANEOPS,
-                    "unit": "Tlane-op/s", "frac": alu_frac}
-    roofline.update({
-        "kernel": "scan_kernel", "traffic": MEASURED_TRAFFIC_BYTES.get(name),
-        "kernel_ms": scan_avg_s * 1e3, "kernel_ms_min": min(scan_ms),
-        "algorithmic_bytes": alg_bytes, "algorithmic_lane_ops_per_elem": alg_ops,
-        "hbm_frac": hbm_frac, "alu_frac": alu_frac,
-    })
+    r = measure_couple(args, args.config, materialised=args.materialised, keys=args.keys, bins=args.bins,
+                       rows=args.rows, want_workload=True)
+    w, bins = r.pop("_workload"), r.pop("_bins")
     result = {
         "metric": "Gelem/s (B*K*V) of list Gumbel-max coupling",
-        "value": value, "unit": "Gelem/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "value": r["value"], "unit": "Gelem/s", "n_gpus": 1, "steps": r["steps"], "warmup": r["warmup"],
+        "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u32/u16+f32 (Philox words, packed 16-bit compares, fp32 thresholds, fp64 tie resolution)",
         "data": "synthetic",
-        "config": {"workload": name, "B": w.B, "K": w.K, "V": w.V, "input_dtype": str(w.dtype),
-                   "temperature": w.temp_target,
-                   "draft_layout": "[B,K,V]" if (args.materialised or not w.shared_draft) else "[B,V] shared by the K drafts",
-                   "outputs": "X,Y,accept,match_k" + (",keyX,keyY" if args.keys else ""),
-                   "accept_rate": float(out["accept"].float().mean())},
-        "roofline": roofline,
+        "config": r["config"],
+        "roofline": r["roofline"],
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = run_cpu_baseline(w, bins=bins)
+    headline = (args.config == 3 and not (args.materialised or args.keys or args.bins or args.rows
+                                          or args.v_chunks or args.k_tile or args.calibrate_copy))
+    if headline and not args.no_secondary:
+        del w, bins
+        import gc
+        import torch
+        gc.collect()
+        torch.cuda.empty_cache()
+        result["secondary"] = secondary_lines(args)
     print(json.dumps(result))
 
 

@@ -28,7 +28,7 @@
 extern "C" {
 #endif
 
-#define LLC_VERSION 107
+#define LLC_VERSION 108
 
 enum {
   LLC_OK = 0,
@@ -57,6 +57,9 @@ enum {
 enum {
   LLC_FLAG_EXACT_SCAN = 1, /* debugging: evaluate every key in fp64, no prefilter     */
   LLC_FLAG_STRONG = 2,     /* llc_verify only: the strongly drafter-invariant loop    */
+  LLC_FLAG_SHARED_RACE = 8,/* llc_compress_select only: the baseline scheme of Section 5.3, in
+                              which all decoders share one set of random numbers: the encoder's
+                              pool and every decoder use the race times of the first set    */
   LLC_FLAG_DRY_RUN = 4     /* llc_couple, llc_couple_is, llc_compress_select, llc_verify: check
                               the arguments, plan every launch of the call and check the
                               workspace against the plan, then return without launching
@@ -163,6 +166,17 @@ typedef struct llc_couple_is_args {
  * are normalised over that bin).  accept[b] = 1 iff some decoder recovers Y[b].  Two passes
  * over the inputs (encoder, then decoders) on the same stream; otherwise as llc_couple_is,
  * with which it coincides when all candidates share one bin.
+ *
+ * Decoder outputs (optional; Appendix C and, for the Gaussian source, Appendix D.2).  Given the
+ * candidates cand[b,i] = U_i (the prior samples the weights were computed on) the call returns
+ * decoder l's output W[b,l] = U_{X[b,l]}.  Given also its side information side[b,l] = T_l and
+ * the two variances of the Gaussian model (W = A + eta, T = A + zeta), it returns the MMSE
+ * estimate A_hat[b,l] = (var_t_given_a * W + var_w_given_a * T_l) /
+ * (var_w_given_a + var_t_given_a + var_w_given_a * var_t_given_a), and, given the source sample
+ * source[b] = A (which only an evaluation knows), the trial's distortion sq_err[b] =
+ * min_l (A_hat[b,l] - A)^2, the estimate with the least error among the decoders (Section 5.3).
+ * A decoder that found no candidate (X = -1) gives NaN and takes no part in the minimum
+ * (+inf if none did).  Arithmetic in fp64 on the fp32 inputs, results rounded to fp32.
  */
 typedef struct llc_compress_select_args {
   int64_t B, L, N;
@@ -184,8 +198,19 @@ typedef struct llc_compress_select_args {
   void *workspace;          /* >= llc_couple_workspace_size(B, L, N) */
   size_t workspace_bytes;
   void *stream;
-  int32_t flags, v_chunks, k_tile;
+  int32_t flags, v_chunks, k_tile;   /* LLC_FLAG_SHARED_RACE is taken here                   */
   void *ev_scan_begin, *ev_scan_end; /* recorded around the decoders' scan */
+  /* decoder outputs: all optional; W needs cand, A_hat also side and the variances, sq_err also source */
+  const float *cand;        /* device [B,N] candidates U_i                                  */
+  int64_t cand_stride_b;
+  const float *side;        /* device [B,L] side information T_l                            */
+  int64_t side_stride_b;
+  const float *source;      /* device [B] source samples A                                  */
+  float var_w_given_a;      /* finite and > 0 when any of the outputs below is asked for     */
+  float var_t_given_a;
+  float *W;                 /* [B,L] */
+  float *A_hat;             /* [B,L] */
+  float *sq_err;            /* [B]   */
 } llc_compress_select_args;
 
 /* Arguments of llc_verify: the verification loop of Algorithm 2 (Section 4.2,

@@ -102,7 +102,7 @@ def lib():
         _lib.llc_compress_select_ref.argtypes = (
             [ctypes.c_int64] * 3 + [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
                                     ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64,
-                                    ctypes.c_uint64] + [ctypes.c_void_p] * 9 + [ctypes.c_int32])
+                                    ctypes.c_uint64] + [ctypes.c_void_p] * 9 + [ctypes.c_int32, ctypes.c_int32])
         _lib.llc_compress_select_ref.restype = ctypes.c_int
         _lib.llc_couple_topm_ref.argtypes = [ctypes.POINTER(_TopmArgs)]
         _lib.llc_couple_topm_ref.restype = ctypes.c_int
@@ -303,11 +303,12 @@ def couple_topm(draft_ids, draft_val, target_ids, target_val, K, *, dtype=F32, k
     return out
 
 
-def compress_select(logw_enc, logw_dec, bins, *, seed=0, row_offset=0, threads=0):
+def compress_select(logw_enc, logw_dec, bins, *, seed=0, row_offset=0, threads=0, shared_race=False):
     """Index selection of the compression scheme with bins (Section 5.1 / Appendix C).
 
     logw_enc [B,N], logw_dec [B,L,N] fp32, bins [B,N] uint8.  Returns Y, message (the bin of Y),
-    X [B,L] (drawn among the candidates of that bin), accept, match_k, keys and gaps."""
+    X [B,L] (drawn among the candidates of that bin), accept, match_k, keys and gaps.
+    shared_race=True: the baseline of Section 5.3 (all decoders use the first set of race times)."""
     enc = _check_input(logw_enc, F32)
     dec = _check_input(logw_dec, F32)
     bins = np.asarray(bins)
@@ -327,7 +328,8 @@ def compress_select(logw_enc, logw_dec, bins, *, seed=0, row_offset=0, threads=0
         dec.strides[1] // 4, bins.ctypes.data, bins.strides[0], seed, row_offset,
         out["X"].ctypes.data, out["Y"].ctypes.data, out["message"].ctypes.data,
         out["accept"].ctypes.data, out["match_k"].ctypes.data, out["keyX"].ctypes.data,
-        out["keyY"].ctypes.data, out["gapX"].ctypes.data, out["gapY"].ctypes.data, threads)
+        out["keyY"].ctypes.data, out["gapX"].ctypes.data, out["gapY"].ctypes.data, threads,
+        1 if shared_race else 0)
     if rc != 0:
         raise ValueError("llc_compress_select_ref rejected its arguments")
     return out

@@ -344,13 +344,17 @@ int llc_couple_is_ref(int64_t B, int64_t L, int64_t N,
 // S_i^(l) / lambda_q,i over all candidates and sends the message M = l_Y; decoder l draws
 // X^(l) = argmin_i S_i^(l) / lambda_p,i^(l) over the candidates with l_i = M only (its weights
 // carry the indicator 1{l_i = M} and are normalised over those candidates).  bins: [B,N] uint8.
+// shared_race != 0 is the baseline scheme that Section 5.3 compares with: all decoders share the
+// same set of random numbers, i.e. every decoder (and the encoder's pool) uses the race times of
+// the first set, S_i^(1).
 int llc_compress_select_ref(int64_t B, int64_t L, int64_t N,
                             const float *logw_enc, int64_t enc_stride_b,
                             const float *logw_dec, int64_t dec_stride_b, int64_t dec_stride_l,
                             const uint8_t *bins, int64_t bins_stride_b,
                             uint64_t seed, uint64_t row_offset,
                             int32_t *X, int32_t *Y, int32_t *message, uint8_t *accept, int32_t *match_l,
-                            double *keyX, double *keyY, double *gapX, double *gapY, int32_t threads) {
+                            double *keyX, double *keyY, double *gapX, double *gapY, int32_t threads,
+                            int32_t shared_race) {
   if (!logw_enc || !logw_dec || !bins || !X || !Y || !accept) return -1;
   if (B < 0 || L < 1 || N < 1) return -1;
   int nthreads = threads;
@@ -367,7 +371,7 @@ int llc_compress_select_ref(int64_t B, int64_t L, int64_t N,
     // encoder: lambda_q over all N candidates, pool over the L sets of race times
     row_distribution(logw_enc, DT_F32, b * enc_stride_b, N, KIND_LOGW, 1.0, q);
     Race pool;
-    for (int64_t l = 0; l < L; ++l)
+    for (int64_t l = 0; l < (shared_race ? 1 : L); ++l)
       for (int64_t i = 0; i < N; ++i) {
         const double S = race_time(shared_word(seed, row, (uint32_t)l, (uint64_t)i));
         pool.offer(q[i] > 0.0 ? S / q[i] : kInf, i, l);
@@ -395,7 +399,7 @@ int llc_compress_select_ref(int64_t B, int64_t L, int64_t N,
       for (int64_t i = 0; i < N; ++i) {
         const double w = zmax > -kInf ? std::exp(p[i] - zmax - std::log(sum)) : 0.0;
         if (!(w > 0.0)) continue;
-        const double S = race_time(shared_word(seed, row, (uint32_t)l, (uint64_t)i));
+        const double S = race_time(shared_word(seed, row, (uint32_t)(shared_race ? 0 : l), (uint64_t)i));
         dec.offer(S / w, i, l);
       }
       X[b * L + l] = (int32_t)dec.idx;

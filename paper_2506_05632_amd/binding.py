@@ -18,6 +18,7 @@ LOGITS, PROBS, LOGW = 0, 1, 2
 FLAG_EXACT_SCAN = 1
 FLAG_STRONG = 2
 FLAG_DRY_RUN = 4
+FLAG_SHARED_RACE = 8
 
 _KINDS = {"logits": LOGITS, "probs": PROBS, "logw": LOGW}
 EXPORTS = ["llc_couple", "llc_couple_static", "llc_couple_is", "llc_couple_topm", "llc_compress_select", "llc_verify", "llc_lml_bound",
@@ -87,6 +88,11 @@ class CompressSelectArgs(ctypes.Structure):
         ("stream", ctypes.c_void_p),
         ("flags", ctypes.c_int32), ("v_chunks", ctypes.c_int32), ("k_tile", ctypes.c_int32),
         ("ev_scan_begin", ctypes.c_void_p), ("ev_scan_end", ctypes.c_void_p),
+        ("cand", ctypes.c_void_p), ("cand_stride_b", ctypes.c_int64),
+        ("side", ctypes.c_void_p), ("side_stride_b", ctypes.c_int64),
+        ("source", ctypes.c_void_p),
+        ("var_w_given_a", ctypes.c_float), ("var_t_given_a", ctypes.c_float),
+        ("W", ctypes.c_void_p), ("A_hat", ctypes.c_void_p), ("sq_err", ctypes.c_void_p),
     ]
 
 
@@ -356,10 +362,16 @@ def llc_compress_select(logw_enc: torch.Tensor, logw_dec: torch.Tensor, bins: to
                         seed: int = 0, row_offset: int = 0, want_keys: bool = False,
                         stats: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
                         out: Optional[dict] = None, flags: int = 0, v_chunks: int = 0, k_tile: int = 0,
-                        scan_events=None) -> dict:
+                        scan_events=None, shared_race: bool = False,
+                        cand: Optional[torch.Tensor] = None, side: Optional[torch.Tensor] = None,
+                        source: Optional[torch.Tensor] = None, var_w_given_a: float = 0.0,
+                        var_t_given_a: float = 0.0) -> dict:
     """Binned index selection of the compression scheme: logw_enc [B,N], logw_dec [B,L,N]
     float32, bins [B,N] uint8, all on the device.  Returns Y, message, X [B,L], accept, match_k
-    and, if asked, keyX, keyY.  Asynchronous on torch's current stream."""
+    and, if asked, keyX, keyY.  shared_race: the baseline in which all decoders share one set of
+    race times.  With cand [B,N] (the candidates U_i) also W [B,L]; with side [B,L] and the two
+    variances also the MMSE estimates A_hat [B,L]; with source [B] also sq_err [B], the least
+    squared error among the decoders.  Asynchronous on torch's current stream."""
     lib = load()
     if not (logw_enc.is_cuda and logw_dec.is_cuda and bins.is_cuda):
         raise ValueError("llc_compress_select needs device tensors (there is no CPU path)")
@@ -380,6 +392,16 @@ def llc_compress_select(logw_enc: torch.Tensor, logw_dec: torch.Tensor, bins: to
         if want_keys:
             out["keyX"] = torch.empty(B, L, dtype=torch.float32, device=dev)
             out["keyY"] = torch.empty(B, dtype=torch.float32, device=dev)
+        if cand is not None:
+            out["W"] = torch.empty(B, L, dtype=torch.float32, device=dev)
+            if side is not None:
+                out["A_hat"] = torch.empty(B, L, dtype=torch.float32, device=dev)
+                if source is not None:
+                    out["sq_err"] = torch.empty(B, dtype=torch.float32, device=dev)
+    for t, shape in ((cand, (B, N)), (side, (B, L)), (source, (B,))):
+        if t is not None and (not t.is_cuda or t.dtype != torch.float32 or tuple(t.shape) != shape
+                              or t.stride(-1) != 1):
+            raise ValueError("cand [B,N], side [B,L], source [B]: float32 device tensors, last dimension contiguous")
     if workspace is None:
         workspace = new_workspace(B, L, N, dev)
     a = CompressSelectArgs()
@@ -397,6 +419,15 @@ def llc_compress_select(logw_enc: torch.Tensor, logw_dec: torch.Tensor, bins: to
     a.flags, a.v_chunks, a.k_tile = flags, v_chunks, k_tile
     if scan_events is not None:
         a.ev_scan_begin, a.ev_scan_end = scan_events
+    if shared_race:
+        a.flags |= FLAG_SHARED_RACE
+    if cand is not None:
+        a.cand, a.cand_stride_b = cand.data_ptr(), cand.stride(0)
+    if side is not None:
+        a.side, a.side_stride_b = side.data_ptr(), side.stride(0)
+    a.source = _ptr(source)
+    a.var_w_given_a, a.var_t_given_a = var_w_given_a, var_t_given_a
+    a.W, a.A_hat, a.sq_err = _ptr(out.get("W")), _ptr(out.get("A_hat")), _ptr(out.get("sq_err"))
     rc = lib.llc_compress_select(ctypes.byref(a))
     if rc != 0:
         raise LlcError(rc)

@@ -122,6 +122,7 @@ struct ScanJob {
   bool no_pool;      // draft-side reductions only
   bool need_lse;     // also compute the row normalisers (log kinds)
   bool no_draft = false;    // pool only
+  bool same_race = false;   // every draft uses draft 0's race times
   bool force_perk = false;  // every draft has its own row even if draft_stride_k == 0
   const uint8_t *bins = nullptr;  // binned candidates: mask of the draft rows (see ScanParams)
   long long bins_stride_b = 0;
@@ -224,7 +225,7 @@ int launch_scan_job(const ScanJob &j, const ScanPlan &plan, Partials *partials, 
 
   // Row normalisers: with per-draft rows the scan forms them on its way (no second pass over the
   // inputs); the shared layout and the binned passes use the normaliser kernel.
-  const bool masked = j.bins != nullptr || j.no_draft;
+  const bool masked = j.bins != nullptr || j.no_draft || j.same_race;
   const bool fused_lse = j.need_lse && j.kind != LLC_PROBS && !shared && !masked;
   part.lse_part = fused_lse ? (double *)(ws + lay.lse_part) : nullptr;
   // (the target row's normaliser always comes from the normaliser kernel, so that keyY does not
@@ -277,6 +278,7 @@ int launch_scan_job(const ScanJob &j, const ScanPlan &plan, Partials *partials, 
   sp.force_exact = (j.flags & LLC_FLAG_EXACT_SCAN) ? 1 : 0;
   sp.no_pool = j.no_pool ? 1 : 0;
   sp.no_draft = j.no_draft ? 1 : 0;
+  sp.same_race = j.same_race ? 1 : 0;
   sp.out = part;
   sp.stats = j.stats;
 
@@ -341,6 +343,8 @@ int couple_on(const llc_couple_args *a, void *workspace, size_t workspace_bytes)
   if (rc != LLC_OK || dry) return rc;
 
   FinalizeParams fp;
+  fp.cand = nullptr; fp.side = nullptr; fp.source = nullptr; fp.W = nullptr; fp.A_hat = nullptr; fp.sq_err = nullptr;
+  fp.cand_stride_b = 0; fp.side_stride_b = 0; fp.var_e = 0.0; fp.var_z = 0.0;
   fp.B = a->B; fp.K = (int)a->K; fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
   fp.log_kind = a->kind != LLC_PROBS ? 1 : 0;
   fp.in = part;
@@ -402,13 +406,24 @@ int llc_compress_select(const llc_compress_select_args *a) {
     return LLC_E_NULL;
   if (a->enc_stride_b < 0 || a->dec_stride_b < 0 || a->dec_stride_l < 0 || a->bins_stride_b < 0)
     return LLC_E_SHAPE;
+  // the decoders' outputs (optional): candidates, side information and the two variances
+  const bool decode = a->W != nullptr || a->A_hat != nullptr || a->sq_err != nullptr;
+  if (decode) {
+    const bool estimate = a->A_hat != nullptr || a->sq_err != nullptr;
+    if (a->cand == nullptr || (estimate && a->side == nullptr)) return LLC_E_NULL;
+    if (a->sq_err != nullptr && a->source == nullptr) return LLC_E_NULL;
+    if (a->cand_stride_b < 0 || a->side_stride_b < 0) return LLC_E_SHAPE;
+    if (estimate && (!good_temp(a->var_w_given_a) || !good_temp(a->var_t_given_a))) return LLC_E_OPTION;
+  }
   hipStream_t st = (hipStream_t)a->stream;
   const bool dry = (a->flags & LLC_FLAG_DRY_RUN) != 0;
+  // the baseline of Section 5.3: one set of race times for the encoder and every decoder
+  const bool same_race = (a->flags & LLC_FLAG_SHARED_RACE) != 0;
 
   // pass 1, the encoder: Y = the pool argmin under lambda_q over the L sets of race times (the
   // shared-proposal scan without a draft side; its X comes out as -1 and pass 2 overwrites it)
   ScanJob j;
-  j.B = a->B; j.K = a->L; j.V = a->N; j.dtype = LLC_F32; j.kind = LLC_LOGW;
+  j.B = a->B; j.K = same_race ? 1 : a->L; j.V = a->N; j.dtype = LLC_F32; j.kind = LLC_LOGW;
   j.draft = a->logw_enc; j.target = a->logw_enc;
   j.map = plain_rows(a->enc_stride_b, a->enc_stride_b);
   j.draft_stride_k = 0;
@@ -417,7 +432,7 @@ int llc_compress_select(const llc_compress_select_args *a) {
   j.no_pool = false;
   j.no_draft = true;
   j.need_lse = a->keyY != nullptr;
-  j.flags = a->flags & ~LLC_FLAG_DRY_RUN; j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;
+  j.flags = a->flags & ~(LLC_FLAG_DRY_RUN | LLC_FLAG_SHARED_RACE); j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;
   j.stats = a->stats; j.workspace = a->workspace; j.workspace_bytes = a->workspace_bytes;
   j.stream = a->stream; j.ev_begin = nullptr; j.ev_end = nullptr;
   j.extra_bytes = 0;
@@ -426,13 +441,17 @@ int llc_compress_select(const llc_compress_select_args *a) {
   int rc = run_scan(j, dry, &pl, &part, nullptr);
   if (rc != LLC_OK) return rc;
   if (dry) {  // the decoders' pass is planned as well, nothing is launched
+    j.K = a->L; j.same_race = same_race;
     j.draft = a->logw_dec; j.map = plain_rows(a->dec_stride_b, a->enc_stride_b);
     j.draft_stride_k = a->dec_stride_l; j.no_pool = true; j.no_draft = false;
     j.bins = a->bins; j.bins_stride_b = a->bins_stride_b; j.bin_of = a->Y;
     return run_scan(j, true, &pl, &part, nullptr);
   }
   FinalizeParams fp;
-  fp.B = a->B; fp.K = (int)a->L; fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
+  fp.cand = nullptr; fp.side = nullptr; fp.source = nullptr; fp.W = nullptr; fp.A_hat = nullptr; fp.sq_err = nullptr;
+  fp.cand_stride_b = 0; fp.side_stride_b = 0; fp.var_e = 0.0; fp.var_z = 0.0;
+  // (with one shared set of race times the pool runs over that set alone: K = 1 in this pass)
+  fp.B = a->B; fp.K = (int)j.K; fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
   fp.log_kind = 1;
   fp.in = part;
   fp.X = a->X; fp.Y = a->Y; fp.match_k = nullptr; fp.accept = a->accept;
@@ -443,6 +462,7 @@ int llc_compress_select(const llc_compress_select_args *a) {
   if (launch_finalize(st, fp) != hipSuccess) return LLC_E_LAUNCH;
 
   // pass 2, the decoders: X^(l) = argmin under lambda_p^(l) over the candidates of Y's bin
+  j.K = a->L; j.same_race = same_race;
   j.draft = a->logw_dec; j.target = a->logw_enc;
   j.map = plain_rows(a->dec_stride_b, a->enc_stride_b);
   j.draft_stride_k = a->dec_stride_l;
@@ -453,8 +473,15 @@ int llc_compress_select(const llc_compress_select_args *a) {
   j.ev_begin = a->ev_scan_begin; j.ev_end = a->ev_scan_end;
   rc = run_scan(j, false, &pl, &part, nullptr);
   if (rc != LLC_OK) return rc;
-  fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
+  fp.K = (int)a->L; fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
   fp.in = part;
+  if (decode) {
+    fp.cand = a->cand; fp.cand_stride_b = a->cand_stride_b;
+    fp.side = a->side; fp.side_stride_b = a->side_stride_b;
+    fp.source = a->source;
+    fp.var_e = (double)a->var_w_given_a; fp.var_z = (double)a->var_t_given_a;
+    fp.W = a->W; fp.A_hat = a->A_hat; fp.sq_err = a->sq_err;
+  }
   fp.X = a->X; fp.Y = a->Y; fp.match_k = a->match_l; fp.accept = a->accept;
   fp.keyX = a->keyX; fp.keyY = nullptr;
   fp.y_given = 1; fp.bins = a->bins; fp.bins_stride_b = a->bins_stride_b; fp.message = a->message;
@@ -640,6 +667,8 @@ int llc_verify(const llc_verify_args *a) {
 
   hipStream_t st = (hipStream_t)a->stream;
   FinalizeParams fp;
+  fp.cand = nullptr; fp.side = nullptr; fp.source = nullptr; fp.W = nullptr; fp.A_hat = nullptr; fp.sq_err = nullptr;
+  fp.cand_stride_b = 0; fp.side_stride_b = 0; fp.var_e = 0.0; fp.var_z = 0.0;
   fp.B = B; fp.K = (int)a->K; fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
   fp.log_kind = 1;
   fp.in = part;

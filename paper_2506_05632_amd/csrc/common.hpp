@@ -62,6 +62,7 @@ struct ScanParams {
   int force_exact;
   int no_pool;              // draft-side reductions only: the target is never read
   int no_draft;             // pool only: the draft rows are never read, X comes out as -1
+  int same_race;            // every draft uses draft 0's race times (binned / pool-only variant only)
   const uint8_t *bins;      // optional [B][V] bins of the candidates (bins_stride_b bytes per row):
   long long bins_stride_b;  // on the draft side only candidates in the bin of index bin_of[b] count
   const int32_t *bin_of;    // [B]
@@ -89,6 +90,16 @@ struct FinalizeParams {
   float *keyX, *keyY;  // optional
   double *log_keyX;    // optional [B][K]: ln of the normalised winning key (log kinds)
   double *log_secX;    // optional [B][K]: the same for the runner-up (another index) of that reduction
+  // optional decoder outputs of the compression scheme (Appendix C, Appendix D.2): W_k = cand[X_k],
+  // the estimate g(W_k, T_k) = (vz W_k + ve T_k) / (ve + vz + ve vz), the best squared error
+  const float *cand;         // [B][V'] candidates U_i, or nullptr
+  long long cand_stride_b;
+  const float *side;         // [B][K] side information T_k
+  long long side_stride_b;
+  const float *source;       // [B] the source sample A (known to an evaluation only), or nullptr
+  double var_e, var_z;       // variance of W given A, of T given A
+  float *W, *A_hat;          // [B][K] optional
+  float *sq_err;             // [B] optional: min_k (g(W_k, T_k) - A)^2
   int count_draft;     // count the draft side's reductions in stats->degenerate
   int count_pool;      // count the pool's
   int count_near;      // also count the near-ties of the sides that are counted

@@ -32,9 +32,11 @@ __device__ __forceinline__ bool near_tie(double best, double second, int log_kin
 __global__ void __launch_bounds__(64) finalize_kernel(const FinalizeParams p) {
   __shared__ int s_match;
   __shared__ int s_y;
+  __shared__ unsigned long long s_err;  // ordered image of the smallest squared error among the decoders
   const long long b = blockIdx.x;
   const int tid = threadIdx.x;
-  if (tid == 0) s_match = 0x7FFFFFFF;
+  if (tid == 0) { s_match = 0x7FFFFFFF; s_err = 0x7FF0000000000000ull; }  // (+inf; squared errors are >= 0)
+  if (p.cand != nullptr) __syncthreads();
   if (p.in.lse_part != nullptr) {
     // the scan left every chunk's share of the normalisers: ln sum_chunks exp(share)
     for (int k = tid; k < p.K; k += 64) {  // (the target's normaliser is already in place)
@@ -80,6 +82,25 @@ __global__ void __launch_bounds__(64) finalize_kernel(const FinalizeParams p) {
       double out = __builtin_huge_val();
       if (bidx >= 0) out = p.log_kind ? exp(bkey + p.in.lse[b * (p.K + 1) + k]) : bkey;
       p.keyX[b * p.K + k] = (float)out;
+    }
+    if (p.cand != nullptr) {
+      // the decoder's output W_k = U_{X^(k)} (Appendix C) and its MMSE estimate of the source
+      // (Appendix D.2), in fp64 from the fp32 inputs; NaN where the decoder found no candidate
+      double w = __builtin_nan(""), est = __builtin_nan("");
+      if (bidx >= 0) {
+        w = (double)p.cand[b * p.cand_stride_b + bidx];
+        if (p.side != nullptr) {
+          const double t = (double)p.side[b * p.side_stride_b + k];
+          est = (p.var_z * w + p.var_e * t) / (p.var_e + p.var_z + p.var_e * p.var_z);
+        }
+        if (p.sq_err != nullptr) {
+          const double d = est - (double)p.source[b];
+          const double e2 = d * d;
+          if (e2 == e2) atomicMin(&s_err, (unsigned long long)__double_as_longlong(e2));
+        }
+      }
+      if (p.W != nullptr) p.W[b * p.K + k] = (float)w;
+      if (p.A_hat != nullptr) p.A_hat[b * p.K + k] = (float)est;
     }
   }
   if (!p.count_draft) { degenerate = 0; near = 0; }
@@ -138,6 +159,8 @@ __global__ void __launch_bounds__(64) finalize_kernel(const FinalizeParams p) {
     const bool hit = s_match != 0x7FFFFFFF;
     p.accept[b] = hit ? 1 : 0;
     if (p.match_k != nullptr) p.match_k[b] = hit ? s_match : -1;
+    // (the barriers above order the decoders' offers before this read)
+    if (p.cand != nullptr && p.sq_err != nullptr) p.sq_err[b] = (float)__longlong_as_double((long long)s_err);
   }
   if (p.stats != nullptr && degenerate) atomicAdd(&p.stats->degenerate, degenerate);
   if (p.stats != nullptr && near && p.count_near) atomicAdd(&p.stats->near_ties, near);

@@ -492,7 +492,10 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
   const int kg = (int)((bid / (unsigned)p.n_chunks) % (unsigned)p.n_kgroups);
   const long long b = (long long)(bid / ((unsigned)p.n_chunks * (unsigned)p.n_kgroups));
   const int kbase = kg * KT;
-  const uint32_t pair_base = (uint32_t)(kg * KB);
+  // same_race: every draft of the row uses the race times of draft 0 (the compression scheme's
+  // baseline, in which all decoders share one set of random numbers; paper Section 5.3)
+  const bool same_race = MASKED && p.same_race != 0;
+  const uint32_t pair_base = same_race ? 0u : (uint32_t)(kg * KB);
   const int V = p.V;
   const int G = (V + 3) >> 2;
   const int g_begin = chunk * p.groups_per_chunk;
@@ -623,8 +626,9 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         float vq[4] = {fill, fill, fill, fill};
         if (with_pool) load4<T>(trow, g * 4, V, vec, fill, vq);
         uint32_t up[4], lo[4];
-        philox_block(row_lo, (uint32_t)g, row_hi, pair_base + m, p.seed_lo, p.seed_hi, up);
-        philox_block(row_lo, (uint32_t)g, row_hi, (pair_base + m) | kLowBlock, p.seed_lo, p.seed_hi, lo);
+        const uint32_t pair = same_race ? 0u : pair_base + m;
+        philox_block(row_lo, (uint32_t)g, row_hi, pair, p.seed_lo, p.seed_hi, up);
+        philox_block(row_lo, (uint32_t)g, row_hi, pair | kLowBlock, p.seed_lo, p.seed_hi, lo);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
           const int k = kbase + 2 * m + h;
@@ -639,7 +643,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             float a_k = __builtin_huge_valf();
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-              const float l2S = approx_log2_race_time(element_word(up[j], lo[j], h));
+              const float l2S = approx_log2_race_time(element_word(up[j], lo[j], same_race ? 0 : h));
               float ell;
               if (ok && approx_log2_mass<PROBS>(vd[j], ck, ell)) a_k = fminf(a_k, l2S - ell);
               if (with_pool && approx_log2_mass<PROBS>(vq[j], cq, ell)) a_pool = fminf(a_pool, l2S - ell);
@@ -753,7 +757,19 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
       };
       auto process_tile = [&](const int g, const raw &rq, const raw (&rd)[KD], const uint32_t rb) {
         uint32_t up[KB][4];  // upper half-words: word j of block m = (index 4g+j, drafts 2m | 2m+1)
-        philox_blocks<KB>((uint32_t)g, pair_base, row_lo, row_hi, p.seed_lo, p.seed_hi, up);
+        if (same_race) {
+          // one block for all drafts: draft 0's half-word of every index, in both halves of every pair
+          uint32_t one[1][4];
+          philox_blocks<1>((uint32_t)g, 0u, row_lo, row_hi, p.seed_lo, p.seed_hi, one);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const uint32_t w = (one[0][j] & 0xFFFFu) * 0x10001u;
+#pragma unroll
+            for (int m = 0; m < KB; ++m) up[m][j] = w;
+          }
+        } else {
+          philox_blocks<KB>((uint32_t)g, pair_base, row_lo, row_hi, p.seed_lo, p.seed_hi, up);
+        }
 
         // The main loop works with exponents lowered by 32 (kShift32): see packed_hi16.
         const float OY = load_offset(&s.OL[KT]);  // (-inf without a pool)
@@ -855,9 +871,9 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
                 const uint32_t hw = h ? (uw >> 16) : (uw & 0xFFFFu);
                 if (F >= kCapHot || hw >= 0xFFFFu - (t >> 16)) {
                   uint32_t lo[4];
-                  philox_block(row_lo, (uint32_t)gs, row_hi, (pair_base + m) | kLowBlock, p.seed_lo, p.seed_hi, lo);
+                  philox_block(row_lo, (uint32_t)gs, row_hi, (same_race ? 0u : pair_base + m) | kLowBlock, p.seed_lo, p.seed_hi, lo);
                   const uint32_t lw = j == 0 ? lo[0] : j == 1 ? lo[1] : j == 2 ? lo[2] : lo[3];
-                  const uint32_t x = element_word(uw, lw, h);
+                  const uint32_t x = element_word(uw, lw, same_race ? 0 : h);
                   if (F >= kCapHot || x >= ~t) {
                     ++my_survivors;
                     level2<KT, SHARED, PROBS>(s, x, ds, qs, i, kk, okk, with_pool,
@@ -961,12 +977,13 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
           const int i = s.rec_i[r];
           const int k = kbase + kk;
           uint32_t up[4], lo[4];
-          philox_block(row_lo, (uint32_t)(i >> 2), row_hi, (uint32_t)(k >> 1), p.seed_lo, p.seed_hi, up);
-          philox_block(row_lo, (uint32_t)(i >> 2), row_hi, (uint32_t)(k >> 1) | kLowBlock, p.seed_lo, p.seed_hi, lo);
+          const int kr = same_race ? 0 : k;  // the draft whose race times this one uses
+          philox_block(row_lo, (uint32_t)(i >> 2), row_hi, (uint32_t)(kr >> 1), p.seed_lo, p.seed_hi, up);
+          philox_block(row_lo, (uint32_t)(i >> 2), row_hi, (uint32_t)(kr >> 1) | kLowBlock, p.seed_lo, p.seed_hi, lo);
           const int j = i & 3;
           const uint32_t uw = j == 0 ? up[0] : j == 1 ? up[1] : j == 2 ? up[2] : up[3];
           const uint32_t lw = j == 0 ? lo[0] : j == 1 ? lo[1] : j == 2 ? lo[2] : lo[3];
-          const double S = exact_race_time(element_word(uw, lw, k & 1));
+          const double S = exact_race_time(element_word(uw, lw, kr & 1));
           float temp = Tq;
           float v;
           if (pool) {
@@ -1018,8 +1035,9 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         load4<T>(drow0 + (SHARED ? 0 : (long long)k * p.draft_stride_k), g * 4, V, false, fill, vd);
         if (draft_masked) mask_bins(no_draft ? 0u : load_bins4(brow, g * 4, V, bins_aligned), announced, fill, vd);
         uint32_t up[4], lo[4];
-        philox_block(row_lo, (uint32_t)g, row_hi, (uint32_t)(k >> 1), p.seed_lo, p.seed_hi, up);
-        philox_block(row_lo, (uint32_t)g, row_hi, (uint32_t)(k >> 1) | kLowBlock, p.seed_lo, p.seed_hi, lo);
+        const int kr = same_race ? 0 : k;
+        philox_block(row_lo, (uint32_t)g, row_hi, (uint32_t)(kr >> 1), p.seed_lo, p.seed_hi, up);
+        philox_block(row_lo, (uint32_t)g, row_hi, (uint32_t)(kr >> 1) | kLowBlock, p.seed_lo, p.seed_hi, lo);
         const float tk = p.temp_draft != nullptr ? p.temp_draft[k] : p.temp_draft_all;
         const bool ok = (tk > 0.0f) && (tk < __builtin_huge_valf());
         double bx = __builtin_huge_val();
@@ -1028,7 +1046,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         for (int j = 0; j < 4; ++j) {
           const int i = g * 4 + j;
           if (i >= V) continue;
-          const double S = exact_race_time(element_word(up[j], lo[j], k & 1));
+          const double S = exact_race_time(element_word(up[j], lo[j], kr & 1));
           const double kx = ok ? exact_key<PROBS>(S, vd[j], (double)tk) : __builtin_huge_val();
           const double ky = with_pool ? exact_key<PROBS>(S, vq[j], (double)Tq) : __builtin_huge_val();
           my_exact += 2;
@@ -1177,7 +1195,7 @@ hipError_t launch_scan(int kt, bool probs, unsigned grid, hipStream_t st, const 
 #define LLC_LAUNCH(KB_, PR_, MK_, LS_)                                                                  \
   hipLaunchKernelGGL((scan_kernel<T, KB_, SHARED, PR_, MK_, LS_>), dim3(grid), dim3(kBlock), 0, st, p); \
   return hipGetLastError();
-  const bool masked = p.bins != nullptr || p.no_draft != 0;
+  const bool masked = p.bins != nullptr || p.no_draft != 0 || p.same_race != 0;
   if (p.lse_part != nullptr) {
     // fused normalisers: per-draft layout, logit kinds, no bins
     if constexpr (!SHARED) {

@@ -124,9 +124,11 @@ def make(cfg: int, device="cpu", rows: Optional[int] = None) -> Workload:
         var_d = 1.0 - rho * rho / (1.0 + s2)
         for l in range(K):
             dec[:, l, :] = log_ratio(u, rho * y[:, l:l + 1] / (1.0 + s2), var_d)
+        # (in the paper's parametrisation W / rho = A + eta: var of W/rho given A is (1 - rho^2) / rho^2)
         return Workload("is_n65536_l4_f32", 5, B, K, V, torch.float32, "logw", dec, enc,
                         1.0, 1.0, seed, shared_draft=False,
-                        extra={"x": x, "y": y, "u": u})
+                        extra={"x": x, "y": y, "u": u, "rho": rho, "var_t_given_a": s2,
+                               "var_w_given_a": (1.0 - rho * rho) / (rho * rho)})
     raise ValueError(f"unknown config {cfg}")
 
 
@@ -253,3 +255,52 @@ def make_topm(name: str, device="cpu", rows: Optional[int] = None) -> TopmWorklo
                         d_ids.to(torch.int32).contiguous(), d_val.to(dt).contiguous(),
                         t_ids.to(torch.int32).contiguous(), t_val.to(dt).contiguous(),
                         1.0, 1.0, SAMPLER_SEED_BASE + 80)
+
+
+@dataclass
+class GaussianSource:
+    """Inputs of the compression scheme on the synthetic Gaussian source (Section 5.3, Appendix D.2)."""
+    name: str
+    B: int                         # trials
+    K: int                         # decoders
+    N: int                         # prior samples
+    l_max: int
+    var_w_given_a: float
+    var_t_given_a: float
+    a: torch.Tensor                # [B] source samples A ~ N(0, 1)
+    t: torch.Tensor                # [B,K] side information T_k = A + N(0, var_t_given_a)
+    u: torch.Tensor                # [B,N] candidates U_i ~ p_W = N(0, 1 + var_w_given_a)
+    bins: torch.Tensor             # [B,N] uint8, uniform on 0..l_max-1
+    logw_enc: torch.Tensor         # [B,N]   ln p_{W|A}(U_i|a) - ln p_W(U_i)
+    logw_dec: torch.Tensor         # [B,K,N] ln p_{W|T}(U_i|t_k) - ln p_W(U_i)
+    seed: int = 0
+
+
+def make_gaussian_source(trials: int, K: int, l_max: int, var_w_given_a: float, device="cpu", *,
+                         N: int = 1 << 15, var_t_given_a: float = 0.5, input_seed: int = 0) -> GaussianSource:
+    """The synthetic Gaussian source of Appendix D.2 with the appendix's own parametrisation:
+    W = A + eta, T_k = A + zeta_k; p_{W|T}(.|t) = N(t / var T, var W - 1 / var T).  Only inputs are
+    drawn and the log-weights formed (the importance weights of Appendix C are the caller's); the
+    selection, the decoders' outputs and the distortion are the library's."""
+    device = torch.device(device)
+    g = torch.Generator(device=device)
+    g.manual_seed(INPUT_SEED_BASE + 300 + input_seed)
+    s_e, s_z = float(var_w_given_a), float(var_t_given_a)
+    var_w, var_t = 1.0 + s_e, 1.0 + s_z
+    var_wt = var_w - 1.0 / var_t
+    a = torch.randn(trials, generator=g, device=device)
+    t = a[:, None] + math.sqrt(s_z) * torch.randn(trials, K, generator=g, device=device)
+    u = math.sqrt(var_w) * torch.randn(trials, N, generator=g, device=device)
+    bins = torch.randint(0, l_max, (trials, N), generator=g, device=device, dtype=torch.uint8)
+
+    def log_ratio(mean, var):
+        # ln N(u; mean, var) - ln N(u; 0, var_w), in fp64, rounded once to fp32
+        u64 = u.double()
+        return (-0.5 * math.log(var / var_w) - 0.5 * (u64 - mean) ** 2 / var + 0.5 * u64 ** 2 / var_w).float()
+
+    enc = log_ratio(a.double()[:, None], s_e)
+    dec = torch.empty(trials, K, N, dtype=torch.float32, device=device)
+    for k in range(K):
+        dec[:, k] = log_ratio(t.double()[:, k:k + 1] / var_t, var_wt)
+    return GaussianSource(f"gaussian_source_k{K}_lmax{l_max}_n{N}", trials, K, N, l_max, s_e, s_z,
+                          a, t, u, bins, enc, dec, SAMPLER_SEED_BASE + 96)

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(binding.EXPORTS)
     for name in names:
         assert getattr(lib, name) is not None
-    assert llc.llc_version() == 107
+    assert llc.llc_version() == 108
     assert llc.llc_status_string(0) == "ok"
     assert "workspace" in llc.llc_status_string(-6)
 

@@ -5,6 +5,7 @@ import pytest
 import torch
 
 import oracle
+from oracle import compress as oracle_compress
 import paper_2506_05632_amd as llc
 from paper_2506_05632_amd import workloads
 from parity_util import KEY_RTOL, NEAR_TIE, oracle_borderline, oracle_near_ties, stats_dict
@@ -130,3 +131,97 @@ def test_compress_select_config5_with_bins_full():
           f"match rate {gpu['accept'].float().mean().item():.3f}")
     assert s["slow_blocks"] == 0
     assert abs(s["near_ties"] - near_oracle) <= borderline and near_oracle <= 2 and excused <= near_oracle
+
+
+# ------------------------------------------------------------------ the baseline scheme and the decoders' outputs
+@pytest.mark.parametrize("B,L,N,l_max", [(40, 4, 5000, 8), (9, 1, 1023, 2), (6, 7, 4099, 64), (25, 3, 3000, 1)])
+def test_shared_race_times_baseline_matches_the_oracle(B, L, N, l_max):
+    # Section 5.3's baseline: all decoders (and the encoder's pool) use the first set of race times
+    enc, dec, bins = _case(B, L, N, l_max, seed=B * 7 + L)
+    ref = oracle.compress_select(enc.cpu().numpy(), dec.cpu().numpy(), bins.cpu().numpy(), seed=4,
+                                 row_offset=(1 << 34) + 5, shared_race=True)
+    base = None
+    for kw in (dict(), dict(v_chunks=3, k_tile=2), dict(k_tile=8), dict(flags=llc.FLAG_EXACT_SCAN)):
+        stats = llc.new_stats(DEV)
+        gpu = llc.llc_compress_select(enc, dec, bins, seed=4, row_offset=(1 << 34) + 5, want_keys=True,
+                                      shared_race=True, stats=stats, **kw)
+        torch.cuda.synchronize()
+        compare_select(gpu, ref)
+        assert abs(stats_dict(stats)["near_ties"] - oracle_near_ties(ref)) <= oracle_borderline(ref)
+        if base is None:
+            base = gpu
+        else:
+            for name in ("X", "Y", "message", "accept", "match_k"):
+                assert torch.equal(base[name], gpu[name]), name
+    if L > 1:
+        # a different scheme, not a relabelling: with their own race times the decoders answer differently
+        own = llc.llc_compress_select(enc, dec, bins, seed=4, row_offset=(1 << 34) + 5)
+        assert not torch.equal(own["X"], base["X"])
+        # with one shared set, decoders that hold the same weights give the same answer
+        same = dec[:, :1].expand(B, L, N)
+        g2 = llc.llc_compress_select(enc, same, bins, seed=4, shared_race=True)
+        assert (g2["X"] == g2["X"][:, :1]).all()
+
+
+@pytest.mark.parametrize("shared", [False, True])
+def test_gaussian_source_end_to_end_on_the_device(shared):
+    """Appendix D.2's experiment, K = 2 decoders, one bit: selection, decoder outputs W_k, MMSE
+    estimates and the best squared error all on the device, against the oracle element by element
+    on the same inputs, and the distortion in dB against the value the paper prints."""
+    K, l_max, s_e = 2, 2, 0.010
+    w = workloads.make_gaussian_source(2048, K, l_max, s_e, DEV)
+    gpu = llc.llc_compress_select(w.logw_enc, w.logw_dec, w.bins, seed=w.seed, shared_race=shared,
+                                  cand=w.u, side=w.t, source=w.a, var_w_given_a=w.var_w_given_a,
+                                  var_t_given_a=w.var_t_given_a)
+    torch.cuda.synchronize()
+    ref = oracle.compress_select(w.logw_enc.cpu().numpy(), w.logw_dec.cpu().numpy(), w.bins.cpu().numpy(),
+                                 seed=w.seed, shared_race=shared)
+    compare_select(gpu, ref)
+    ok = (gpu["X"].cpu().numpy() == ref["X"]).all(axis=1)            # (rows without an excused near-tie)
+    assert ok.mean() > 0.999
+    u, t, a = w.u.cpu().numpy(), w.t.cpu().numpy().astype(np.float64), w.a.cpu().numpy().astype(np.float64)
+    w_ref, a_hat = oracle_compress.decode(u, ref["X"], t, np.float32(s_e).astype(np.float64),
+                                          np.float32(w.var_t_given_a).astype(np.float64))
+    err = oracle_compress.best_squared_error(a_hat, a)
+    np.testing.assert_array_equal(gpu["W"].cpu().numpy()[ok], w_ref[ok].astype(np.float32))
+    np.testing.assert_allclose(gpu["A_hat"].cpu().numpy()[ok], a_hat[ok], rtol=1e-6, atol=1e-9)
+    np.testing.assert_allclose(gpu["sq_err"].cpu().numpy()[ok], err[ok], rtol=1e-5, atol=1e-12)
+    # the paper's figure for this row (tests/golden/gaussian_source_distortion_db.txt)
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "gaussian_source_distortion_db.txt")
+    want = [l.split() for l in open(path) if l.split() and l.split()[0] == ("baseline" if shared else "gls")
+            and l.split()[1:3] == [str(K), str(l_max)]][0]
+    db = 10.0 * np.log10(gpu["sq_err"].double().cpu().numpy())
+    mean, se = db.mean(), db.std(ddof=1) / np.sqrt(len(db))
+    print(f"gaussian source ({'baseline' if shared else 'scheme'}) K={K} Lmax={l_max}: {mean:.3f} +- {se:.3f} dB, "
+          f"paper {want[4]} dB, match rate {gpu['accept'].float().mean().item():.3f}")
+    assert abs(mean - float(want[4])) < 3.0 * np.hypot(se, float(want[5]))
+
+
+def test_decoder_outputs_edge_cases():
+    # a decoder without a candidate gives NaN and stays out of the minimum; W alone needs no side information
+    B, L, N = 5, 3, 2050
+    enc, dec, bins = _case(B, L, N, 4, seed=17)
+    dec = dec.clone()
+    dec[1, 2, :] = float("-inf")
+    dec[3] = float("-inf")
+    g = torch.Generator(device=DEV).manual_seed(18)
+    cand = torch.randn(B, N, generator=g, device=DEV)
+    side = torch.randn(B, L, generator=g, device=DEV)
+    src = torch.randn(B, generator=g, device=DEV)
+    out = llc.llc_compress_select(enc, dec, bins, seed=2, cand=cand, side=side, source=src,
+                                  var_w_given_a=0.05, var_t_given_a=0.5)
+    torch.cuda.synchronize()
+    X = out["X"]
+    assert X[1, 2].item() == -1 and (X[3] == -1).all()
+    assert torch.isnan(out["W"][1, 2]) and torch.isnan(out["A_hat"][1, 2]) and torch.isinf(out["sq_err"][3])
+    w_ref, a_hat = oracle_compress.decode(cand.cpu().numpy(), X.cpu().numpy(), side.cpu().numpy().astype(np.float64),
+                                          float(np.float32(0.05)), 0.5)
+    err = oracle_compress.best_squared_error(a_hat, src.cpu().numpy().astype(np.float64))
+    np.testing.assert_allclose(out["A_hat"].cpu().numpy(), a_hat, rtol=1e-6, equal_nan=True)
+    np.testing.assert_allclose(out["sq_err"].cpu().numpy(), err, rtol=1e-5)
+    only_w = llc.llc_compress_select(enc, dec, bins, seed=2, cand=cand)
+    assert torch.equal(only_w["W"].nan_to_num(7.0), out["W"].nan_to_num(7.0)) and "A_hat" not in only_w
+    with pytest.raises(llc.LlcError) as e:
+        llc.llc_compress_select(enc, dec, bins, cand=cand, side=side, source=src, var_w_given_a=0.0, var_t_given_a=0.5)
+    assert e.value.code == -8
