@@ -223,14 +223,15 @@ int launch_scan_job(const ScanJob &j, const ScanPlan &plan, Partials *partials, 
   part.secY = (double *)(ws + lay.secY);
   part.lse = (double *)(ws + (j.lse_in_extra == (size_t)-1 ? lay.lse : extra_off + j.lse_in_extra));
 
-  // Row normalisers: with per-draft rows the scan forms them on its way (no second pass over the
-  // inputs); the shared layout and the binned passes use the normaliser kernel.
+  // Row normalisers: the scan forms them on its way (no second pass over the inputs): the draft
+  // rows' always, the target row's too when one proposal serves all drafts (the workgroup then
+  // reads two rows in all); the binned passes, and the target row beside per-draft rows, use the
+  // normaliser kernel.
   const bool masked = j.bins != nullptr || j.no_draft || j.same_race;
-  const bool fused_lse = j.need_lse && j.kind != LLC_PROBS && !shared && !masked;
+  const bool fused_lse = j.need_lse && j.kind != LLC_PROBS && !masked;
   part.lse_part = fused_lse ? (double *)(ws + lay.lse_part) : nullptr;
-  // (the target row's normaliser always comes from the normaliser kernel, so that keyY does not
-  // depend on how the drafts are laid out)
-  if (j.need_lse && j.kind != LLC_PROBS && (!fused_lse || !j.no_pool)) {
+  part.lse_part_target = (fused_lse && shared && !j.no_pool) ? 1 : 0;
+  if (j.need_lse && j.kind != LLC_PROBS && (!fused_lse || (!j.no_pool && !part.lse_part_target))) {
     LseParams lp;
     lp.draft = j.draft; lp.target = j.target;
     lp.map = j.map; lp.draft_stride_k = j.draft_stride_k;

@@ -24,6 +24,7 @@ struct Partials {
   double *secY;   // [B][n_kgroups][n_chunks] winner's (+inf if none was seen within the band)
   double *lse;    // [B][K+1]: ln sum exp(x/T) of draft k (k < K) and of the target (k == K)
   double *lse_part;  // [B][K+1][n_chunks] per-chunk shares to merge into lse first, or nullptr
+  int lse_part_target;  // the shares include the target row's (slot K); else lse[.][K] is in place
 };
 
 // Rows may be a two-level index b = outer * inner_count + inner (sequences x positions in

@@ -39,7 +39,8 @@ __global__ void __launch_bounds__(64) finalize_kernel(const FinalizeParams p) {
   if (p.cand != nullptr) __syncthreads();
   if (p.in.lse_part != nullptr) {
     // the scan left every chunk's share of the normalisers: ln sum_chunks exp(share)
-    for (int k = tid; k < p.K; k += 64) {  // (the target's normaliser is already in place)
+    // (without lse_part_target the target's normaliser is already in place)
+    for (int k = tid; k < p.K + (p.in.lse_part_target ? 1 : 0); k += 64) {
       const double *sh = p.in.lse_part + (b * (p.K + 1) + k) * p.n_chunks;
       double m = -__builtin_huge_val();
       for (int c = 0; c < p.n_chunks; ++c) m = fmax(m, sh[c]);

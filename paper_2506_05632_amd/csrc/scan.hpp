@@ -282,6 +282,19 @@ __device__ __forceinline__ float level1_value(float v) {
   return PROBS ? (float)__float_as_int(v) : v;
 }
 
+// The largest of four values' contributions to the level-1 exponent (NaN entries are ignored:
+// they carry no mass; for probabilities the integer images are compared, a NaN's is large and only
+// sends the lane to the survivors' path, which drops it).
+template <bool PROBS>
+__device__ __forceinline__ float level1_max4(const float (&v)[4]) {
+  if (PROBS) {
+    const int a = max(__float_as_int(v[0]), __float_as_int(v[1]));
+    const int b = max(__float_as_int(v[2]), __float_as_int(v[3]));
+    return (float)max(a, b);
+  }
+  return fmaxf(fmaxf(fmaxf(v[0], v[1]), v[2]), v[3]);
+}
+
 // log2 of the unnormalised probability an input value stands for; false if it carries no mass.
 template <bool PROBS>
 __device__ __forceinline__ bool approx_log2_mass(float v, float c, float &ell) {
@@ -565,7 +578,9 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
   const float cq23 = PROBS ? 1.0f : cq * kTwo23;
   // LSE: log2(e)/T of every slot as a two-float sum (no systematic rounding of 1/T in the exponent)
   float lse_hi[KT + 1], lse_lo[KT + 1];
-  const bool lse_target = false;  // the target row's normaliser is left to the normaliser kernel
+  // With one shared proposal the scan also forms the target row's normaliser (two rows per
+  // workgroup in all); with per-draft rows it is left to the normaliser kernel.
+  const bool lse_target = SHARED && with_pool;
   if (LSE) {
 #pragma unroll
     for (int kk = 0; kk <= KT; ++kk) {
@@ -579,10 +594,13 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
   bool lse_ran = false;  // the main loop (which feeds the sums) was executed
   // LSE: per lane and slot the largest value seen so far and the sum of exp((x - that)/T): the
   // terms that matter then have small exponents, where fp32 arithmetic is accurate enough
-  double lse_acc[LSE ? KT + 1 : 1];
-  float lse_m[LSE ? KT + 1 : 1];
+  // (with one shared proposal only two rows are summed: slot 0 for the drafts, slot KT for the target)
+  constexpr int NL = LSE ? (SHARED ? 2 : KT + 1) : 1;
+  auto lidx = [](const int slot) { return LSE ? (SHARED ? (slot == KT ? 1 : 0) : slot) : 0; };
+  double lse_acc[NL];
+  float lse_m[NL];
 #pragma unroll
-  for (int kk = 0; kk < (LSE ? KT + 1 : 1); ++kk) { lse_acc[kk] = 0.0; lse_m[kk] = -__builtin_huge_valf(); }
+  for (int kk = 0; kk < NL; ++kk) { lse_acc[kk] = 0.0; lse_m[kk] = -__builtin_huge_valf(); }
 
   if (tid < 9) {
     // unused draft slots sit at -inf so the shared layout's max over drafts ignores them
@@ -731,7 +749,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
       // value so far (the sum is rescaled when that moves): fp32 terms, four at a time, into the
       // fp64 sum.  NaN and +inf entries carry no mass.
       auto lse_add = [&](const int slot, const float (&v)[4]) {
-        const int sl = LSE ? slot : 0;
+        const int sl = lidx(slot);
         float w[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) w[j] = v[j] < __builtin_huge_valf() ? v[j] : -__builtin_huge_valf();
@@ -772,35 +790,40 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         }
 
         // The main loop works with exponents lowered by 32 (kShift32): see packed_hi16.
+        // One threshold serves the lane's four indices: that of the largest of the four values (the
+        // exponent grows with the value), so a half-word that passes its own index's threshold also
+        // passes this one; the survivors' path below tests every element against its own.
         const float OY = load_offset(&s.OL[KT]);  // (-inf without a pool)
-        float FY[4];
+        float FY;
         {
           float vq[4];
           unpack(rq, vq);  // (without a pool the tile's target part keeps its initial zeros, and OY is -inf)
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            FY[j] = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vq[j]), cq23, OY), 0.0f, kCapOne32);
+          FY = fmaf(level1_max4<PROBS>(vq), cq23, OY);
           if (LSE && lse_target) lse_add(KT, vq);
         }
 
-        // A half-word h passes its threshold th iff h + th >= 0xFFFF, i.e. iff the saturating sum
-        // is 0xFFFF; the largest sum of the tile is kept and looked at once.
+        // A half-word h passes the threshold th iff h + th >= 0xFFFF, i.e. iff the saturating sum
+        // is 0xFFFF: the largest half-words of the tile are found first, then tested once.
         uint32_t most = 0u;
         if (SHARED) {
-          // one threshold per index serves every draft: any_k (h_k > c) == (max_k h_k > c)
+          // the threshold also serves every draft (it is built from the loosest of their bounds):
+          // any (h > c) == (max h > c) over the tile's 8 KB half-words
           const float OX = load_offset(&s.OL[0]);
           float vd[4];
           unpack(rd[0], vd);
           if (draft_masked) mask_bins(rb, announced, fill, vd);
+          if (LSE) lse_add(0, vd);  // (one row stands for all drafts: slot 0)
+          const float FX = fmaf(level1_max4<PROBS>(vd), cd23[0], OX);
+          const float F = __builtin_amdgcn_fmed3f(fmaxf(FX, FY), 0.0f, kCapOne32);
+          uint32_t mx = up[0][0];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const float F = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(vd[j]), cd23[0], OX), FY[j], kCapOne32);
-            uint32_t mx = up[0][j];
+          for (int m = 0; m < KB; ++m)
 #pragma unroll
-            for (int m = 1; m < KB; ++m) mx = pk_max_u16(mx, up[m][j]);
-            most = pk_max_u16(most, pk_add_sat_u16(mx, packed_hi16(F, F)));
-          }
+            for (int j = 0; j < 4; ++j)
+              if (m + j > 0) mx = pk_max_u16(mx, up[m][j]);
+          most = pk_add_sat_u16(mx, packed_hi16(F, F));
         } else {
+          const float FYc = __builtin_amdgcn_fmed3f(FY, 0.0f, kCapOne32);
 #pragma unroll
           for (int m = 0; m < KB; ++m) {
             const float OX0 = load_offset(&s.OL[2 * m]);  // (-inf for a draft that is not taken)
@@ -810,12 +833,10 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             unpack(rd[SHARED ? 0 : 2 * m + 1], v1);
             if (draft_masked) { mask_bins(rb, announced, fill, v0); mask_bins(rb, announced, fill, v1); }
             if (LSE) { lse_add(2 * m, v0); lse_add(2 * m + 1, v1); }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const float F0 = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(v0[j]), cd23[2 * m], OX0), FY[j], kCapOne32);
-              const float F1 = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(v1[j]), cd23[2 * m + 1], OX1), FY[j], kCapOne32);
-              most = pk_max_u16(most, pk_add_sat_u16(up[m][j], packed_hi16(F0, F1)));
-            }
+            const float F0 = __builtin_amdgcn_fmed3f(fmaf(level1_max4<PROBS>(v0), cd23[2 * m], OX0), FYc, kCapOne32);
+            const float F1 = __builtin_amdgcn_fmed3f(fmaf(level1_max4<PROBS>(v1), cd23[2 * m + 1], OX1), FYc, kCapOne32);
+            const uint32_t mx = pk_max_u16(pk_max_u16(up[m][0], up[m][1]), pk_max_u16(up[m][2], up[m][3]));
+            most = pk_max_u16(most, pk_add_sat_u16(mx, packed_hi16(F0, F1)));
           }
         }
         // Rare (about one wave and tile in ten): some lane has a half-word that passed, or a hot
@@ -1095,20 +1116,23 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
     const int wv = tid >> 6;
 #pragma unroll
     for (int kk = 0; kk <= KT; ++kk) {
+      if (SHARED && kk != 0 && kk != KT) continue;
       // bring the lanes' sums to the wave's largest value (exactly, in fp64), then add them up
-      const float m = lse_m[LSE ? kk : 0];
+      const float m = lse_m[lidx(kk)];
       float wm = m;
 #pragma unroll
       for (int d = 32; d >= 1; d >>= 1) wm = fmaxf(wm, __shfl_xor(wm, d));
       double v = 0.0;
       if (m > -__builtin_huge_valf())
-        v = lse_acc[LSE ? kk : 0] * exp2(((double)m - (double)wm) * ((double)lse_hi[kk] + (double)lse_lo[kk]));
+        v = lse_acc[lidx(kk)] * exp2(((double)m - (double)wm) * ((double)lse_hi[kk] + (double)lse_lo[kk]));
 #pragma unroll
       for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
       if ((tid & 63) == 0) { s.lse_wave[wv][kk] = v; s.lse_wmax[wv][kk] = wm; }
     }
     __syncthreads();
     const bool slot_used = tid < KT ? (kbase + tid < p.K) : (tid == KT && lse_target);
+    // the slot whose sums this thread reports: with one shared proposal slot 0 stands for every draft
+    const int from = SHARED ? (tid < KT ? 0 : KT) : tid;
     double share = -__builtin_huge_val();
     if (tid <= KT && slot_used) {
       float tk = tid == KT ? Tq : p.temp_draft_all;
@@ -1121,11 +1145,11 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
       } else {
         const double c64 = 1.4426950408889634 / (double)tk;
         float gm = -__builtin_huge_valf();
-        for (int w = 0; w < 4; ++w) gm = fmaxf(gm, s.lse_wmax[w][tid]);
+        for (int w = 0; w < 4; ++w) gm = fmaxf(gm, s.lse_wmax[w][from]);
         double tot = 0.0;
         for (int w = 0; w < 4; ++w)
-          if (s.lse_wmax[w][tid] > -__builtin_huge_valf())
-            tot += s.lse_wave[w][tid] * exp2(((double)s.lse_wmax[w][tid] - (double)gm) * c64);
+          if (s.lse_wmax[w][from] > -__builtin_huge_valf())
+            tot += s.lse_wave[w][from] * exp2(((double)s.lse_wmax[w][from] - (double)gm) * c64);
         if (!(gm > -__builtin_huge_valf())) {
           share = -__builtin_huge_val();   // no entry of the chunk carries mass
         } else if (!(tot >= 1.0 && tot < __builtin_huge_val())) {
@@ -1141,13 +1165,13 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
       double *s_sum = &s.lse_wave[0][0];
 #pragma unroll 1
       for (int kk = 0; kk <= KT; ++kk) {
-        const bool used = kk < KT ? (kbase + kk < p.K) : lse_target;
+        const bool used = kk < KT ? (SHARED ? kk == 0 : kbase + kk < p.K) : lse_target;
         if (!used) continue;  // uniform
         float tk = kk == KT ? Tq : p.temp_draft_all;
         if (kk < KT && p.temp_draft != nullptr) tk = p.temp_draft[kbase + kk];
-        const elem *rowp = kk == KT ? trow : drow0 + (long long)(kbase + kk) * p.draft_stride_k;
+        const elem *rowp = kk == KT ? trow : drow0 + (SHARED ? 0 : (long long)(kbase + kk) * p.draft_stride_k);
         const double v = chunk_lse_exact<T>(rowp, g_begin, g_end, V, (double)tk, s_max, s_sum);
-        if (tid == kk) share = v;
+        if (from == kk) share = v;
       }
     }
     if (tid <= KT && slot_used) {
@@ -1197,14 +1221,12 @@ hipError_t launch_scan(int kt, bool probs, unsigned grid, hipStream_t st, const 
   return hipGetLastError();
   const bool masked = p.bins != nullptr || p.no_draft != 0 || p.same_race != 0;
   if (p.lse_part != nullptr) {
-    // fused normalisers: per-draft layout, logit kinds, no bins
-    if constexpr (!SHARED) {
-      if (probs || masked) return hipErrorInvalidValue;
-      switch (kt) {
-        case 2: LLC_LAUNCH(1, false, false, true)
-        case 4: LLC_LAUNCH(2, false, false, true)
-        case 8: LLC_LAUNCH(4, false, false, true)
-      }
+    // fused normalisers: logit kinds, no bins
+    if (probs || masked) return hipErrorInvalidValue;
+    switch (kt) {
+      case 2: LLC_LAUNCH(1, false, false, true)
+      case 4: LLC_LAUNCH(2, false, false, true)
+      case 8: LLC_LAUNCH(4, false, false, true)
     }
     return hipErrorInvalidValue;
   }

@@ -88,5 +88,11 @@ def stats_dict(stats: torch.Tensor) -> dict:
 
 
 def same_outputs(a: dict, b: dict):
+    """Indices and flags bit for bit.  Reported keys carry the rows' normalisers, which the scan
+    sums chunk by chunk: their last bits may depend on the launch shape (far inside the 1e-6 that
+    keys are held to)."""
     for name in a:
-        assert torch.equal(a[name], b[name]), name
+        if name.startswith("key"):
+            torch.testing.assert_close(a[name], b[name], rtol=1e-6, atol=0)
+        else:
+            assert torch.equal(a[name], b[name]), name

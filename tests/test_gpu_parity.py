@@ -332,7 +332,10 @@ def test_target_sample_ignores_the_drafts():
     a = llc.llc_couple(torch.randn(B, V, generator=g, device=DEV), tq, K, seed=3, want_keys=True)
     b = llc.llc_couple(5 * torch.randn(B, K, V, generator=g, device=DEV), tq, K, seed=3, want_keys=True,
                        temp_draft=3.0)
-    assert torch.equal(a["Y"], b["Y"]) and torch.equal(a["keyY"], b["keyY"])
+    assert torch.equal(a["Y"], b["Y"])
+    # (the target row's normaliser is summed by different kernels for the two draft layouts: the
+    # reported key may differ in its last bits, far inside the 1e-6 that keys are held to)
+    torch.testing.assert_close(a["keyY"], b["keyY"], rtol=1e-6, atol=0)
 
 
 def test_extreme_logits_fall_back_to_the_exact_scan():
