@@ -12,17 +12,17 @@ SRC = os.path.join(HERE, "llc_ref.cpp")
 LIB = os.path.join(HERE, "libllc_ref.so")
 
 
-def build(force: bool = False, sanitize: bool = False) -> str:
-    out = LIB if not sanitize else os.path.join(HERE, "libllc_ref_asan.so")
+def build(force: bool = False) -> str:
+    """(The sanitizer build of the same source is tests/asan_driver.cpp, run by
+    tests/test_oracle_sanitizers.py.)"""
+    out = LIB
     if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(SRC):
         return out
     cmd = ["g++", "-std=c++17", "-O2", "-fno-fast-math", "-ffp-contract=off", "-fopenmp",
            "-shared", "-fPIC", "-Wall", "-Wextra", SRC, "-o", out]
-    if sanitize:
-        cmd[4:4] = ["-g", "-fsanitize=address,undefined", "-fno-omit-frame-pointer"]
     subprocess.run(cmd, check=True)
     return out
 
 
 if __name__ == "__main__":
-    print(build(force=True, sanitize="--asan" in sys.argv))
+    print(build(force=True))
