@@ -132,6 +132,8 @@ struct ScanJob {
   size_t lse_in_extra = (size_t)-1;  // keep the normalisers at this offset of the caller's region
   size_t extra_at = (size_t)-1;      // where the caller's region starts (default: right behind the partials)
   int32_t *tau_ready = nullptr;      // the rows' shared running bests, already reset, if not in the workspace
+  const FinalizeParams *fin = nullptr;  // if given, the scan may take the finalize step itself (plain
+                                     // scans only); `in`, n_chunks and n_kgroups are filled in here
   int flags, v_chunks, k_tile;
   llc_stats *stats;
   void *workspace;
@@ -201,7 +203,8 @@ bool workspace_ok(const ScanJob &j, const ScanPlan &sp) {
 
 // Carves the workspace and enqueues the normaliser pass (if asked) and the scan kernel of a
 // planned job whose workspace has been checked.  *extra (if given) receives the caller's region.
-int launch_scan_job(const ScanJob &j, const ScanPlan &plan, Partials *partials, char **extra) {
+int launch_scan_job(const ScanJob &j, const ScanPlan &plan, Partials *partials, char **extra,
+                    bool *finished = nullptr) {
   const Plan &pl = plan.pl;
   const Layout &lay = plan.lay;
   const bool shared = plan.shared, vec = plan.vec;
@@ -250,6 +253,15 @@ int launch_scan_job(const ScanJob &j, const ScanPlan &plan, Partials *partials, 
     if (launch_lse(st, lp) != hipSuccess) return LLC_E_LAUNCH;
   }
 
+  // Where every row is one workgroup, a plain scan (no bins, no normalisers to merge) takes the
+  // finalize step itself: one launch less.  (For rows spread over several workgroups the same was
+  // tried with a ticket per row, the last workgroup finishing the row: publishing the partial
+  // results needs either device-scope fences, which write back and invalidate an XCD's whole L2
+  // and doubled the scan's time, or write-through stores and reads, whose latency at the end of
+  // the launch cost more than the finalize launch they saved.)
+  const bool finish = j.fin != nullptr && !masked && !fused_lse && pl.n_chunks * pl.n_kgroups == 1;
+  if (finished != nullptr) *finished = finish;
+
   // a row spread over several workgroups shares its running bests through the workspace
   int32_t *shared_tau = nullptr;
   if (pl.n_chunks * pl.n_kgroups > 1) {
@@ -282,17 +294,25 @@ int launch_scan_job(const ScanJob &j, const ScanPlan &plan, Partials *partials, 
   sp.same_race = j.same_race ? 1 : 0;
   sp.out = part;
   sp.stats = j.stats;
+  if (finish) {
+    sp.fin = *j.fin;
+    sp.fin.in = part;
+    sp.fin.n_chunks = pl.n_chunks;
+    sp.fin.n_kgroups = pl.n_kgroups;
+  } else {
+    std::memset(&sp.fin, 0, sizeof(sp.fin));
+  }
 
   const bool probs = j.kind == LLC_PROBS;
   if (j.ev_begin != nullptr && hipEventRecord((hipEvent_t)j.ev_begin, st) != hipSuccess)
     return LLC_E_LAUNCH;
   hipError_t e;
   if (j.dtype == LLC_F32)
-    e = shared ? launch_scan_f32_shared(pl.kt, probs, (unsigned)blocks, st, sp)
-               : launch_scan_f32_perk(pl.kt, probs, (unsigned)blocks, st, sp);
+    e = shared ? launch_scan_f32_shared(pl.kt, probs, finish, (unsigned)blocks, st, sp)
+               : launch_scan_f32_perk(pl.kt, probs, finish, (unsigned)blocks, st, sp);
   else
-    e = shared ? launch_scan_bf16_shared(pl.kt, probs, (unsigned)blocks, st, sp)
-               : launch_scan_bf16_perk(pl.kt, probs, (unsigned)blocks, st, sp);
+    e = shared ? launch_scan_bf16_shared(pl.kt, probs, finish, (unsigned)blocks, st, sp)
+               : launch_scan_bf16_perk(pl.kt, probs, finish, (unsigned)blocks, st, sp);
   if (e != hipSuccess) return LLC_E_LAUNCH;
   if (j.ev_end != nullptr && hipEventRecord((hipEvent_t)j.ev_end, st) != hipSuccess)
     return LLC_E_LAUNCH;
@@ -301,14 +321,15 @@ int launch_scan_job(const ScanJob &j, const ScanPlan &plan, Partials *partials, 
 }
 
 // Plan, check the workspace, launch.  With the dry-run flag nothing is launched (*dry is set).
-int run_scan(const ScanJob &j, bool dry_run, Plan *plan, Partials *partials, char **extra) {
+int run_scan(const ScanJob &j, bool dry_run, Plan *plan, Partials *partials, char **extra,
+             bool *finished = nullptr) {
   ScanPlan sp;
   const int rc = plan_scan(j, &sp);
   if (rc != LLC_OK) return rc;
   if (!workspace_ok(j, sp)) return LLC_E_WORKSPACE;
   *plan = sp.pl;
   if (dry_run) return LLC_OK;
-  return launch_scan_job(j, sp, partials, extra);
+  return launch_scan_job(j, sp, partials, extra, finished);
 }
 
 }  // namespace
@@ -338,22 +359,26 @@ int couple_on(const llc_couple_args *a, void *workspace, size_t workspace_bytes)
   j.stream = a->stream; j.ev_begin = a->ev_scan_begin; j.ev_end = a->ev_scan_end;
   j.extra_bytes = 0;
 
-  Plan pl;
-  Partials part;
-  const int rc = run_scan(j, dry, &pl, &part, nullptr);
-  if (rc != LLC_OK || dry) return rc;
-
   FinalizeParams fp;
   fp.cand = nullptr; fp.side = nullptr; fp.source = nullptr; fp.W = nullptr; fp.A_hat = nullptr; fp.sq_err = nullptr;
   fp.cand_stride_b = 0; fp.side_stride_b = 0; fp.var_e = 0.0; fp.var_z = 0.0;
-  fp.B = a->B; fp.K = (int)a->K; fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
+  fp.B = a->B; fp.K = (int)a->K; fp.n_chunks = 0; fp.n_kgroups = 0;
   fp.log_kind = a->kind != LLC_PROBS ? 1 : 0;
-  fp.in = part;
+  std::memset(&fp.in, 0, sizeof(fp.in));
   fp.X = a->X; fp.Y = a->Y; fp.match_k = a->match_k; fp.accept = a->accept;
   fp.keyX = a->keyX; fp.keyY = a->keyY; fp.log_keyX = nullptr; fp.log_secX = nullptr;
   fp.y_given = 0; fp.bins = nullptr; fp.bins_stride_b = 0; fp.message = nullptr;
   fp.count_draft = 1; fp.count_pool = 1; fp.count_near = 1;
   fp.stats = a->stats;
+  j.fin = &fp;  // (where it can, the scan finishes the rows itself and no finalize launch follows)
+
+  Plan pl;
+  Partials part;
+  bool finished = false;
+  const int rc = run_scan(j, dry, &pl, &part, nullptr, &finished);
+  if (rc != LLC_OK || dry || finished) return rc;
+  fp.n_chunks = pl.n_chunks; fp.n_kgroups = pl.n_kgroups;
+  fp.in = part;
   if (launch_finalize((hipStream_t)a->stream, fp) != hipSuccess) return LLC_E_LAUNCH;
   return LLC_OK;
 }

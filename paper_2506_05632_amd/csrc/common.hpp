@@ -45,6 +45,36 @@ struct RowMap {
   }
 };
 
+struct FinalizeParams {
+  long long B;
+  int K, n_chunks, n_kgroups;
+  int log_kind;        // keys are in the log domain and need the normaliser
+  Partials in;
+  int32_t *X, *Y, *match_k;  // Y, accept may be null (draft side only)
+  int y_given;               // Y holds the pool's index already: only the accept test is taken
+  const uint8_t *bins;       // optional: message[b] = bin of candidate Y[b]
+  long long bins_stride_b;
+  int32_t *message;
+  uint8_t *accept;
+  float *keyX, *keyY;  // optional
+  double *log_keyX;    // optional [B][K]: ln of the normalised winning key (log kinds)
+  double *log_secX;    // optional [B][K]: the same for the runner-up (another index) of that reduction
+  // optional decoder outputs of the compression scheme (Appendix C, Appendix D.2): W_k = cand[X_k],
+  // the estimate g(W_k, T_k) = (vz W_k + ve T_k) / (ve + vz + ve vz), the best squared error
+  const float *cand;         // [B][V'] candidates U_i, or nullptr
+  long long cand_stride_b;
+  const float *side;         // [B][K] side information T_k
+  long long side_stride_b;
+  const float *source;       // [B] the source sample A (known to an evaluation only), or nullptr
+  double var_e, var_z;       // variance of W given A, of T given A
+  float *W, *A_hat;          // [B][K] optional
+  float *sq_err;             // [B] optional: min_k (g(W_k, T_k) - A)^2
+  int count_draft;     // count the draft side's reductions in stats->degenerate
+  int count_pool;      // count the pool's
+  int count_near;      // also count the near-ties of the sides that are counted
+  llc_stats *stats;
+};
+
 struct ScanParams {
   const void *draft;
   const void *target;
@@ -75,37 +105,11 @@ struct ScanParams {
                             // the ordered image of +inf; nullptr when a row is one workgroup
   Partials out;
   llc_stats *stats;
+  // The variant for rows that are one workgroup each also takes the finalize step, so that no
+  // finalize launch follows.
+  FinalizeParams fin;       // used by that variant only
 };
 
-struct FinalizeParams {
-  long long B;
-  int K, n_chunks, n_kgroups;
-  int log_kind;        // keys are in the log domain and need the normaliser
-  Partials in;
-  int32_t *X, *Y, *match_k;  // Y, accept may be null (draft side only)
-  int y_given;               // Y holds the pool's index already: only the accept test is taken
-  const uint8_t *bins;       // optional: message[b] = bin of candidate Y[b]
-  long long bins_stride_b;
-  int32_t *message;
-  uint8_t *accept;
-  float *keyX, *keyY;  // optional
-  double *log_keyX;    // optional [B][K]: ln of the normalised winning key (log kinds)
-  double *log_secX;    // optional [B][K]: the same for the runner-up (another index) of that reduction
-  // optional decoder outputs of the compression scheme (Appendix C, Appendix D.2): W_k = cand[X_k],
-  // the estimate g(W_k, T_k) = (vz W_k + ve T_k) / (ve + vz + ve vz), the best squared error
-  const float *cand;         // [B][V'] candidates U_i, or nullptr
-  long long cand_stride_b;
-  const float *side;         // [B][K] side information T_k
-  long long side_stride_b;
-  const float *source;       // [B] the source sample A (known to an evaluation only), or nullptr
-  double var_e, var_z;       // variance of W given A, of T given A
-  float *W, *A_hat;          // [B][K] optional
-  float *sq_err;             // [B] optional: min_k (g(W_k, T_k) - A)^2
-  int count_draft;     // count the draft side's reductions in stats->degenerate
-  int count_pool;      // count the pool's
-  int count_near;      // also count the near-ties of the sides that are counted
-  llc_stats *stats;
-};
 
 // Algorithm 2's sequential epilogue over the per-(position, draft) target-side argmins.
 struct VerifyParams {
@@ -218,11 +222,12 @@ struct LmlParams {
 };
 
 // One launcher per (element type, draft layout); defined in scan_*.hip.
-// kt: drafts per workgroup pass (1, 2, 4, 8); probs: inputs are probabilities.
-hipError_t launch_scan_f32_shared(int kt, bool probs, unsigned grid, hipStream_t s, const ScanParams &p);
-hipError_t launch_scan_f32_perk(int kt, bool probs, unsigned grid, hipStream_t s, const ScanParams &p);
-hipError_t launch_scan_bf16_shared(int kt, bool probs, unsigned grid, hipStream_t s, const ScanParams &p);
-hipError_t launch_scan_bf16_perk(int kt, bool probs, unsigned grid, hipStream_t s, const ScanParams &p);
+// kt: drafts per workgroup pass (1, 2, 4, 8); probs: inputs are probabilities; finish: the
+// variant that also takes the finalize step (plain scans only: no bins, no fused normalisers).
+hipError_t launch_scan_f32_shared(int kt, bool probs, bool finish, unsigned grid, hipStream_t s, const ScanParams &p);
+hipError_t launch_scan_f32_perk(int kt, bool probs, bool finish, unsigned grid, hipStream_t s, const ScanParams &p);
+hipError_t launch_scan_bf16_shared(int kt, bool probs, bool finish, unsigned grid, hipStream_t s, const ScanParams &p);
+hipError_t launch_scan_bf16_perk(int kt, bool probs, bool finish, unsigned grid, hipStream_t s, const ScanParams &p);
 
 // llc_couple on a given workspace (api.hip).
 int couple_on(const llc_couple_args *a, void *workspace, size_t workspace_bytes);

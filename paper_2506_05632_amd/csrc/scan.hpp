@@ -30,6 +30,7 @@
 #pragma once
 
 #include "common.hpp"
+#include "finalize_row.hpp"
 
 namespace llc {
 
@@ -484,8 +485,10 @@ __device__ double chunk_lse_exact(const typename T::elem *row, int g_begin, int 
 // MASKED: the variant that knows binned candidates and the pool-only mode (built for fp32
 // log-weights only, which is what the compression scheme uses).
 // LSE: the variant that also accumulates the rows' normalisers ln sum exp(x/T) while it scans
-// them (per-draft layouts of the logit kinds), so that no second pass over the inputs is needed.
-template <typename T, int KB, bool SHARED, bool PROBS, bool MASKED, bool LSE>
+// them (logit kinds), so that no second pass over the inputs is needed.
+// FIN: the variant for rows that are one workgroup each: it also takes the finalize step (Algorithm
+// 1's accept test and the outputs), so that no finalize launch follows.
+template <typename T, int KB, bool SHARED, bool PROBS, bool MASKED, bool LSE, bool FIN>
 __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kernel(const ScanParams p) {
   using elem = typename T::elem;
   constexpr int KT = 2 * KB;
@@ -1211,48 +1214,71 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
       if (exact_all && !p.force_exact) atomicAdd(&p.stats->slow_blocks, 1ull);
     }
   }
+  if (FIN) {
+    // the row is this workgroup's alone (the host launches this variant only then): its partial
+    // results are complete, written by this workgroup's own threads
+    __shared__ FinalizeShared s_fin;
+    __syncthreads();
+    finalize_row<kBlock>(p.fin, b, tid, s_fin);
+  }
 }
 
 // kt: drafts per workgroup pass (2, 4 or 8; 1 runs as 2: a draft pair shares its blocks).
 template <typename T, bool SHARED>
-hipError_t launch_scan(int kt, bool probs, unsigned grid, hipStream_t st, const ScanParams &p) {
-#define LLC_LAUNCH(KB_, PR_, MK_, LS_)                                                                  \
-  hipLaunchKernelGGL((scan_kernel<T, KB_, SHARED, PR_, MK_, LS_>), dim3(grid), dim3(kBlock), 0, st, p); \
+hipError_t launch_scan(int kt, bool probs, bool finish, unsigned grid, hipStream_t st, const ScanParams &p) {
+#define LLC_LAUNCH(KB_, PR_, MK_, LS_, FN_)                                                                  \
+  hipLaunchKernelGGL((scan_kernel<T, KB_, SHARED, PR_, MK_, LS_, FN_>), dim3(grid), dim3(kBlock), 0, st, p); \
   return hipGetLastError();
   const bool masked = p.bins != nullptr || p.no_draft != 0 || p.same_race != 0;
   if (p.lse_part != nullptr) {
     // fused normalisers: logit kinds, no bins
-    if (probs || masked) return hipErrorInvalidValue;
+    if (probs || masked || finish) return hipErrorInvalidValue;
     switch (kt) {
-      case 2: LLC_LAUNCH(1, false, false, true)
-      case 4: LLC_LAUNCH(2, false, false, true)
-      case 8: LLC_LAUNCH(4, false, false, true)
+      case 2: LLC_LAUNCH(1, false, false, true, false)
+      case 4: LLC_LAUNCH(2, false, false, true, false)
+      case 8: LLC_LAUNCH(4, false, false, true, false)
     }
     return hipErrorInvalidValue;
   }
   if (masked) {
     // binned candidates / pool-only passes exist for fp32 log-weights
     if constexpr (sizeof(typename T::elem) == 4) {
-      if (probs) return hipErrorInvalidValue;
+      if (probs || finish) return hipErrorInvalidValue;
       switch (kt) {
-        case 2: LLC_LAUNCH(1, false, true, false)
-        case 4: LLC_LAUNCH(2, false, true, false)
-        case 8: LLC_LAUNCH(4, false, true, false)
+        case 2: LLC_LAUNCH(1, false, true, false, false)
+        case 4: LLC_LAUNCH(2, false, true, false, false)
+        case 8: LLC_LAUNCH(4, false, true, false, false)
       }
     }
     return hipErrorInvalidValue;
   }
   if (!probs) {
-    switch (kt) {
-      case 2: LLC_LAUNCH(1, false, false, false)
-      case 4: LLC_LAUNCH(2, false, false, false)
-      case 8: LLC_LAUNCH(4, false, false, false)
+    if (finish) {
+      switch (kt) {
+        case 2: LLC_LAUNCH(1, false, false, false, true)
+        case 4: LLC_LAUNCH(2, false, false, false, true)
+        case 8: LLC_LAUNCH(4, false, false, false, true)
+      }
+    } else {
+      switch (kt) {
+        case 2: LLC_LAUNCH(1, false, false, false, false)
+        case 4: LLC_LAUNCH(2, false, false, false, false)
+        case 8: LLC_LAUNCH(4, false, false, false, false)
+      }
     }
   } else {
-    switch (kt) {
-      case 2: LLC_LAUNCH(1, true, false, false)
-      case 4: LLC_LAUNCH(2, true, false, false)
-      case 8: LLC_LAUNCH(4, true, false, false)
+    if (finish) {
+      switch (kt) {
+        case 2: LLC_LAUNCH(1, true, false, false, true)
+        case 4: LLC_LAUNCH(2, true, false, false, true)
+        case 8: LLC_LAUNCH(4, true, false, false, true)
+      }
+    } else {
+      switch (kt) {
+        case 2: LLC_LAUNCH(1, true, false, false, false)
+        case 4: LLC_LAUNCH(2, true, false, false, false)
+        case 8: LLC_LAUNCH(4, true, false, false, false)
+      }
     }
   }
 #undef LLC_LAUNCH

@@ -2,7 +2,7 @@
 #include "scan.hpp"
 
 namespace llc {
-hipError_t launch_scan_bf16_perk(int kt, bool probs, unsigned grid, hipStream_t s, const ScanParams &p) {
-  return launch_scan<BF16In, false>(kt, probs, grid, s, p);
+hipError_t launch_scan_bf16_perk(int kt, bool probs, bool finish, unsigned grid, hipStream_t s, const ScanParams &p) {
+  return launch_scan<BF16In, false>(kt, probs, finish, grid, s, p);
 }
 }  // namespace llc

@@ -2,7 +2,7 @@
 #include "scan.hpp"
 
 namespace llc {
-hipError_t launch_scan_f32_shared(int kt, bool probs, unsigned grid, hipStream_t s, const ScanParams &p) {
-  return launch_scan<F32In, true>(kt, probs, grid, s, p);
+hipError_t launch_scan_f32_shared(int kt, bool probs, bool finish, unsigned grid, hipStream_t s, const ScanParams &p) {
+  return launch_scan<F32In, true>(kt, probs, finish, grid, s, p);
 }
 }  // namespace llc
