@@ -10,6 +10,8 @@ the headline metric is quoted on.  Prints ONE JSON line.
                     [--materialised] [--keys] [--no-cpu-baseline]
     python bench.py --workload verify     (Algorithm 2's verification loop, llc_verify)
     python bench.py --workload topm       (Algorithm 1 on top-50 candidate lists, llc_couple_topm)
+    python bench.py --workload lml        (Theorem 1's bound on config 3's rows)
+    python bench.py --workload peaks      (machine probes: issue rates, streaming read, sustained clock)
 """
 import argparse
 import ctypes
@@ -287,6 +289,36 @@ def bench_topm(args):
     print(json.dumps(result))
 
 
+def bench_peaks(args):
+    """What this GPU sustains on the instruction kinds the scan kernel is made of and on a plain
+    streaming read, and the clock it holds meanwhile (libllc_probe.so, csrc/probe.hip)."""
+    import torch
+    torch.cuda.init()
+    path = os.path.join(ROOT, "paper_2506_05632_amd", "libllc_probe.so")
+    lib = ctypes.CDLL(path)
+    lib.llc_probe_run.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lib.llc_probe_run.restype = ctypes.c_int
+    probes = [("fma_f32", 0, 1e12, "Tflop-pairs/s (fused multiply-adds)", 1.0), ("mad_u64_u32_plus_xor", 1, 1e12, "Tpair/s", 2.0),
+              ("xor3", 2, 1e12, "Top/s", 1.0), ("philox4x32_10_words", 3, 1e9, "Gword/s", 10.0),
+              ("stream_read_4GiB", 4, 1e9, "GB/s", None), ("copy_4GiB", 5, 1e9, "GB/s (read + written)", None),
+              ("philox_block_per_8_bytes_read_4GiB", 6, 1e9, "GB/s", 5.0)]
+    out = {}
+    for name, which, scale, unit, slots in probes:
+        res, clk = ctypes.c_double(), ctypes.c_double()
+        reps = args.steps if which >= 4 else max(args.steps, 200)   # the ALU probes run long enough for the clock to settle
+        rc = lib.llc_probe_run(which, reps, ctypes.byref(res), ctypes.byref(clk))
+        assert rc == 0, (name, rc)
+        entry = {"value": res.value / scale, "unit": unit, "launches": reps}
+        if clk.value:
+            entry["clock_ghz"] = clk.value
+        if slots is not None:
+            # issue slots per lane and second that the rate stands for, against 256 CUs x 64 lanes x 2.4 GHz
+            entry["issue_slot_fraction_of_2p4ghz_peak"] = res.value * slots / (ALU_PEAK_TLANEOPS * 1e12)
+        out[name] = entry
+    print(json.dumps({"metric": "machine probes (not the sampler)", "n_gpus": 1, "peaks": out,
+                      "reference": {"hbm_peak_gbs": HBM_PEAK_GBS, "alu_peak_tlaneops_at_2p4ghz": ALU_PEAK_TLANEOPS}}))
+
+
 def bench_lml(args):
     """Theorem 1's bound for K = 1, 2, 4, 8 on config 3's rows (a diagnostic, not the hot path)."""
     import numpy as np
@@ -548,7 +580,7 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--strong", action="store_true",
                     help="--workload verify: the strongly drafter-invariant loop (Appendix B)")
-    ap.add_argument("--workload", choices=["couple", "verify", "topm", "lml"], default="couple")
+    ap.add_argument("--workload", choices=["couple", "verify", "topm", "lml", "peaks"], default="couple")
     ap.add_argument("--bins", type=int, default=0,
                     help="with --config 5: give every candidate one of BINS bins and run the compression "
                          "scheme's binned selection (llc_compress_select) instead of llc_couple_is")
@@ -575,6 +607,8 @@ def main():
         return
     if args.workload == "lml":
         return bench_lml(args)
+    if args.workload == "peaks":
+        return bench_peaks(args)
     if args.workload == "topm":
         bench_topm(args)
         return

@@ -8,6 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libllc_hip.so")
+PROBE_LIB = os.path.join(HERE, "libllc_probe.so")   # machine probes for bench.py --workload peaks
 SOURCES = ["api.hip", "static_scratch.hip", "finalize.hip", "topm.hip", "lml.hip", "scan_f32_shared.hip", "scan_f32_perk.hip",
            "scan_bf16_shared.hip", "scan_bf16_perk.hip"]
 HEADERS = ["common.hpp", "scan.hpp", os.path.join("..", "..", "include", "llc.h")]
@@ -51,6 +52,9 @@ def build(force: bool = False, verbose: bool = False, extra_flags=()) -> str:
     objs = [os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES]
     if jobs or not os.path.exists(LIB):
         run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB])
+    probe_src = os.path.join(CSRC, "probe.hip")
+    if force or not os.path.exists(PROBE_LIB) or os.path.getmtime(PROBE_LIB) < os.path.getmtime(probe_src):
+        run([hipcc, *FLAGS, *extra_flags, "-shared", probe_src, "-o", PROBE_LIB])
     return LIB
 
 
