@@ -35,7 +35,7 @@ class _Args(ctypes.Structure):
         ("keyX", ctypes.c_void_p), ("keyY", ctypes.c_void_p),
         ("Yk", ctypes.c_void_p), ("keyYk", ctypes.c_void_p),
         ("gapX", ctypes.c_void_p), ("gapY", ctypes.c_void_p), ("gapYk", ctypes.c_void_p),
-        ("threads", ctypes.c_int32),
+        ("threads", ctypes.c_int32), ("min_first", ctypes.c_int32),
     ]
 
 
@@ -92,10 +92,15 @@ def lib():
         _lib.llc_ref_race_time.argtypes = [ctypes.c_uint32]
         _lib.llc_ref_race_time.restype = ctypes.c_double
         _lib.llc_ref_threads.restype = ctypes.c_int
+        _lib.llc_ref_aux_word.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint32]
+        _lib.llc_ref_aux_word.restype = ctypes.c_uint32
+        _lib.llc_ref_race_times.argtypes = [ctypes.c_int32, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int64,
+                                            ctypes.c_uint64, ctypes.c_int64, ctypes.c_void_p]
+        _lib.llc_ref_race_times.restype = None
         _lib.llc_couple_is_ref.argtypes = (
             [ctypes.c_int64] * 3 + [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
                                     ctypes.c_int64, ctypes.c_int64, ctypes.c_uint64,
-                                    ctypes.c_uint64] + [ctypes.c_void_p] * 8 + [ctypes.c_int32])
+                                    ctypes.c_uint64] + [ctypes.c_void_p] * 8 + [ctypes.c_int32, ctypes.c_int32])
         _lib.llc_couple_is_ref.restype = ctypes.c_int
         _lib.llc_verify_ref.argtypes = [ctypes.POINTER(_VerifyArgs)]
         _lib.llc_verify_ref.restype = ctypes.c_int
@@ -130,6 +135,17 @@ def threads():
     return int(lib().llc_ref_threads())
 
 
+def aux_word(seed, row, i, which):
+    return int(lib().llc_ref_aux_word(seed, row, i, which))
+
+
+def race_times(seed, row0, n_rows, i, K, *, min_first=False):
+    """S_i^(k) of rows row0 .. row0 + n_rows - 1 at index i: [n_rows, K] (see row_race_time)."""
+    out = np.zeros((n_rows, K))
+    lib().llc_ref_race_times(1 if min_first else 0, seed, row0, n_rows, i, K, out.ctypes.data)
+    return out
+
+
 def _check_input(arr, dtype):
     arr = np.asarray(arr)
     if dtype == F32:
@@ -141,13 +157,15 @@ def _check_input(arr, dtype):
 
 
 def couple(draft, target, K, *, dtype=F32, kind=LOGITS, temp_target=1.0, temp_draft=None,
-           temp_draft_all=1.0, seed=0, row_offset=0, threads=0, partials=False):
+           temp_draft_all=1.0, seed=0, row_offset=0, threads=0, partials=False, min_first=False):
     """Algorithm 1 on host arrays.
 
     draft: [B,V] (one proposal per row, shared by the K drafts) or [B,K,V];
     target: [B,V].  Returns a dict of numpy arrays: X [B,K], Y [B], accept [B],
     match_k [B], keyX [B,K], keyY [B], gapX [B,K], gapY [B] (relative gap to the
     runner-up), and with partials=True also Yk, keyYk, gapYk [B,K].
+    min_first: the K race times of an index are drawn through their minimum (llc_ref.cpp,
+    row_race_time) instead of one word per (k, i).
     """
     draft = _check_input(draft, dtype)
     target = _check_input(target, dtype)
@@ -184,13 +202,14 @@ def couple(draft, target, K, *, dtype=F32, kind=LOGITS, temp_target=1.0, temp_dr
     for name in out:
         setattr(a, name, out[name].ctypes.data)
     a.threads = threads
+    a.min_first = 1 if min_first else 0
     rc = lib().llc_couple_ref(ctypes.byref(a))
     if rc != 0:
         raise ValueError("llc_couple_ref rejected its arguments")
     return out
 
 
-def couple_is(logw_enc, logw_dec, *, seed=0, row_offset=0, threads=0):
+def couple_is(logw_enc, logw_dec, *, seed=0, row_offset=0, threads=0, min_first=False):
     """Importance-weight form (Appendix C): logw_enc [B,N], logw_dec [B,L,N], fp32."""
     enc = _check_input(logw_enc, F32)
     dec = _check_input(logw_dec, F32)
@@ -207,7 +226,8 @@ def couple_is(logw_enc, logw_dec, *, seed=0, row_offset=0, threads=0):
         B, L, N, enc.ctypes.data, enc.strides[0] // 4, dec.ctypes.data, dec.strides[0] // 4,
         dec.strides[1] // 4, seed, row_offset, out["X"].ctypes.data, out["Y"].ctypes.data,
         out["accept"].ctypes.data, out["match_k"].ctypes.data, out["keyX"].ctypes.data,
-        out["keyY"].ctypes.data, out["gapX"].ctypes.data, out["gapY"].ctypes.data, threads)
+        out["keyY"].ctypes.data, out["gapX"].ctypes.data, out["gapY"].ctypes.data, threads,
+        1 if min_first else 0)
     if rc != 0:
         raise ValueError("llc_couple_is_ref rejected its arguments")
     return out

@@ -10,18 +10,27 @@ import math
 from . import philox_py
 
 
-def race_times(seed, row, K, V):
-    return [[philox_py.race_time(philox_py.shared_word(seed, row, k, i)) for i in range(V)]
-            for k in range(K)]
+def race_times(seed, row, K, V, min_first=False):
+    """S[k][i].  min_first: index i's K times are its smallest one, M = -ln(U0) / K, at draft
+    kappa = floor(K r / 2^32), and M plus the per-(k, i) word's time at every other draft."""
+    S = [[philox_py.race_time(philox_py.shared_word(seed, row, k, i)) for i in range(V)]
+         for k in range(K)]
+    if min_first:
+        for i in range(V):
+            M = philox_py.race_time(philox_py.aux_word(seed, row, i, 0)) / K
+            kappa = (philox_py.aux_word(seed, row, i, 1) * K) >> 32
+            for k in range(K):
+                S[k][i] = M if k == kappa else M + S[k][i]
+    return S
 
 
-def sample_gls(p_list, q, seed, row):
+def sample_gls(p_list, q, seed, row, min_first=False):
     """p_list: K proposal distributions (lists of V floats); q: target distribution.
 
     Returns (X list of K indices, Y, accept).  Zero-probability entries never win.
     """
     K, V = len(p_list), len(q)
-    S = race_times(seed, row, K, V)
+    S = race_times(seed, row, K, V, min_first)
 
     def argmin(keys):
         best, arg = math.inf, -1

@@ -26,6 +26,8 @@
 //     two halves of `seed`; the 32-bit word of element (row, k, i) is made of two
 //     16-bit halves taken from two blocks (see shared_word).  row = row_offset + b.
 //   * U on the open interval: U = (x + 1/2) / 2^32 for the 32-bit word x.
+//   * how step 1's K N independent uniforms come out of the stream: one word per (k, i), or
+//     (min_first) the K race times of an index drawn through their minimum (see row_race_time).
 //   * argmin ties: smallest key, then smallest i, then (pool only) smallest k.
 //   * entries that are NaN or +inf (logit kinds) / NaN, +inf or negative
 //     (probability kind) carry zero probability.  A reduction with no finite
@@ -98,6 +100,36 @@ uint32_t shared_word(uint64_t seed, uint64_t row, uint32_t k, uint64_t i) {
 double race_time(uint32_t x) {
   const double U = ((double)x + 0.5) * (1.0 / 4294967296.0);
   return -std::log(U);
+}
+
+// Auxiliary 32-bit word of (row, i): output word (i & 3) of the block with counter
+// (lo32(row), i >> 2, hi32(row), 0x40000000 | which).  Bit 30 of the fourth counter word keeps
+// these blocks apart from the per-draft ones.  which = 0: the word of the smallest race time of
+// index i; which = 1: the word that picks the draft holding it.
+uint32_t aux_word(uint64_t seed, uint64_t row, uint64_t i, uint32_t which) {
+  const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  const uint32_t ctr[4] = {(uint32_t)row, (uint32_t)(i >> 2), (uint32_t)(row >> 32), 0x40000000u | which};
+  uint32_t out[4];
+  philox4x32_10(ctr, key, out);
+  return out[i & 3];
+}
+
+// Race time S_i^(k) of a row with K drafts.  Algorithm 1's first step asks for K N independent
+// uniforms U_i^(k), i.e. independent Exp(1) race times S = -ln U; it does not say how to draw them.
+//   min_first == 0: one word per (k, i), S = -ln U of that word.
+//   min_first != 0: the K race times of index i are drawn through their minimum.  The smallest of
+//     K independent Exp(1) variables is Exp(K), it sits at a uniformly random draft, and the
+//     others exceed it by independent Exp(1) amounts (memorylessness): with M = -ln(U0) / K from
+//     the index's first auxiliary word and kappa = floor(K r / 2^32) from its second, S^(kappa) = M
+//     and S^(k) = M - ln U_i^(k) for k != kappa, U_i^(k) from the word of (k, i) as above.  The K
+//     times are again independent Exp(1) (so the U = exp(-S) are the independent uniforms of step
+//     1), and the pool's key of index i, min_k S_i^(k) / q_i, is M / q_i.
+double row_race_time(int min_first, uint64_t seed, uint64_t row, uint32_t k, uint64_t i, int64_t K) {
+  if (!min_first) return race_time(shared_word(seed, row, k, i));
+  const double M = race_time(aux_word(seed, row, i, 0)) / (double)K;
+  const uint32_t kappa = (uint32_t)(((uint64_t)aux_word(seed, row, i, 1) * (uint64_t)K) >> 32);
+  if (k == kappa) return M;
+  return M + race_time(shared_word(seed, row, k, i));
 }
 
 // ---- inputs ---------------------------------------------------------------
@@ -238,6 +270,7 @@ struct llc_ref_args {
   double *gapY;      // [B]   optional: same for the pool, runner-up with index != Y
   double *gapYk;     // [B,K] optional
   int32_t threads;   // <=0: all
+  int32_t min_first; // how the race times are drawn from the stream (see row_race_time)
 };
 
 void llc_ref_philox4x32_10(const uint32_t *ctr, const uint32_t *key, uint32_t *out) {
@@ -249,6 +282,18 @@ uint32_t llc_ref_shared_word(uint64_t seed, uint64_t row, uint32_t k, uint64_t i
 }
 
 double llc_ref_race_time(uint32_t x) { return race_time(x); }
+
+uint32_t llc_ref_aux_word(uint64_t seed, uint64_t row, uint64_t i, uint32_t which) {
+  return aux_word(seed, row, i, which);
+}
+
+// out[r * K + k] = S_i^(k) of row row0 + r, for r = 0..n_rows-1.
+void llc_ref_race_times(int32_t min_first, uint64_t seed, uint64_t row0, int64_t n_rows, uint64_t i,
+                        int64_t K, double *out) {
+  for (int64_t r = 0; r < n_rows; ++r)
+    for (int64_t k = 0; k < K; ++k)
+      out[r * K + k] = row_race_time(min_first, seed, row0 + (uint64_t)r, (uint32_t)k, i, K);
+}
 
 int llc_ref_threads(void) {
 #ifdef _OPENMP
@@ -287,7 +332,7 @@ int llc_couple_ref(const llc_ref_args *a) {
       }
       Race draft, tk;
       for (int64_t i = 0; i < V; ++i) {
-        const double S = race_time(shared_word(a->seed, row, (uint32_t)k, (uint64_t)i));
+        const double S = row_race_time(a->min_first, a->seed, row, (uint32_t)k, (uint64_t)i, K);
         const double kx = p[i] > 0.0 ? S / p[i] : kInf;
         const double ky = q[i] > 0.0 ? S / q[i] : kInf;
         draft.offer(kx, i, k);
@@ -324,7 +369,8 @@ int llc_couple_is_ref(int64_t B, int64_t L, int64_t N,
                       const float *logw_dec, int64_t dec_stride_b, int64_t dec_stride_l,
                       uint64_t seed, uint64_t row_offset,
                       int32_t *X, int32_t *Y, uint8_t *accept, int32_t *match_l,
-                      double *keyX, double *keyY, double *gapX, double *gapY, int32_t threads) {
+                      double *keyX, double *keyY, double *gapX, double *gapY, int32_t threads,
+                      int32_t min_first) {
   llc_ref_args a;
   std::memset(&a, 0, sizeof(a));
   a.B = B; a.K = L; a.V = N;
@@ -336,6 +382,7 @@ int llc_couple_is_ref(int64_t B, int64_t L, int64_t N,
   a.X = X; a.Y = Y; a.accept = accept; a.match_k = match_l;
   a.keyX = keyX; a.keyY = keyY; a.gapX = gapX; a.gapY = gapY;
   a.threads = threads;
+  a.min_first = min_first;
   return llc_couple_ref(&a);
 }
 

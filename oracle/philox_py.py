@@ -43,6 +43,13 @@ def shared_word(seed, row, k, i):
     return (((hi_block[i & 3] >> shift) & 0xFFFF) << 16) | ((lo_block[i & 3] >> shift) & 0xFFFF)
 
 
+def aux_word(seed, row, i, which):
+    """Auxiliary word of (row, i): output word i & 3 of the block with counter
+    (lo32(row), i >> 2, hi32(row), 0x40000000 | which)."""
+    key = [seed & MASK, (seed >> 32) & MASK]
+    return philox4x32([row & MASK, i >> 2, (row >> 32) & MASK, 0x40000000 | which], key)[i & 3]
+
+
 def uniform(x):
     """Open-interval uniform from a 32-bit word: the midpoint of its 2^-32 cell."""
     return (x + 0.5) / 4294967296.0

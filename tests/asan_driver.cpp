@@ -18,7 +18,7 @@ struct Lcg {  // inputs only: any fixed sequence will do
 
 uint16_t bf16_of(float f) { uint32_t w; std::memcpy(&w, &f, 4); return (uint16_t)(w >> 16); }
 
-void couple_case(int64_t B, int64_t K, int64_t V, int kind, bool per_k, bool bf16, bool edge, Lcg &g) {
+void couple_case(int64_t B, int64_t K, int64_t V, int kind, bool per_k, bool bf16, bool edge, Lcg &g, int min_first = 0) {
   const int64_t rows_d = per_k ? B * K : B;
   std::vector<float> d((size_t)(rows_d * V)), t((size_t)(B * V)), temps((size_t)K);
   for (auto &v : d) v = kind == KIND_PROBS ? (float)g.next() : 2.0f * g.normal();
@@ -53,6 +53,7 @@ void couple_case(int64_t B, int64_t K, int64_t V, int kind, bool per_k, bool bf1
   a.keyX = keyX.data(); a.keyY = keyY.data(); a.Yk = Yk.data(); a.keyYk = keyYk.data();
   a.gapX = gapX.data(); a.gapY = gapY.data(); a.gapYk = gapYk.data();
   a.threads = 2;
+  a.min_first = min_first;
   if (llc_couple_ref(&a) != 0) { std::puts("llc_couple_ref rejected its arguments"); std::exit(2); }
 }
 
@@ -62,12 +63,13 @@ int main() {
   Lcg g{12345};
   // the tiny configuration (B=64, V=1024, K=4, one shared proposal, fp32 logits)
   couple_case(64, 4, 1024, KIND_LOGITS, false, false, false, g);
+  couple_case(64, 4, 1024, KIND_LOGITS, false, false, false, g, 1);
   // edge rows, every kind and layout, ragged and one-entry rows
   for (int kind : {KIND_LOGITS, KIND_PROBS, KIND_LOGW})
     for (int per_k = 0; per_k < 2; ++per_k)
       for (int bf = 0; bf < 2; ++bf)
         for (int64_t V : {1, 3, 5, 255, 1001})
-          couple_case(5, 3, V, kind, per_k != 0, bf != 0, true, g);
+          for (int mf = 0; mf < 2; ++mf) couple_case(5, 3, V, kind, per_k != 0, bf != 0, true, g, mf);
   // importance weights, binned selection (own race times and the shared-race baseline)
   {
     const int64_t B = 6, L = 3, N = 777;
@@ -82,7 +84,9 @@ int main() {
     std::vector<uint8_t> acc((size_t)B);
     std::vector<double> keyX((size_t)(B * L)), keyY((size_t)B), gapX((size_t)(B * L)), gapY((size_t)B);
     if (llc_couple_is_ref(B, L, N, enc.data(), N, dec.data(), L * N, N, 9, 1, X.data(), Y.data(), acc.data(), match.data(),
-                          keyX.data(), keyY.data(), gapX.data(), gapY.data(), 2) != 0) return 2;
+                          keyX.data(), keyY.data(), gapX.data(), gapY.data(), 2, 0) != 0) return 2;
+    if (llc_couple_is_ref(B, L, N, enc.data(), N, dec.data(), L * N, N, 9, 1, X.data(), Y.data(), acc.data(), match.data(),
+                          keyX.data(), keyY.data(), gapX.data(), gapY.data(), 2, 1) != 0) return 2;
     for (int shared = 0; shared < 2; ++shared)
       if (llc_compress_select_ref(B, L, N, enc.data(), N, dec.data(), L * N, N, bins.data(), N, 9, 1, X.data(), Y.data(),
                                   msg.data(), acc.data(), match.data(), keyX.data(), keyY.data(), gapX.data(), gapY.data(),
