@@ -424,7 +424,7 @@ def run_cpu_baseline(w, budget_s=12.0, bins=None):
 
 
 def measure_couple(args, config, *, materialised=False, keys=False, bins=0, rows=0, steps=None, warmup=None,
-                   want_workload=False):
+                   want_workload=False, min_first=None):
     """Time llc_couple (or, with bins, llc_compress_select) on one configuration; returns the
     fields of a bench line (without cpu_baseline)."""
     import torch
@@ -433,6 +433,8 @@ def measure_couple(args, config, *, materialised=False, keys=False, bins=0, rows
 
     steps = steps or args.steps
     warmup = args.warmup if warmup is None else warmup
+    min_first = args.min_first if min_first is None else min_first
+    flags = llc.FLAG_MIN_FIRST if min_first else 0
     dev = "cuda:0"
     w = workloads.make(config, dev, rows=rows or None)
     draft = w.draft
@@ -473,7 +475,7 @@ def measure_couple(args, config, *, materialised=False, keys=False, bins=0, rows
         llc.llc_couple(draft, w.target, w.K, kind=w.kind, temp_target=w.temp_target,
                        temp_draft=w.temp_draft, seed=w.seed + (0 if i is None else i),
                        row_offset=w.row_offset, workspace=ws, out=out,
-                       v_chunks=args.v_chunks, k_tile=args.k_tile,
+                       v_chunks=args.v_chunks, k_tile=args.k_tile, flags=flags,
                        scan_events=None if i is None else ev.pairs[i], stats=stats)
 
     for _ in range(warmup):
@@ -513,6 +515,8 @@ def measure_couple(args, config, *, materialised=False, keys=False, bins=0, rows
         alg_bytes = w.B * w.K * w.V * 4 + w.B * w.V
     if rows:
         name += f"_rows{w.B}"
+    if min_first:
+        name += "_minfirst"
     hbm_achieved = alg_bytes / scan_avg_s / 1e9
     alu_frac, hbm_frac = alu_achieved / ALU_PEAK_TLANEOPS, hbm_achieved / HBM_PEAK_GBS
     # The figure of merit is the fraction of the HBM roofline on the algorithmic bytes; the
@@ -529,6 +533,7 @@ def measure_couple(args, config, *, materialised=False, keys=False, bins=0, rows
     config_d = {"workload": name, "B": w.B, "K": w.K, "V": w.V, "input_dtype": str(w.dtype),
                 "temperature": w.temp_target,
                 "draft_layout": "[B,K,V]" if (materialised or not w.shared_draft) else "[B,V] shared by the K drafts",
+                "race_times": "min-first (LLC_FLAG_MIN_FIRST)" if min_first else "one word per (k, i)",
                 "outputs": "X,Y,accept,match_k" + (",keyX,keyY" if keys else ""),
                 "accept_rate": float(out["accept"].float().mean()),
                 "near_ties": counters["near_ties"], "prefilter_survivors": counters["survivors"],
@@ -588,6 +593,8 @@ def main():
     ap.add_argument("--materialised", action="store_true",
                     help="give the K i.i.d. drafts as a [B,K,V] tensor instead of one shared [B,V] row")
     ap.add_argument("--keys", action="store_true", help="also produce the winning keys (adds the normaliser pass)")
+    ap.add_argument("--min-first", action="store_true",
+                    help="draw the race times min-first (LLC_FLAG_MIN_FIRST) instead of one word per (k, i)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-secondary", action="store_true",
                     help="only the headline line: skip the other workloads that the default run also times")

@@ -28,7 +28,7 @@
 extern "C" {
 #endif
 
-#define LLC_VERSION 108
+#define LLC_VERSION 109
 
 enum {
   LLC_OK = 0,
@@ -60,10 +60,24 @@ enum {
   LLC_FLAG_SHARED_RACE = 8,/* llc_compress_select only: the baseline scheme of Section 5.3, in
                               which all decoders share one set of random numbers: the encoder's
                               pool and every decoder use the race times of the first set    */
-  LLC_FLAG_DRY_RUN = 4     /* llc_couple, llc_couple_is, llc_compress_select, llc_verify: check
+  LLC_FLAG_DRY_RUN = 4,    /* llc_couple, llc_couple_is, llc_compress_select, llc_verify: check
                               the arguments, plan every launch of the call and check the
                               workspace against the plan, then return without launching
                               anything (no pointer is dereferenced)                    */
+  LLC_FLAG_MIN_FIRST = 16  /* llc_couple, llc_couple_static, llc_couple_is, llc_verify: how Algorithm 1's
+                              first step draws its K N independent Exp(1) race times from the row's
+                              stream.  Default: one 32-bit word per (k, i), S = -ln U.  With this flag
+                              the K times of an index are drawn through their minimum: M = -ln(U0) / K
+                              (U0 from the index's own word) is the smallest, the draft kappa =
+                              floor(K r / 2^32) (r: the index's second word) holds it, and every other
+                              draft's time is M - ln U_i^(k), U_i^(k) its word as above.  The K times
+                              are again independent Exp(1) variables (the minimum of K of them is
+                              Exp(K), sits at a uniform position, and the others exceed it by
+                              independent Exp(1) amounts), so every statement of Section 3 holds
+                              unchanged; the samples differ from the default's for the same seed.
+                              The scan then tests one word per index instead of one per (k, i).  All
+                              calls that are to be coupled (the drafters' and the verifier's) must
+                              agree on the flag.  LLC_E_OPTION in llc_compress_select, llc_couple_topm */
 };
 
 /* Optional device counters, accumulated with atomics (zero them yourself). */

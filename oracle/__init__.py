@@ -53,7 +53,7 @@ class _VerifyArgs(ctypes.Structure):
         ("strong", ctypes.c_int32),
         ("Y", ctypes.c_void_p), ("n_out", ctypes.c_void_p), ("active", ctypes.c_void_p),
         ("key", ctypes.c_void_p), ("gap", ctypes.c_void_p),
-        ("threads", ctypes.c_int32),
+        ("threads", ctypes.c_int32), ("min_first", ctypes.c_int32),
     ]
 
 
@@ -234,7 +234,7 @@ def couple_is(logw_enc, logw_dec, *, seed=0, row_offset=0, threads=0, min_first=
 
 
 def verify(target, tokens, *, dtype=F32, kind=LOGITS, temp_target=1.0, seed=0, row_offset=0,
-           row_stride_s=None, row_stride_j=1, strong=False, threads=0):
+           row_stride_s=None, row_stride_j=1, strong=False, threads=0, min_first=False):
     """Algorithm 2's verification loop on host arrays.
 
     target: [S, L+1, K, V] (q^(j,k), position L is the bonus position); tokens: [S, L, K] int32
@@ -264,6 +264,7 @@ def verify(target, tokens, *, dtype=F32, kind=LOGITS, temp_target=1.0, seed=0, r
     for name in out:
         setattr(a, name, out[name].ctypes.data)
     a.threads = threads
+    a.min_first = 1 if min_first else 0
     if lib().llc_verify_ref(ctypes.byref(a)) != 0:
         raise ValueError("llc_verify_ref rejected its arguments")
     return out

@@ -566,6 +566,7 @@ struct llc_verify_ref_args {
   double *key;       // [S, L+1] optional: winning S/q (normalised q)
   double *gap;       // [S, L+1] optional: relative gap to the best entry with another index
   int32_t threads;
+  int32_t min_first; // how the race times are drawn from the stream (see row_race_time)
 };
 
 int llc_verify_ref(const llc_verify_ref_args *a) {
@@ -604,7 +605,7 @@ int llc_verify_ref(const llc_verify_ref_args *a) {
         row_distribution(a->target, a->dtype, s * a->stride_s + j * a->stride_j + krow * a->stride_k, V,
                          a->kind, (double)a->temp_target, q);
         for (int64_t i = 0; i < V; ++i) {
-          const double St = race_time(shared_word(a->seed, row, (uint32_t)k, (uint64_t)i));
+          const double St = row_race_time(a->min_first, a->seed, row, (uint32_t)k, (uint64_t)i, K);
           pool.offer(q[i] > 0.0 ? St / q[i] : kInf, i, k);
         }
       }

@@ -19,6 +19,7 @@ FLAG_EXACT_SCAN = 1
 FLAG_STRONG = 2
 FLAG_DRY_RUN = 4
 FLAG_SHARED_RACE = 8
+FLAG_MIN_FIRST = 16  # the K race times of an index are drawn through their minimum (see llc.h)
 
 _KINDS = {"logits": LOGITS, "probs": PROBS, "logw": LOGW}
 EXPORTS = ["llc_couple", "llc_couple_static", "llc_couple_is", "llc_couple_topm", "llc_compress_select", "llc_verify", "llc_lml_bound",

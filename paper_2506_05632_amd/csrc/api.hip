@@ -123,6 +123,7 @@ struct ScanJob {
   bool need_lse;     // also compute the row normalisers (log kinds)
   bool no_draft = false;    // pool only
   bool same_race = false;   // every draft uses draft 0's race times
+  bool min_first = false;   // the race times of an index are drawn through their minimum
   bool force_perk = false;  // every draft has its own row even if draft_stride_k == 0
   const uint8_t *bins = nullptr;  // binned candidates: mask of the draft rows (see ScanParams)
   long long bins_stride_b = 0;
@@ -154,6 +155,7 @@ int plan_scan(const ScanJob &j, ScanPlan *out) {
   if (j.dtype != LLC_F32 && j.dtype != LLC_BF16) return LLC_E_DTYPE;
   if (j.kind != LLC_LOGITS && j.kind != LLC_PROBS && j.kind != LLC_LOGW) return LLC_E_DTYPE;
   if (j.flags & ~LLC_FLAG_EXACT_SCAN) return LLC_E_OPTION;  // (the entry points strip their own flags)
+  if (j.min_first && (j.bins != nullptr || j.no_draft || j.same_race)) return LLC_E_OPTION;
   if (j.v_chunks < 0 || j.v_chunks > kMaxChunks) return LLC_E_OPTION;
   if (j.k_tile != 0 && j.k_tile != 1 && j.k_tile != 2 && j.k_tile != 4 && j.k_tile != 8)
     return LLC_E_OPTION;
@@ -307,12 +309,20 @@ int launch_scan_job(const ScanJob &j, const ScanPlan &plan, Partials *partials, 
   if (j.ev_begin != nullptr && hipEventRecord((hipEvent_t)j.ev_begin, st) != hipSuccess)
     return LLC_E_LAUNCH;
   hipError_t e;
-  if (j.dtype == LLC_F32)
+  if (j.min_first) {
+    if (j.dtype == LLC_F32)
+      e = shared ? launch_scan_f32_shared_minf(pl.kt, probs, finish, (unsigned)blocks, st, sp)
+                 : launch_scan_f32_perk_minf(pl.kt, probs, finish, (unsigned)blocks, st, sp);
+    else
+      e = shared ? launch_scan_bf16_shared_minf(pl.kt, probs, finish, (unsigned)blocks, st, sp)
+                 : launch_scan_bf16_perk_minf(pl.kt, probs, finish, (unsigned)blocks, st, sp);
+  } else if (j.dtype == LLC_F32) {
     e = shared ? launch_scan_f32_shared(pl.kt, probs, finish, (unsigned)blocks, st, sp)
                : launch_scan_f32_perk(pl.kt, probs, finish, (unsigned)blocks, st, sp);
-  else
+  } else {
     e = shared ? launch_scan_bf16_shared(pl.kt, probs, finish, (unsigned)blocks, st, sp)
                : launch_scan_bf16_perk(pl.kt, probs, finish, (unsigned)blocks, st, sp);
+  }
   if (e != hipSuccess) return LLC_E_LAUNCH;
   if (j.ev_end != nullptr && hipEventRecord((hipEvent_t)j.ev_end, st) != hipSuccess)
     return LLC_E_LAUNCH;
@@ -354,7 +364,8 @@ int couple_on(const llc_couple_args *a, void *workspace, size_t workspace_bytes)
   j.seed = a->seed; j.row_offset = a->row_offset;
   j.no_pool = false;
   j.need_lse = a->keyX != nullptr || a->keyY != nullptr;
-  j.flags = a->flags & ~LLC_FLAG_DRY_RUN; j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;
+  j.min_first = (a->flags & LLC_FLAG_MIN_FIRST) != 0;
+  j.flags = a->flags & ~(LLC_FLAG_DRY_RUN | LLC_FLAG_MIN_FIRST); j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;
   j.stats = a->stats; j.workspace = workspace; j.workspace_bytes = workspace_bytes;
   j.stream = a->stream; j.ev_begin = a->ev_scan_begin; j.ev_end = a->ev_scan_end;
   j.extra_bytes = 0;
@@ -639,7 +650,8 @@ int llc_verify(const llc_verify_args *a) {
   j.no_pool = true;
   j.need_lse = true;  // keys of different rows are compared: they must be normalised
   j.force_perk = true;
-  if (a->flags & ~(LLC_FLAG_EXACT_SCAN | LLC_FLAG_STRONG | LLC_FLAG_DRY_RUN)) return LLC_E_OPTION;
+  if (a->flags & ~(LLC_FLAG_EXACT_SCAN | LLC_FLAG_STRONG | LLC_FLAG_DRY_RUN | LLC_FLAG_MIN_FIRST)) return LLC_E_OPTION;
+  j.min_first = (a->flags & LLC_FLAG_MIN_FIRST) != 0;
   const bool strong = (a->flags & LLC_FLAG_STRONG) != 0;
   const bool dry = (a->flags & LLC_FLAG_DRY_RUN) != 0;
   j.flags = a->flags & LLC_FLAG_EXACT_SCAN; j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;

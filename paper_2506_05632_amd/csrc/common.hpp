@@ -228,6 +228,11 @@ hipError_t launch_scan_f32_shared(int kt, bool probs, bool finish, unsigned grid
 hipError_t launch_scan_f32_perk(int kt, bool probs, bool finish, unsigned grid, hipStream_t s, const ScanParams &p);
 hipError_t launch_scan_bf16_shared(int kt, bool probs, bool finish, unsigned grid, hipStream_t s, const ScanParams &p);
 hipError_t launch_scan_bf16_perk(int kt, bool probs, bool finish, unsigned grid, hipStream_t s, const ScanParams &p);
+// the same with the race times drawn min-first (no binned or pool-only passes)
+hipError_t launch_scan_f32_shared_minf(int kt, bool probs, bool finish, unsigned grid, hipStream_t s, const ScanParams &p);
+hipError_t launch_scan_f32_perk_minf(int kt, bool probs, bool finish, unsigned grid, hipStream_t s, const ScanParams &p);
+hipError_t launch_scan_bf16_shared_minf(int kt, bool probs, bool finish, unsigned grid, hipStream_t s, const ScanParams &p);
+hipError_t launch_scan_bf16_perk_minf(int kt, bool probs, bool finish, unsigned grid, hipStream_t s, const ScanParams &p);
 
 // llc_couple on a given workspace (api.hip).
 int couple_on(const llc_couple_args *a, void *workspace, size_t workspace_bytes);

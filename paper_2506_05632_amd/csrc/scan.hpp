@@ -27,6 +27,14 @@
 // Because every element whose exact key could be the minimum passes levels 1
 // and 2 (the margins below bound the fp32 error of both), the result is the
 // exact fp64 argmin, independent of grid shape and of the order of arrival.
+//
+// MINF (the min-first way of drawing Algorithm 1's race times): the K race times of an index are
+// drawn through their minimum M = -ln(U0) / K, which sits at draft kappa = floor(K r / 2^32); every
+// other draft's time is M - ln U_i^(k).  No draft's time is below M, so level 1 tests M alone: one
+// 32-bit word per index instead of one half-word per (index, draft), against the loosest of the
+// bounds (raised by log2 K).  The survivors' path draws kappa, hands M to the draft that holds it
+// (and to the pool, whose key of the index is M / q_i), and for the other drafts runs the old
+// half-word test on their own word: M - ln U can only win if -ln U alone is below the bound.
 #pragma once
 
 #include "common.hpp"
@@ -59,6 +67,10 @@ constexpr float kCapHot = 1333788288.0f;
 constexpr float kShift32 = 268435456.0f - 1024.0f;       // 32 * 2^23, less the raise
 constexpr float kCapOne32 = 1065353216.0f;               // 0x3F800000 read as an integer
 constexpr uint32_t kLowBlock = 0x80000000u;  // bit 31 of counter word 3 marks the lower-half block
+// min-first: counter word 3 of the block with the smallest race times of four indices (one 32-bit
+// word each) and of the block whose words pick the drafts that hold them
+constexpr uint32_t kMinBlock = 0x40000000u;
+constexpr uint32_t kHolderBlock = 0x40000001u;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLog2Ln2 = -0.5287663729448977f;  // log2(ln 2)
 
@@ -270,6 +282,19 @@ __device__ __forceinline__ float approx_log2_race_time(uint32_t x) {
   return __log2f(-__log2f(U)) + kLog2Ln2;
 }
 
+// The race time itself in fp32 (relative error below 2^-16).
+__device__ __forceinline__ float approx_race_time(uint32_t x) {
+  const uint32_t xt = ~x;
+  if (xt < (1u << 25)) {
+    const float W = ((float)xt + 0.5f) * 0x1p-32f;
+    return W * fmaf(W, fmaf(W, 0.33333334f, 0.5f), 1.0f);
+  }
+  const float U = ((float)x + 0.5f) * 0x1p-32f;
+  return -__log2f(U) * 0.6931471805599453f;
+}
+// min-first: the draft that holds an index's smallest race time, from the index's second word.
+__device__ __forceinline__ int holder_of(uint32_t r, int K) { return (int)__umulhi(r, (uint32_t)K); }
+
 // The race time S = -ln U in fp64.
 __device__ __forceinline__ double exact_race_time(uint32_t x) {
   const double U = ((double)x + 0.5) * 0x1p-32;
@@ -324,6 +349,7 @@ struct Lds {
   int tau[9];            // ordered-int log2 keys: drafts 0..KT-1, pool at [KT]
   int O[9];              // bits of the level-1 offsets (tau + slack + bias) 2^23; shared layout: [0] = max over drafts
   int OL[9];             // the same lowered for the main loop (see kShift32); -inf for a reduction that is not taken
+  float lgK;             // min-first: log2 K, by which the level-1 bounds on the smallest time are raised (else 0)
   int count;             // records appended (may exceed kListCap)
   int unsafe;            // chunk must be redone in fp64
   unsigned long long best[9];
@@ -348,10 +374,10 @@ struct Lds {
 };
 
 template <bool PROBS>
-__device__ __forceinline__ float make_offset(float tau) {
+__device__ __forceinline__ float make_offset(float tau, float lgK = 0.0f) {
   // logits: exponent bias 127 plus the 2^32 scale of the integer word; probabilities: the
   // bias is already in the float's own bits
-  return (tau + ((PROBS ? 32.0f + kPseudoLog : 159.0f) + kEps1)) * kTwo23;
+  return (tau + lgK + ((PROBS ? 32.0f + kPseudoLog : 159.0f) + kEps1)) * kTwo23;
 }
 __device__ __forceinline__ void store_offset(int *slot, float O) {
   __atomic_store_n(slot, __float_as_int(O), __ATOMIC_RELAXED);
@@ -359,10 +385,12 @@ __device__ __forceinline__ void store_offset(int *slot, float O) {
 __device__ __forceinline__ float load_offset(const int *slot) {
   return __int_as_float(__atomic_load_n(slot, __ATOMIC_RELAXED));
 }
-// An offset is kept in both forms: as it is (candidates' path) and lowered for the main loop.
+// An offset is kept in both forms: as it is (candidates' path) and lowered for the main loop
+// (min-first: the main loop tests whole words, its copy is not lowered).
+template <bool MINF>
 __device__ __forceinline__ void store_offsets(Lds &s, int slot, float O) {
   store_offset(&s.O[slot], O);
-  store_offset(&s.OL[slot], O - kShift32);
+  store_offset(&s.OL[slot], MINF ? O : O - kShift32);
 }
 // Scaled exponent of one element's threshold, merged with the target side's (FY) and capped.
 template <bool PROBS>
@@ -381,7 +409,7 @@ __device__ __forceinline__ uint32_t packed_hi16(float F0, float F1) {
 // Lower tau[slot] to `a` and refresh the level-1 offset that depends on it.  When the row is
 // spread over several workgroups the new best is also posted to the row's shared array, from
 // which the others pick it up (a bound found in one chunk prunes all of them).
-template <int KT, bool SHARED, bool PROBS>
+template <int KT, bool SHARED, bool PROBS, bool MINF>
 __device__ __forceinline__ void publish(Lds &s, int slot, float a, bool post = true) {
   atomicMin(&s.tau[slot], ord32(a));
   if (post && s.shared_tau != nullptr)
@@ -391,26 +419,25 @@ __device__ __forceinline__ void publish(Lds &s, int slot, float a, bool post = t
     int m = s.tau[0];
 #pragma unroll
     for (int kk = 1; kk < KT; ++kk) m = max(m, __atomic_load_n(&s.tau[kk], __ATOMIC_RELAXED));
-    store_offsets(s, 0, make_offset<PROBS>(unord32(m)));
+    store_offsets<MINF>(s, 0, make_offset<PROBS>(unord32(m), s.lgK));
   } else {
-    store_offsets(s, slot, make_offset<PROBS>(unord32(__atomic_load_n(&s.tau[slot], __ATOMIC_RELAXED))));
+    store_offsets<MINF>(s, slot, make_offset<PROBS>(unord32(__atomic_load_n(&s.tau[slot], __ATOMIC_RELAXED)), s.lgK));
   }
 }
 
 // Level 2 for one survivor of level 1.  tau_d / tau_p: the draft's and the pool's running best
 // as read a little earlier (a stale, larger value only lets more candidates through).
-template <int KT, bool SHARED, bool PROBS>
-__device__ __forceinline__ void level2(Lds &s, uint32_t x, float vd, float vq, int i, int kk,
+template <int KT, bool SHARED, bool PROBS, bool MINF>
+__device__ __forceinline__ void level2(Lds &s, float l2S, float vd, float vq, int i, int kk,
                                        bool draft_ok, bool pool_ok, float cd, float cq,
                                        float tau_d, float tau_p) {
-  const float l2S = approx_log2_race_time(x);
   float ell;
   if (draft_ok && approx_log2_mass<PROBS>(vd, cd, ell)) {
     const float a = l2S - ell;
     if (a <= tau_d + kEps2) {
       const int pos = atomicAdd(&s.count, 1);
       if (pos < kListCap) { s.rec_a[pos] = a; s.rec_i[pos] = i; s.rec_tag[pos] = kk; }
-      if (a < tau_d) publish<KT, SHARED, PROBS>(s, kk, a);
+      if (a < tau_d) publish<KT, SHARED, PROBS, MINF>(s, kk, a);
     }
   }
   if (pool_ok && approx_log2_mass<PROBS>(vq, cq, ell)) {
@@ -418,7 +445,7 @@ __device__ __forceinline__ void level2(Lds &s, uint32_t x, float vd, float vq, i
     if (a <= tau_p + kEps2) {
       const int pos = atomicAdd(&s.count, 1);
       if (pos < kListCap) { s.rec_a[pos] = a; s.rec_i[pos] = i; s.rec_tag[pos] = KT + kk; }
-      if (a < tau_p) publish<KT, SHARED, PROBS>(s, KT, a);
+      if (a < tau_p) publish<KT, SHARED, PROBS, MINF>(s, KT, a);
     }
   }
 }
@@ -488,10 +515,12 @@ __device__ double chunk_lse_exact(const typename T::elem *row, int g_begin, int 
 // them (logit kinds), so that no second pass over the inputs is needed.
 // FIN: the variant for rows that are one workgroup each: it also takes the finalize step (Algorithm
 // 1's accept test and the outputs), so that no finalize launch follows.
-template <typename T, int KB, bool SHARED, bool PROBS, bool MASKED, bool LSE, bool FIN>
+// MINF: the race times are drawn min-first (see the top of the file).
+template <typename T, int KB, bool SHARED, bool PROBS, bool MASKED, bool LSE, bool FIN, bool MINF>
 __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kernel(const ScanParams p) {
   using elem = typename T::elem;
   constexpr int KT = 2 * KB;
+  static_assert(!(MINF && MASKED), "the binned and pool-only passes draw one word per (index, draft)");
   __shared__ Lds s;
 
   const int tid = threadIdx.x;
@@ -576,6 +605,9 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
     kok[kk] = (k < p.K) && (t > 0.0f) && (t < __builtin_huge_valf());
     cd23[kk] = PROBS ? 1.0f : (kLog2e / t) * kTwo23;
   }
+  // min-first: the smallest of an index's K times is (-ln U0) / K
+  const float lgK = MINF ? log2f((float)p.K) : 0.0f;
+  const float invK = MINF ? 1.0f / (float)p.K : 1.0f;
   const float Tq = p.temp_target;
   const float cq = PROBS ? 1.0f : kLog2e / Tq;
   const float cq23 = PROBS ? 1.0f : cq * kTwo23;
@@ -624,6 +656,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
   if (tid == 0) {
 #pragma unroll
     for (int kk = 0; kk < KT; ++kk) { s.cd23[kk] = cd23[kk]; s.kok[kk] = kok[kk] ? 1 : 0; }
+    s.lgK = lgK;
     s.count = 0; s.unsafe = p.force_exact ? 1 : 0; s.n_survivors = 0; s.n_exact = 0;
     s.shared_tau = p.shared_tau != nullptr ? p.shared_tau + b * (p.K + 1) : nullptr;
     s.shared_base = kbase;
@@ -650,6 +683,20 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         const uint32_t pair = same_race ? 0u : pair_base + m;
         philox_block(row_lo, (uint32_t)g, row_hi, pair, p.seed_lo, p.seed_hi, up);
         philox_block(row_lo, (uint32_t)g, row_hi, pair | kLowBlock, p.seed_lo, p.seed_hi, lo);
+        float Mj[4] = {0.0f, 0.0f, 0.0f, 0.0f};  // min-first: the indices' smallest times ...
+        int holder[4] = {-1, -1, -1, -1};        // ... and the drafts that hold them
+        if (MINF) {
+          uint32_t mn[4], hd[4];
+          philox_block(row_lo, (uint32_t)g, row_hi, kMinBlock, p.seed_lo, p.seed_hi, mn);
+          philox_block(row_lo, (uint32_t)g, row_hi, kHolderBlock, p.seed_lo, p.seed_hi, hd);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            Mj[j] = approx_race_time(mn[j]) * invK;
+            holder[j] = holder_of(hd[j], p.K);
+            float ell;
+            if (with_pool && approx_log2_mass<PROBS>(vq[j], cq, ell)) a_pool = fminf(a_pool, __log2f(Mj[j]) - ell);
+          }
+        }
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
           const int k = kbase + 2 * m + h;
@@ -664,10 +711,12 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             float a_k = __builtin_huge_valf();
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-              const float l2S = approx_log2_race_time(element_word(up[j], lo[j], same_race ? 0 : h));
+              const uint32_t x = element_word(up[j], lo[j], same_race ? 0 : h);
+              const float l2S = MINF ? __log2f(holder[j] == k ? Mj[j] : Mj[j] + approx_race_time(x))
+                                     : approx_log2_race_time(x);
               float ell;
               if (ok && approx_log2_mass<PROBS>(vd[j], ck, ell)) a_k = fminf(a_k, l2S - ell);
-              if (with_pool && approx_log2_mass<PROBS>(vq[j], cq, ell)) a_pool = fminf(a_pool, l2S - ell);
+              if (!MINF && with_pool && approx_log2_mass<PROBS>(vq[j], cq, ell)) a_pool = fminf(a_pool, l2S - ell);
             }
             if (h == 0) a_even = a_k; else a_odd = a_k;
           }
@@ -705,13 +754,13 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
           int m = s.tau[0];
 #pragma unroll
           for (int kk = 1; kk < KT; ++kk) m = max(m, s.tau[kk]);
-          if (kok[0]) store_offsets(s, 0, make_offset<PROBS>(unord32(m)));
+          if (kok[0]) store_offsets<MINF>(s, 0, make_offset<PROBS>(unord32(m), lgK));
         } else {
 #pragma unroll
           for (int kk = 0; kk < KT; ++kk)
-            if (kok[kk]) store_offsets(s, kk, make_offset<PROBS>(unord32(s.tau[kk])));
+            if (kok[kk]) store_offsets<MINF>(s, kk, make_offset<PROBS>(unord32(s.tau[kk]), lgK));
         }
-        if (with_pool) store_offsets(s, KT, make_offset<PROBS>(unord32(s.tau[KT])));
+        if (with_pool) store_offsets<MINF>(s, KT, make_offset<PROBS>(unord32(s.tau[KT]), lgK));
       }
       __syncthreads();
     }
@@ -776,7 +825,112 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
           lse_acc[sl] += (double)part;
         }
       };
-      auto process_tile = [&](const int g, const raw &rq, const raw (&rd)[KD], const uint32_t rb) {
+      // min-first: one block holds the four indices' smallest race times, one word each; the tile's
+      // largest word is tested against the loosest bound (every draft's and the pool's, each raised
+      // by log2 K in its offset), and the survivors' path sorts out which draft the time belongs to.
+      auto process_tile_minf = [&](const int g, const raw &rq, const raw (&rd)[KD], const uint32_t rb) {
+        uint32_t mn[1][4];
+        philox_blocks<1>((uint32_t)g, kMinBlock, row_lo, row_hi, p.seed_lo, p.seed_hi, mn);
+        float F;
+        {
+          float vq[4];
+          unpack(rq, vq);  // (without a pool the tile's target part keeps its initial zeros, and the offset is -inf)
+          F = fmaf(level1_max4<PROBS>(vq), cq23, load_offset(&s.OL[KT]));
+          if (LSE && lse_target) lse_add(KT, vq);
+        }
+#pragma unroll
+        for (int kk = 0; kk < KD; ++kk) {
+          float vd[4];
+          unpack(rd[kk], vd);
+          if (LSE) lse_add(kk, vd);  // (one shared row stands for all drafts: slot 0)
+          F = fmaxf(F, fmaf(level1_max4<PROBS>(vd), cd23[kk], load_offset(&s.OL[kk])));
+        }
+        F = __builtin_amdgcn_fmed3f(F, 0.0f, kCapHot);
+        const uint32_t mx = max(max(mn[0][0], mn[0][1]), max(mn[0][2], mn[0][3]));
+        // Rare: some lane's largest word passed, or it holds a hot element.  The wave takes such lanes
+        // one at a time: the lane lays its tile out in LDS and the first 8 KB lanes each take one
+        // (index j, draft 2m + h) of it.  A lane redoes the test on the index's smallest time with
+        // its draft's own bound (merged with the pool's); where that passes it draws the holder: if
+        // its draft holds the smallest time, that time goes to level 2 for the draft and the pool;
+        // if not, its draft's time is the smallest plus that of its own word, which can only matter
+        // if the word alone passes the draft's bound (half-word first, as in the other variant).
+        unsigned long long todo = __ballot(F >= kCapHot || mx >= ~threshold_of(F));
+        if (todo != 0ull) {
+          const int lane = tid & 63;
+          Lds::Stage &st = s.stage[tid >> 6];
+          while (todo != 0ull) {
+            const int src = __ffsll((long long)todo) - 1;
+            todo &= todo - 1ull;
+            if (lane == src) {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) st.up[j] = mn[0][j];
+              float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+              if (with_pool) unpack(rq, vq);
+#pragma unroll
+              for (int j = 0; j < 4; ++j) st.vq[j] = vq[j];
+#pragma unroll
+              for (int kk = 0; kk < KD; ++kk) {
+                float vd[4];
+                unpack(rd[kk], vd);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) st.vd[kk * 4 + j] = vd[j];
+              }
+            }
+            __builtin_amdgcn_wave_barrier();
+            const int gs = g - lane + src;  // the lanes of a wave hold consecutive groups
+            if (lane < 8 * KB) {
+              const int m = lane >> 3, j = (lane >> 1) & 3, h = lane & 1;
+              const int kk = 2 * m + h;
+              const int i = gs * 4 + j;
+              if (kbase + kk < p.K && i < V) {
+                const uint32_t x0 = st.up[j];
+                const float ds = st.vd[(SHARED ? 0 : kk) * 4 + j], qs = st.vq[j];
+                const float c23 = s.cd23[kk];
+                const bool okk = s.kok[kk] != 0;
+                const float tau_d = unord32(__atomic_load_n(&s.tau[kk], __ATOMIC_RELAXED));
+                const float tau_y = unord32(__atomic_load_n(&s.tau[KT], __ATOMIC_RELAXED));
+                const float OYs = with_pool ? load_offset(&s.O[KT]) : -__builtin_huge_valf();
+                const float fy = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(qs), cq23, OYs), 0.0f, kCapHot);
+                const float OX = okk ? make_offset<PROBS>(tau_d, lgK) : -__builtin_huge_valf();
+                const float Fs = merged_exponent<PROBS>(ds, c23, OX, fy);
+                if (Fs >= kCapHot || x0 >= ~threshold_of(Fs)) {
+                  uint32_t hd[4];
+                  philox_block(row_lo, (uint32_t)gs, row_hi, kHolderBlock, p.seed_lo, p.seed_hi, hd);
+                  const uint32_t r = j == 0 ? hd[0] : j == 1 ? hd[1] : j == 2 ? hd[2] : hd[3];
+                  const float cdk = PROBS ? 1.0f : c23 * (1.0f / kTwo23);
+                  if (holder_of(r, p.K) == kbase + kk) {
+                    ++my_survivors;
+                    level2<KT, SHARED, PROBS, MINF>(s, approx_log2_race_time(x0) - lgK, ds, qs, i, kk, okk, with_pool,
+                                                    cdk, cq, tau_d, tau_y);
+                  } else if (okk) {
+                    const float Fd = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(ds), c23, make_offset<PROBS>(tau_d)),
+                                                             0.0f, kCapHot);
+                    const uint32_t t = threshold_of(Fd);
+                    uint32_t up[4];
+                    philox_block(row_lo, (uint32_t)gs, row_hi, pair_base + m, p.seed_lo, p.seed_hi, up);
+                    const uint32_t uw = j == 0 ? up[0] : j == 1 ? up[1] : j == 2 ? up[2] : up[3];
+                    const uint32_t hw = h ? (uw >> 16) : (uw & 0xFFFFu);
+                    if (Fd >= kCapHot || hw >= 0xFFFFu - (t >> 16)) {
+                      uint32_t lo[4];
+                      philox_block(row_lo, (uint32_t)gs, row_hi, (pair_base + m) | kLowBlock, p.seed_lo, p.seed_hi, lo);
+                      const uint32_t lw = j == 0 ? lo[0] : j == 1 ? lo[1] : j == 2 ? lo[2] : lo[3];
+                      const uint32_t x = element_word(uw, lw, h);
+                      if (Fd >= kCapHot || x >= ~t) {
+                        ++my_survivors;
+                        const float S = approx_race_time(x0) * invK + approx_race_time(x);
+                        level2<KT, SHARED, PROBS, MINF>(s, __log2f(S), ds, qs, i, kk, true, false, cdk, cq, tau_d, tau_y);
+                      }
+                    }
+                  }
+                }
+              }
+            }
+            __builtin_amdgcn_wave_barrier();
+          }
+        }
+        (void)rb;
+      };
+      auto process_tile_words = [&](const int g, const raw &rq, const raw (&rd)[KD], const uint32_t rb) {
         uint32_t up[KB][4];  // upper half-words: word j of block m = (index 4g+j, drafts 2m | 2m+1)
         if (same_race) {
           // one block for all drafts: draft 0's half-word of every index, in both halves of every pair
@@ -900,8 +1054,8 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
                   const uint32_t x = element_word(uw, lw, same_race ? 0 : h);
                   if (F >= kCapHot || x >= ~t) {
                     ++my_survivors;
-                    level2<KT, SHARED, PROBS>(s, x, ds, qs, i, kk, okk, with_pool,
-                                              PROBS ? 1.0f : c23 * (1.0f / kTwo23), cq, tau_d, tau_y);
+                    level2<KT, SHARED, PROBS, MINF>(s, approx_log2_race_time(x), ds, qs, i, kk, okk, with_pool,
+                                                    PROBS ? 1.0f : c23 * (1.0f / kTwo23), cq, tau_d, tau_y);
                   }
                 }
               }
@@ -909,6 +1063,10 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
             __builtin_amdgcn_wave_barrier();
           }
         }
+      };
+      auto process_tile = [&](const int g, const raw &rq, const raw (&rd)[KD], const uint32_t rb) {
+        if constexpr (MINF) process_tile_minf(g, rq, rd, rb);
+        else process_tile_words(g, rq, rd, rb);
       };
       // A tile is interior when every lane's group is complete and inside the chunk: all rows
       // are then read with unconditional vector loads.
@@ -952,7 +1110,7 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
           }
           if (follows && (it & 3) == 0) {
             if (seen < __atomic_load_n(&s.tau[tid], __ATOMIC_RELAXED))
-              publish<KT, SHARED, PROBS>(s, tid, unord32(seen), false);
+              publish<KT, SHARED, PROBS, MINF>(s, tid, unord32(seen), false);
             seen = __hip_atomic_load(row_tau + follow_idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           }
           load_tile(g0 + min(it + 1, n_interior - 1) * kBlock, true, bq, bd, bb);
@@ -1007,7 +1165,15 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
           const int j = i & 3;
           const uint32_t uw = j == 0 ? up[0] : j == 1 ? up[1] : j == 2 ? up[2] : up[3];
           const uint32_t lw = j == 0 ? lo[0] : j == 1 ? lo[1] : j == 2 ? lo[2] : lo[3];
-          const double S = exact_race_time(element_word(uw, lw, kr & 1));
+          double S = exact_race_time(element_word(uw, lw, kr & 1));
+          if (MINF) {
+            uint32_t mn[4], hd[4];
+            philox_block(row_lo, (uint32_t)(i >> 2), row_hi, kMinBlock, p.seed_lo, p.seed_hi, mn);
+            philox_block(row_lo, (uint32_t)(i >> 2), row_hi, kHolderBlock, p.seed_lo, p.seed_hi, hd);
+            const double M = exact_race_time(j == 0 ? mn[0] : j == 1 ? mn[1] : j == 2 ? mn[2] : mn[3]) / (double)p.K;
+            const int holder = holder_of(j == 0 ? hd[0] : j == 1 ? hd[1] : j == 2 ? hd[2] : hd[3], p.K);
+            S = (pool || holder == k) ? M : M + S;  // (a pool record is the holder's: the index's smallest time)
+          }
           float temp = Tq;
           float v;
           if (pool) {
@@ -1062,6 +1228,11 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         const int kr = same_race ? 0 : k;
         philox_block(row_lo, (uint32_t)g, row_hi, (uint32_t)(kr >> 1), p.seed_lo, p.seed_hi, up);
         philox_block(row_lo, (uint32_t)g, row_hi, (uint32_t)(kr >> 1) | kLowBlock, p.seed_lo, p.seed_hi, lo);
+        uint32_t mn[4] = {0u, 0u, 0u, 0u}, hd[4] = {0u, 0u, 0u, 0u};
+        if (MINF) {  // (drawn again for every draft: this path is cold, and fewer registers stay live)
+          philox_block(row_lo, (uint32_t)g, row_hi, kMinBlock, p.seed_lo, p.seed_hi, mn);
+          philox_block(row_lo, (uint32_t)g, row_hi, kHolderBlock, p.seed_lo, p.seed_hi, hd);
+        }
         const float tk = p.temp_draft != nullptr ? p.temp_draft[k] : p.temp_draft_all;
         const bool ok = (tk > 0.0f) && (tk < __builtin_huge_valf());
         double bx = __builtin_huge_val();
@@ -1070,7 +1241,11 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         for (int j = 0; j < 4; ++j) {
           const int i = g * 4 + j;
           if (i >= V) continue;
-          const double S = exact_race_time(element_word(up[j], lo[j], kr & 1));
+          double S = exact_race_time(element_word(up[j], lo[j], kr & 1));
+          if (MINF) {
+            const double M = exact_race_time(mn[j]) / (double)p.K;
+            S = holder_of(hd[j], p.K) == k ? M : M + S;
+          }
           const double kx = ok ? exact_key<PROBS>(S, vd[j], (double)tk) : __builtin_huge_val();
           const double ky = with_pool ? exact_key<PROBS>(S, vq[j], (double)Tq) : __builtin_huge_val();
           my_exact += 2;
@@ -1224,10 +1399,10 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
 }
 
 // kt: drafts per workgroup pass (2, 4 or 8; 1 runs as 2: a draft pair shares its blocks).
-template <typename T, bool SHARED>
+template <typename T, bool SHARED, bool MINF>
 hipError_t launch_scan(int kt, bool probs, bool finish, unsigned grid, hipStream_t st, const ScanParams &p) {
-#define LLC_LAUNCH(KB_, PR_, MK_, LS_, FN_)                                                                  \
-  hipLaunchKernelGGL((scan_kernel<T, KB_, SHARED, PR_, MK_, LS_, FN_>), dim3(grid), dim3(kBlock), 0, st, p); \
+#define LLC_LAUNCH(KB_, PR_, MK_, LS_, FN_)                                                                        \
+  hipLaunchKernelGGL((scan_kernel<T, KB_, SHARED, PR_, MK_, LS_, FN_, MINF>), dim3(grid), dim3(kBlock), 0, st, p); \
   return hipGetLastError();
   const bool masked = p.bins != nullptr || p.no_draft != 0 || p.same_race != 0;
   if (p.lse_part != nullptr) {
@@ -1241,8 +1416,8 @@ hipError_t launch_scan(int kt, bool probs, bool finish, unsigned grid, hipStream
     return hipErrorInvalidValue;
   }
   if (masked) {
-    // binned candidates / pool-only passes exist for fp32 log-weights
-    if constexpr (sizeof(typename T::elem) == 4) {
+    // binned candidates / pool-only passes exist for fp32 log-weights, one word per (index, draft)
+    if constexpr (sizeof(typename T::elem) == 4 && !MINF) {
       if (probs || finish) return hipErrorInvalidValue;
       switch (kt) {
         case 2: LLC_LAUNCH(1, false, true, false, false)

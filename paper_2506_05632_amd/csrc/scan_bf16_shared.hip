@@ -1,8 +1,8 @@
-// Instantiates the scan kernel for one (element type, draft layout) pair.
+// Instantiates the scan kernel for one (element type, draft layout) pair, one word per (index, draft).
 #include "scan.hpp"
 
 namespace llc {
 hipError_t launch_scan_bf16_shared(int kt, bool probs, bool finish, unsigned grid, hipStream_t s, const ScanParams &p) {
-  return launch_scan<BF16In, true>(kt, probs, finish, grid, s, p);
+  return launch_scan<BF16In, true, false>(kt, probs, finish, grid, s, p);
 }
 }  // namespace llc

@@ -1,0 +1,8 @@
+// Instantiates the scan kernel for one (element type, draft layout) pair, race times drawn min-first.
+#include "scan.hpp"
+
+namespace llc {
+hipError_t launch_scan_f32_shared_minf(int kt, bool probs, bool finish, unsigned grid, hipStream_t s, const ScanParams &p) {
+  return launch_scan<F32In, true, true>(kt, probs, finish, grid, s, p);
+}
+}  // namespace llc

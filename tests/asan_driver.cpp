@@ -133,7 +133,10 @@ int main() {
     a.tokens = tok.data(); a.tok_stride_s = L * K; a.tok_stride_j = K;
     a.seed = 5; a.row_offset = 11; a.row_stride_s = L + 1; a.row_stride_j = 1; a.strong = strong;
     a.Y = Y.data(); a.n_out = n.data(); a.active = active.data(); a.key = key.data(); a.gap = gap.data(); a.threads = 2;
-    if (llc_verify_ref(&a) != 0) return 2;
+    for (int mf = 0; mf < 2; ++mf) {
+      a.min_first = mf;
+      if (llc_verify_ref(&a) != 0) return 2;
+    }
   }
   std::puts("sanitizer run clean");
   return 0;

@@ -23,7 +23,7 @@ def to_host(t: torch.Tensor):
 
 
 def oracle_rows(draft, target, K, rows, *, kind, temp_target, temp_draft, temp_draft_per_k=None,
-                seed=0, row_offset=0):
+                seed=0, row_offset=0, min_first=False):
     """Oracle on rows [r0, r1) of the batch, keyed as the same global rows."""
     r0, r1 = rows
     d, dt = to_host(draft[r0:r1])
@@ -31,7 +31,7 @@ def oracle_rows(draft, target, K, rows, *, kind, temp_target, temp_draft, temp_d
     tk = None if temp_draft_per_k is None else temp_draft_per_k.detach().cpu().numpy()
     return oracle.couple(d, t, K, dtype=dt, kind=_KIND[kind], temp_target=temp_target,
                          temp_draft=tk, temp_draft_all=temp_draft, seed=seed,
-                         row_offset=row_offset + r0)
+                         row_offset=row_offset + r0, min_first=min_first)
 
 
 def compare(gpu: dict, ref: dict, rows=None, check_keys=True):
@@ -96,3 +96,36 @@ def same_outputs(a: dict, b: dict):
             torch.testing.assert_close(a[name], b[name], rtol=1e-6, atol=0)
         else:
             assert torch.equal(a[name], b[name]), name
+
+
+# Near-ties per configuration (reductions whose runner-up is within 1e-6 of the winner): with keys
+# that are continuous up to the 2^-32 grid of the uniforms, one reduction is a near-tie with
+# probability of the order of 1e-6, so a whole configuration (10^4 reductions) almost surely has
+# none; more than this many would point at a defect, not at chance.
+NEAR_TIE_BOUND = 2
+
+
+def check_all_rows(w, gpu, stats, block, is_form=False, min_first=False):
+    """Every row of the workload against the oracle, `block` rows at a time (host memory), and the
+    device's near-tie counter against the oracle's own count.  Returns the report line's numbers."""
+    mismatches, near_oracle, borderline = 0, 0, 0
+    for r0 in range(0, w.B, block):
+        rows = (r0, min(w.B, r0 + block))
+        if is_form:
+            enc, _ = to_host(w.target[rows[0]:rows[1]])
+            dec, _ = to_host(w.draft[rows[0]:rows[1]])
+            ref = oracle.couple_is(enc, dec, seed=w.seed, row_offset=w.row_offset + rows[0], min_first=min_first)
+        else:
+            ref = oracle_rows(w.draft, w.target, w.K, rows, kind=w.kind, temp_target=w.temp_target,
+                              temp_draft=w.temp_draft, seed=w.seed, row_offset=w.row_offset, min_first=min_first)
+        mismatches += compare(gpu, ref, rows)
+        near_oracle += oracle_near_ties(ref)
+        borderline += oracle_borderline(ref)
+    s = stats_dict(stats)
+    print(f"{w.name}{' (min-first)' if min_first else ''}: {w.B} rows compared, excused mismatches {mismatches}, "
+          f"near-ties oracle {near_oracle} / device {s['near_ties']}, survivors {s['survivors']} of {w.elems}, "
+          f"exact {s['exact_evals']}, slow blocks {s['slow_blocks']}")
+    assert abs(s["near_ties"] - near_oracle) <= borderline
+    assert near_oracle <= NEAR_TIE_BOUND and mismatches <= near_oracle
+    assert s["slow_blocks"] == 0
+    return s

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(binding.EXPORTS)
     for name in names:
         assert getattr(lib, name) is not None
-    assert llc.llc_version() == 108
+    assert llc.llc_version() == 109
     assert llc.llc_status_string(0) == "ok"
     assert "workspace" in llc.llc_status_string(-6)
 
@@ -157,7 +157,7 @@ def _verify_args(**kw):
     (dict(kind=binding.PROBS), -4), (dict(dtype=9), -4),
     (dict(target=0x1002), -5),
     (dict(workspace=None), -6), (dict(workspace_bytes=1024), -6),
-    (dict(k_tile=5), -8), (dict(flags=16), -8),
+    (dict(k_tile=5), -8), (dict(flags=32), -8),
 ])
 def test_verify_argument_errors_are_reported_before_any_launch(kw, code):
     lib = llc.load()

@@ -1,0 +1,223 @@
+"""GPU parity of the min-first way of drawing the race times (LLC_FLAG_MIN_FIRST), through the C ABI.
+
+Same bar as the default generator: X, Y, accept, match_k bit-exact against the oracle run with the
+same construction, near-ties counted, keys within 1e-6; every configuration in full, the launch
+shapes, ragged sizes, draft counts, both layouts, every input kind, edge rows, the verifier.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2506_05632_amd as llc
+from paper_2506_05632_amd import workloads
+from parity_util import check_all_rows, compare, oracle_rows, same_outputs, stats_dict, to_host
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+MF = llc.FLAG_MIN_FIRST
+
+
+def run_gpu(w, **kw):
+    flags = kw.pop("flags", 0) | MF
+    if kw.pop("is_form", False):
+        return llc.llc_couple_is(w.target, w.draft, seed=w.seed, row_offset=w.row_offset, flags=flags, **kw)
+    return llc.llc_couple(w.draft, w.target, w.K, kind=w.kind, temp_target=w.temp_target,
+                          temp_draft=w.temp_draft, seed=w.seed, row_offset=w.row_offset, flags=flags, **kw)
+
+
+@pytest.mark.parametrize("cfg,block", [(1, 64), (2, 256), (3, 128), (4, 64), (5, 512)])
+def test_every_configuration_in_full(cfg, block):
+    w = workloads.make(cfg, DEV)
+    stats = llc.new_stats(DEV)
+    if cfg == 3:
+        plain = run_gpu(w, stats=stats)                 # the launch configuration bench.py times
+        gpu = run_gpu(w, want_keys=True)
+        for name in ("X", "Y", "accept", "match_k"):
+            assert torch.equal(gpu[name], plain[name])
+    else:
+        gpu = run_gpu(w, want_keys=True, stats=stats, is_form=cfg == 5)
+    torch.cuda.synchronize()
+    check_all_rows(w, gpu, stats, block, is_form=cfg == 5, min_first=True)
+    # not the default generator's samples: the two constructions read the stream differently
+    other = llc.llc_couple(w.draft, w.target, w.K, kind=w.kind, temp_target=w.temp_target,
+                           temp_draft=w.temp_draft, seed=w.seed, row_offset=w.row_offset)
+    assert (other["Y"] != gpu["Y"]).float().mean().item() > 0.2
+
+
+def test_results_do_not_depend_on_launch_shape_or_path():
+    w = workloads.make(2, DEV, rows=24)
+    base = run_gpu(w, want_keys=True)
+    ref = oracle_rows(w.draft, w.target, w.K, (0, w.B), kind=w.kind, temp_target=w.temp_target,
+                      temp_draft=w.temp_draft, seed=w.seed, row_offset=w.row_offset, min_first=True)
+    compare(base, ref)
+    for vc in (1, 2, 5, 32):
+        for kt in (1, 2, 4, 8):
+            ws = llc.new_workspace(w.B, w.K, w.V, DEV, v_chunks=vc)
+            same_outputs(base, run_gpu(w, want_keys=True, v_chunks=vc, k_tile=kt, workspace=ws))
+    same_outputs(base, run_gpu(w, want_keys=True, flags=llc.FLAG_EXACT_SCAN))
+    same_outputs(base, run_gpu(w, want_keys=True, flags=llc.FLAG_EXACT_SCAN, v_chunks=3, k_tile=2))
+    w4 = workloads.make(4, DEV, rows=6)
+    base = run_gpu(w4, want_keys=True)
+    ref = oracle_rows(w4.draft, w4.target, w4.K, (0, w4.B), kind=w4.kind, temp_target=w4.temp_target,
+                      temp_draft=w4.temp_draft, seed=w4.seed, row_offset=w4.row_offset, min_first=True)
+    compare(base, ref)
+    for vc, kt in ((1, 8), (7, 2), (3, 4), (16, 1)):
+        same_outputs(base, run_gpu(w4, want_keys=True, v_chunks=vc, k_tile=kt))
+    same_outputs(base, run_gpu(w4, want_keys=True, flags=llc.FLAG_EXACT_SCAN))
+
+
+@pytest.mark.parametrize("V", [1, 3, 5, 255, 1001, 1023, 1025, 4099])
+@pytest.mark.parametrize("K", [1, 3])
+def test_ragged_vocab_sizes(V, K):
+    g = torch.Generator(device=DEV).manual_seed(V * 10 + K)
+    B = 33
+    tq = 2 * torch.randn(B, V, generator=g, device=DEV)
+    td = tq + torch.randn(B, V, generator=g, device=DEV)
+    gpu = llc.llc_couple(td, tq, K, temp_target=0.8, temp_draft=1.3, seed=77, row_offset=(1 << 35) + 3,
+                         want_keys=True, flags=MF)
+    torch.cuda.synchronize()
+    ref = oracle_rows(td, tq, K, (0, B), kind="logits", temp_target=0.8, temp_draft=1.3, seed=77,
+                      row_offset=(1 << 35) + 3, min_first=True)
+    compare(gpu, ref)
+
+
+@pytest.mark.parametrize("K", [1, 2, 5, 8, 9, 17, 40])
+@pytest.mark.parametrize("shared", [True, False])
+def test_draft_counts(K, shared):
+    g = torch.Generator(device=DEV).manual_seed(K + (100 if shared else 0))
+    B, V = 12, 3000
+    tq = 2 * torch.randn(B, V, generator=g, device=DEV)
+    td = tq + torch.randn(B, V, generator=g, device=DEV) if shared else \
+        tq[:, None, :] + torch.randn(B, K, V, generator=g, device=DEV)
+    stats = llc.new_stats(DEV)
+    gpu = llc.llc_couple(td, tq, K, seed=5, want_keys=True, flags=MF, stats=stats)
+    torch.cuda.synchronize()
+    ref = oracle_rows(td, tq, K, (0, B), kind="logits", temp_target=1.0, temp_draft=1.0, seed=5, min_first=True)
+    compare(gpu, ref)
+    assert stats_dict(stats)["slow_blocks"] == 0
+
+
+def test_many_drafts_and_long_rows():
+    g = torch.Generator(device=DEV).manual_seed(300)
+    for K, shared, B, V in ((300, True, 3, 700), (70, False, 3, 700), (65535, True, 2, 37)):
+        tq = 2 * torch.randn(B, V, generator=g, device=DEV)
+        td = tq + torch.randn(B, V, generator=g, device=DEV) if shared else \
+            tq[:, None, :] + torch.randn(B, K, V, generator=g, device=DEV)
+        gpu = llc.llc_couple(td, tq, K, seed=19, want_keys=True, flags=MF)
+        torch.cuda.synchronize()
+        ref = oracle_rows(td, tq, K, (0, B), kind="logits", temp_target=1.0, temp_draft=1.0, seed=19, min_first=True)
+        compare(gpu, ref)
+    V, K = 2_000_003, 3
+    tq = 2 * torch.randn(1, V, generator=g, device=DEV)
+    td = tq + torch.randn(1, V, generator=g, device=DEV)
+    stats = llc.new_stats(DEV)
+    gpu = llc.llc_couple(td, tq, K, seed=2, want_keys=True, stats=stats, flags=MF)
+    torch.cuda.synchronize()
+    ref = oracle_rows(td, tq, K, (0, 1), kind="logits", temp_target=1.0, temp_draft=1.0, seed=2, min_first=True)
+    compare(gpu, ref)
+    assert stats_dict(stats)["slow_blocks"] == 0
+
+
+def test_probability_inputs_temperatures_and_views():
+    g = torch.Generator(device=DEV).manual_seed(4)
+    B, V, K = 40, 5000, 4
+    q = torch.rand(B, V, generator=g, device=DEV) ** 8
+    p = torch.rand(B, K, V, generator=g, device=DEV) ** 8
+    p[:, :, ::7] = 0.0
+    q[:, 5::11] = 0.0
+    p[0, 0, 1] = float("nan"); p[0, 1, 2] = -1.0; q[1, 3] = float("inf")
+    for pp, qq in ((p, q), (p[:, 0].contiguous(), q), (p.to(torch.bfloat16), q.to(torch.bfloat16))):
+        gpu = llc.llc_couple(pp, qq, K, kind="probs", seed=11, want_keys=True, flags=MF)
+        torch.cuda.synchronize()
+        compare(gpu, oracle_rows(pp, qq, K, (0, B), kind="probs", temp_target=1.0, temp_draft=1.0, seed=11, min_first=True))
+    # per-draft temperatures (one row, K temperatures: the per-draft layout)
+    tq = 2 * torch.randn(B, V, generator=g, device=DEV)
+    td = tq + torch.randn(B, V, generator=g, device=DEV)
+    temps = torch.tensor([0.5, 1.0, 1.5, 2.0], dtype=torch.float32, device=DEV)
+    gpu = llc.llc_couple(td, tq, K, temp_target=2.0, temp_draft_per_k=temps, seed=13, want_keys=True, flags=MF)
+    torch.cuda.synchronize()
+    compare(gpu, oracle_rows(td, tq, K, (0, B), kind="logits", temp_target=2.0, temp_draft=1.0,
+                             temp_draft_per_k=temps, seed=13, min_first=True))
+    # odd offsets and strides
+    big_q = torch.randn(11, 2049 + 7, generator=g, device=DEV)
+    big_d = torch.randn(11, 3, 2049 + 5, generator=g, device=DEV)
+    for cast in (lambda t: t, lambda t: t.to(torch.bfloat16)):
+        vq, vd = cast(big_q)[:, 3:3 + 2049], cast(big_d)[:, :, 1:1 + 2049]
+        gpu = llc.llc_couple(vd, vq, 3, seed=9, want_keys=True, flags=MF)
+        torch.cuda.synchronize()
+        compare(gpu, oracle_rows(vd, vq, 3, (0, 11), kind="logits", temp_target=1.0, temp_draft=1.0, seed=9, min_first=True))
+
+
+def test_masked_degenerate_and_one_hot_rows():
+    g = torch.Generator(device=DEV).manual_seed(8)
+    B, V, K = 8, 3001, 3
+    tq = torch.randn(B, V, generator=g, device=DEV)
+    td = torch.randn(B, V, generator=g, device=DEV)
+    ninf = float("-inf")
+    tq[0, :] = ninf
+    td[1, :] = ninf
+    tq[2, :] = ninf; tq[2, 1234] = 0.0
+    td[2, :] = ninf; td[2, 1234] = 3.0
+    td[3, :] = ninf; td[3, 3000] = 0.0
+    tq[4, 100:] = ninf
+    td[5, :2900] = ninf
+    tq[6, 7] = float("nan"); td[6, 9] = float("inf")
+    stats = llc.new_stats(DEV)
+    gpu = llc.llc_couple(td, tq, K, seed=21, want_keys=True, stats=stats, flags=MF)
+    torch.cuda.synchronize()
+    compare(gpu, oracle_rows(td, tq, K, (0, B), kind="logits", temp_target=1.0, temp_draft=1.0, seed=21, min_first=True))
+    assert gpu["Y"][0].item() == -1 and gpu["accept"][0].item() == 0
+    assert (gpu["X"][1] == -1).all() and (gpu["X"][3] == 3000).all()
+    assert stats_dict(stats)["degenerate"] == 1 + K
+    # extreme logits: the prefilter's range is left, the exact scan takes over, results stay exact
+    tq = 300 * torch.randn(6, 5000, generator=g, device=DEV)
+    td = tq + 50 * torch.randn(6, 5000, generator=g, device=DEV)
+    gpu = llc.llc_couple(td, tq, 4, temp_target=0.05, temp_draft=0.05, seed=4, want_keys=True, flags=MF)
+    torch.cuda.synchronize()
+    compare(gpu, oracle_rows(td, tq, 4, (0, 6), kind="logits", temp_target=0.05, temp_draft=0.05, seed=4, min_first=True))
+
+
+def test_identical_distributions_always_accept_and_the_target_ignores_the_drafts():
+    g = torch.Generator(device=DEV).manual_seed(12)
+    B, V, K = 500, 2000, 6
+    tq = 2 * torch.randn(B, V, generator=g, device=DEV)
+    same = llc.llc_couple(tq, tq, K, seed=8, flags=MF)
+    assert same["accept"].all() and (same["match_k"] >= 0).all()
+    a = llc.llc_couple(tq + torch.randn(B, V, generator=g, device=DEV), tq, K, seed=8, flags=MF, want_keys=True)
+    b = llc.llc_couple(3 * torch.randn(B, K, V, generator=g, device=DEV), tq, K, seed=8, flags=MF, want_keys=True)
+    assert torch.equal(a["Y"], b["Y"]) and torch.equal(a["Y"], same["Y"])
+    np.testing.assert_allclose(a["keyY"].cpu().numpy(), b["keyY"].cpu().numpy(), rtol=1e-6)
+
+
+@pytest.mark.parametrize("strong", [False, True])
+def test_verifier(strong):
+    g = torch.Generator(device=DEV).manual_seed(31)
+    S, L, K, V = 24, 4, 5, 3001
+    target = 2 * torch.randn(S, L + 1, K, V, generator=g, device=DEV)
+    tokens = torch.randint(0, V, (S, L, K), generator=g, device=DEV, dtype=torch.int32)
+    # make acceptance likely: draft 0 carries what the verifier picks (one more position per pass)
+    for _ in range(L):
+        ref0 = oracle.verify(target.cpu().numpy(), tokens.cpu().numpy(), seed=9, temp_target=0.9, strong=strong, min_first=True)
+        guess = torch.from_numpy(np.maximum(ref0["Y"][:, :L], 0)).to(DEV)
+        tokens[: S // 2, :, 0] = guess[: S // 2]
+        tokens[:, :2, 1] = guess[:, :2]
+    ref = oracle.verify(target.cpu().numpy(), tokens.cpu().numpy(), seed=9, temp_target=0.9, strong=strong, min_first=True)
+    got = llc.llc_verify(target, tokens, temp_target=0.9, seed=9, strong=strong, flags=MF)
+    torch.cuda.synchronize()
+    assert np.array_equal(got["n_out"].cpu().numpy(), ref["n_out"])
+    assert np.array_equal(got["Y"].cpu().numpy(), ref["Y"])
+    assert ref["n_out"].max() > 2
+    # and it differs from the default generator's verdicts
+    other = llc.llc_verify(target, tokens, temp_target=0.9, seed=9, strong=strong)
+    assert not torch.equal(other["Y"], got["Y"])
+
+
+def test_calls_that_do_not_take_the_flag_refuse_it():
+    g = torch.Generator(device=DEV).manual_seed(1)
+    enc = torch.randn(4, 512, generator=g, device=DEV)
+    dec = torch.randn(4, 2, 512, generator=g, device=DEV)
+    bins = torch.randint(0, 4, (4, 512), generator=g, device=DEV, dtype=torch.uint8)
+    with pytest.raises(llc.LlcError) as e:
+        llc.llc_compress_select(enc, dec, bins, flags=MF)
+    assert e.value.code == -8

@@ -6,7 +6,7 @@ import torch
 import oracle
 import paper_2506_05632_amd as llc
 from paper_2506_05632_amd import workloads
-from parity_util import compare, oracle_borderline, oracle_near_ties, oracle_rows, same_outputs, stats_dict, to_host
+from parity_util import check_all_rows, compare, oracle_borderline, oracle_near_ties, oracle_rows, same_outputs, stats_dict, to_host
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -18,39 +18,6 @@ def run_gpu(w, **kw):
         return llc.llc_couple_is(w.target, w.draft, seed=w.seed, row_offset=w.row_offset, **kw)
     return llc.llc_couple(w.draft, w.target, w.K, kind=kind, temp_target=w.temp_target,
                           temp_draft=w.temp_draft, seed=w.seed, row_offset=w.row_offset, **kw)
-
-
-# Near-ties per configuration (reductions whose runner-up is within 1e-6 of the winner): with keys
-# that are continuous up to the 2^-32 grid of the uniforms, one reduction is a near-tie with
-# probability of the order of 1e-6, so a whole configuration (10^4 reductions) almost surely has
-# none; more than this many would point at a defect, not at chance.
-NEAR_TIE_BOUND = 2
-
-
-def check_all_rows(w, gpu, stats, block, is_form=False):
-    """Every row of the workload against the oracle, `block` rows at a time (host memory), and the
-    device's near-tie counter against the oracle's own count.  Returns the report line's numbers."""
-    mismatches, near_oracle, borderline = 0, 0, 0
-    for r0 in range(0, w.B, block):
-        rows = (r0, min(w.B, r0 + block))
-        if is_form:
-            enc, _ = to_host(w.target[rows[0]:rows[1]])
-            dec, _ = to_host(w.draft[rows[0]:rows[1]])
-            ref = oracle.couple_is(enc, dec, seed=w.seed, row_offset=w.row_offset + rows[0])
-        else:
-            ref = oracle_rows(w.draft, w.target, w.K, rows, kind=w.kind, temp_target=w.temp_target,
-                              temp_draft=w.temp_draft, seed=w.seed, row_offset=w.row_offset)
-        mismatches += compare(gpu, ref, rows)
-        near_oracle += oracle_near_ties(ref)
-        borderline += oracle_borderline(ref)
-    s = stats_dict(stats)
-    print(f"{w.name}: {w.B} rows compared, excused mismatches {mismatches}, near-ties oracle {near_oracle} / "
-          f"device {s['near_ties']}, survivors {s['survivors']} of {w.elems}, exact {s['exact_evals']}, "
-          f"slow blocks {s['slow_blocks']}")
-    assert abs(s["near_ties"] - near_oracle) <= borderline
-    assert near_oracle <= NEAR_TIE_BOUND and mismatches <= near_oracle
-    assert s["slow_blocks"] == 0
-    return s
 
 
 # ------------------------------------------------------------------ the five configurations, every row

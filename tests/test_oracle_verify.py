@@ -12,7 +12,7 @@ import pytest
 from scipy import stats
 
 import oracle
-from oracle import philox_py
+from oracle import gls_py
 
 
 def _markov(rng, V, conc=1.0):
@@ -21,7 +21,7 @@ def _markov(rng, V, conc=1.0):
     return M, np.log(M).astype(np.float32)
 
 
-def _speculate(logMb, logMs, S, L, K, n_tokens, seed, strong=False, draft_temp=1.0):
+def _speculate(logMb, logMs, S, L, K, n_tokens, seed, strong=False, draft_temp=1.0, min_first=False):
     """Run blocks of (draft L tokens with K drafts, verify) until every sequence has n_tokens."""
     V = logMb.shape[0]
     ctx = np.zeros(S, np.int64)                       # context = the last emitted token, start at 0
@@ -36,12 +36,12 @@ def _speculate(logMb, logMs, S, L, K, n_tokens, seed, strong=False, draft_temp=1
             target[:, j] = logMb[prev]
             draft = np.ascontiguousarray(logMs[prev])  # [S, K, V]
             res = oracle.couple(draft, draft[:, 0], K, seed=seed, row_offset=base + j * S,
-                                temp_draft_all=draft_temp)
+                                temp_draft_all=draft_temp, min_first=min_first)
             tokens[:, j] = res["X"]
             prev = res["X"].astype(np.int64)
         target[:, L] = logMb[prev]
         ver = oracle.verify(target, tokens, seed=seed, row_offset=base, row_stride_s=1, row_stride_j=S,
-                            strong=strong)
+                            strong=strong, min_first=min_first)
         for s in range(S):
             n = ver["n_out"][s]
             out[s].extend(int(t) for t in ver["Y"][s, :n])
@@ -51,13 +51,13 @@ def _speculate(logMb, logMs, S, L, K, n_tokens, seed, strong=False, draft_temp=1
     return np.array([o[:n_tokens] for o in out]), n_blocks
 
 
-@pytest.mark.parametrize("strong", [False, True])
-def test_output_follows_the_target_models_autoregressive_law(strong):
+@pytest.mark.parametrize("strong,min_first", [(False, False), (True, False), (False, True), (True, True)])
+def test_output_follows_the_target_models_autoregressive_law(strong, min_first):
     rng = np.random.default_rng(3)
     V, S, L, K, N = 3, 60_000, 2, 2, 3
     Mb, logMb = _markov(rng, V)
     _, logMs = _markov(rng, V)
-    seqs, _ = _speculate(logMb, logMs, S, L, K, N, seed=11, strong=strong)
+    seqs, _ = _speculate(logMb, logMs, S, L, K, N, seed=11, strong=strong, min_first=min_first)
     Mb32 = np.exp(logMb.astype(np.float64))
     Mb32 /= Mb32.sum(axis=1, keepdims=True)
     expected = np.zeros(V ** N)
@@ -73,14 +73,15 @@ def test_output_follows_the_target_models_autoregressive_law(strong):
     assert stats.chisquare(counts, expected * S).pvalue > 1e-4
 
 
-def test_first_token_is_algorithm_1_and_block_length_is_accepted_plus_one():
+@pytest.mark.parametrize("min_first", [False, True])
+def test_first_token_is_algorithm_1_and_block_length_is_accepted_plus_one(min_first):
     rng = np.random.default_rng(5)
     S, K, V = 4000, 3, 12
     q = rng.normal(0, 2, (S, V)).astype(np.float32)
     p = (q + rng.normal(0, 1, (S, V))).astype(np.float32)
-    one = oracle.couple(p, q, K, seed=21)                      # rows 0..S-1
+    one = oracle.couple(p, q, K, seed=21, min_first=min_first)  # rows 0..S-1
     target = np.repeat(np.repeat(q[:, None, None, :], 2, axis=1), K, axis=2)   # [S, 2, K, V]
-    ver = oracle.verify(target, one["X"][:, None, :], seed=21, row_stride_s=1, row_stride_j=S)
+    ver = oracle.verify(target, one["X"][:, None, :], seed=21, row_stride_s=1, row_stride_j=S, min_first=min_first)
     assert np.array_equal(ver["Y"][:, 0], one["Y"])
     np.testing.assert_array_equal(ver["key"][:, 0], one["keyY"])
     assert np.array_equal(ver["n_out"], 1 + one["accept"].astype(np.int32))
@@ -88,21 +89,22 @@ def test_first_token_is_algorithm_1_and_block_length_is_accepted_plus_one():
     assert ((ver["Y"][:, 1] >= 0) == (one["accept"] == 1)).all()
 
 
-def test_matches_a_pure_python_transcription_on_tiny_inputs():
+@pytest.mark.parametrize("min_first", [False, True])
+def test_matches_a_pure_python_transcription_on_tiny_inputs(min_first):
     rng = np.random.default_rng(7)
     S, L, K, V = 60, 3, 3, 5
     target = rng.normal(0, 1.5, (S, L + 1, K, V)).astype(np.float32)
     tokens = rng.integers(0, V, (S, L, K)).astype(np.int32)
     # make acceptance likely: half of the draft tokens are replaced by what the verifier will pick
     seed = 31
-    ver = oracle.verify(target, tokens, seed=seed, temp_target=0.8)
     for strong in (False, True):
-        ver = oracle.verify(target, tokens, seed=seed, temp_target=0.8, strong=strong)
+        ver = oracle.verify(target, tokens, seed=seed, temp_target=0.8, strong=strong, min_first=min_first)
         for s in range(S):
             viable = [True] * K
             Y = []
             for j in range(L + 1):
                 row = s * (L + 1) + j
+                times = gls_py.race_times(seed, row, K, V, min_first)
                 best, arg = math.inf, -1
                 kref = viable.index(True)
                 for k in range(K):
@@ -111,7 +113,7 @@ def test_matches_a_pure_python_transcription_on_tiny_inputs():
                     z = target[s, j, k if viable[k] else kref].astype(np.float64) / np.float64(np.float32(0.8))
                     q = np.exp(z - z.max()) / np.exp(z - z.max()).sum()
                     for i in range(V):
-                        key = philox_py.race_time(philox_py.shared_word(seed, row, k, i)) / q[i]
+                        key = times[k][i] / q[i]
                         if key < best or (key == best and i < arg):
                             best, arg = key, i
                 Y.append(arg)
