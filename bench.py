@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0
 ALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12
 
 
-def algorithmic_lane_ops(K):
+def algorithmic_lane_ops(K, min_first=False):
     """Vector-ALU lane operations per element that the method cannot avoid given how the shared
     uniforms are defined: one Philox4x32-10 block serves 8 elements
     (4 indices x 2 drafts, 16 upper bits each); per block 14 32x32->64 products and 16
@@ -38,7 +38,10 @@ def algorithmic_lane_ops(K):
     xors), 2 + 2 more are shared by the draft pairs of a pass (both instructions issue at full rate
     on gfx950: measured), plus one packed compare per two elements.  The lower 16 bits are drawn
     for about one element in 10^4 and are not counted; nor are threshold construction and
-    everything else the kernel executes."""
+    everything else the kernel executes.  With the race times drawn min-first one block serves four
+    indices whatever K is (a 32-bit word each, none of its rounds shared), plus one compare per index."""
+    if min_first:
+        return (40.0 / 4.0 + 1.0) / K
     pairs = max(1, min(4, (K + 1) // 2))
     return (30.0 + 4.0 / pairs) / 8.0 + 0.5
 
@@ -46,13 +49,17 @@ def algorithmic_lane_ops(K):
 # each scaled by what the counter reads for a plain 1 GiB copy (x2.0 and x1.0); the summaries are
 # under profiles/.  None for workloads that have not been measured.
 MEASURED_TRAFFIC_BYTES = {
-    "largevocab_v128256_k8_f32": 1051.9e6 + 0.1e6,
-    "largevocab_v128256_k8_f32_materialised": 4926.1e6 + 1.9e6,
-    "distinct_v152064_k16_bf16": 2697.6e6 + 2.0e6,
-    "is_n65536_l4_f32": 5381.6e6 + 0.3e6,
-    "specdec_v32000_k4_bf16": 33.3e6 + 0.5e6,
-    "verify_largevocab_s128_l7_k8_v128256": 4214.8e6 + 1.5e6,
-    "lml_largevocab_v128256_k8_f32": 11557.8e6 + 9424.1e6,
+    "largevocab_v128256_k8_f32": 1052.3e6 + 0.3e6,
+    "largevocab_v128256_k8_f32_minfirst": 1052.4e6 + 0.3e6,
+    "largevocab_v128256_k8_f32_keys": 1060.8e6 + 24.3e6,
+    "largevocab_v128256_k8_f32_materialised": 4948.7e6 + 2.0e6,
+    "distinct_v152064_k16_bf16": 2726.6e6 + 2.1e6,
+    "distinct_v152064_k16_bf16_minfirst": 2907.4e6 + 2.2e6,
+    "is_n65536_l4_f32": 5379.9e6 + 0.6e6,
+    "is_n65536_l4_f32_bins16": 2825.0e6 + 0.5e6,
+    "specdec_v32000_k4_bf16": 33.4e6 + 0.5e6,
+    "verify_largevocab_s128_l7_k8_v128256": 4220.0e6 + 10.1e6,
+    "lml_largevocab_v128256_k8_f32": 11557.8e6 + 9397.3e6,
 }
 
 
@@ -392,7 +399,7 @@ def bench_lml(args):
     print(json.dumps(result))
 
 
-def run_cpu_baseline(w, budget_s=12.0, bins=None):
+def run_cpu_baseline(w, budget_s=12.0, bins=None, min_first=False):
     import oracle
     kinds = {"logits": oracle.LOGITS, "probs": oracle.PROBS, "logw": oracle.LOGW}
     cores = oracle.threads()
@@ -407,7 +414,7 @@ def run_cpu_baseline(w, budget_s=12.0, bins=None):
             return time.perf_counter() - t0
         t0 = time.perf_counter()
         oracle.couple(d, t, w.K, dtype=dt, kind=kinds[w.kind], temp_target=w.temp_target,
-                      temp_draft_all=w.temp_draft, seed=w.seed, row_offset=w.row_offset)
+                      temp_draft_all=w.temp_draft, seed=w.seed, row_offset=w.row_offset, min_first=min_first)
         return time.perf_counter() - t0
 
     probe_rows = min(w.B, cores)
@@ -505,7 +512,7 @@ def measure_couple(args, config, *, materialised=False, keys=False, bins=0, rows
     elems = w.elems
     value = elems / (wall / steps) / 1e9
     alg_bytes = algorithmic_bytes(w, materialised)
-    alg_ops = algorithmic_lane_ops(w.K)
+    alg_ops = algorithmic_lane_ops(w.K, min_first)
     alu_achieved = alg_ops * elems / scan_avg_s / 1e12
     name = w.name + ("_materialised" if materialised and w.shared_draft else "")
     if bin_t is not None:
@@ -517,6 +524,8 @@ def measure_couple(args, config, *, materialised=False, keys=False, bins=0, rows
         name += f"_rows{w.B}"
     if min_first:
         name += "_minfirst"
+    if keys:
+        name += "_keys"
     hbm_achieved = alg_bytes / scan_avg_s / 1e9
     alu_frac, hbm_frac = alu_achieved / ALU_PEAK_TLANEOPS, hbm_achieved / HBM_PEAK_GBS
     # The figure of merit is the fraction of the HBM roofline on the algorithmic bytes; the
@@ -560,14 +569,18 @@ def secondary_lines(args):
     out = []
     todo = [("couple", dict(config=3, materialised=True)), ("couple", dict(config=3, keys=True)),
             ("couple", dict(config=4)), ("couple", dict(config=5)), ("couple", dict(config=5, bins=16)),
-            ("couple", dict(config=2)), ("verify", dict(strong=False)), ("verify", dict(strong=True))]
+            ("couple", dict(config=2)), ("verify", dict(strong=False)), ("verify", dict(strong=True)),
+            # the same workloads with the race times drawn min-first (LLC_FLAG_MIN_FIRST)
+            ("couple", dict(config=3, min_first=True)), ("couple", dict(config=3, keys=True, min_first=True)),
+            ("couple", dict(config=4, min_first=True)), ("couple", dict(config=5, min_first=True)),
+            ("couple", dict(config=2, min_first=True))]
     for kind, kw in todo:
         if kind == "couple":
             r = measure_couple(args, steps=30, warmup=10, **kw)
         else:
             r = measure_verify(args, steps=30, warmup=10, **kw)
         rl = r["roofline"]
-        out.append({"workload": r["config"]["workload"] + ("_keys" if kw.get("keys") else ""),
+        out.append({"workload": r["config"]["workload"],
                     "value": r["value"], "unit": "Gelem/s", "ms_per_step": r["ms_per_step"], "steps": r["steps"],
                     "kernel_ms": rl["kernel_ms"], "frac": rl["frac"], "bound": rl["bound"],
                     "algorithmic_bytes": rl["algorithmic_bytes"], "traffic": rl["traffic"],
@@ -633,8 +646,8 @@ def main():
         "roofline": r["roofline"],
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = run_cpu_baseline(w, bins=bins)
-    headline = (args.config == 3 and not (args.materialised or args.keys or args.bins or args.rows
+        result["cpu_baseline"] = run_cpu_baseline(w, bins=bins, min_first=args.min_first)
+    headline = (args.config == 3 and not (args.materialised or args.keys or args.bins or args.rows or args.min_first
                                           or args.v_chunks or args.k_tile or args.calibrate_copy))
     if headline and not args.no_secondary:
         del w, bins
