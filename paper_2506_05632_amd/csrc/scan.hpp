@@ -854,7 +854,37 @@ __global__ void __launch_bounds__(kBlock, (SHARED || KB <= 2) ? 4 : 2) scan_kern
         // its draft holds the smallest time, that time goes to level 2 for the draft and the pool;
         // if not, its draft's time is the smallest plus that of its own word, which can only matter
         // if the word alone passes the draft's bound (half-word first, as in the other variant).
-        unsigned long long todo = __ballot(F >= kCapHot || mx >= ~threshold_of(F));
+        const bool hit = F >= kCapHot || mx >= ~threshold_of(F);
+        unsigned long long todo = 0ull;
+        if (__ballot(hit) != 0ull) {
+          // The tile's one threshold is that of its largest value: most hits are another index's word
+          // under it.  The lane first tests each of its indices against the index's own exponent
+          // (still the loosest over the drafts, merged with the pool's); only what is left is worth
+          // the wave's time.
+          bool real = false;
+          if (hit) {
+            float vq[4];
+            unpack(rq, vq);
+            const float OYl = load_offset(&s.OL[KT]);
+            float Fj[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) Fj[j] = fmaf(level1_value<PROBS>(vq[j]), cq23, OYl);
+#pragma unroll
+            for (int kk = 0; kk < KD; ++kk) {
+              float vd[4];
+              unpack(rd[kk], vd);
+              const float OXl = load_offset(&s.OL[kk]);
+#pragma unroll
+              for (int j = 0; j < 4; ++j) Fj[j] = fmaxf(Fj[j], fmaf(level1_value<PROBS>(vd[j]), cd23[kk], OXl));
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const float Fc = __builtin_amdgcn_fmed3f(Fj[j], 0.0f, kCapHot);
+              real = real || Fc >= kCapHot || mn[0][j] >= ~threshold_of(Fc);
+            }
+          }
+          todo = __ballot(real);
+        }
         if (todo != 0ull) {
           const int lane = tid & 63;
           Lds::Stage &st = s.stage[tid >> 6];
