@@ -212,6 +212,25 @@ def test_dry_run_plans_the_other_calls_too():
         assert lib.llc_couple(ctypes.byref(a)) == -6
 
 
+def test_the_min_first_flag_is_planned_like_the_default_and_refused_where_it_is_not_built():
+    lib = llc.load()
+    mf = binding.FLAG_MIN_FIRST | binding.FLAG_DRY_RUN
+    for B, K, V in [(1024, 8, 128256), (512, 16, 152064), (7, 65535, 37)]:
+        need = llc.llc_couple_workspace_size(B, K, V)
+        for sk in (0, V):
+            a = _args(B=B, K=K, V=V, draft_stride_b=max(sk * K, V), draft_stride_k=sk, target_stride_b=V,
+                      workspace_bytes=need, flags=mf)
+            assert lib.llc_couple(ctypes.byref(a)) == 0
+    a = _verify_args(flags=mf)
+    a.workspace_bytes = llc.llc_verify_workspace_size(a.S, a.L, a.K, a.V)
+    assert lib.llc_verify(ctypes.byref(a)) == 0
+    a = _verify_args(flags=mf | binding.FLAG_STRONG)
+    a.workspace_bytes = llc.llc_verify_workspace_size(a.S, a.L, a.K, a.V)
+    assert lib.llc_verify(ctypes.byref(a)) == 0
+    # the binned passes draw one word per (index, draft) only
+    assert lib.llc_compress_select(ctypes.byref(_select_args(flags=mf))) == -8
+
+
 def _topm_args(**kw):
     a = binding.TopmArgs()
     a.B, a.K, a.Md, a.Mt = 4, 2, 8, 8

@@ -47,6 +47,8 @@ def test_two_calls_in_a_row_the_second_smaller():
     _both(td, tq, K, seed=11, temp_target=0.9, temp_draft=1.1)
     # and the first shape once more, after the smaller call has left its results in the array
     _both(w.draft, w.target, w.K, temp_target=w.temp_target, temp_draft=w.temp_draft, seed=w.seed + 1)
+    # the race times drawn min-first go through the same entry point
+    _both(td, tq, K, seed=11, temp_target=0.9, temp_draft=1.1, flags=llc.FLAG_MIN_FIRST)
 
 
 def test_the_headline_shape_fits_and_an_oversized_one_is_refused_up_front():
