@@ -134,7 +134,7 @@ typedef struct llc_couple_args {
   void *workspace;          /* device, 256-byte aligned, >= llc_couple_workspace_size()  */
   size_t workspace_bytes;
   void *stream;             /* hipStream_t; NULL = the default stream                    */
-  int32_t flags;            /* LLC_FLAG_*                                                */
+  int32_t flags;            /* LLC_FLAG_EXACT_SCAN | LLC_FLAG_DRY_RUN | LLC_FLAG_MIN_FIRST     */
   int32_t v_chunks;         /* 0 = choose; else split V over this many workgroups (1..4096).
                                Results do not depend on it.                              */
   int32_t k_tile;           /* 0 = choose; else drafts per workgroup pass: 2, 4 or 8 (1 is
@@ -167,7 +167,7 @@ typedef struct llc_couple_is_args {
   void *workspace;          /* >= llc_couple_workspace_size(B, L, N) */
   size_t workspace_bytes;
   void *stream;
-  int32_t flags, v_chunks, k_tile;
+  int32_t flags, v_chunks, k_tile;   /* as in llc_couple_args */
   void *ev_scan_begin, *ev_scan_end; /* as in llc_couple_args */
 } llc_couple_is_args;
 
@@ -277,7 +277,7 @@ typedef struct llc_verify_args {
   void *workspace;          /* device, 256-byte aligned, >= llc_verify_workspace_size()  */
   size_t workspace_bytes;
   void *stream;
-  int32_t flags, v_chunks, k_tile;   /* as in llc_couple_args                            */
+  int32_t flags, v_chunks, k_tile;   /* as in llc_couple_args, and LLC_FLAG_STRONG       */
   void *ev_scan_begin, *ev_scan_end; /* as in llc_couple_args                            */
 } llc_verify_args;
 
