@@ -137,7 +137,7 @@ def run_cpu_baseline_verify(w, budget_s=12.0):
                       f"first rejection, the GPU path evaluates every position)"}
 
 
-def measure_verify(args, *, strong=False, steps=None, warmup=None, want_workload=False):
+def measure_verify(args, *, strong=False, steps=None, warmup=None, want_workload=False, min_first=None):
     import torch
     import paper_2506_05632_amd as llc
     from paper_2506_05632_amd import workloads
@@ -145,6 +145,8 @@ def measure_verify(args, *, strong=False, steps=None, warmup=None, want_workload
     steps = steps or args.steps
     warmup = args.warmup if warmup is None else warmup
     dev = "cuda:0"
+    min_first = args.min_first if min_first is None else min_first
+    flags = llc.FLAG_MIN_FIRST if min_first else 0
     w = workloads.make_verify("largevocab", dev)
     ws = torch.empty(llc.llc_verify_workspace_size(w.S, w.L, w.K, w.V), dtype=torch.uint8, device=dev)
     out = {"Y": torch.empty(w.S, w.L + 1, dtype=torch.int32, device=dev),
@@ -154,7 +156,7 @@ def measure_verify(args, *, strong=False, steps=None, warmup=None, want_workload
 
     def step(i=None, stats=None):
         llc.llc_verify(w.target, w.tokens, temp_target=w.temp_target, seed=w.seed + (0 if i is None else i),
-                       workspace=ws, out=out, v_chunks=args.v_chunks, k_tile=args.k_tile,
+                       workspace=ws, out=out, v_chunks=args.v_chunks, k_tile=args.k_tile, flags=flags,
                        scan_events=None if i is None else ev.pairs[i], strong=strong, stats=stats)
 
     for _ in range(warmup):
@@ -194,7 +196,8 @@ def measure_verify(args, *, strong=False, steps=None, warmup=None, want_workload
                 "hbm_frac": hbm_frac, "alu_frac": alu_frac,
                 "step_hbm_frac": alg_bytes / (wall / steps) / 1e9 / HBM_PEAK_GBS}
     res = {"value": elems / (wall / steps) / 1e9, "ms_per_step": wall / steps * 1e3, "steps": steps, "warmup": warmup,
-           "config": {"workload": w.name + ("_strong" if strong else ""), "S": w.S, "L": w.L, "K": w.K, "V": w.V,
+           "config": {"workload": w.name + ("_strong" if strong else "") + ("_minfirst" if min_first else ""),
+                      "S": w.S, "L": w.L, "K": w.K, "V": w.V,
                       "input_dtype": str(w.dtype), "temperature": w.temp_target,
                       "outputs": "Y,n_out,active",
                       "mean_tokens_per_block": float(out["n_out"].float().mean()),
