@@ -345,6 +345,13 @@ __device__ __forceinline__ double exact_key(double S, float v, double T) {
   return log(S) - (double)v / T;
 }
 
+// LSE with one shared proposal: the lanes' two running sums, kept in LDS (the other variants carry
+// an empty stand-in).
+template <bool ON, int N>
+struct LaneSums { double v[N][kBlock]; };
+template <int N>
+struct LaneSums<false, N> { double v[1][1]; };
+
 struct Lds {
   int tau[9];            // ordered-int log2 keys: drafts 0..KT-1, pool at [KT]
   int O[9];              // bits of the level-1 offsets (tau + slack + bias) 2^23; shared layout: [0] = max over drafts
@@ -524,6 +531,9 @@ __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE 
   constexpr int KT = 2 * KB;
   static_assert(!(MINF && MASKED), "the binned and pool-only passes draw one word per (index, draft)");
   __shared__ Lds s;
+  // (with per-draft rows the sums stay in registers: in LDS they measured slower there)
+  constexpr bool kSumsInLds = LSE && SHARED;
+  __shared__ LaneSums<kSumsInLds, 2> sums;
 
   const int tid = threadIdx.x;
   // Workgroups are handed to the 8 XCDs round-robin by index.  Renumber them so that the
@@ -638,6 +648,13 @@ __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE 
   float lse_m[NL];
 #pragma unroll
   for (int kk = 0; kk < NL; ++kk) { lse_acc[kk] = 0.0; lse_m[kk] = -__builtin_huge_valf(); }
+  // With one shared proposal the two running sums live in LDS: the kernel has no two registers to
+  // spare for them across the main loop, and the compiler's own choice, scratch memory, costs a
+  // round trip through the memory system per tile.
+  if (kSumsInLds) {
+#pragma unroll
+    for (int kk = 0; kk < NL; ++kk) sums.v[kSumsInLds ? kk : 0][tid] = 0.0;
+  }
 
   if (tid < 9) {
     // unused draft slots sit at -inf so the shared layout's max over drafts ignores them
@@ -811,7 +828,9 @@ __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE 
         if (gm > lse_m[sl]) {
           if (lse_m[sl] > -__builtin_huge_valf()) {
             const float d = lse_m[sl] - gm;
-            lse_acc[sl] *= (double)__builtin_amdgcn_exp2f(fmaf(d, lse_hi[slot], d * lse_lo[slot]));
+            const double f = (double)__builtin_amdgcn_exp2f(fmaf(d, lse_hi[slot], d * lse_lo[slot]));
+            if (kSumsInLds) sums.v[kSumsInLds ? sl : 0][tid] *= f;
+            else lse_acc[sl] *= f;
           }
           lse_m[sl] = gm;
         }
@@ -824,7 +843,8 @@ __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE 
             const float d = fmaxf(w[j] - lse_m[sl], -65536.0f);
             part += __builtin_amdgcn_exp2f(fmaf(d, lse_hi[slot], d * lse_lo[slot]));
           }
-          lse_acc[sl] += (double)part;
+          if (kSumsInLds) sums.v[kSumsInLds ? sl : 0][tid] += (double)part;
+          else lse_acc[sl] += (double)part;
         }
       };
       // min-first: one block holds the four indices' smallest race times, one word each; the tile's
@@ -1334,7 +1354,11 @@ __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE 
       for (int d = 32; d >= 1; d >>= 1) wm = fmaxf(wm, __shfl_xor(wm, d));
       double v = 0.0;
       if (m > -__builtin_huge_valf())
-        v = lse_acc[lidx(kk)] * exp2(((double)m - (double)wm) * ((double)lse_hi[kk] + (double)lse_lo[kk]));
+        {
+          double acc = lse_acc[lidx(kk)];
+          if (kSumsInLds) acc = sums.v[kSumsInLds ? lidx(kk) : 0][tid];
+          v = acc * exp2(((double)m - (double)wm) * ((double)lse_hi[kk] + (double)lse_lo[kk]));
+        }
 #pragma unroll
       for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
       if ((tid & 63) == 0) { s.lse_wave[wv][kk] = v; s.lse_wmax[wv][kk] = wm; }
