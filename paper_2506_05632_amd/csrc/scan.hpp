@@ -522,11 +522,11 @@ __device__ double chunk_lse_exact(const typename T::elem *row, int g_begin, int 
 // them (logit kinds), so that no second pass over the inputs is needed.
 // FIN: the variant for rows that are one workgroup each: it also takes the finalize step (Algorithm
 // 1's accept test and the outputs), so that no finalize launch follows.
-// MINF: the race times are drawn min-first (see the top of the file).  (With per-draft rows and the
-// normalisers' sums it does not fit 128 registers without spilling inside the main loop: that variant
-// runs with two workgroups per CU.)
+// MINF: the race times are drawn min-first (see the top of the file).  (Together with the
+// normalisers' sums it does not fit 128 registers without spilling inside the main loop: those
+// variants run with two workgroups per CU.)
 template <typename T, int KB, bool SHARED, bool PROBS, bool MASKED, bool LSE, bool FIN, bool MINF>
-__global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE && !SHARED)) ? 4 : 2) scan_kernel(const ScanParams p) {
+__global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE)) ? 4 : 2) scan_kernel(const ScanParams p) {
   using elem = typename T::elem;
   constexpr int KT = 2 * KB;
   static_assert(!(MINF && MASKED), "the binned and pool-only passes draw one word per (index, draft)");
