@@ -31,6 +31,22 @@ def test_library_exports_every_declared_symbol():
     assert "workspace" in llc.llc_status_string(-6)
 
 
+def test_probe_library_exports_its_declared_symbol_and_its_header_is_plain_c(tmp_path):
+    # the machine probes of the benchmark live in a library of their own (no compute call here)
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "llc_probe.h")).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(llc_[a-z_]+)\s*\(", text)))
+    assert names == ["llc_probe_run"]
+    lib = ctypes.CDLL(os.path.join(ROOT, "paper_2506_05632_amd", "libllc_probe.so"))
+    for name in names:
+        assert getattr(lib, name) is not None
+    src = tmp_path / "probe.c"
+    src.write_text('#include "llc_probe.h"\nint main(void){ return LLC_PROBE_PHILOX_READ == 6 ? 0 : 1; }\n')
+    exe = tmp_path / "probe"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    assert subprocess.run([str(exe)]).returncode == 0
+
+
 def test_header_is_plain_c_and_matches_the_binding_layout(tmp_path):
     src = tmp_path / "layout.c"
     src.write_text(
