@@ -435,7 +435,7 @@ def run_cpu_baseline(w, budget_s=12.0, bins=None, min_first=False):
 
 
 def measure_couple(args, config, *, materialised=False, keys=False, bins=0, rows=0, steps=None, warmup=None,
-                   want_workload=False, min_first=None):
+                   want_workload=False, min_first=None, draft_only=None):
     """Time llc_couple (or, with bins, llc_compress_select) on one configuration; returns the
     fields of a bench line (without cpu_baseline)."""
     import torch
@@ -445,7 +445,8 @@ def measure_couple(args, config, *, materialised=False, keys=False, bins=0, rows
     steps = steps or args.steps
     warmup = args.warmup if warmup is None else warmup
     min_first = args.min_first if min_first is None else min_first
-    flags = llc.FLAG_MIN_FIRST if min_first else 0
+    draft_only = args.draft_only if draft_only is None else draft_only
+    flags = (llc.FLAG_MIN_FIRST if min_first else 0) | (llc.FLAG_DRAFT_ONLY if draft_only else 0)
     every = max(1, args.event_every)   # the scan kernel is timed on every `every`-th step of the timed region
     dev = "cuda:0"
     w = workloads.make(config, dev, rows=rows or None)
@@ -460,6 +461,9 @@ def measure_couple(args, config, *, materialised=False, keys=False, bins=0, rows
     if keys:
         out["keyX"] = torch.empty(w.B, w.K, dtype=torch.float32, device=dev)
         out["keyY"] = torch.empty(w.B, dtype=torch.float32, device=dev)
+    if draft_only:   # the drafters' step of Algorithm 2: no target, no Y, no accept test
+        assert not bins, "--draft-only goes with llc_couple"
+        out = {k: v for k, v in out.items() if k in ("X", "keyX")}
     ev = HipEvents(steps)
 
     bin_t, decode = None, {}
@@ -484,7 +488,7 @@ def measure_couple(args, config, *, materialised=False, keys=False, bins=0, rows
                                     k_tile=args.k_tile, scan_events=None if (i is None or i % every) else ev.pairs[i],
                                     stats=stats, **decode)
             return
-        llc.llc_couple(draft, w.target, w.K, kind=w.kind, temp_target=w.temp_target,
+        llc.llc_couple(draft, None if draft_only else w.target, w.K, kind=w.kind, temp_target=w.temp_target,
                        temp_draft=w.temp_draft, seed=w.seed + (0 if i is None else i),
                        row_offset=w.row_offset, workspace=ws, out=out,
                        v_chunks=args.v_chunks, k_tile=args.k_tile, flags=flags,
@@ -517,6 +521,8 @@ def measure_couple(args, config, *, materialised=False, keys=False, bins=0, rows
     elems = w.elems
     value = elems / (wall / steps) / 1e9
     alg_bytes = algorithmic_bytes(w, materialised)
+    if draft_only:
+        alg_bytes -= w.B * w.V * (4 if str(w.dtype).endswith("float32") else 2)   # the target row is not read
     alg_ops = algorithmic_lane_ops(w.K, min_first)
     alu_achieved = alg_ops * elems / scan_avg_s / 1e12
     name = w.name + ("_materialised" if materialised and w.shared_draft else "")
@@ -531,6 +537,8 @@ def measure_couple(args, config, *, materialised=False, keys=False, bins=0, rows
         name += "_minfirst"
     if keys:
         name += "_keys"
+    if draft_only:
+        name += "_draftonly"
     hbm_achieved = alg_bytes / scan_avg_s / 1e9
     alu_frac, hbm_frac = alu_achieved / ALU_PEAK_TLANEOPS, hbm_achieved / HBM_PEAK_GBS
     # The figure of merit is the fraction of the HBM roofline on the algorithmic bytes; the
@@ -548,8 +556,8 @@ def measure_couple(args, config, *, materialised=False, keys=False, bins=0, rows
                 "temperature": w.temp_target,
                 "draft_layout": "[B,K,V]" if (materialised or not w.shared_draft) else "[B,V] shared by the K drafts",
                 "race_times": "min-first (LLC_FLAG_MIN_FIRST)" if min_first else "one word per (k, i)",
-                "outputs": "X,Y,accept,match_k" + (",keyX,keyY" if keys else ""),
-                "accept_rate": float(out["accept"].float().mean()),
+                "outputs": ("X" + (",keyX" if keys else "")) if draft_only else "X,Y,accept,match_k" + (",keyX,keyY" if keys else ""),
+                "accept_rate": None if draft_only else float(out["accept"].float().mean()),
                 "near_ties": counters["near_ties"], "prefilter_survivors": counters["survivors"],
                 "exact_evaluations": counters["exact_evals"], "slow_blocks": counters["slow_blocks"]}
     if bin_t is not None:
@@ -578,7 +586,10 @@ def secondary_lines(args):
             # the same workloads with the race times drawn min-first (LLC_FLAG_MIN_FIRST)
             ("couple", dict(config=3, min_first=True)), ("couple", dict(config=3, keys=True, min_first=True)),
             ("couple", dict(config=4, min_first=True)), ("couple", dict(config=5, min_first=True)),
-            ("couple", dict(config=2, min_first=True))]
+            ("couple", dict(config=2, min_first=True)),
+            # the drafters' step of Algorithm 2 (LLC_FLAG_DRAFT_ONLY: the draft side alone)
+            ("couple", dict(config=3, draft_only=True)), ("couple", dict(config=3, draft_only=True, min_first=True)),
+            ("couple", dict(config=4, draft_only=True))]
     for kind, kw in todo:
         if kind == "couple":
             r = measure_couple(args, steps=30, warmup=10, **kw)
@@ -613,6 +624,8 @@ def main():
     ap.add_argument("--keys", action="store_true", help="also produce the winning keys (adds the normaliser pass)")
     ap.add_argument("--min-first", action="store_true",
                     help="draw the race times min-first (LLC_FLAG_MIN_FIRST) instead of one word per (k, i)")
+    ap.add_argument("--draft-only", action="store_true",
+                    help="the draft side alone (LLC_FLAG_DRAFT_ONLY): the drafters' step of Algorithm 2")
     ap.add_argument("--event-every", type=int, default=4,
                     help="record the event pair around the scan kernel on every N-th timed step only (an event "
                          "pair costs about 1.5 us of the step it brackets: 2 %% of the headline step, 13 %% of config 2's)")
@@ -655,7 +668,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = run_cpu_baseline(w, bins=bins, min_first=args.min_first)
-    headline = (args.config == 3 and not (args.materialised or args.keys or args.bins or args.rows or args.min_first
+    headline = (args.config == 3 and not (args.materialised or args.keys or args.bins or args.rows or args.min_first or args.draft_only
                                           or args.v_chunks or args.k_tile or args.calibrate_copy))
     if headline and not args.no_secondary:
         del w, bins

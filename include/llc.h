@@ -28,7 +28,7 @@
 extern "C" {
 #endif
 
-#define LLC_VERSION 109
+#define LLC_VERSION 110
 
 enum {
   LLC_OK = 0,
@@ -64,6 +64,13 @@ enum {
                               the arguments, plan every launch of the call and check the
                               workspace against the plan, then return without launching
                               anything (no pointer is dereferenced)                    */
+  LLC_FLAG_DRAFT_ONLY = 32,/* llc_couple, llc_couple_static, llc_couple_is: the draft side alone, i.e. the
+                              drafters' step of Algorithm 2 (Section 4.2: every draft k samples its
+                              next token X^(k) = argmin_i S_i^(k) / p_i^(k) with the randomness that
+                              the verification of the same position will use).  No target is read
+                              and nothing is written to Y, accept, match_k, keyY: those pointers,
+                              `target` and its stride may be NULL / 0.  X and keyX are as without
+                              the flag                                                  */
   LLC_FLAG_MIN_FIRST = 16  /* llc_couple, llc_couple_static, llc_couple_is, llc_verify: how Algorithm 1's
                               first step draws its K N independent Exp(1) race times from the row's
                               stream.  Default: one 32-bit word per (k, i), S = -ln U.  With this flag
@@ -134,7 +141,7 @@ typedef struct llc_couple_args {
   void *workspace;          /* device, 256-byte aligned, >= llc_couple_workspace_size()  */
   size_t workspace_bytes;
   void *stream;             /* hipStream_t; NULL = the default stream                    */
-  int32_t flags;            /* LLC_FLAG_EXACT_SCAN | LLC_FLAG_DRY_RUN | LLC_FLAG_MIN_FIRST     */
+  int32_t flags;            /* LLC_FLAG_EXACT_SCAN | _DRY_RUN | _MIN_FIRST | _DRAFT_ONLY        */
   int32_t v_chunks;         /* 0 = choose; else split V over this many workgroups (1..4096).
                                Results do not depend on it.                              */
   int32_t k_tile;           /* 0 = choose; else drafts per workgroup pass: 2, 4 or 8 (1 is

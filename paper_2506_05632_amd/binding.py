@@ -20,6 +20,7 @@ FLAG_STRONG = 2
 FLAG_DRY_RUN = 4
 FLAG_SHARED_RACE = 8
 FLAG_MIN_FIRST = 16  # the K race times of an index are drawn through their minimum (see llc.h)
+FLAG_DRAFT_ONLY = 32  # the draft side alone: no target, no Y, no accept test
 
 _KINDS = {"logits": LOGITS, "probs": PROBS, "logw": LOGW}
 EXPORTS = ["llc_couple", "llc_couple_static", "llc_couple_is", "llc_couple_topm", "llc_compress_select", "llc_verify", "llc_lml_bound",
@@ -245,16 +246,20 @@ def llc_couple(draft: torch.Tensor, target: torch.Tensor, K: int, *, kind="logit
     draft: [B,V] (the K drafts of a row share it) or [B,K,V]; target: [B,V]; both
     float32 or bfloat16 with a contiguous last dimension.  Returns device tensors
     X [B,K] int32, Y [B] int32, accept [B] uint8 and, if asked, match_k, keyX, keyY.
+    With flags & FLAG_DRAFT_ONLY the target may be None: only X (and keyX) come back.
     The call is asynchronous on torch's current stream.
     """
     lib = load()
-    if not (draft.is_cuda and target.is_cuda):
+    draft_only = (flags & FLAG_DRAFT_ONLY) != 0
+    if draft_only:
+        target = None
+    if not (draft.is_cuda and (draft_only or target.is_cuda)):
         raise ValueError("llc_couple needs device tensors (there is no CPU path)")
-    if draft.dtype != target.dtype or draft.dtype not in (torch.float32, torch.bfloat16):
+    if draft.dtype not in (torch.float32, torch.bfloat16) or not (draft_only or draft.dtype == target.dtype):
         raise ValueError("draft and target must both be float32 or both bfloat16")
-    if draft.stride(-1) != 1 or target.stride(-1) != 1 or target.dim() != 2:
+    if draft.stride(-1) != 1 or not (draft_only or (target.stride(-1) == 1 and target.dim() == 2)):
         raise ValueError("last dimension must be contiguous; target must be [B,V]")
-    B, V = target.shape
+    B, V = (draft.shape[0], draft.shape[-1]) if draft_only else target.shape
     if draft.dim() == 2:
         if tuple(draft.shape) != (B, V):
             raise ValueError("draft must be [B,V] or [B,K,V]")
@@ -263,16 +268,18 @@ def llc_couple(draft: torch.Tensor, target: torch.Tensor, K: int, *, kind="logit
         if tuple(draft.shape) != (B, K, V):
             raise ValueError("draft must be [B,V] or [B,K,V]")
         sb, sk = draft.stride(0), draft.stride(1)
-    dev = target.device
+    dev = draft.device
     if out is None:
-        out = {"X": torch.empty(B, K, dtype=torch.int32, device=dev),
-               "Y": torch.empty(B, dtype=torch.int32, device=dev),
-               "accept": torch.empty(B, dtype=torch.uint8, device=dev)}
-        if want_match:
-            out["match_k"] = torch.empty(B, dtype=torch.int32, device=dev)
+        out = {"X": torch.empty(B, K, dtype=torch.int32, device=dev)}
+        if not draft_only:
+            out["Y"] = torch.empty(B, dtype=torch.int32, device=dev)
+            out["accept"] = torch.empty(B, dtype=torch.uint8, device=dev)
+            if want_match:
+                out["match_k"] = torch.empty(B, dtype=torch.int32, device=dev)
         if want_keys:
             out["keyX"] = torch.empty(B, K, dtype=torch.float32, device=dev)
-            out["keyY"] = torch.empty(B, dtype=torch.float32, device=dev)
+            if not draft_only:
+                out["keyY"] = torch.empty(B, dtype=torch.float32, device=dev)
     if workspace is None and not _static:
         workspace = new_workspace(B, K, V, dev)
     a = CoupleArgs()
@@ -280,14 +287,15 @@ def llc_couple(draft: torch.Tensor, target: torch.Tensor, K: int, *, kind="logit
     a.dtype = F32 if draft.dtype == torch.float32 else BF16
     a.kind = _KINDS[kind]
     a.draft, a.draft_stride_b, a.draft_stride_k = draft.data_ptr(), sb, sk
-    a.target, a.target_stride_b = target.data_ptr(), target.stride(0)
+    if not draft_only:
+        a.target, a.target_stride_b = target.data_ptr(), target.stride(0)
     a.temp_target, a.temp_draft_all = temp_target, temp_draft
     if temp_draft_per_k is not None:
         if temp_draft_per_k.dtype != torch.float32 or temp_draft_per_k.numel() != K or not temp_draft_per_k.is_cuda:
             raise ValueError("temp_draft_per_k must be K float32 values on the device")
         a.temp_draft = temp_draft_per_k.data_ptr()
     a.seed, a.row_offset = seed, row_offset
-    a.X, a.Y, a.accept = out["X"].data_ptr(), out["Y"].data_ptr(), out["accept"].data_ptr()
+    a.X, a.Y, a.accept = out["X"].data_ptr(), _ptr(out.get("Y")), _ptr(out.get("accept"))
     a.match_k = _ptr(out.get("match_k"))
     a.keyX, a.keyY = _ptr(out.get("keyX")), _ptr(out.get("keyY"))
     a.stats = _ptr(stats)
@@ -311,7 +319,7 @@ def llc_couple_static(draft: torch.Tensor, target: torch.Tensor, K: int, *, out:
     that may overlap in time race on the array."""
     if kw.get("workspace") is not None:
         raise ValueError("llc_couple_static takes no workspace")
-    with torch.cuda.device(target.device):
+    with torch.cuda.device(draft.device):
         return llc_couple(draft, target, K, out=out, _static=True, **kw)
 
 
@@ -495,7 +503,7 @@ def llc_couple_topm(draft_ids: torch.Tensor, draft_val: torch.Tensor, target_ids
             raise ValueError("temp_draft_per_k must be K float32 values on the device")
         a.temp_draft = temp_draft_per_k.data_ptr()
     a.seed, a.row_offset = seed, row_offset
-    a.X, a.Y, a.accept = out["X"].data_ptr(), out["Y"].data_ptr(), out["accept"].data_ptr()
+    a.X, a.Y, a.accept = out["X"].data_ptr(), _ptr(out.get("Y")), _ptr(out.get("accept"))
     a.match_k = _ptr(out.get("match_k"))
     a.keyX, a.keyY = _ptr(out.get("keyX")), _ptr(out.get("keyY"))
     a.stats = _ptr(stats)

@@ -349,23 +349,27 @@ int couple_on(const llc_couple_args *a, void *workspace, size_t workspace_bytes)
   if (a == nullptr) return LLC_E_NULL;
   if (!shape_ok(a->B, a->K, a->V)) return LLC_E_SHAPE;
   if (a->B == 0) return LLC_OK;  // nothing to read or write: pointers may be NULL
-  if (a->draft == nullptr || a->target == nullptr || a->X == nullptr || a->Y == nullptr ||
-      a->accept == nullptr)
-    return LLC_E_NULL;
-  if (a->draft_stride_b < 0 || a->draft_stride_k < 0 || a->target_stride_b < 0) return LLC_E_SHAPE;
+  // the drafters' step of Algorithm 2: the draft side alone (no target is read, no Y, no accept test)
+  const bool draft_only = (a->flags & LLC_FLAG_DRAFT_ONLY) != 0;
+  if (a->draft == nullptr || a->X == nullptr) return LLC_E_NULL;
+  if (!draft_only && (a->target == nullptr || a->Y == nullptr || a->accept == nullptr)) return LLC_E_NULL;
+  if (a->draft_stride_b < 0 || a->draft_stride_k < 0 || (!draft_only && a->target_stride_b < 0)) return LLC_E_SHAPE;
   const bool dry = (a->flags & LLC_FLAG_DRY_RUN) != 0;
 
   ScanJob j;
   j.B = a->B; j.K = a->K; j.V = a->V; j.dtype = a->dtype; j.kind = a->kind;
-  j.draft = a->draft; j.target = a->target;
-  j.map = plain_rows(a->draft_stride_b, a->target_stride_b);
+  j.draft = a->draft;
+  j.target = draft_only ? a->draft : a->target;  // (without a pool the target is never read)
+  j.map = plain_rows(a->draft_stride_b, draft_only ? a->draft_stride_b : a->target_stride_b);
   j.draft_stride_k = a->draft_stride_k;
-  j.temp_target = a->temp_target; j.temp_draft_all = a->temp_draft_all; j.temp_draft = a->temp_draft;
+  j.temp_target = draft_only ? 1.0f : a->temp_target;
+  j.temp_draft_all = a->temp_draft_all; j.temp_draft = a->temp_draft;
   j.seed = a->seed; j.row_offset = a->row_offset;
-  j.no_pool = false;
-  j.need_lse = a->keyX != nullptr || a->keyY != nullptr;
+  j.no_pool = draft_only;
+  j.need_lse = a->keyX != nullptr || (!draft_only && a->keyY != nullptr);
   j.min_first = (a->flags & LLC_FLAG_MIN_FIRST) != 0;
-  j.flags = a->flags & ~(LLC_FLAG_DRY_RUN | LLC_FLAG_MIN_FIRST); j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;
+  j.flags = a->flags & ~(LLC_FLAG_DRY_RUN | LLC_FLAG_MIN_FIRST | LLC_FLAG_DRAFT_ONLY);
+  j.v_chunks = a->v_chunks; j.k_tile = a->k_tile;
   j.stats = a->stats; j.workspace = workspace; j.workspace_bytes = workspace_bytes;
   j.stream = a->stream; j.ev_begin = a->ev_scan_begin; j.ev_end = a->ev_scan_end;
   j.extra_bytes = 0;
@@ -380,6 +384,9 @@ int couple_on(const llc_couple_args *a, void *workspace, size_t workspace_bytes)
   fp.keyX = a->keyX; fp.keyY = a->keyY; fp.log_keyX = nullptr; fp.log_secX = nullptr;
   fp.y_given = 0; fp.bins = nullptr; fp.bins_stride_b = 0; fp.message = nullptr;
   fp.count_draft = 1; fp.count_pool = 1; fp.count_near = 1;
+  if (draft_only) {  // (Y == nullptr is what tells the finalize step that there is no pool)
+    fp.Y = nullptr; fp.accept = nullptr; fp.match_k = nullptr; fp.keyY = nullptr; fp.count_pool = 0;
+  }
   fp.stats = a->stats;
   j.fin = &fp;  // (where it can, the scan finishes the rows itself and no finalize launch follows)
 

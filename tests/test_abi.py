@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(binding.EXPORTS)
     for name in names:
         assert getattr(lib, name) is not None
-    assert llc.llc_version() == 109
+    assert llc.llc_version() == 110
     assert llc.llc_status_string(0) == "ok"
     assert "workspace" in llc.llc_status_string(-6)
 
@@ -226,6 +226,21 @@ def test_dry_run_plans_the_other_calls_too():
         a = _args(B=B, K=K, V=V, draft_stride_b=V, target_stride_b=V, workspace_bytes=512,
                   flags=binding.FLAG_DRY_RUN)
         assert lib.llc_couple(ctypes.byref(a)) == -6
+
+
+def test_the_draft_only_flag_needs_neither_target_nor_target_side_outputs():
+    lib = llc.load()
+    do = binding.FLAG_DRAFT_ONLY | binding.FLAG_DRY_RUN
+    a = _args(flags=do, target=None, Y=None, accept=None, target_stride_b=0)
+    assert lib.llc_couple(ctypes.byref(a)) == 0
+    assert lib.llc_couple(ctypes.byref(_args(flags=do | binding.FLAG_MIN_FIRST, target=None, Y=None, accept=None))) == 0
+    assert lib.llc_couple(ctypes.byref(_args(flags=do, draft=None))) == -1
+    assert lib.llc_couple(ctypes.byref(_args(flags=do, X=None))) == -1
+    assert lib.llc_couple(ctypes.byref(_args(flags=binding.FLAG_DRY_RUN, target=None))) == -1   # without the flag
+    assert lib.llc_couple(ctypes.byref(_args(flags=do, temp_target=0.0, target=None, Y=None, accept=None))) == 0
+    assert lib.llc_couple(ctypes.byref(_args(flags=do, temp_draft_all=0.0))) == -3
+    a = _verify_args(flags=binding.FLAG_DRAFT_ONLY)
+    assert lib.llc_verify(ctypes.byref(a)) == -8
 
 
 def test_the_min_first_flag_is_planned_like_the_default_and_refused_where_it_is_not_built():
