@@ -347,8 +347,9 @@ typedef struct llc_couple_topm_args {
  * formula); NaN and +inf entries carry no mass.  Results are fp64; indices whose q/p agree to fp32
  * precision are ordered arbitrarily and the masses enter the running sums rounded to fp32, which
  * together move a result by a relative 2^-22 at most.
- * The workspace (llc_lml_workspace_size bytes, 256-byte aligned, device) belongs to the call
- * until it has finished. */
+ * The workspace (256-byte aligned, device) belongs to the call until it has finished: 24 V bytes
+ * serve one row at a time, llc_lml_workspace_size gives what keeps the whole GPU busy (at most 512
+ * rows' worth, whatever B is); a smaller one, down to one row's, is accepted and only costs time. */
 #define LLC_LML_MAX_K 8
 typedef struct llc_lml_args {
   int64_t B, V;             /* 0 <= B < 2^31, 1 <= V <= 2^28                              */
@@ -402,7 +403,8 @@ int llc_verify(const llc_verify_args *a);
 /* Theorem 1's lower bound on the matching probability, per row (Section 3).  Asynchronous. */
 int llc_lml_bound(const llc_lml_args *a);
 
-/* Bytes of device scratch llc_lml_bound needs; 0 on bad shapes. */
+/* Bytes of device scratch with which llc_lml_bound runs at full speed (min(B, 512) x 24 V + 256);
+ * 0 on bad shapes. */
 size_t llc_lml_workspace_size(int64_t B, int64_t V);
 
 /* Bytes of device scratch llc_couple, llc_couple_is and llc_compress_select need for this shape:

@@ -579,8 +579,10 @@ constexpr long long kLmlMaxV = 1LL << 28;
 
 size_t llc_lml_workspace_size(int64_t B, int64_t V) {
   if (!shape_ok(B, 1, V) || V > kLmlMaxV) return 0;
-  // per row two buffers of sort keys (4 bytes) and two of mass pairs (8 bytes)
-  return align256((size_t)B * 24 * (size_t)V) + 256;
+  // per slot two buffers of sort keys (4 bytes) and two of mass pairs (8 bytes); a slot serves one
+  // row per launch, and no more rows than kLmlSlots can be in work at once
+  const long long slots = B < kLmlSlots ? B : kLmlSlots;
+  return align256((size_t)slots * 24 * (size_t)V) + 256;
 }
 
 int llc_lml_bound(const llc_lml_args *a) {
@@ -598,8 +600,10 @@ int llc_lml_bound(const llc_lml_args *a) {
   if (logits && (!good_temp(a->temp_target) || !good_temp(a->temp_draft))) return LLC_E_TEMP;
   const size_t esize = a->dtype == LLC_F32 ? 4 : 2;
   if (((uintptr_t)a->draft % esize) != 0 || ((uintptr_t)a->target % esize) != 0) return LLC_E_ALIGN;
+  // any workspace that holds at least one row will do (rows / slots launches follow each other);
+  // the size llc_lml_workspace_size gives fills the GPU with each launch
   if (a->workspace == nullptr || ((uintptr_t)a->workspace & 255) != 0 ||
-      a->workspace_bytes < llc_lml_workspace_size(a->B, a->V))
+      a->workspace_bytes < (size_t)24 * (size_t)a->V)
     return LLC_E_WORKSPACE;
   LmlParams p;
   p.B = a->B; p.V = (int)a->V; p.dtype = a->dtype; p.probs = a->kind == LLC_PROBS ? 1 : 0;
@@ -611,6 +615,11 @@ int llc_lml_bound(const llc_lml_args *a) {
   for (int n = 0; n < LLC_LML_MAX_K; ++n) p.k[n] = n < a->n_k ? a->k[n] : 1;
   p.bound = a->bound; p.relaxed = a->relaxed; p.tv = a->tv;
   p.work = (char *)a->workspace;
+  {
+    // a larger workspace than llc_lml_workspace_size asks for means fewer, larger launches
+    const size_t slots = a->workspace_bytes / ((size_t)24 * (size_t)a->V);
+    p.slots = (int)(slots < (size_t)a->B ? slots : (size_t)a->B);
+  }
   hipStream_t st = (hipStream_t)a->stream;
   if (a->ev_begin != nullptr && hipEventRecord((hipEvent_t)a->ev_begin, st) != hipSuccess) return LLC_E_LAUNCH;
   if (launch_lml(st, p) != hipSuccess) return LLC_E_LAUNCH;

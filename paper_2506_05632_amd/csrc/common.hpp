@@ -204,6 +204,7 @@ struct TopmParams {
 
 // Theorem 1's bound per row (diagnostics): one workgroup sorts a row by q/p and sums.
 constexpr int kLmlMaxK = LLC_LML_MAX_K;
+constexpr int kLmlSlots = 512;  // two 512-thread workgroups on each of 256 CUs: more cannot be resident
 struct LmlParams {
   long long B;
   int V;
@@ -218,7 +219,9 @@ struct LmlParams {
   double *bound;    // [B][n_k]
   double *relaxed;  // [B][n_k] or nullptr
   double *tv;       // [B] or nullptr
-  char *work;       // workspace: per row two buffers of V sort keys, then two of V (p-mass, q-mass) pairs
+  char *work;       // workspace: per slot two buffers of V sort keys, then two of V (p-mass, q-mass) pairs
+  int slots;        // rows the workspace holds at a time (= rows per launch; a call is ceil(B / slots) launches)
+  long long row0;   // first row of this launch (set by the launcher)
 };
 
 // One launcher per (element type, draft layout); defined in scan_*.hip.

@@ -122,12 +122,14 @@ __global__ void __launch_bounds__(kThreads) lml_kernel(const LmlParams p) {
   int (*hist)[kWaves][256] = reinterpret_cast<int (*)[kWaves][256]>(st_mass);
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const long long b = blockIdx.x;
+  const long long b = p.row0 + blockIdx.x;
   const int V = p.V;
   const E *prow = reinterpret_cast<const E *>(p.draft) + b * p.draft_stride_b;
   const E *qrow = reinterpret_cast<const E *>(p.target) + b * p.target_stride_b;
-  // per row: two key buffers, then two buffers of (p-mass, q-mass)
-  char *work = p.work + (size_t)b * 24u * (size_t)V;
+  // A launch takes as many rows as the workspace has slots (two key buffers, then two buffers of
+  // (p-mass, q-mass) each); the launches of one call follow each other on the stream, so the
+  // workspace is as large as the workgroups that can be resident need, not as the batch.
+  char *work = p.work + (size_t)blockIdx.x * 24u * (size_t)V;
   uint32_t *key_a = reinterpret_cast<uint32_t *>(work), *key_b = key_a + V;
   float2 *mass_a = reinterpret_cast<float2 *>(work + 8u * (size_t)V), *mass_b = mass_a + V;
 
@@ -371,13 +373,19 @@ __global__ void __launch_bounds__(kThreads) lml_kernel(const LmlParams p) {
 
 }  // namespace
 
-hipError_t launch_lml(hipStream_t s, const LmlParams &p) {
-  if (p.B == 0) return hipSuccess;
-  if (p.dtype == LLC_F32)
-    hipLaunchKernelGGL(lml_kernel<float>, dim3((unsigned)p.B), dim3(kThreads), 0, s, p);
-  else
-    hipLaunchKernelGGL(lml_kernel<uint16_t>, dim3((unsigned)p.B), dim3(kThreads), 0, s, p);
-  return hipGetLastError();
+hipError_t launch_lml(hipStream_t s, const LmlParams &params) {
+  LmlParams p = params;
+  for (p.row0 = 0; p.row0 < p.B; p.row0 += p.slots) {
+    const long long left = p.B - p.row0;
+    const unsigned grid = (unsigned)(left < (long long)p.slots ? left : (long long)p.slots);
+    if (p.dtype == LLC_F32)
+      hipLaunchKernelGGL(lml_kernel<float>, dim3(grid), dim3(kThreads), 0, s, p);
+    else
+      hipLaunchKernelGGL(lml_kernel<uint16_t>, dim3(grid), dim3(kThreads), 0, s, p);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 }  // namespace llc

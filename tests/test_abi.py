@@ -353,4 +353,5 @@ def test_lml_argument_errors_are_reported_before_any_launch(kw, code):
     assert lib.llc_lml_bound(ctypes.byref(_lml_args(B=0, draft=None, bound=None))) == 0
     assert llc.llc_lml_workspace_size(4, 64) >= 4 * 64 * 24
     assert llc.llc_lml_workspace_size(4, 0) == 0
+    assert llc.llc_lml_workspace_size(100000, 128256) == llc.llc_lml_workspace_size(512, 128256)   # capped
     assert llc.llc_lml_workspace_size(1, 1 << 28) >= 24 << 28 and llc.llc_lml_workspace_size(1, (1 << 28) + 1) == 0

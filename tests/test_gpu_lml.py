@@ -83,6 +83,24 @@ def test_many_equal_ratios_and_sorted_inputs():
     check(td.contiguous(), tq.contiguous(), KS)
 
 
+def test_more_rows_than_workspace_slots_and_a_workspace_of_one_row():
+    # a call is as many launches as its rows need slots of the workspace: more rows than slots
+    # (the library's size caps at 512 rows' worth), a workspace that holds a single row (one
+    # launch per row), and a larger one than asked for (one launch) give the same bits
+    g = torch.Generator(device=DEV).manual_seed(600)
+    B, V = 1300, 700
+    assert llc.llc_lml_workspace_size(B, V) == llc.llc_lml_workspace_size(512, V) < 24 * B * V
+    tq = 2 * torch.randn(B, V, generator=g, device=DEV)
+    td = tq + torch.randn(B, V, generator=g, device=DEV)
+    gpu, _ = check(td, tq, KS, rows=list(range(0, B, 37)) + [511, 512, 513, 1023, 1024, B - 1], temp_draft=1.1, temp_target=0.9)
+    for rows in (1, 3, 600, 1400):
+        ws = torch.empty(24 * V * rows + 256, dtype=torch.uint8, device=DEV)
+        other = llc.llc_lml_bound(td, tq, KS, temp_draft=1.1, temp_target=0.9, workspace=ws)
+        torch.cuda.synchronize()
+        for name in ("bound", "relaxed", "tv"):
+            assert torch.equal(other[name], gpu[name]), (rows, name)
+
+
 def test_acceptance_of_the_sampler_respects_the_bound():
     # the measured acceptance rate of llc_couple on one pair (p, q) repeated over many rows of
     # randomness is at least Theorem 1's bound (up to sampling error)
