@@ -352,6 +352,12 @@ struct LaneSums { double v[N][kBlock]; };
 template <int N>
 struct LaneSums<false, N> { double v[1][1]; };
 
+// Min-first survivors' path: words of a wavefront's staging area (eight lanes' tiles of 4 words, 4 target
+// values, the group's number (padded) and up to 32 draft values) and of its queue (up to 8 + 32
+// indices of 3 words and up to 8 draft values).
+constexpr int kStageWords = 8 * 44;
+constexpr int kQueueWords = 40 * 11;
+
 struct Lds {
   int tau[9];            // ordered-int log2 keys: drafts 0..KT-1, pool at [KT]
   int O[9];              // bits of the level-1 offsets (tau + slack + bias) 2^23; shared layout: [0] = max over drafts
@@ -370,6 +376,7 @@ struct Lds {
     float vq[4];
     float vd[32];
   } stage[4];
+  int qn[4];             // min-first: candidates in each wavefront's queue
   int lse_redo;          // LSE: the running sums were not formed (the main loop was skipped) or are not finite
   float lse_wmax[4][9];  // LSE: per-wave maxima ...
   double lse_wave[4][9]; // ... and per-wave sums relative to them, merged in a fixed order
@@ -531,6 +538,7 @@ __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE)
   constexpr int KT = 2 * KB;
   static_assert(!(MINF && MASKED), "the binned and pool-only passes draw one word per (index, draft)");
   __shared__ Lds s;
+  __shared__ __align__(16) uint32_t s_minf[MINF ? 4 * (kStageWords + kQueueWords) : 4];  // (see the main loop)
   // (with per-draft rows the sums stay in registers: in LDS they measured slower there)
   constexpr bool kSumsInLds = LSE && SHARED;
   __shared__ LaneSums<kSumsInLds, 2> sums;
@@ -681,6 +689,7 @@ __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE)
     s.shared_base = kbase;
     s.shared_pool = p.K;
     s.lse_redo = 0;
+    s.qn[0] = 0; s.qn[1] = 0; s.qn[2] = 0; s.qn[3] = 0;
   }
   __syncthreads();
 
@@ -847,6 +856,85 @@ __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE)
           else lse_acc[sl] += (double)part;
         }
       };
+      // min-first, survivors of the main loop's test.  The lanes whose tile passed lay it out in LDS,
+      // eight lanes at a time, and a lane per laid-out index tests it against the index's own
+      // exponent (the main loop's threshold is that of the tile's largest value).  What still passes
+      // is not finished on the spot but put into the wavefront's queue: when enough indices have
+      // gathered, and after the last tile, one lane per queued index and draft redoes the test with
+      // its draft's bound as it stands by then (bounds only ever tighten, and a tighter bound is
+      // still valid), draws the holder where that passes, and hands survivors to level 2.  One pass
+      // serves the indices of many tiles: its Philox blocks and its level 2 cost a wavefront the
+      // same whether one lane or all of them have work.
+      const int wv = tid >> 6, lane = tid & 63;
+      uint32_t *const stg = s_minf + wv * (kStageWords + kQueueWords);
+      uint32_t *const que = stg + kStageWords;
+      constexpr int kEntry = 3 + KD;  // index, word, target value, draft values
+      constexpr int kPerPass = 64 / KT;
+      constexpr int kQueueFlush = 8;
+      static_assert((kQueueFlush + 32) * kEntry <= kQueueWords, "queue too small");
+      auto drain = [&]() {
+        __builtin_amdgcn_wave_barrier();
+        const int n = __atomic_load_n(&s.qn[wv], __ATOMIC_RELAXED);
+        for (int base = 0; base < n; base += kPerPass) {
+          const int e = base + lane / KT;
+          const int kk = lane % KT;
+          if (e < n && kbase + kk < p.K) {
+            const uint32_t *q = que + e * kEntry;
+            const int i = (int)q[0];
+            const uint32_t w = q[1];
+            const float qs = __uint_as_float(q[2]);
+            const float ds = __uint_as_float(q[3 + (SHARED ? 0 : kk)]);
+            const int m = kk >> 1, h = kk & 1, j = i & 3;
+            const uint32_t gs = (uint32_t)(i >> 2);
+            const float c23 = s.cd23[kk];
+            const bool okk = s.kok[kk] != 0;
+            const float tau_d = unord32(__atomic_load_n(&s.tau[kk], __ATOMIC_RELAXED));
+            const float tau_y = unord32(__atomic_load_n(&s.tau[KT], __ATOMIC_RELAXED));
+            const float OYs = with_pool ? load_offset(&s.O[KT]) : -__builtin_huge_valf();
+            const float fy = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(qs), cq23, OYs), 0.0f, kCapHot);
+            const float cdk = PROBS ? 1.0f : c23 * (1.0f / kTwo23);
+            // w is the index's smallest time.  The test is redone with the draft's own bound (merged
+            // with the pool's); where it passes the holder is drawn: if this draft holds the smallest
+            // time, that time goes to level 2 for the draft and the pool; if not, the draft's time is
+            // the smallest plus that of its own word, which can only matter if the word alone passes
+            // the draft's bound (half-word first, as in the other variant).
+            const float OX = okk ? make_offset<PROBS>(tau_d, lgK) : -__builtin_huge_valf();
+            const float Fs = merged_exponent<PROBS>(ds, c23, OX, fy);
+            if (Fs >= kCapHot || w >= ~threshold_of(Fs)) {
+              uint32_t hd[4];
+              philox_block(row_lo, gs, row_hi, kHolderBlock, p.seed_lo, p.seed_hi, hd);
+              const uint32_t r = j == 0 ? hd[0] : j == 1 ? hd[1] : j == 2 ? hd[2] : hd[3];
+              if (holder_of(r, p.K) == kbase + kk) {
+                ++my_survivors;
+                level2<KT, SHARED, PROBS, MINF>(s, approx_log2_race_time(w) - lgK, ds, qs, i, kk, okk, with_pool,
+                                                cdk, cq, tau_d, tau_y);
+              } else if (okk) {
+                const float Fd = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(ds), c23, make_offset<PROBS>(tau_d)),
+                                                         0.0f, kCapHot);
+                const uint32_t t = threshold_of(Fd);
+                uint32_t up[4];
+                philox_block(row_lo, gs, row_hi, pair_base + m, p.seed_lo, p.seed_hi, up);
+                const uint32_t uw = j == 0 ? up[0] : j == 1 ? up[1] : j == 2 ? up[2] : up[3];
+                const uint32_t hw = h ? (uw >> 16) : (uw & 0xFFFFu);
+                if (Fd >= kCapHot || hw >= 0xFFFFu - (t >> 16)) {
+                  uint32_t lo[4];
+                  philox_block(row_lo, gs, row_hi, (pair_base + m) | kLowBlock, p.seed_lo, p.seed_hi, lo);
+                  const uint32_t lw = j == 0 ? lo[0] : j == 1 ? lo[1] : j == 2 ? lo[2] : lo[3];
+                  const uint32_t x = element_word(uw, lw, h);
+                  if (Fd >= kCapHot || x >= ~t) {
+                    ++my_survivors;
+                    const float S = approx_race_time(w) * invK + approx_race_time(x);
+                    level2<KT, SHARED, PROBS, MINF>(s, __log2f(S), ds, qs, i, kk, true, false, cdk, cq, tau_d, tau_y);
+                  }
+                }
+              }
+            }
+          }
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (lane == 0) __atomic_store_n(&s.qn[wv], 0, __ATOMIC_RELAXED);
+        __builtin_amdgcn_wave_barrier();
+      };
       // min-first: one block holds the four indices' smallest race times, one word each; the tile's
       // largest word is tested against the loosest bound (every draft's and the pool's, each raised
       // by log2 K in its offset), and the survivors' path sorts out which draft the time belongs to.
@@ -869,115 +957,57 @@ __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE)
         }
         F = __builtin_amdgcn_fmed3f(F, 0.0f, kCapHot);
         const uint32_t mx = max(max(mn[0][0], mn[0][1]), max(mn[0][2], mn[0][3]));
-        // Rare: some lane's largest word passed, or it holds a hot element.  The wave takes such lanes
-        // one at a time: the lane lays its tile out in LDS and the first 8 KB lanes each take one
-        // (index j, draft 2m + h) of it.  A lane redoes the test on the index's smallest time with
-        // its draft's own bound (merged with the pool's); where that passes it draws the holder: if
-        // its draft holds the smallest time, that time goes to level 2 for the draft and the pool;
-        // if not, its draft's time is the smallest plus that of its own word, which can only matter
-        // if the word alone passes the draft's bound (half-word first, as in the other variant).
+        // Rare: some lane's largest word passed, or it holds a hot element.  The tile's one threshold
+        // is that of its largest value, so most hits are another index's word under it.  Up to eight
+        // such lanes at a time lay their tiles out; a lane per laid-out index tests it against the
+        // index's own exponent (still the loosest over the drafts, merged with the pool's) and
+        // queues it if it passes.
         const bool hit = F >= kCapHot || mx >= ~threshold_of(F);
-        unsigned long long todo = 0ull;
-        if (__ballot(hit) != 0ull) {
-          // The tile's one threshold is that of its largest value: most hits are another index's word
-          // under it.  The lane first tests each of its indices against the index's own exponent
-          // (still the loosest over the drafts, merged with the pool's); only what is left is worth
-          // the wave's time.
-          bool real = false;
-          if (hit) {
-            float vq[4];
-            unpack(rq, vq);
-            const float OYl = load_offset(&s.OL[KT]);
-            float Fj[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) Fj[j] = fmaf(level1_value<PROBS>(vq[j]), cq23, OYl);
-#pragma unroll
-            for (int kk = 0; kk < KD; ++kk) {
-              float vd[4];
-              unpack(rd[kk], vd);
-              const float OXl = load_offset(&s.OL[kk]);
-#pragma unroll
-              for (int j = 0; j < 4; ++j) Fj[j] = fmaxf(Fj[j], fmaf(level1_value<PROBS>(vd[j]), cd23[kk], OXl));
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const float Fc = __builtin_amdgcn_fmed3f(Fj[j], 0.0f, kCapHot);
-              real = real || Fc >= kCapHot || mn[0][j] >= ~threshold_of(Fc);
-            }
-          }
-          todo = __ballot(real);
-        }
+        unsigned long long todo = __ballot(hit);
         if (todo != 0ull) {
-          const int lane = tid & 63;
-          Lds::Stage &st = s.stage[tid >> 6];
+          constexpr int kSlot = 12 + 4 * KD;  // words, target values, the group's number (padded), draft values
+          static_assert(8 * kSlot <= kStageWords, "staging area too small");
           while (todo != 0ull) {
-            const int src = __ffsll((long long)todo) - 1;
-            todo &= todo - 1ull;
-            if (lane == src) {
-#pragma unroll
-              for (int j = 0; j < 4; ++j) st.up[j] = mn[0][j];
+            const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(todo >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)todo, 0u));
+            const bool mine = ((todo >> lane) & 1ull) != 0ull && rank < 8;
+            const unsigned long long taken = __ballot(mine);
+            todo &= ~taken;
+            if (mine) {
+              uint32_t *o = stg + rank * kSlot;
+              *reinterpret_cast<uint4 *>(o) = make_uint4(mn[0][0], mn[0][1], mn[0][2], mn[0][3]);
               float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
               if (with_pool) unpack(rq, vq);
-#pragma unroll
-              for (int j = 0; j < 4; ++j) st.vq[j] = vq[j];
+              *reinterpret_cast<float4 *>(o + 4) = make_float4(vq[0], vq[1], vq[2], vq[3]);
+              o[8] = (uint32_t)g;
 #pragma unroll
               for (int kk = 0; kk < KD; ++kk) {
                 float vd[4];
                 unpack(rd[kk], vd);
+                *reinterpret_cast<float4 *>(o + 12 + 4 * kk) = make_float4(vd[0], vd[1], vd[2], vd[3]);
+              }
+            }
+            __builtin_amdgcn_wave_barrier();
+            const int n_taken = __popcll(taken);
+            if (lane < 4 * n_taken) {
+              const uint32_t *o = stg + (lane >> 2) * kSlot;
+              const int j = lane & 3;
+              const uint32_t x0 = o[j];
+              const float qs = __uint_as_float(o[4 + j]);
+              const int i = (int)o[8] * 4 + j;
+              float Fj = fmaf(level1_value<PROBS>(qs), cq23, load_offset(&s.OL[KT]));
 #pragma unroll
-                for (int j = 0; j < 4; ++j) st.vd[kk * 4 + j] = vd[j];
+              for (int kk = 0; kk < KD; ++kk)
+                Fj = fmaxf(Fj, fmaf(level1_value<PROBS>(__uint_as_float(o[12 + 4 * kk + j])), cd23[kk], load_offset(&s.OL[kk])));
+              Fj = __builtin_amdgcn_fmed3f(Fj, 0.0f, kCapHot);
+              if ((Fj >= kCapHot || x0 >= ~threshold_of(Fj)) && i < V) {
+                uint32_t *q = que + atomicAdd(&s.qn[wv], 1) * kEntry;
+                q[0] = (uint32_t)i; q[1] = x0; q[2] = o[4 + j];
+#pragma unroll
+                for (int kk = 0; kk < KD; ++kk) q[3 + kk] = o[12 + 4 * kk + j];
               }
             }
             __builtin_amdgcn_wave_barrier();
-            const int gs = g - lane + src;  // the lanes of a wave hold consecutive groups
-            if (lane < 8 * KB) {
-              const int m = lane >> 3, j = (lane >> 1) & 3, h = lane & 1;
-              const int kk = 2 * m + h;
-              const int i = gs * 4 + j;
-              if (kbase + kk < p.K && i < V) {
-                const uint32_t x0 = st.up[j];
-                const float ds = st.vd[(SHARED ? 0 : kk) * 4 + j], qs = st.vq[j];
-                const float c23 = s.cd23[kk];
-                const bool okk = s.kok[kk] != 0;
-                const float tau_d = unord32(__atomic_load_n(&s.tau[kk], __ATOMIC_RELAXED));
-                const float tau_y = unord32(__atomic_load_n(&s.tau[KT], __ATOMIC_RELAXED));
-                const float OYs = with_pool ? load_offset(&s.O[KT]) : -__builtin_huge_valf();
-                const float fy = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(qs), cq23, OYs), 0.0f, kCapHot);
-                const float OX = okk ? make_offset<PROBS>(tau_d, lgK) : -__builtin_huge_valf();
-                const float Fs = merged_exponent<PROBS>(ds, c23, OX, fy);
-                if (Fs >= kCapHot || x0 >= ~threshold_of(Fs)) {
-                  uint32_t hd[4];
-                  philox_block(row_lo, (uint32_t)gs, row_hi, kHolderBlock, p.seed_lo, p.seed_hi, hd);
-                  const uint32_t r = j == 0 ? hd[0] : j == 1 ? hd[1] : j == 2 ? hd[2] : hd[3];
-                  const float cdk = PROBS ? 1.0f : c23 * (1.0f / kTwo23);
-                  if (holder_of(r, p.K) == kbase + kk) {
-                    ++my_survivors;
-                    level2<KT, SHARED, PROBS, MINF>(s, approx_log2_race_time(x0) - lgK, ds, qs, i, kk, okk, with_pool,
-                                                    cdk, cq, tau_d, tau_y);
-                  } else if (okk) {
-                    const float Fd = __builtin_amdgcn_fmed3f(fmaf(level1_value<PROBS>(ds), c23, make_offset<PROBS>(tau_d)),
-                                                             0.0f, kCapHot);
-                    const uint32_t t = threshold_of(Fd);
-                    uint32_t up[4];
-                    philox_block(row_lo, (uint32_t)gs, row_hi, pair_base + m, p.seed_lo, p.seed_hi, up);
-                    const uint32_t uw = j == 0 ? up[0] : j == 1 ? up[1] : j == 2 ? up[2] : up[3];
-                    const uint32_t hw = h ? (uw >> 16) : (uw & 0xFFFFu);
-                    if (Fd >= kCapHot || hw >= 0xFFFFu - (t >> 16)) {
-                      uint32_t lo[4];
-                      philox_block(row_lo, (uint32_t)gs, row_hi, (pair_base + m) | kLowBlock, p.seed_lo, p.seed_hi, lo);
-                      const uint32_t lw = j == 0 ? lo[0] : j == 1 ? lo[1] : j == 2 ? lo[2] : lo[3];
-                      const uint32_t x = element_word(uw, lw, h);
-                      if (Fd >= kCapHot || x >= ~t) {
-                        ++my_survivors;
-                        const float S = approx_race_time(x0) * invK + approx_race_time(x);
-                        level2<KT, SHARED, PROBS, MINF>(s, __log2f(S), ds, qs, i, kk, true, false, cdk, cq, tau_d, tau_y);
-                      }
-                    }
-                  }
-                }
-              }
-            }
-            __builtin_amdgcn_wave_barrier();
+            if (__atomic_load_n(&s.qn[wv], __ATOMIC_RELAXED) >= kQueueFlush) drain();
           }
         }
         (void)rb;
@@ -1181,6 +1211,7 @@ __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE)
         load_tile(g, false, rq, rd, rb);
         process_tile(g, rq, rd, rb);
       }
+      if constexpr (MINF) drain();  // what is still queued
     }
     __syncthreads();
     if (tid == 0 && s.count > kListCap) s.unsafe = 1;
