@@ -11,7 +11,7 @@ import torch
 import oracle
 import paper_2506_05632_amd as llc
 from paper_2506_05632_amd import workloads
-from parity_util import check_all_rows, compare, oracle_rows, same_outputs, stats_dict, to_host
+from parity_util import check_all_rows, compare, oracle_near_ties as oracle_near_ties_of, oracle_rows, same_outputs, stats_dict, to_host
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -205,6 +205,34 @@ def test_sorted_logits_overflow_the_candidate_list_and_millions_of_small_races_a
         got, want = stats_dict(stats)["near_ties"], oracle_near_ties(ref)
         print(f"4M small races (min-first): near-ties oracle {want}, device {got}, excused mismatches {excused}")
         assert abs(got - want) <= oracle_borderline(ref) and excused <= want
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shared", [True, False])
+def test_bursts_of_candidates_fill_and_empty_the_queues_many_times(shared, dtype):
+    # The first tile of every row carries next to no mass, so the bounds the warm-up finds are
+    # loose by many orders of magnitude; then come long runs of equal, likely entries: every lane of
+    # every wavefront has a passing tile at once, the lanes are taken eight at a time, and the
+    # queues of candidates are emptied over and over until the bounds have tightened.  Later runs
+    # of still larger values do the same again in the middle of the row.
+    g = torch.Generator(device=DEV).manual_seed(77)
+    B, V, K = 12, 40000, 8
+    tq = torch.full((B, V), -60.0, device=DEV)
+    tq[:, 1024:9000] = 0.0
+    tq[:, 20000:23000] = 6.0
+    tq[:, 39000:] = 9.0
+    tq += 0.01 * torch.randn(B, V, generator=g, device=DEV)
+    td = tq if shared else (tq[:, None, :] + 0.5 * torch.randn(B, K, V, generator=g, device=DEV))
+    td, tq = td.to(dtype), tq.to(dtype)
+    ref = oracle_rows(td, tq, K, (0, B), kind="logits", temp_target=1.0, temp_draft=0.8, seed=9, min_first=True)
+    for kw in (dict(), dict(v_chunks=3), dict(k_tile=2)):
+        stats = llc.new_stats(DEV)
+        ws = llc.new_workspace(B, K, V, DEV, v_chunks=kw.get("v_chunks", 0))
+        gpu = llc.llc_couple(td, tq, K, temp_target=1.0, temp_draft=0.8, seed=9, want_keys=True, stats=stats,
+                             workspace=ws, flags=MF, **kw)
+        torch.cuda.synchronize()
+        assert compare(gpu, ref) <= oracle_near_ties_of(ref)
+        assert stats_dict(stats)["survivors"] > 50 * B      # the bursts did go through the candidates' path
 
 
 def test_identical_distributions_always_accept_and_the_target_ignores_the_drafts():
