@@ -531,7 +531,8 @@ __device__ double chunk_lse_exact(const typename T::elem *row, int g_begin, int 
 // 1's accept test and the outputs), so that no finalize launch follows.
 // MINF: the race times are drawn min-first (see the top of the file).  (Together with the
 // normalisers' sums it does not fit 128 registers without spilling inside the main loop: those
-// variants run with two workgroups per CU.)
+// variants are allowed more, and with the 132 to 151 that they take for up to four drafts per
+// workgroup, or eight that share a proposal, three workgroups fit a CU instead of four.)
 template <typename T, int KB, bool SHARED, bool PROBS, bool MASKED, bool LSE, bool FIN, bool MINF>
 __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE)) ? 4 : 2) scan_kernel(const ScanParams p) {
   using elem = typename T::elem;
