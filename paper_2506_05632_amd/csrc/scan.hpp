@@ -529,12 +529,12 @@ __device__ double chunk_lse_exact(const typename T::elem *row, int g_begin, int 
 // them (logit kinds), so that no second pass over the inputs is needed.
 // FIN: the variant for rows that are one workgroup each: it also takes the finalize step (Algorithm
 // 1's accept test and the outputs), so that no finalize launch follows.
-// MINF: the race times are drawn min-first (see the top of the file).  (Together with the
-// normalisers' sums it does not fit 128 registers without spilling inside the main loop: those
-// variants are allowed more, and with the 132 to 151 that they take for up to four drafts per
-// workgroup, or eight that share a proposal, three workgroups fit a CU instead of four.)
+// MINF: the race times are drawn min-first (see the top of the file).  (With per-draft rows and
+// the normalisers' sums it does not fit 128 registers without reloading spilled values inside the
+// main loop, each reload waiting for the next tile's loads as well: those variants are allowed more,
+// and with the 131 to 147 that they take three workgroups fit a CU instead of four.)
 template <typename T, int KB, bool SHARED, bool PROBS, bool MASKED, bool LSE, bool FIN, bool MINF>
-__global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE)) ? 4 : 2) scan_kernel(const ScanParams p) {
+__global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE && !SHARED)) ? 4 : 2) scan_kernel(const ScanParams p) {
   using elem = typename T::elem;
   constexpr int KT = 2 * KB;
   static_assert(!(MINF && MASKED), "the binned and pool-only passes draw one word per (index, draft)");
@@ -1219,6 +1219,31 @@ __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE)
     __syncthreads();
   }
 
+  // ---- LSE: the lanes' running sums become per-wave sums in LDS right away (they are merged after
+  // level 3), so that the registers that carried them through the main loop are free from here on
+  if (LSE) {
+    const int wv = tid >> 6;
+#pragma unroll
+    for (int kk = 0; kk <= KT; ++kk) {
+      if (SHARED && kk != 0 && kk != KT) continue;
+      // bring the lanes' sums to the wave's largest value (exactly, in fp64), then add them up
+      const float m = lse_m[lidx(kk)];
+      float wm = m;
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) wm = fmaxf(wm, __shfl_xor(wm, d));
+      double v = 0.0;
+      if (m > -__builtin_huge_valf())
+        {
+          double acc = lse_acc[lidx(kk)];
+          if (kSumsInLds) acc = sums.v[kSumsInLds ? lidx(kk) : 0][tid];
+          v = acc * exp2(((double)m - (double)wm) * ((double)lse_hi[kk] + (double)lse_lo[kk]));
+        }
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+      if ((tid & 63) == 0) { s.lse_wave[wv][kk] = v; s.lse_wmax[wv][kk] = wm; }
+    }
+  }
+
   unsigned long long my_exact = 0;
   const bool exact_all = s.unsafe != 0;  // uniform: read after the barrier
 
@@ -1375,26 +1400,6 @@ __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE)
 
   // ---- LSE: this chunk's share of every slot's normaliser, ln of (sum of exp(x/T) over the chunk)
   if (LSE) {
-    const int wv = tid >> 6;
-#pragma unroll
-    for (int kk = 0; kk <= KT; ++kk) {
-      if (SHARED && kk != 0 && kk != KT) continue;
-      // bring the lanes' sums to the wave's largest value (exactly, in fp64), then add them up
-      const float m = lse_m[lidx(kk)];
-      float wm = m;
-#pragma unroll
-      for (int d = 32; d >= 1; d >>= 1) wm = fmaxf(wm, __shfl_xor(wm, d));
-      double v = 0.0;
-      if (m > -__builtin_huge_valf())
-        {
-          double acc = lse_acc[lidx(kk)];
-          if (kSumsInLds) acc = sums.v[kSumsInLds ? lidx(kk) : 0][tid];
-          v = acc * exp2(((double)m - (double)wm) * ((double)lse_hi[kk] + (double)lse_lo[kk]));
-        }
-#pragma unroll
-      for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
-      if ((tid & 63) == 0) { s.lse_wave[wv][kk] = v; s.lse_wmax[wv][kk] = wm; }
-    }
     __syncthreads();
     const bool slot_used = tid < KT ? (kbase + tid < p.K) : (tid == KT && lse_target);
     // the slot whose sums this thread reports: with one shared proposal slot 0 stands for every draft
