@@ -378,7 +378,7 @@ struct Lds {
   } stage[4];
   int qn[4];             // min-first: candidates in each wavefront's queue
   int lse_redo;          // LSE: the running sums were not formed (the main loop was skipped) or are not finite
-  float lse_wmax[4][9];  // LSE: per-wave maxima ...
+  float lse_wmax[4][9];  // LSE: per-wave references (whole numbers, in powers of two) ...
   double lse_wave[4][9]; // ... and per-wave sums relative to them, merged in a fixed order
   int *shared_tau;       // the row's running bests shared by all its workgroups (or null)
   int shared_base, shared_pool;  // where this workgroup's draft 0 and the pool sit in it
@@ -529,12 +529,15 @@ __device__ double chunk_lse_exact(const typename T::elem *row, int g_begin, int 
 // them (logit kinds), so that no second pass over the inputs is needed.
 // FIN: the variant for rows that are one workgroup each: it also takes the finalize step (Algorithm
 // 1's accept test and the outputs), so that no finalize launch follows.
-// MINF: the race times are drawn min-first (see the top of the file).  (With per-draft rows and
-// the normalisers' sums it does not fit 128 registers without reloading spilled values inside the
-// main loop, each reload waiting for the next tile's loads as well: those variants are allowed more,
-// and with the 131 to 147 that they take three workgroups fit a CU instead of four.)
+// MINF: the race times are drawn min-first (see the top of the file).
+// Registers: four workgroups per CU (128 registers) where a workgroup reads one shared proposal or
+// at most four drafts' rows, except for the variants that read per-draft rows and form their
+// normalisers: held to 128 registers those reload spilled values inside the main loop, each reload
+// waiting for the next tile's loads as well (and one such build returned wrong target-side results,
+// which the parity tests caught and which went away with the spills), so they are allowed more and
+// take about 150: three workgroups per CU.
 template <typename T, int KB, bool SHARED, bool PROBS, bool MASKED, bool LSE, bool FIN, bool MINF>
-__global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE && !SHARED)) ? 4 : 2) scan_kernel(const ScanParams p) {
+__global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(LSE && !SHARED)) ? 4 : 2) scan_kernel(const ScanParams p) {
   using elem = typename T::elem;
   constexpr int KT = 2 * KB;
   static_assert(!(MINF && MASKED), "the binned and pool-only passes draw one word per (index, draft)");
@@ -643,20 +646,26 @@ __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE 
       float t = kk == KT ? Tq : p.temp_draft_all;
       if (kk < KT && p.temp_draft != nullptr && kbase + kk < p.K) t = p.temp_draft[kbase + kk];
       const double c64 = 1.4426950408889634 / (double)t;
-      lse_hi[kk] = (float)c64;
-      lse_lo[kk] = (float)(c64 - (double)lse_hi[kk]);
+      // (hi rounded towards zero and lo kept above zero, so that lo has hi's sign and is not 0: an
+      // entry of -inf then gives -inf in both products, never NaN)
+      float hi = (float)c64;
+      if (fabs((double)hi) > fabs(c64)) hi = __uint_as_float(__float_as_uint(hi) - 1u);
+      lse_hi[kk] = hi;
+      lse_lo[kk] = fmaxf((float)(c64 - (double)hi), 1e-30f);
     }
   }
   bool lse_ran = false;  // the main loop (which feeds the sums) was executed
-  // LSE: per lane and slot the largest value seen so far and the sum of exp((x - that)/T): the
-  // terms that matter then have small exponents, where fp32 arithmetic is accurate enough
+  // LSE: per slot a whole number n that is the same in all lanes of a wavefront (about the largest
+  // x log2(e)/T the wavefront has seen) and per lane the sum of 2^(x log2(e)/T - n): the terms that
+  // matter then have small exponents, where fp32 arithmetic is accurate enough, and moving n
+  // rescales a sum by a power of two, exactly
   // (with one shared proposal only two rows are summed: slot 0 for the drafts, slot KT for the target)
   constexpr int NL = LSE ? (SHARED ? 2 : KT + 1) : 1;
   auto lidx = [](const int slot) { return LSE ? (SHARED ? (slot == KT ? 1 : 0) : slot) : 0; };
   double lse_acc[NL];
-  float lse_m[NL];
+  float lse_n[NL];
 #pragma unroll
-  for (int kk = 0; kk < NL; ++kk) { lse_acc[kk] = 0.0; lse_m[kk] = -__builtin_huge_valf(); }
+  for (int kk = 0; kk < NL; ++kk) { lse_acc[kk] = 0.0; lse_n[kk] = -__builtin_huge_valf(); }
   // With one shared proposal the two running sums live in LDS: the kernel has no two registers to
   // spare for them across the main loop, and the compiler's own choice, scratch memory, costs a
   // round trip through the memory system per tile.
@@ -826,33 +835,43 @@ __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE 
       };
       // The tile is kept in its raw form and widened where it is used, so that few registers
       // are live across the (rare) branch to the survivors' path, which widens it again.
-      // LSE: four more terms of one slot's sum of exp(x/T), kept relative to the lane's largest
-      // value so far (the sum is rescaled when that moves): fp32 terms, four at a time, into the
-      // fp64 sum.  NaN and +inf entries carry no mass.
+      // LSE: four more terms of one slot's sum of exp(x/T), as 2^(x c - n) with c = log2(e)/T a
+      // two-float sum and n the wavefront's whole-number reference: x c_hi - n in one fused step (the
+      // product is not rounded before n is taken off), then x c_lo on top; fp32 terms, four at a
+      // time, into the lane's fp64 sum.  When some lane meets an exponent above 1 (a few times per
+      // row; always at the first entry with mass, n starting at -inf), n moves to the wavefront's
+      // largest x c, rounded, and the lanes' sums move with it by a power of two.  An entry of -inf
+      // adds an exact 0; a NaN or +inf entry makes the sum NaN or +inf, which sends the workgroup
+      // to the exact two-pass form at the end (there such entries carry no mass).
       auto lse_add = [&](const int slot, const float (&v)[4]) {
         const int sl = lidx(slot);
-        float w[4];
+        float e[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) w[j] = v[j] < __builtin_huge_valf() ? v[j] : -__builtin_huge_valf();
-        const float gm = fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3]));
-        if (gm > lse_m[sl]) {
-          if (lse_m[sl] > -__builtin_huge_valf()) {
-            const float d = lse_m[sl] - gm;
-            const double f = (double)__builtin_amdgcn_exp2f(fmaf(d, lse_hi[slot], d * lse_lo[slot]));
-            if (kSumsInLds) sums.v[kSumsInLds ? sl : 0][tid] *= f;
-            else lse_acc[sl] *= f;
+        for (int j = 0; j < 4; ++j) e[j] = fmaf(v[j], lse_lo[slot], fmaf(v[j], lse_hi[slot], -lse_n[sl]));
+        const float em = fmaxf(fmaxf(e[0], e[1]), fmaxf(e[2], e[3]));  // (a NaN among them is passed over)
+        if (__ballot(em > 1.0f) != 0ull) {
+          float wm = -__builtin_huge_valf();
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (v[j] < __builtin_huge_valf()) wm = fmaxf(wm, v[j]);
+#pragma unroll
+          for (int d = 32; d >= 1; d >>= 1) wm = fmaxf(wm, __shfl_xor(wm, d));
+          const float nn = rintf(__builtin_amdgcn_fmed3f(wm * lse_hi[slot], -1e9f, 1e9f));
+          if (nn > lse_n[sl]) {  // (not so if only a +inf entry brought us here)
+            if (lse_n[sl] > -__builtin_huge_valf()) {
+              const int down = (int)fmaxf(lse_n[sl] - nn, -4000.0f);
+              if (kSumsInLds) sums.v[kSumsInLds ? sl : 0][tid] = ldexp(sums.v[kSumsInLds ? sl : 0][tid], down);
+              else lse_acc[sl] = ldexp(lse_acc[sl], down);
+            }
+            lse_n[sl] = nn;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e[j] = fmaf(v[j], lse_lo[slot], fmaf(v[j], lse_hi[slot], -nn));
           }
-          lse_m[sl] = gm;
         }
-        if (lse_m[sl] > -__builtin_huge_valf()) {
-          float part = 0.0f;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            // <= 0; entries without mass are clamped to a finite distance whose term is exactly 0
-            // (the bare hardware exp2: a term below 2^-126 of the largest one may flush to 0)
-            const float d = fmaxf(w[j] - lse_m[sl], -65536.0f);
-            part += __builtin_amdgcn_exp2f(fmaf(d, lse_hi[slot], d * lse_lo[slot]));
-          }
+        if (lse_n[sl] > -__builtin_huge_valf()) {
+          // (the bare hardware exp2: a term below 2^-126 may flush to 0)
+          const float part = (__builtin_amdgcn_exp2f(e[0]) + __builtin_amdgcn_exp2f(e[1])) +
+                             (__builtin_amdgcn_exp2f(e[2]) + __builtin_amdgcn_exp2f(e[3]));
           if (kSumsInLds) sums.v[kSumsInLds ? sl : 0][tid] += (double)part;
           else lse_acc[sl] += (double)part;
         }
@@ -1226,18 +1245,11 @@ __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE 
 #pragma unroll
     for (int kk = 0; kk <= KT; ++kk) {
       if (SHARED && kk != 0 && kk != KT) continue;
-      // bring the lanes' sums to the wave's largest value (exactly, in fp64), then add them up
-      const float m = lse_m[lidx(kk)];
-      float wm = m;
-#pragma unroll
-      for (int d = 32; d >= 1; d >>= 1) wm = fmaxf(wm, __shfl_xor(wm, d));
-      double v = 0.0;
-      if (m > -__builtin_huge_valf())
-        {
-          double acc = lse_acc[lidx(kk)];
-          if (kSumsInLds) acc = sums.v[kSumsInLds ? lidx(kk) : 0][tid];
-          v = acc * exp2(((double)m - (double)wm) * ((double)lse_hi[kk] + (double)lse_lo[kk]));
-        }
+      // the lanes of a wave share the reference: their sums add up as they are
+      const float wm = lse_n[lidx(kk)];
+      double v = lse_acc[lidx(kk)];
+      if (kSumsInLds) v = sums.v[kSumsInLds ? lidx(kk) : 0][tid];
+      if (!(wm > -__builtin_huge_valf())) v = 0.0;
 #pragma unroll
       for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
       if ((tid & 63) == 0) { s.lse_wave[wv][kk] = v; s.lse_wmax[wv][kk] = wm; }
@@ -1414,19 +1426,19 @@ __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(MINF && LSE 
       } else if (!lse_ran) {
         s.lse_redo = 1;
       } else {
-        const double c64 = 1.4426950408889634 / (double)tk;
+        // the waves' sums, each relative to 2^(its reference), brought to the largest reference
         float gm = -__builtin_huge_valf();
         for (int w = 0; w < 4; ++w) gm = fmaxf(gm, s.lse_wmax[w][from]);
         double tot = 0.0;
         for (int w = 0; w < 4; ++w)
           if (s.lse_wmax[w][from] > -__builtin_huge_valf())
-            tot += s.lse_wave[w][from] * exp2(((double)s.lse_wmax[w][from] - (double)gm) * c64);
+            tot += ldexp(s.lse_wave[w][from], (int)fmaxf(s.lse_wmax[w][from] - gm, -4000.0f));
         if (!(gm > -__builtin_huge_valf())) {
           share = -__builtin_huge_val();   // no entry of the chunk carries mass
-        } else if (!(tot >= 1.0 && tot < __builtin_huge_val())) {
-          s.lse_redo = 1;                  // not finite, or the largest entry's own term is missing
+        } else if (!(tot >= 0.5 && tot < __builtin_huge_val())) {
+          s.lse_redo = 1;                  // not finite, or the largest entry's own term (>= 2^-1/2) is missing
         } else {
-          share = (double)gm / (double)tk + log(tot);
+          share = (double)gm * 0.6931471805599453 + log(tot);
         }
       }
     }
