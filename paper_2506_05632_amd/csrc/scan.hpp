@@ -533,9 +533,11 @@ __device__ double chunk_lse_exact(const typename T::elem *row, int g_begin, int 
 // Registers: four workgroups per CU (128 registers) where a workgroup reads one shared proposal or
 // at most four drafts' rows, except for the variants that read per-draft rows and form their
 // normalisers: held to 128 registers those reload spilled values inside the main loop, each reload
-// waiting for the next tile's loads as well (and one such build returned wrong target-side results,
-// which the parity tests caught and which went away with the spills), so they are allowed more and
-// take about 150: three workgroups per CU.
+// waiting for the next tile's loads as well.  (One such build also returned wrong target-side
+// results, which the parity tests caught: the compiler had put the spill store of a value that
+// every lane needs into a stretch of code that runs with the exec mask narrowed to a few lanes.
+// The build's audit looks for that in the assembly of every kernel.)  They are allowed more
+// and take about 150: three workgroups per CU.
 template <typename T, int KB, bool SHARED, bool PROBS, bool MASKED, bool LSE, bool FIN, bool MINF>
 __global__ void __launch_bounds__(kBlock, ((SHARED || KB <= 2) && !(LSE && !SHARED)) ? 4 : 2) scan_kernel(const ScanParams p) {
   using elem = typename T::elem;
