@@ -12,7 +12,7 @@ PROBE_LIB = os.path.join(HERE, "libllc_probe.so")   # machine probes for bench.p
 SOURCES = ["api.hip", "static_scratch.hip", "finalize.hip", "topm.hip", "lml.hip", "scan_f32_shared.hip", "scan_f32_perk.hip",
            "scan_bf16_shared.hip", "scan_bf16_perk.hip", "scan_f32_shared_minf.hip", "scan_f32_perk_minf.hip",
            "scan_bf16_shared_minf.hip", "scan_bf16_perk_minf.hip"]
-HEADERS = ["common.hpp", "scan.hpp", os.path.join("..", "..", "include", "llc.h")]
+HEADERS = ["common.hpp", "scan.hpp", "finalize_row.hpp", os.path.join("..", "..", "include", "llc.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
