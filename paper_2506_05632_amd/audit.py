@@ -85,8 +85,8 @@ def device_assembly(source: str, out_dir: str) -> str:
         return fh.read()
 
 
-def audit(sources=SOURCES, workers: int = 6):
-    """{source: findings} over the library's sources (only those with findings)."""
+def audit(sources=tuple(SOURCES) + ("probe.hip",), workers: int = 6):
+    """{source: findings} over the sources of both libraries (only those with findings)."""
     with tempfile.TemporaryDirectory() as tmp:
         def one(src):
             return src, spill_stores_under_narrowed_exec(device_assembly(src, tmp))
